@@ -1,0 +1,259 @@
+"""CPU oracle for the Matryoshka-Quantization nested quantized linear layer.
+
+TEST INFRASTRUCTURE ONLY: tests, the smoke check and the bench's cpu_baseline
+leg may import this package; the product path never does.  It wraps the plain
+C functions of ``mq_oracle.c`` (numpy arrays in, numpy arrays out) and shares
+nothing with the HIP path.  bf16 tensors travel as ``uint16`` bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mq_oracle.c")
+_LIB = os.path.join(_HERE, "libmq_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile mq_oracle.c with gcc (fp contraction off, OpenMP on)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+               "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.mqo_overflow_csr.restype = ctypes.c_int64
+        _lib.mqo_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i64(v):
+    return ctypes.c_int64(int(v))
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().mqo_num_threads())
+
+
+# --------------------------------------------------------------------------
+# quantize / slice / pack
+# --------------------------------------------------------------------------
+def quantize_int8(W, gamma=None, beta=None):
+    """MinMax quantizer (section 3.1.1), optional clip factors (section 3.1.2).
+
+    W float32 [N, K] -> (q uint8 [N, K], alpha float32 [N], zero float32 [N]).
+    """
+    W = _c(W, np.float32)
+    N, K = W.shape
+    g = None if gamma is None else _c(gamma, np.float32)
+    b = None if beta is None else _c(beta, np.float32)
+    q = np.empty((N, K), np.uint8)
+    alpha = np.empty(N, np.float32)
+    zero = np.empty(N, np.float32)
+    _load().mqo_quantize_int8(_p(W), _i64(N), _i64(K), _i64(K), _p(g), _p(b), _p(q), _p(alpha), _p(zero))
+    return q, alpha, zero
+
+
+def slice_codes(q, r: int, ep: bool = False):
+    """r-bit code of every int8 code (slicing equation, section 3.2; ep: errata)."""
+    q = _c(q, np.uint8)
+    out = np.empty(q.shape, np.uint8)
+    _load().mqo_slice_codes(_p(q), _i64(q.size), ctypes.c_int(r), ctypes.c_int(int(ep)), _p(out))
+    return out
+
+
+def slice_values(q, r: int, ep: bool = False):
+    """S(q, r) on the int8 grid as uint16 (256 is reachable with ep)."""
+    q = _c(q, np.uint8)
+    out = np.empty(q.shape, np.uint16)
+    _load().mqo_slice_values(_p(q), _i64(q.size), ctypes.c_int(r), ctypes.c_int(int(ep)), _p(out))
+    return out
+
+
+def pack(codes, r: int):
+    codes = _c(codes, np.uint8)
+    N, K = codes.shape
+    per = 8 // r
+    assert r in (8, 4, 2) and K % per == 0
+    out = np.empty((N, K // per), np.uint8)
+    _load().mqo_pack(_p(codes), _i64(N), _i64(K), ctypes.c_int(r), _p(out))
+    return out
+
+
+def unpack(packed, K: int, r: int):
+    packed = _c(packed, np.uint8)
+    N = packed.shape[0]
+    out = np.empty((N, K), np.uint8)
+    _load().mqo_unpack(_p(packed), _i64(N), _i64(K), ctypes.c_int(r), _p(out))
+    return out
+
+
+def overflow_csr(q, r: int):
+    """Extra-precision overflow set as (row_ptr int32 [N+1], col_idx uint16 [nnz])."""
+    q = _c(q, np.uint8)
+    N, K = q.shape
+    assert K <= 65536
+    row_ptr = np.empty(N + 1, np.int32)
+    cap = q.size
+    col = np.empty(cap, np.uint16)
+    nnz = _load().mqo_overflow_csr(_p(q), _i64(N), _i64(K), ctypes.c_int(r), _p(row_ptr), _p(col), _i64(cap))
+    return row_ptr, col[:nnz].copy()
+
+
+def dequant(q, alpha, zero, r: int, ep: bool = False):
+    q = _c(q, np.uint8)
+    N, K = q.shape
+    alpha = _c(alpha, np.float32)
+    zero = _c(zero, np.float32)
+    out = np.empty((N, K), np.float64)
+    _load().mqo_dequant(_p(q), _p(alpha), _p(zero), _i64(N), _i64(K), ctypes.c_int(r), ctypes.c_int(int(ep)), _p(out))
+    return out
+
+
+# --------------------------------------------------------------------------
+# forward / backward / gemv
+# --------------------------------------------------------------------------
+def linear_fwd(X_bf16, q, alpha, zero, r: int, ep: bool = False):
+    """Y_r = X . What_r^T in fp64.  X_bf16: uint16 [M, K]."""
+    X = _c(X_bf16, np.uint16)
+    q = _c(q, np.uint8)
+    M, K = X.shape
+    N = q.shape[0]
+    assert q.shape[1] == K
+    alpha = _c(alpha, np.float32)
+    zero = _c(zero, np.float32)
+    Y = np.empty((M, N), np.float64)
+    _load().mqo_linear_fwd(_p(X), _p(q), _p(alpha), _p(zero), _i64(M), _i64(N), _i64(K),
+                           ctypes.c_int(r), ctypes.c_int(int(ep)), _p(Y))
+    return Y
+
+
+def linear_fwd_sampled(X_bf16, q, alpha, zero, r: int, ms, ns, ep: bool = False):
+    X = _c(X_bf16, np.uint16)
+    q = _c(q, np.uint8)
+    M, K = X.shape
+    N = q.shape[0]
+    alpha = _c(alpha, np.float32)
+    zero = _c(zero, np.float32)
+    ms = _c(ms, np.int64)
+    ns = _c(ns, np.int64)
+    out = np.empty(ms.size, np.float64)
+    _load().mqo_linear_fwd_sampled(_p(X), _p(q), _p(alpha), _p(zero), _i64(M), _i64(N), _i64(K),
+                                   ctypes.c_int(r), ctypes.c_int(int(ep)), _p(ms), _p(ns),
+                                   _i64(ms.size), _p(out))
+    return out
+
+
+def _ptr_array(arrs):
+    arr_t = ctypes.c_void_p * len(arrs)
+    return arr_t(*[a.ctypes.data for a in arrs])
+
+
+def _lam(lambdas, nr):
+    if lambdas is None:
+        return None
+    lam = _c(lambdas, np.float32)
+    assert lam.size == nr
+    return lam
+
+
+def linear_bwd_dx(q, alpha, zero, dYs_bf16, lambdas, rs, ep: bool = False):
+    """dX = sum_r lambda_r dY_r . What_r in fp64 (identity STE)."""
+    q = _c(q, np.uint8)
+    N, K = q.shape
+    dYs = [_c(d, np.uint16) for d in dYs_bf16]
+    M = dYs[0].shape[0]
+    alpha = _c(alpha, np.float32)
+    zero = _c(zero, np.float32)
+    lam = _lam(lambdas, len(rs))
+    rs_c = (ctypes.c_int * len(rs))(*rs)
+    dX = np.empty((M, K), np.float64)
+    _load().mqo_linear_bwd_dx(_p(q), _p(alpha), _p(zero), _ptr_array(dYs), _p(lam), _i64(M), _i64(N),
+                              _i64(K), rs_c, ctypes.c_int(len(rs)), ctypes.c_int(int(ep)), _p(dX))
+    return dX
+
+
+def linear_bwd_dx_sampled(q, alpha, zero, dYs_bf16, lambdas, rs, ms, ks, ep: bool = False):
+    q = _c(q, np.uint8)
+    N, K = q.shape
+    dYs = [_c(d, np.uint16) for d in dYs_bf16]
+    M = dYs[0].shape[0]
+    alpha = _c(alpha, np.float32)
+    zero = _c(zero, np.float32)
+    lam = _lam(lambdas, len(rs))
+    rs_c = (ctypes.c_int * len(rs))(*rs)
+    ms = _c(ms, np.int64)
+    ks = _c(ks, np.int64)
+    out = np.empty(ms.size, np.float64)
+    _load().mqo_linear_bwd_dx_sampled(_p(q), _p(alpha), _p(zero), _ptr_array(dYs), _p(lam), _i64(M),
+                                      _i64(N), _i64(K), rs_c, ctypes.c_int(len(rs)),
+                                      ctypes.c_int(int(ep)), _p(ms), _p(ks), _i64(ms.size), _p(out))
+    return out
+
+
+def linear_bwd_dw(X_bf16, dYs_bf16, lambdas):
+    """dW = (sum_r lambda_r dY_r)^T . X in fp64; independent of the codes."""
+    X = _c(X_bf16, np.uint16)
+    M, K = X.shape
+    dYs = [_c(d, np.uint16) for d in dYs_bf16]
+    N = dYs[0].shape[1]
+    lam = _lam(lambdas, len(dYs))
+    dW = np.empty((N, K), np.float64)
+    _load().mqo_linear_bwd_dw(_p(X), _ptr_array(dYs), _p(lam), _i64(M), _i64(N), _i64(K),
+                              ctypes.c_int(len(dYs)), _p(dW))
+    return dW
+
+
+def linear_bwd_dw_sampled(X_bf16, dYs_bf16, lambdas, ns, ks):
+    X = _c(X_bf16, np.uint16)
+    M, K = X.shape
+    dYs = [_c(d, np.uint16) for d in dYs_bf16]
+    N = dYs[0].shape[1]
+    lam = _lam(lambdas, len(dYs))
+    ns = _c(ns, np.int64)
+    ks = _c(ks, np.int64)
+    out = np.empty(ns.size, np.float64)
+    _load().mqo_linear_bwd_dw_sampled(_p(X), _ptr_array(dYs), _p(lam), _i64(M), _i64(N), _i64(K),
+                                      ctypes.c_int(len(dYs)), _p(ns), _p(ks), _i64(ns.size), _p(out))
+    return out
+
+
+def gemv_sliced(x_bf16, packed, alpha_bf16, zero_bf16, r: int, K: int, ovf=None):
+    """y = x . What_r^T from a packed plane with bf16 alpha, z; ovf = (row_ptr, col_idx) or None."""
+    x = _c(x_bf16, np.uint16)
+    B = x.shape[0]
+    assert x.shape[1] == K
+    packed = _c(packed, np.uint8)
+    N = packed.shape[0]
+    assert packed.shape[1] == K * r // 8
+    a = _c(alpha_bf16, np.uint16)
+    z = _c(zero_bf16, np.uint16)
+    rp = ci = None
+    if ovf is not None:
+        rp = _c(ovf[0], np.int32)
+        ci = _c(ovf[1], np.uint16)
+    y = np.empty((B, N), np.float64)
+    _load().mqo_gemv_sliced(_p(x), _p(packed), _p(a), _p(z), _p(rp), _p(ci), _i64(B), _i64(N), _i64(K),
+                            ctypes.c_int(r), _p(y))
+    return y

@@ -1,0 +1,425 @@
+"""Pins of the CPU oracle against things other than itself.
+
+Each test names what fixes the expected value: numbers the paper prints
+(tests/golden/), closed forms, exhaustive brute force written a different way
+(bit rule of appendix A instead of the rounding formula), or a library routine
+(torch CPU float64 matmul / autograd).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from tests.util import bf16_bits, bits_to_f64
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+# --------------------------------------------------------------------------
+# slicing operator
+# --------------------------------------------------------------------------
+def test_slice_paper_worked_examples(oracle):
+    # Appendix A (53 -> 1; 240 -> 3) and errata section (234 -> 3 -> 192; unclamped 256).
+    for q, r, code, value, ep_code, ep_value in (map(int, row) for row in _rows("slicing_examples.txt")):
+        qa = np.array([[q]], np.uint8)
+        assert oracle.slice_codes(qa, r)[0, 0] == code
+        assert oracle.slice_values(qa, r)[0, 0] == value
+        assert oracle.slice_codes(qa, r, ep=True)[0, 0] == ep_code
+        assert oracle.slice_values(qa, r, ep=True)[0, 0] == ep_value
+
+
+def test_slice_level_sets(oracle):
+    # Section 5.5 / errata: int2 levels are 0, 64, 128, 192; extra precision has 2^r + 1 levels.
+    allq = np.arange(256, dtype=np.uint8)[None, :]
+    rows = {row[0]: sorted(map(int, row[1:])) for row in _rows("int2_levels.txt")}
+    assert sorted(set(oracle.slice_values(allq, 2).ravel().tolist())) == rows["plain"]
+    assert sorted(set(oracle.slice_values(allq, 2, ep=True).ravel().tolist())) == rows["ep"]
+    for r in range(1, 8):
+        assert len(set(oracle.slice_codes(allq, r).ravel().tolist())) == 2 ** r
+        assert len(set(oracle.slice_codes(allq, r, ep=True).ravel().tolist())) == 2 ** r + 1
+
+
+def test_slice_bit_rule_exhaustive(oracle):
+    # Appendix A states the rule on bits: keep the top bits and push up by one when the
+    # next lower bit is set; the clamp then curtails the overflow.  All 256 codes, r = 1..8.
+    allq = np.arange(256, dtype=np.uint8)[None, :]
+    for r in range(1, 9):
+        s = 8 - r
+        got = oracle.slice_codes(allq, r).ravel()
+        got_ep = oracle.slice_codes(allq, r, ep=True).ravel()
+        for q in range(256):
+            top = q >> s
+            nxt = (q >> (s - 1)) & 1 if s > 0 else 0
+            assert got_ep[q] == top + nxt
+            assert got[q] == min(top + nxt, 2 ** r - 1)
+
+
+def test_slice_identity_at_r8(oracle):
+    q = np.random.default_rng(0).integers(0, 256, (7, 33), dtype=np.uint8)
+    assert np.array_equal(oracle.slice_codes(q, 8), q)
+    assert np.array_equal(oracle.slice_codes(q, 8, ep=True), q)
+    assert np.array_equal(oracle.slice_values(q, 8), q.astype(np.uint16))
+
+
+def test_slice_histograms_closed_form(oracle):
+    # q = 0..255 once each.  Interior buckets hold 2^s codes, the first holds half of that,
+    # the clamped last one holds 2^s + 2^(s-1); unclamped, the extra bucket holds 2^(s-1).
+    allq = np.arange(256, dtype=np.uint8)[None, :]
+    h2 = np.bincount(oracle.slice_codes(allq, 2).ravel(), minlength=4)
+    assert h2.tolist() == [32, 64, 64, 96]
+    h4 = np.bincount(oracle.slice_codes(allq, 4).ravel(), minlength=16)
+    assert h4.tolist() == [8] + [16] * 14 + [24]
+    e2 = np.bincount(oracle.slice_codes(allq, 2, ep=True).ravel(), minlength=5)
+    assert e2.tolist() == [32, 64, 64, 64, 32]
+    e4 = np.bincount(oracle.slice_codes(allq, 4, ep=True).ravel(), minlength=17)
+    assert e4.tolist() == [8] + [16] * 15 + [8]
+
+
+def test_slice_invariants(oracle):
+    allq = np.arange(256, dtype=np.int64)
+    qa = allq.astype(np.uint8)[None, :]
+    for r in range(1, 8):
+        s, half = 8 - r, 1 << (7 - r)
+        code = oracle.slice_codes(qa, r).ravel().astype(np.int64)
+        ep = oracle.slice_codes(qa, r, ep=True).ravel().astype(np.int64)
+        val = oracle.slice_values(qa, r).ravel().astype(np.int64)
+        assert code.min() == 0 and code.max() == 2 ** r - 1
+        assert ep.max() == 2 ** r
+        assert np.all(np.diff(code) >= 0) and np.all(np.diff(ep) >= 0)     # monotone in q
+        assert np.all(val == code << s)                                      # rescale to the int8 grid
+        assert np.all(np.abs((ep << s) - allq) <= half)                       # nearest bucket when unclamped
+        assert np.all(np.abs(val - allq) <= (1 << s) - 1)
+        assert np.all(code == np.minimum(allq + half, 255) >> s)             # MSB prefix of the biased code
+        assert np.all(ep == code + (allq >= 256 - half))                      # overflow bucket
+
+
+def test_slice_is_not_composable(oracle):
+    # Rounding twice differs from rounding once (q = 31: direct 2-bit code 0; via 4 bits it is 1),
+    # so slices are always taken from the 8-bit code.
+    q = np.array([[31]], np.uint8)
+    direct = int(oracle.slice_codes(q, 2)[0, 0])
+    via4 = int(oracle.slice_codes(oracle.slice_values(q, 4).astype(np.uint8), 2)[0, 0])
+    assert direct == 0 and via4 == 1
+
+
+# --------------------------------------------------------------------------
+# MinMax quantizer
+# --------------------------------------------------------------------------
+def test_quantize_ramp_closed_form(oracle):
+    # w_k = k, k = 0..255: alpha = 1, z = 0, q = k exactly.  Shifted/scaled ramp keeps q = k.
+    ramp = np.arange(256, dtype=np.float32)[None, :]
+    q, a, z = oracle.quantize_int8(ramp)
+    assert a[0] == 1.0 and z[0] == 0.0 and np.array_equal(q[0], np.arange(256))
+    q, a, z = oracle.quantize_int8(ramp * 0.5 - 64.0)
+    assert a[0] == 0.5 and z[0] == 128.0 and np.array_equal(q[0], np.arange(256))
+
+
+def test_quantize_extremes_range_and_bound(oracle):
+    rng = np.random.default_rng(1)
+    W = (rng.standard_normal((64, 300)) * 0.02).astype(np.float32)
+    q, a, z = oracle.quantize_int8(W)
+    rows = np.arange(64)
+    assert np.all(q[rows, W.argmin(1)] == 0)
+    assert np.all(q[rows, W.argmax(1)] == 255)
+    np.testing.assert_allclose(a, (W.max(1).astype(np.float64) - W.min(1)) / 255.0, rtol=1e-6)
+    np.testing.assert_allclose(z, -W.min(1).astype(np.float64) / a, rtol=1e-6)
+    recon = a[:, None].astype(np.float64) * (q.astype(np.float64) - z[:, None])
+    assert np.all(np.abs(recon - W) <= a[:, None] * 0.5 * (1 + 1e-4))
+
+
+def test_quantize_constant_row(oracle):
+    W = np.full((2, 16), 0.37, np.float32)
+    W[1] = -2.0
+    q, a, z = oracle.quantize_int8(W)
+    assert np.all(q == 0) and np.all(a == 1.0)
+    np.testing.assert_array_equal(a[:, None] * (q - z[:, None]), W)
+
+
+def test_quantize_vs_fp64_and_library(oracle):
+    rng = np.random.default_rng(2)
+    W = (rng.standard_normal((128, 1024)) * 0.02).astype(np.float32)
+    q, a, z = oracle.quantize_int8(W)
+    # fp64 evaluation of the quantizer equation: codes may differ only by +-1 and only rarely.
+    W64 = W.astype(np.float64)
+    a64 = (W64.max(1) - W64.min(1)) / 255.0
+    z64 = -W64.min(1) / a64
+    q64 = np.clip(np.rint(W64 / a64[:, None] + z64[:, None]), 0, 255)
+    diff = np.abs(q.astype(np.int64) - q64.astype(np.int64))
+    assert diff.max() <= 1 and (diff != 0).mean() <= 1e-3
+    # torch CPU fp32 library ops, same operation order: bit-identical codes.
+    Wt = torch.from_numpy(W)
+    at = (Wt.max(1).values - Wt.min(1).values) / 255.0
+    zt = -Wt.min(1).values / at
+    qt = torch.clamp(torch.round(Wt / at[:, None] + zt[:, None]), 0, 255).to(torch.uint8)
+    assert np.array_equal(a, at.numpy()) and np.array_equal(z, zt.numpy())
+    assert np.array_equal(q, qt.numpy())
+
+
+def test_quantize_round_half_even(oracle):
+    # alpha = 1, z = 0 (row spans 0..255): x.5 goes to the even neighbour.
+    row = np.zeros((1, 8), np.float32)
+    row[0, :] = [0.0, 255.0, 0.5, 1.5, 2.5, 3.5, 100.5, 101.5]
+    q, a, z = oracle.quantize_int8(row)
+    assert a[0] == 1.0 and z[0] == 0.0
+    assert q[0].tolist() == [0, 255, 0, 2, 2, 4, 100, 102]
+
+
+def test_quantize_clip_factors(oracle):
+    # Section 3.1.2: gamma scales the max, beta the min; clipped weights saturate at 0 / 255.
+    rng = np.random.default_rng(3)
+    W = rng.standard_normal((8, 512)).astype(np.float32)
+    gamma = np.full(8, 0.5, np.float32)
+    beta = np.full(8, 0.75, np.float32)
+    q, a, z = oracle.quantize_int8(W, gamma, beta)
+    hi, lo = 0.5 * W.max(1), 0.75 * W.min(1)
+    np.testing.assert_allclose(a, (hi - lo) / 255.0, rtol=1e-6)
+    np.testing.assert_allclose(z, -lo / a, rtol=1e-6)
+    assert np.all(q[W >= hi[:, None]] == 255) and np.all(q[W <= lo[:, None]] == 0)
+    # gamma = beta = 1 is the plain MinMax quantizer
+    q1, a1, z1 = oracle.quantize_int8(W, np.ones(8, np.float32), np.ones(8, np.float32))
+    q0, a0, z0 = oracle.quantize_int8(W)
+    assert np.array_equal(q1, q0) and np.array_equal(a1, a0) and np.array_equal(z1, z0)
+
+
+def test_quantize_row_stride(oracle):
+    # per-output-channel: every row uses its own alpha, z.
+    rng = np.random.default_rng(4)
+    W = rng.standard_normal((5, 64)).astype(np.float32) * np.array([[1], [10], [0.1], [3], [7]], np.float32)
+    q, a, z = oracle.quantize_int8(W)
+    for n in range(5):
+        qn, an, zn = oracle.quantize_int8(W[n:n + 1])
+        assert np.array_equal(q[n], qn[0]) and a[n] == an[0] and z[n] == zn[0]
+
+
+# --------------------------------------------------------------------------
+# packing and the overflow list
+# --------------------------------------------------------------------------
+def test_pack_hand_examples(oracle):
+    codes4 = np.array([[1, 2, 3, 4, 15, 0, 9, 10]], np.uint8)
+    assert oracle.pack(codes4, 4).tolist() == [[0x21, 0x43, 0x0F, 0xA9]]
+    codes2 = np.array([[0, 1, 2, 3, 3, 2, 1, 0]], np.uint8)
+    assert oracle.pack(codes2, 2).tolist() == [[0b11100100, 0b00011011]]
+    codes8 = np.array([[7, 200]], np.uint8)
+    assert oracle.pack(codes8, 8).tolist() == [[7, 200]]
+
+
+def test_pack_roundtrip(oracle):
+    rng = np.random.default_rng(5)
+    for r in (8, 4, 2):
+        codes = rng.integers(0, 2 ** r, (9, 64), dtype=np.uint8)
+        p = oracle.pack(codes, r)
+        assert p.shape == (9, 64 * r // 8)
+        assert np.array_equal(oracle.unpack(p, 64, r), codes)
+
+
+def test_overflow_csr(oracle):
+    rng = np.random.default_rng(6)
+    q = rng.integers(0, 256, (50, 512), dtype=np.uint8)
+    for r in (2, 4, 3, 6):
+        half = 1 << (7 - r)
+        rp, ci = oracle.overflow_csr(q, r)
+        mask = q >= 256 - half                                  # brute count of the overflow bucket
+        assert rp[0] == 0 and rp[-1] == mask.sum() == ci.size
+        assert np.array_equal(np.diff(rp), mask.sum(1))
+        for n in (0, 17, 49):
+            assert np.array_equal(ci[rp[n]:rp[n + 1]], np.nonzero(mask[n])[0])
+        # the clamped dense plane plus the list rebuilds the unclamped code
+        dense = oracle.slice_codes(q, r).astype(np.int64)
+        dense[mask] += 1
+        assert np.array_equal(dense, oracle.slice_codes(q, r, ep=True))
+    # uniform codes: the bucket holds a 2^(s-1)/256 share -> 1/8 at r = 2, 1/32 at r = 4
+    big = rng.integers(0, 256, (64, 4096), dtype=np.uint8)
+    assert abs(oracle.overflow_csr(big, 2)[1].size / big.size - 1 / 8) < 5e-3
+    assert abs(oracle.overflow_csr(big, 4)[1].size / big.size - 1 / 32) < 3e-3
+    rp8, ci8 = oracle.overflow_csr(q, 8)
+    assert ci8.size == 0 and np.all(rp8 == 0)
+
+
+# --------------------------------------------------------------------------
+# dequant / forward
+# --------------------------------------------------------------------------
+def _small_layer(oracle, seed=0, M=5, N=24, K=64):
+    g = torch.Generator().manual_seed(seed)
+    W = (torch.randn(N, K, generator=g) * 0.02).numpy()
+    X = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    q, a, z = oracle.quantize_int8(W)
+    return W, X, q, a, z
+
+
+def test_dequant_reconstruction(oracle):
+    W, X, q, a, z = _small_layer(oracle)
+    W8 = oracle.dequant(q, a, z, 8)
+    assert np.all(np.abs(W8 - W) <= a[:, None] * 0.5 * (1 + 1e-4))
+    for r in (4, 2):
+        Wr = oracle.dequant(q, a, z, r)
+        S = oracle.slice_values(q, r).astype(np.float64)
+        np.testing.assert_allclose(Wr, a[:, None].astype(np.float64) * (S - z[:, None]), rtol=1e-15)
+        levels = {round(v, 9) for v in ((Wr[0] / a[0]) + z[0])}
+        assert len(levels) <= 2 ** r
+
+
+def test_forward_vs_library_matmul(oracle):
+    W, X, q, a, z = _small_layer(oracle)
+    Xd = X.to(torch.float64)
+    # r = 8: no slicing involved, a plain dense linear with the dequantized weight.
+    W8 = torch.from_numpy(a.astype(np.float64))[:, None] * (torch.from_numpy(q.astype(np.float64)) -
+                                                            torch.from_numpy(z.astype(np.float64))[:, None])
+    np.testing.assert_allclose(oracle.linear_fwd(bf16_bits(X), q, a, z, 8), (Xd @ W8.T).numpy(), rtol=1e-12, atol=1e-15)
+    for r, ep in ((4, False), (2, False), (2, True), (4, True), (3, False), (6, True)):
+        S = torch.from_numpy(oracle.slice_values(q, r, ep=ep).astype(np.float64))
+        Wr = torch.from_numpy(a.astype(np.float64))[:, None] * (S - torch.from_numpy(z.astype(np.float64))[:, None])
+        np.testing.assert_allclose(oracle.linear_fwd(bf16_bits(X), q, a, z, r, ep=ep), (Xd @ Wr.T).numpy(),
+                                   rtol=1e-12, atol=1e-15)
+
+
+def test_forward_one_hot_and_orientation(oracle):
+    # X = e_k returns column k of What_r: pins the [N, K] orientation and the index order.
+    W, X, q, a, z = _small_layer(oracle, N=24, K=64)
+    eye = torch.eye(64).to(torch.bfloat16)
+    for r in (8, 4, 2):
+        Y = oracle.linear_fwd(bf16_bits(eye), q, a, z, r)      # [K, N]
+        np.testing.assert_allclose(Y, oracle.dequant(q, a, z, r).T, rtol=1e-15)
+
+
+def test_forward_ramp_closed_form(oracle):
+    # One row w_k = k (alpha = 1, z = 0, q = k), x = ones: Y_8 = sum k = 32640 and
+    # Y_r = 2^s * (sum over the closed-form histogram of code * count).
+    ramp = np.arange(256, dtype=np.float32)[None, :]
+    q, a, z = oracle.quantize_int8(ramp)
+    ones = torch.ones(1, 256).to(torch.bfloat16)
+    assert oracle.linear_fwd(bf16_bits(ones), q, a, z, 8)[0, 0] == 32640.0
+    assert oracle.linear_fwd(bf16_bits(ones), q, a, z, 2)[0, 0] == 64.0 * (64 * 1 + 64 * 2 + 96 * 3)
+    assert oracle.linear_fwd(bf16_bits(ones), q, a, z, 4)[0, 0] == 16.0 * (16 * sum(range(1, 15)) + 24 * 15)
+    assert oracle.linear_fwd(bf16_bits(ones), q, a, z, 2, ep=True)[0, 0] == 64.0 * (64 * 1 + 64 * 2 + 64 * 3 + 32 * 4)
+
+
+def test_forward_sampled_matches_full(oracle):
+    W, X, q, a, z = _small_layer(oracle, M=7, N=24, K=64)
+    ms = np.array([0, 3, 6, 6, 2])
+    ns = np.array([23, 0, 5, 11, 7])
+    for r, ep in ((8, False), (4, False), (2, True)):
+        full = oracle.linear_fwd(bf16_bits(X), q, a, z, r, ep=ep)
+        np.testing.assert_array_equal(oracle.linear_fwd_sampled(bf16_bits(X), q, a, z, r, ms, ns, ep=ep), full[ms, ns])
+
+
+def test_forward_config1_brute_force(oracle):
+    # The whole tiny configuration (16 x 256 x 256, r = 8, 4, 2) against pure-Python loops on a
+    # sample of outputs and the library matmul on all of them.
+    from paper_2502_06786_amd import synth
+    case = synth.linear_case(1, with_grads=False)
+    q, a, z = oracle.quantize_int8(case.W.numpy())
+    Xb = bf16_bits(case.X)
+    Xf = bits_to_f64(Xb)
+    for r in (8, 4, 2):
+        Y = oracle.linear_fwd(Xb, q, a, z, r)
+        S = oracle.slice_values(q, r).astype(np.float64)
+        for m, n in ((0, 0), (15, 255), (7, 100)):
+            acc = 0.0
+            for k in range(256):
+                acc += Xf[m, k] * (float(a[n]) * (S[n, k] - float(z[n])))
+            assert math.isclose(Y[m, n], acc, rel_tol=1e-12, abs_tol=1e-15)
+        lib = case.X.to(torch.float64) @ torch.from_numpy(a.astype(np.float64)[:, None] * (S - z.astype(np.float64)[:, None])).T
+        np.testing.assert_allclose(Y, lib.numpy(), rtol=1e-10, atol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# backward (identity straight-through estimator)
+# --------------------------------------------------------------------------
+def test_backward_vs_autograd(oracle):
+    M, N, K = 6, 24, 64
+    W, X, q, a, z = _small_layer(oracle, M=M, N=N, K=K)
+    g = torch.Generator().manual_seed(9)
+    dYs = [(torch.randn(M, N, generator=g) * 1e-3).to(torch.bfloat16) for _ in range(3)]
+    lambdas = (0.1, 0.4, 1.0)
+    rs = (8, 4, 2)
+    for ep in (False, True):
+        Wt = torch.from_numpy(W).to(torch.float64).requires_grad_(True)
+        Xt = X.to(torch.float64).requires_grad_(True)
+        loss = 0.0
+        for lam, r, dY in zip(lambdas, rs, dYs):
+            What = torch.from_numpy(oracle.dequant(q, a, z, r, ep=ep))
+            Wste = Wt + (What - Wt).detach()          # value What_r, gradient identity
+            # lambda is float32 at the oracle's interface
+            loss = loss + float(np.float32(lam)) * (dY.to(torch.float64) * (Xt @ Wste.T)).sum()
+        loss.backward()
+        dX = oracle.linear_bwd_dx(q, a, z, [bf16_bits(d) for d in dYs], lambdas, rs, ep=ep)
+        dW = oracle.linear_bwd_dw(bf16_bits(X), [bf16_bits(d) for d in dYs], lambdas)
+        np.testing.assert_allclose(dX, Xt.grad.numpy(), rtol=1e-10, atol=1e-18)
+        np.testing.assert_allclose(dW, Wt.grad.numpy(), rtol=1e-10, atol=1e-18)
+
+
+def test_backward_single_r8_is_dense_linear_backward(oracle):
+    M, N, K = 4, 16, 32
+    W, X, q, a, z = _small_layer(oracle, seed=3, M=M, N=N, K=K)
+    g = torch.Generator().manual_seed(11)
+    dY = torch.randn(M, N, generator=g).to(torch.bfloat16)
+    W8 = oracle.dequant(q, a, z, 8)
+    dX = oracle.linear_bwd_dx(q, a, z, [bf16_bits(dY)], None, (8,))
+    dW = oracle.linear_bwd_dw(bf16_bits(X), [bf16_bits(dY)], None)
+    np.testing.assert_allclose(dX, dY.to(torch.float64).numpy() @ W8, rtol=1e-12)
+    np.testing.assert_allclose(dW, dY.to(torch.float64).numpy().T @ X.to(torch.float64).numpy(), rtol=1e-12)
+
+
+def test_backward_sampled_matches_full(oracle):
+    M, N, K = 6, 24, 64
+    W, X, q, a, z = _small_layer(oracle, M=M, N=N, K=K)
+    g = torch.Generator().manual_seed(10)
+    dYs = [bf16_bits((torch.randn(M, N, generator=g) * 1e-3).to(torch.bfloat16)) for _ in range(3)]
+    lambdas, rs = (0.1, 0.1, 1.0), (8, 4, 2)
+    dX = oracle.linear_bwd_dx(q, a, z, dYs, lambdas, rs)
+    dW = oracle.linear_bwd_dw(bf16_bits(X), dYs, lambdas)
+    ms, ks, ns = np.array([0, 5, 2]), np.array([63, 0, 31]), np.array([23, 1, 12])
+    np.testing.assert_allclose(oracle.linear_bwd_dx_sampled(q, a, z, dYs, lambdas, rs, ms, ks), dX[ms, ks], rtol=1e-13)
+    np.testing.assert_allclose(oracle.linear_bwd_dw_sampled(bf16_bits(X), dYs, lambdas, ns, ks), dW[ns, ks], rtol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# decode GEMV
+# --------------------------------------------------------------------------
+def _bf16_round(a32: np.ndarray):
+    t = torch.from_numpy(a32).to(torch.bfloat16)
+    return bf16_bits(t), t.to(torch.float32).numpy()
+
+
+def test_gemv_equals_forward_with_bf16_params(oracle):
+    W, X, q, a, z = _small_layer(oracle, M=4, N=24, K=64)
+    ab, a32 = _bf16_round(a)
+    zb, z32 = _bf16_round(z)
+    for r in (8, 4, 2):
+        packed = oracle.pack(oracle.slice_codes(q, r), r)
+        y = oracle.gemv_sliced(bf16_bits(X), packed, ab, zb, r, 64)
+        np.testing.assert_allclose(y, oracle.linear_fwd(bf16_bits(X), q, a32, z32, r), rtol=1e-12, atol=1e-15)
+        y_ep = oracle.gemv_sliced(bf16_bits(X), packed, ab, zb, r, 64, ovf=oracle.overflow_csr(q, r))
+        np.testing.assert_allclose(y_ep, oracle.linear_fwd(bf16_bits(X), q, a32, z32, r, ep=True), rtol=1e-12, atol=1e-15)
+
+
+def test_gemv_one_hot_and_ep_difference(oracle):
+    rng = np.random.default_rng(12)
+    N, K = 16, 128
+    q = rng.integers(0, 256, (N, K), dtype=np.uint8)
+    ab, a32 = _bf16_round((rng.random(N) * 1e-3 + 1e-4).astype(np.float32))
+    zb, z32 = _bf16_round((rng.random(N) * 255).astype(np.float32))
+    eye = torch.eye(K).to(torch.bfloat16)[:16]                      # 16 one-hot rows
+    for r in (4, 2):
+        s = 8 - r
+        codes = oracle.slice_codes(q, r)
+        packed = oracle.pack(codes, r)
+        y = oracle.gemv_sliced(bf16_bits(eye), packed, ab, zb, r, K)   # y[b, n] = What[n, b]
+        want = a32[None, :].astype(np.float64) * ((codes[:, :16].T.astype(np.float64) * 2 ** s) - z32[None, :])
+        np.testing.assert_allclose(y, want, rtol=1e-14)
+        # extra precision minus plain = alpha_n * 2^s * (sum of x over the row's overflow columns)
+        g = torch.Generator().manual_seed(13)
+        x = torch.randn(3, K, generator=g).to(torch.bfloat16)
+        rp, ci = oracle.overflow_csr(q, r)
+        d = oracle.gemv_sliced(bf16_bits(x), packed, ab, zb, r, K, ovf=(rp, ci)) - \
+            oracle.gemv_sliced(bf16_bits(x), packed, ab, zb, r, K)
+        xf = x.to(torch.float64).numpy()
+        want = np.stack([[a32[n] * 2.0 ** s * xf[b, ci[rp[n]:rp[n + 1]]].sum() for n in range(N)] for b in range(3)])
+        np.testing.assert_allclose(d, want, rtol=1e-9, atol=1e-12)
