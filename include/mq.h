@@ -1,0 +1,179 @@
+/*
+ * mq.h - C ABI of the MI355X (gfx950) nested quantized linear layer of
+ * Matryoshka Quantization (arXiv 2502.06786).
+ *
+ * One int8 code per weight, one (alpha, z) pair per output channel; every lower
+ * bit-width r is read out of the same int8 code with the paper's slicing
+ * operator and shares alpha and z.  The five operations below are the whole
+ * hot path: quantize, slice (+pack), fused multi-precision forward, the
+ * straight-through backward used in co-training, and the weight-only decode
+ * GEMV.
+ *
+ * Conventions
+ *   - Weight W[N][K] row-major: N output channels, K input features.  M tokens.
+ *   - s = 8 - r, half = 2^(s-1) (0 for r = 8).
+ *   - bf16 tensors are passed as uint16_t bit patterns.
+ *   - EVERY pointer is a DEVICE pointer unless its comment says "host".
+ *   - The caller owns every buffer.  The library allocates nothing, frees
+ *     nothing and never synchronises: all work is enqueued on `hip_stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream).  Scratch
+ *     memory comes from a caller-provided workspace sized by
+ *     mq_workspace_bytes().
+ *   - Errors are return codes; arguments are checked on the host before any
+ *     launch and nothing is enqueued when a call fails.  After a failure no
+ *     output is defined.
+ *   - Device pointers must be 16-byte aligned and all matrices are dense
+ *     (row stride = row length) except W, which has `ldw`.
+ *   - Reentrant: no mutable global state.  Two calls may run concurrently on
+ *     different streams when their buffers (workspace included) do not overlap.
+ */
+#ifndef MQ_H
+#define MQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MQ_OK = 0,
+    MQ_ERR_NULL = 1,      /* a required pointer is NULL                                    */
+    MQ_ERR_SHAPE = 2,     /* negative size, size beyond a documented limit                 */
+    MQ_ERR_BITS = 3,      /* r outside the accepted set, duplicate r, nr out of range      */
+    MQ_ERR_ALIGN = 4,     /* pointer not 16-byte aligned or a row length not a legal multiple */
+    MQ_ERR_WORKSPACE = 5, /* workspace NULL or smaller than mq_workspace_bytes()           */
+    MQ_ERR_CAPACITY = 6,  /* reserved: overflow-list capacity (see mq_overflow.nnz)         */
+    MQ_ERR_DEVICE = 7     /* a HIP call failed (launch error)                              */
+} mq_status;
+
+enum {
+    MQ_FLAG_EXTRA_PRECISION = 1, /* errata section: slice without the clamp (2^r + 1 levels) */
+    MQ_FLAG_PACKED = 2,          /* mq_slice: write 8/r codes per byte instead of one        */
+    MQ_FLAG_ACCUM_DW = 4         /* mq_linear_bwd: dW += instead of dW =                     */
+};
+
+enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1 };
+
+/*
+ * Extra-precision overflow set (errata section: weights whose rounded r-bit
+ * code equals 2^r need "an extra bit").  The paper gives no storage format;
+ * this one is CSR over output channels: the columns k of row n with
+ * q[n,k] >= 256 - half, ascending, are col_idx[row_ptr[n] .. row_ptr[n+1]).
+ * K <= 65536 so a column fits uint16_t.
+ */
+typedef struct {
+    int32_t *row_ptr;  /* device [N+1]                                                    */
+    uint16_t *col_idx; /* device [capacity]                                               */
+    int64_t capacity;  /* in: number of entries col_idx can hold                          */
+    int64_t *nnz;      /* device scalar, out: total size of the set.  If it exceeds
+                          `capacity`, col_idx holds only the first `capacity` entries in
+                          row order and row_ptr still describes the full set; the caller
+                          must check after the stream has completed.                      */
+} mq_overflow;
+
+/*
+ * MinMax quantizer to c = 8 bits, one (alpha, z) per output channel
+ * (section 3.1.1, MinMax equation; with gamma/beta the OmniQuant form of
+ * section 3.1.2):
+ *     hi = gamma_n * max_k W[n,k]     lo = beta_n * min_k W[n,k]
+ *     alpha_n = (hi - lo) / 255       z_n = -lo / alpha_n
+ *     Q[n,k]  = clamp(round(W[n,k] / alpha_n + z_n), 0, 255)
+ * fp32 throughout, one IEEE operation per symbol in that order (division is
+ * correctly rounded, the add is not fused), round = half-to-even.  A row with
+ * hi == lo takes alpha = 1, z = -lo (all codes 0).  W must be finite.
+ *   W      [N, ldw] fp32, ldw >= K
+ *   gamma  [N] fp32 or NULL (= 1)      beta [N] fp32 or NULL (= 1)
+ *   Q      [N, K] uint8 out            alpha, zero [N] fp32 out
+ * K >= 1 when N > 0.  N == 0 is a no-op.
+ */
+mq_status mq_quantize_int8(const float *W, int64_t N, int64_t K, int64_t ldw,
+                           const float *gamma, const float *beta,
+                           uint8_t *Q, float *alpha, float *zero, void *hip_stream);
+
+/*
+ * Slicing operator S(q, r) of section 3.2 (slicing equation; appendix A for
+ * the rounding):  code = min((q + half) >> s, 2^r - 1), S = code << s.
+ *   Q    [N, K] uint8
+ *   r    1..8 (r = 8 is the identity)
+ *   out  without MQ_FLAG_PACKED: [N, K] uint8, the codes (NOT shifted back up);
+ *        with MQ_FLAG_PACKED (r in {8, 4, 2}, K a multiple of 8/r):
+ *        [N, K*r/8] bytes, element k of a row in byte k/(8/r) at bit offset
+ *        r * (k mod 8/r).  The packing order is this library's definition.
+ *   ovf  required iff MQ_FLAG_EXTRA_PRECISION (errata section): the dense plane
+ *        written to `out` is the clamped one (bit-identical to the plain
+ *        slice) and the weights whose unclamped code is 2^r are listed in *ovf.
+ *        `ovf` itself is a host struct holding device pointers.  Needs K <= 65536.
+ */
+mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uint32_t flags,
+                   uint8_t *out, const mq_overflow *ovf, void *hip_stream);
+
+/*
+ * Fused multi-precision forward, the F(S(Q(theta, c), r), x) of the MatQuant
+ * objective (section 3.2) for every r in rs[] in ONE pass over X and Q:
+ *     Y_i[m,n] = sum_k X[m,k] * alpha_n * (S(Q[n,k], rs[i]) - z_n)
+ * bf16 x bf16 -> fp32 matrix-core accumulation, rounded once to bf16.
+ *   X      [M, K] bf16               Q [N, K] uint8        alpha, zero [N] fp32
+ *   rs     host int[nr], distinct values in 1..8; nr in 1..3
+ *   flags  MQ_FLAG_EXTRA_PRECISION: slices use the unclamped code
+ *   Y      host array of nr device pointers, each [M, N] bf16 out
+ *   ws     workspace of at least mq_workspace_bytes(MQ_OP_LINEAR_FWD, M, N, K, nr)
+ * K must be a multiple of 16 and N a multiple of 8 (16-byte rows).  M is free.
+ * M == 0 or N == 0 is a no-op.
+ */
+mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, const float *alpha,
+                              const float *zero, int64_t M, int64_t N, int64_t K,
+                              const int *rs, int nr, uint32_t flags,
+                              uint16_t *const *Y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Straight-through backward of the same layer (sections 3.1.1 / 3.1.2 use an
+ * STE through the quantizer; identity through both rounds and both clamps,
+ * alpha and z held constant) for the weighted sum of per-bit-width losses of
+ * the MatQuant objective (section 3.2):
+ *     dX[m,k] = sum_i lambda_i sum_n dY_i[m,n] * alpha_n * (S(Q[n,k], rs[i]) - z_n)
+ *     dW[n,k] = sum_m (sum_i lambda_i dY_i[m,n]) * X[m,k]
+ *   dY      host array of nr device pointers, each [M, N] bf16
+ *   lambda  host float[nr] or NULL (= 1)
+ *   dX      [M, K] bf16 out, or NULL to skip
+ *   dW      [N, K] fp32 out (accumulated into with MQ_FLAG_ACCUM_DW), or NULL to skip
+ *   ws      workspace of at least mq_workspace_bytes(MQ_OP_LINEAR_BWD, M, N, K, nr)
+ * K must be a multiple of 16, N a multiple of 16 and M a multiple of 8.
+ * The bf16 rounding of lambda_i * alpha_n * dY_i (dX) and of
+ * sum_i lambda_i dY_i (dW) before the matrix-core contraction is part of the
+ * stated tolerance.
+ */
+mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero,
+                        const uint16_t *const *dY, const float *lambda,
+                        int64_t M, int64_t N, int64_t K, const int *rs, int nr, uint32_t flags,
+                        uint16_t *dX, float *dW, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Weight-only decode GEMV on a packed r-bit plane (section 1: decode is bound
+ * by moving the weights out of HBM; the errata section asks for sparse
+ * additions of the extra bits):
+ *     y[b,n] = alpha_n * (2^s * (sum_k code[n,k] x[b,k] + sum_{k in O_n} x[b,k])
+ *                         - z_n * sum_k x[b,k])
+ *   x       [B, K] bf16, 1 <= B <= 16
+ *   packed  [N, K*r/8] as written by mq_slice with MQ_FLAG_PACKED, r in {8, 4, 2}
+ *   alpha_bf16, zero_bf16  [N] bf16
+ *   ovf     host struct or NULL (= plain slice); row_ptr/col_idx as written by mq_slice
+ *           with nnz <= capacity
+ *   y       [B, N] bf16 out
+ * K must be a multiple of 128.  N == 0 is a no-op.
+ */
+mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
+                         const uint16_t *zero_bf16, const mq_overflow *ovf,
+                         int64_t B, int64_t N, int64_t K, int r, uint16_t *y, void *hip_stream);
+
+/* Bytes of workspace `op` needs at these sizes (0 on invalid arguments). */
+size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int nr);
+
+/* Static, human-readable name of a status code. */
+const char *mq_status_string(mq_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MQ_H */

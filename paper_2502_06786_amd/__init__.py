@@ -1,0 +1,18 @@
+"""MI355X-native nested quantized linear layer of Matryoshka Quantization (arXiv 2502.06786).
+
+The implementation is the HIP library ``libmq.so`` (C ABI in ``include/mq.h``); ``binding`` marshals
+torch tensors into it.  The binding is loaded on first use and raises ImportError when the library
+has not been built: there is no other implementation to fall back to.
+"""
+_BINDING_NAMES = {
+    "mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
+    "mq_workspace_bytes", "status_string", "Overflow", "MqError", "lib", "LIB_PATH", "EXPORTS",
+    "MQ_FLAG_EXTRA_PRECISION", "MQ_FLAG_PACKED", "MQ_FLAG_ACCUM_DW", "MQ_OP_LINEAR_FWD", "MQ_OP_LINEAR_BWD",
+}
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES:
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError(name)

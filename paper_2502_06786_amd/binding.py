@@ -1,0 +1,212 @@
+"""Thin Python binding of the C ABI in include/mq.h.
+
+Argument marshalling only: every function checks dtypes/devices, passes
+``tensor.data_ptr()`` and the current HIP stream to libmq.so and raises on a
+non-zero status.  PyTorch is used for device memory and streams, nothing else;
+there is no CPU fallback: if libmq.so is missing the import fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmq.so")
+
+MQ_FLAG_EXTRA_PRECISION = 1
+MQ_FLAG_PACKED = 2
+MQ_FLAG_ACCUM_DW = 4
+MQ_OP_LINEAR_FWD = 0
+MQ_OP_LINEAR_BWD = 1
+
+EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
+           "mq_workspace_bytes", "mq_status_string"]
+
+
+class MqError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: mq_status {status} ({status_string(status)})")
+        self.status = status
+
+
+class _Overflow(ctypes.Structure):
+    _fields_ = [("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p),
+                ("capacity", ctypes.c_int64), ("nnz", ctypes.c_void_p)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(the HIP library is the only implementation; there is no fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, ci, u32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t
+    lib.mq_quantize_int8.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
+    lib.mq_slice.argtypes = [vp, i64, i64, ci, u32, vp, ctypes.POINTER(_Overflow), vp]
+    lib.mq_linear_fwd_multi.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32,
+                                        ctypes.POINTER(vp), vp, sz, vp]
+    lib.mq_linear_bwd.argtypes = [vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float), i64, i64,
+                                  i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
+    lib.mq_gemv_sliced.argtypes = [vp, vp, vp, vp, ctypes.POINTER(_Overflow), i64, i64, i64, ci, vp, vp]
+    lib.mq_workspace_bytes.argtypes = [ci, i64, i64, i64, ci]
+    lib.mq_workspace_bytes.restype = sz
+    lib.mq_status_string.argtypes = [ci]
+    lib.mq_status_string.restype = ctypes.c_char_p
+    for name in EXPORTS[:5]:
+        getattr(lib, name).restype = ci
+    return lib
+
+
+_lib = _load()
+
+
+def lib() -> ctypes.CDLL:
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return _lib.mq_status_string(int(status)).decode()
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("tensor must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise MqError(status, what)
+
+
+class Overflow:
+    """Device buffers of the extra-precision overflow set (CSR rows, uint16 columns)."""
+
+    def __init__(self, N: int, capacity: int, device="cuda"):
+        self.row_ptr = torch.empty(N + 1, dtype=torch.int32, device=device)
+        self.col_idx = torch.empty(max(capacity, 1), dtype=torch.int16, device=device)  # uint16 bit patterns
+        self.nnz = torch.zeros(1, dtype=torch.int64, device=device)
+        self.capacity = capacity
+
+    def c_struct(self) -> _Overflow:
+        return _Overflow(self.row_ptr.data_ptr(), self.col_idx.data_ptr(), self.capacity, self.nnz.data_ptr())
+
+
+def mq_workspace_bytes(op: int, M: int, N: int, K: int, nr: int) -> int:
+    return int(_lib.mq_workspace_bytes(op, M, N, K, nr))
+
+
+def mq_quantize_int8(W, gamma=None, beta=None, Q=None, alpha=None, zero=None):
+    """W fp32 [N, K] (row stride allowed) -> (Q uint8 [N, K], alpha fp32 [N], zero fp32 [N])."""
+    if W.dtype != torch.float32 or not W.is_cuda or W.dim() != 2 or W.stride(1) != 1:
+        raise ValueError("W must be a 2-D fp32 GPU tensor with unit column stride")
+    N, K = W.shape
+    ldw = W.stride(0) if N > 1 else max(K, W.stride(0))
+    Q = torch.empty(N, K, dtype=torch.uint8, device=W.device) if Q is None else Q
+    alpha = torch.empty(N, dtype=torch.float32, device=W.device) if alpha is None else alpha
+    zero = torch.empty(N, dtype=torch.float32, device=W.device) if zero is None else zero
+    st = _lib.mq_quantize_int8(ctypes.c_void_p(W.data_ptr()), N, K, ldw, _ptr(gamma, torch.float32),
+                               _ptr(beta, torch.float32), _ptr(Q, torch.uint8), _ptr(alpha, torch.float32),
+                               _ptr(zero, torch.float32), _stream())
+    _check(st, "mq_quantize_int8")
+    return Q, alpha, zero
+
+
+def mq_slice(Q, r: int, packed: bool = False, extra_precision: bool = False, out=None, ovf: Overflow | None = None,
+             capacity: int | None = None):
+    """Slice int8 codes to r bits.  Returns `out`, or (out, Overflow) with extra_precision."""
+    N, K = Q.shape
+    flags = (MQ_FLAG_PACKED if packed else 0) | (MQ_FLAG_EXTRA_PRECISION if extra_precision else 0)
+    if out is None:
+        cols = K * r // 8 if packed else K
+        out = torch.empty(N, cols, dtype=torch.uint8, device=Q.device)
+    c_ovf = None
+    if extra_precision:
+        if ovf is None:
+            ovf = Overflow(N, N * K if capacity is None else capacity, Q.device)
+        c_ovf = ctypes.byref(ovf.c_struct())
+    st = _lib.mq_slice(_ptr(Q, torch.uint8), N, K, r, flags, _ptr(out, torch.uint8), c_ovf, _stream())
+    _check(st, "mq_slice")
+    return (out, ovf) if extra_precision else out
+
+
+def _int_array(vals):
+    return (ctypes.c_int * len(vals))(*[int(v) for v in vals])
+
+
+def _ptr_array(tensors, dtype):
+    return (ctypes.c_void_p * len(tensors))(*[t.data_ptr() if _ptr(t, dtype) else None for t in tensors])
+
+
+def mq_linear_fwd_multi(X, Q, alpha, zero, rs, extra_precision: bool = False, Y=None, ws=None):
+    """X bf16 [M, K], Q uint8 [N, K] -> list of Y_r bf16 [M, N], one per r in rs."""
+    M, K = X.shape
+    N = Q.shape[0]
+    if Q.shape[1] != K:
+        raise ValueError("X and Q disagree on K")
+    nr = len(rs)
+    if Y is None:
+        Y = [torch.empty(M, N, dtype=torch.bfloat16, device=X.device) for _ in range(nr)]
+    need = mq_workspace_bytes(MQ_OP_LINEAR_FWD, M, N, K, nr)
+    if ws is None:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=X.device)
+    flags = MQ_FLAG_EXTRA_PRECISION if extra_precision else 0
+    st = _lib.mq_linear_fwd_multi(_ptr(X, torch.bfloat16), _ptr(Q, torch.uint8), _ptr(alpha, torch.float32),
+                                  _ptr(zero, torch.float32), M, N, K, _int_array(rs), nr, flags,
+                                  _ptr_array(Y, torch.bfloat16), _ptr(ws), ws.numel(), _stream())
+    _check(st, "mq_linear_fwd_multi")
+    return Y
+
+
+def mq_linear_bwd(X, Q, alpha, zero, dY, lambdas, rs, extra_precision: bool = False, need_dX: bool = True,
+                  need_dW: bool = True, dX=None, dW=None, accumulate_dW: bool = False, ws=None):
+    """STE backward: returns (dX bf16 [M, K] or None, dW fp32 [N, K] or None)."""
+    M, K = X.shape
+    N = Q.shape[0]
+    nr = len(rs)
+    if len(dY) != nr:
+        raise ValueError("one dY per r")
+    if need_dX and dX is None:
+        dX = torch.empty(M, K, dtype=torch.bfloat16, device=X.device)
+    if need_dW and dW is None:
+        dW = torch.zeros(N, K, dtype=torch.float32, device=X.device) if accumulate_dW else \
+            torch.empty(N, K, dtype=torch.float32, device=X.device)
+    need = mq_workspace_bytes(MQ_OP_LINEAR_BWD, M, N, K, nr)
+    if ws is None:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=X.device)
+    lam = None
+    if lambdas is not None:
+        lam = (ctypes.c_float * nr)(*[float(v) for v in lambdas])
+    flags = (MQ_FLAG_EXTRA_PRECISION if extra_precision else 0) | (MQ_FLAG_ACCUM_DW if accumulate_dW else 0)
+    st = _lib.mq_linear_bwd(_ptr(X, torch.bfloat16), _ptr(Q, torch.uint8), _ptr(alpha, torch.float32),
+                            _ptr(zero, torch.float32), _ptr_array(dY, torch.bfloat16), lam, M, N, K,
+                            _int_array(rs), nr, flags, _ptr(dX if need_dX else None, torch.bfloat16),
+                            _ptr(dW if need_dW else None, torch.float32), _ptr(ws), ws.numel(), _stream())
+    _check(st, "mq_linear_bwd")
+    return (dX if need_dX else None), (dW if need_dW else None)
+
+
+def mq_gemv_sliced(x, packed, alpha_bf16, zero_bf16, r: int, K: int, ovf: Overflow | None = None, y=None):
+    """x bf16 [B, K], packed uint8 [N, K*r/8] -> y bf16 [B, N]."""
+    B = x.shape[0]
+    N = packed.shape[0]
+    if x.shape[1] != K or packed.shape[1] != K * r // 8:
+        raise ValueError("shape mismatch")
+    if y is None:
+        y = torch.empty(B, N, dtype=torch.bfloat16, device=x.device)
+    c_ovf = ctypes.byref(ovf.c_struct()) if ovf is not None else None
+    st = _lib.mq_gemv_sliced(_ptr(x, torch.bfloat16), _ptr(packed, torch.uint8), _ptr(alpha_bf16, torch.bfloat16),
+                             _ptr(zero_bf16, torch.bfloat16), c_ovf, B, N, K, r, _ptr(y, torch.bfloat16), _stream())
+    _check(st, "mq_gemv_sliced")
+    return y

@@ -1,0 +1,52 @@
+// Shared host/device helpers of the gfx950 kernels (not part of the public ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/mq.h"
+
+namespace mq {
+
+typedef uint32_t u32;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+union Frag8 {  // eight bf16 = one MFMA operand register quad
+    u32x4 u;
+    bf16x8 b;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+
+// fp32 -> bf16, round to nearest even (inputs are finite).
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline mq_status launch_status() { return hipGetLastError() == hipSuccess ? MQ_OK : MQ_ERR_DEVICE; }
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  This maps the hardware
+// id to a logical id such that each XCD owns one contiguous range of logical ids, so that tiles
+// which share operands are co-resident under one L2.
+__device__ __forceinline__ uint32_t xcd_contiguous_id(uint32_t hw_id, uint32_t count) {
+    const uint32_t xcd = hw_id & 7u, slot = hw_id >> 3;
+    const uint32_t per = count >> 3, extra = count & 7u;
+    return xcd * per + (xcd < extra ? xcd : extra) + slot;
+}
+
+}  // namespace mq

@@ -1,0 +1,897 @@
+// mq_linear_fwd_multi / mq_linear_bwd: the nested quantized linear on the bf16 matrix cores.
+//
+// Forward (MatQuant objective, section 3.2: the same input goes through the layer once per
+// bit-width): ONE pass over X and the int8 codes.  Each workgroup stages a [256 x 64] bf16 tile of
+// X and a [128 x 64] tile of int8 codes in LDS (direct global->LDS loads, double buffered), every
+// wave turns its codes into one bf16 operand per requested bit-width in registers and issues
+// 32x32x16 MFMAs into one accumulator set per bit-width.
+//
+//   r = 8     : int8 -> fp32 -> bf16 (exact, codes <= 255).
+//   r < 8     : the slicing operator of section 3.2 on 16-bit lanes.  The byte is placed in the high
+//               half of a 16-bit lane, a saturating add of half << 8 implements min(q + half, 255)
+//               (the clamp of the slicing equation), a shift leaves the r-bit code, and OR-ing
+//               0x4300 makes the bf16 number 128 + code.  The 128 is removed in the epilogue with
+//               the per-token sum of X.  Extra precision (errata section) skips the saturation.
+//
+// Epilogue: Y = alpha_n * (2^s * acc - (2^s * 128 + z_n) * sum_k X[m,k]).
+//
+// Backward (identity STE): dX reuses the same in-register slicing on a transposed copy of the
+// codes, with one pre-scaled gradient operand per bit-width accumulated into a single accumulator;
+// dW is a plain bf16 GEMM of the lambda-weighted gradient sum against X.
+#include "mq_common.h"
+
+namespace mq {
+
+typedef __attribute__((address_space(3))) void *lds_ptr;
+
+constexpr int BKT = 64;                  // contraction elements per LDS stage
+constexpr uint32_t kOOB = 0x80000000u;   // buffer offset beyond any descriptor built here
+constexpr uint32_t kMagic128 = 0x43004300u;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint64_t bytes) {
+    const uint32_t rec = bytes > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)bytes;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)rec, 0x00020000);
+}
+
+__device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ f32x16 mfma32(const u32x4 &a, const u32x4 &b, const f32x16 &c) {
+    Frag8 fa, fb;
+    fa.u = a;
+    fb.u = b;
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.b, fb.b, c, 0, 0, 0);
+}
+
+// ---- LDS tiles ------------------------------------------------------------------------------
+// bf16 tile: ROWS x 64 elements, 128-byte rows of eight 16-byte chunks; chunk c of row r is stored
+// at chunk position c ^ (r & 7).  u8 tile: ROWS x 64 bytes, four chunks per row; chunk c of row r
+// at position c ^ ((r >> 1) & 3).  Both make the 16-byte fragment reads of 32 consecutive rows hit
+// distinct banks.  A direct-to-LDS load writes lane l of a wave at base + 16 l, so the swizzle is
+// applied by choosing which global chunk each lane fetches.
+
+// Per-lane byte offset (row * ld_bytes + chunk * 16) of instruction `inst` of this wave for a bf16
+// tile, and the element column of the chunk (for the tail predicate).
+template <int NWAVES>
+__device__ __forceinline__ void bf16_tile_lane(int wave, int lane, int inst, uint32_t ld_bytes,
+                                               uint32_t &voff, int &col) {
+    const int slot = (wave + inst * NWAVES) * 64 + lane;
+    const int row = slot >> 3, p = slot & 7, c = p ^ (row & 7);
+    voff = (uint32_t)row * ld_bytes + (uint32_t)c * 16u;
+    col = c * 8;
+}
+template <int NWAVES>
+__device__ __forceinline__ void u8_tile_lane(int wave, int lane, int inst, uint32_t ld_bytes,
+                                             uint32_t &voff, int &col) {
+    const int slot = (wave + inst * NWAVES) * 64 + lane;
+    const int row = slot >> 2, p = slot & 3, c = p ^ ((row >> 1) & 3);
+    voff = (uint32_t)row * ld_bytes + (uint32_t)c * 16u;
+    col = c * 16;
+}
+
+// ---- code -> bf16 operand conversions ---------------------------------------------------------
+// Eight int8 codes (two dwords, k ascending) -> eight bf16 of the same value.
+__device__ __forceinline__ u32x4 codes_to_bf16_r8(uint32_t d0, uint32_t d1) {
+    auto two = [](float lo, float hi) {
+        return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+    };
+    return u32x4{two((float)(d0 & 0xFFu), (float)((d0 >> 8) & 0xFFu)),
+                 two((float)((d0 >> 16) & 0xFFu), (float)(d0 >> 24)),
+                 two((float)(d1 & 0xFFu), (float)((d1 >> 8) & 0xFFu)),
+                 two((float)((d1 >> 16) & 0xFFu), (float)(d1 >> 24))};
+}
+
+// Bytes of two dwords placed in 16-bit lanes, k ascending.  HIGH: byte << 8 (for the saturating
+// add), else byte in the low half.
+template <bool HIGH>
+__device__ __forceinline__ u32x4 place_bytes(uint32_t d0, uint32_t d1) {
+    constexpr uint32_t s01 = HIGH ? 0x010C000Cu : 0x0C010C00u;
+    constexpr uint32_t s23 = HIGH ? 0x030C020Cu : 0x0C030C02u;
+    return u32x4{__builtin_amdgcn_perm(0u, d0, s01), __builtin_amdgcn_perm(0u, d0, s23),
+                 __builtin_amdgcn_perm(0u, d1, s01), __builtin_amdgcn_perm(0u, d1, s23)};
+}
+
+// r-bit slice of section 3.2 as bf16(128 + code), from bytes placed by place_bytes<!EP>.
+// half2 = half in both 16-bit lanes (shifted left by 8 unless EP); sh = s (+ 8 unless EP).
+template <bool EP>
+__device__ __forceinline__ u32x4 sliced_to_bf16(const u32x4 &placed, uint32_t half2, uint32_t sh) {
+    u32x4 out;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if constexpr (EP) {
+            out[i] = (((placed[i] + half2) >> sh) & 0x00FF00FFu) | kMagic128;
+        } else {
+            const uint32_t pv = placed[i];
+            u16x2 t = __builtin_elementwise_add_sat(__builtin_bit_cast(u16x2, pv), __builtin_bit_cast(u16x2, half2));
+            const unsigned short s16 = (unsigned short)sh;
+            t = t >> u16x2{s16, s16};
+            out[i] = __builtin_bit_cast(uint32_t, t) | kMagic128;
+        }
+    }
+    return out;
+}
+
+struct SliceParam {  // wave-uniform per bit-width
+    uint32_t half2;  // half (<< 8 unless EP) in both 16-bit lanes
+    uint32_t sh;     // shift that leaves the code
+};
+
+template <bool EP>
+__device__ __forceinline__ SliceParam slice_param(int r) {
+    const uint32_t s = 8 - r, half = (1u << s) >> 1;
+    SliceParam p;
+    if constexpr (EP) {
+        p.half2 = half | (half << 16);
+        p.sh = s;
+    } else {
+        p.half2 = (half << 8) | (half << 24);
+        p.sh = s + 8;
+    }
+    return p;
+}
+
+// ============================================================================================
+// forward
+// ============================================================================================
+struct FwdArgs {
+    const uint16_t *X;
+    const uint8_t *Q;
+    const float *alpha, *zero, *rowsum;
+    uint16_t *Y[3];
+    int M, N, K;
+    int r[3];  // bit-width per slot; slot 0 is the r = 8 slot when HAS8
+    int tiles_m, tiles_n;
+};
+
+constexpr int FWD_BM = 256, FWD_BN = 128;
+constexpr int FWD_X_TILE = FWD_BM * 128, FWD_Q_TILE = FWD_BN * 64;
+constexpr int FWD_LDS = 2 * (FWD_X_TILE + FWD_Q_TILE);
+
+template <int NR, bool HAS8, bool EP>
+__global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 2, wn = wave & 3;  // 2 waves along tokens x 4 along channels
+    const int h = lane >> 5, l32 = lane & 31;
+
+    // XCD-aware tile order: each XCD walks groups of 4 token tiles across the channel tiles
+    const uint32_t lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    constexpr int GROUP = 4;
+    const int width = GROUP * a.tiles_n;
+    const int first_m = (int)(lid / width) * GROUP;
+    const int gsz = min(a.tiles_m - first_m, GROUP);
+    const int tm = first_m + (int)(lid % width) % gsz;
+    const int tn = (int)(lid % width) / gsz;
+    const int m0 = tm * FWD_BM, n0 = tn * FWD_BN;
+
+    const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.X + (size_t)m0 * a.K, (uint64_t)(a.M - m0) * a.K * 2);
+    const __amdgpu_buffer_rsrc_t rQ = make_rsrc(a.Q + (size_t)n0 * a.K, (uint64_t)(a.N - n0) * a.K);
+
+    // global -> LDS lane offsets (constant over the K loop)
+    uint32_t xoff[4];
+    int xcol[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bf16_tile_lane<8>(wave, lane, i, (uint32_t)a.K * 2u, xoff[i], xcol[i]);
+    uint32_t qoff;
+    int qcol;
+    u8_tile_lane<8>(wave, lane, 0, (uint32_t)a.K, qoff, qcol);
+
+    auto issue = [&](int kt, int buf) {
+        const int k0 = kt * BKT;
+        uint8_t *xs = smem + buf * FWD_X_TILE;
+        uint8_t *qs = smem + 2 * FWD_X_TILE + buf * FWD_Q_TILE;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t off = (k0 + xcol[i] < a.K) ? xoff[i] + (uint32_t)k0 * 2u : kOOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rX, (lds_ptr)(xs + (wave + i * 8) * 1024), 16, off, 0, 0, 0);
+        }
+        const uint32_t off = (k0 + qcol < a.K) ? qoff + (uint32_t)k0 : kOOB;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rQ, (lds_ptr)(qs + wave * 1024), 16, off, 0, 0, 0);
+    };
+
+    // LDS fragment addresses
+    const int nl = wn * 32 + l32;
+    const uint32_t qa0 = nl * 64 + ((h ^ ((nl >> 1) & 3)) << 4);
+    const uint32_t qa1 = nl * 64 + (((h + 2) ^ ((nl >> 1) & 3)) << 4);
+    uint32_t xa[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int cx = 2 * h + 4 * (t >> 1) + (t & 1);
+        xa[t] = (wm * 128 + l32) * 128 + ((cx ^ (l32 & 7)) << 4);
+    }
+
+    SliceParam sp[NR];
+#pragma unroll
+    for (int i = 0; i < NR; ++i) sp[i] = slice_param<EP>(a.r[i]);
+
+    f32x16 acc[NR][4];
+#pragma unroll
+    for (int i = 0; i < NR; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nkt = (a.K + BKT - 1) / BKT;
+    issue(0, 0);
+    for (int kt = 0; kt < nkt; ++kt) {
+        wait_vm0();
+        __syncthreads();
+        if (kt + 1 < nkt) issue(kt + 1, (kt + 1) & 1);
+        const uint8_t *xs = smem + (kt & 1) * FWD_X_TILE;
+        const uint8_t *qs = smem + 2 * FWD_X_TILE + (kt & 1) * FWD_Q_TILE;
+        const u32x4 raw0 = *reinterpret_cast<const u32x4 *>(qs + qa0);
+        const u32x4 raw1 = *reinterpret_cast<const u32x4 *>(qs + qa1);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const uint32_t d0 = t < 2 ? raw0[2 * t] : raw1[2 * (t - 2)];
+            const uint32_t d1 = t < 2 ? raw0[2 * t + 1] : raw1[2 * (t - 2) + 1];
+            u32x4 wf[NR];
+            const u32x4 placed = place_bytes<!EP>(d0, d1);
+#pragma unroll
+            for (int i = 0; i < NR; ++i) {
+                if (HAS8 && i == 0) {
+                    wf[i] = codes_to_bf16_r8(d0, d1);
+                } else {
+                    wf[i] = sliced_to_bf16<EP>(placed, sp[i].half2, sp[i].sh);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x4 xf = *reinterpret_cast<const u32x4 *>(xs + xa[t] + j * 4096);
+#pragma unroll
+                for (int i = 0; i < NR; ++i) acc[i][j] = mfma32(wf[i], xf, acc[i][j]);
+            }
+        }
+    }
+
+    // ---- epilogue ---------------------------------------------------------------------------
+    // accumulator v = 4 g + e of a lane holds row (channel) 8 g + 4 h + e, column (token) l32
+    float rs[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int m = m0 + wm * 128 + j * 32 + l32;
+        rs[j] = m < a.M ? a.rowsum[m] : 0.f;
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int n = n0 + wn * 32 + 8 * g + 4 * h;
+        if (n >= a.N) continue;
+        const f32x4 al = *reinterpret_cast<const f32x4 *>(a.alpha + n);
+        const f32x4 ze = *reinterpret_cast<const f32x4 *>(a.zero + n);
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            const bool is8 = HAS8 && i == 0;
+            const float mult = is8 ? 1.0f : (float)(1 << (8 - a.r[i]));
+            const float bias = is8 ? 0.0f : 128.0f * mult;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int m = m0 + wm * 128 + j * 32 + l32;
+                if (m >= a.M) continue;
+                float y[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    y[e] = al[e] * (mult * acc[i][j][4 * g + e] - (bias + ze[e]) * rs[j]);
+                u32x2 o = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+                *reinterpret_cast<u32x2 *>(a.Y[i] + (size_t)m * a.N + n) = o;
+            }
+        }
+    }
+}
+
+// sum_k X[m, k] in fp32, one wave per row
+__global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict__ X, int M, int K,
+                                                     float *__restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(X + (size_t)m * K);
+    float s = 0.f;
+    for (int c = lane; c < K / 8; c += 64) {
+        const u32x4 v = row[c];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s += __uint_as_float(v[i] << 16) + __uint_as_float(v[i] & 0xFFFF0000u);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (lane == 0) out[m] = s;
+}
+
+// ============================================================================================
+// backward: helpers that prepare the operands
+// ============================================================================================
+struct BwdPrepArgs {
+    const uint16_t *dY[3];
+    uint16_t *As[3];  // lambda_i * alpha_n * 2^s_i * dY_i, bf16 [M, N]
+    const float *alpha, *zero;
+    float *cvec;      // [M]
+    float lam[3];
+    float mult[3];    // 2^s_i (1 for the r = 8 slot)
+    float bias[3];    // 128 for sliced slots, 0 for the r = 8 slot
+    int nr, M, N;
+};
+
+// One workgroup per token row: scale the gradients by lambda_i * alpha_n * 2^s_i (rounded to bf16,
+// the operand the matrix core will see) and reduce c[m] = sum_i sum_n As_i[m,n] * (bias_i + z_n / 2^s_i),
+// the constant that the 128 + code representation and the zero-point contribute to dX[m, :].
+__global__ __launch_bounds__(256) void bwd_scale_kernel(BwdPrepArgs a) {
+    __shared__ float red[4];
+    const int m = blockIdx.x;
+    float c = 0.f;
+    for (int ch = threadIdx.x; ch < a.N / 8; ch += 256) {
+        const int n = ch * 8;
+        float al[8], ze[8];
+        *reinterpret_cast<f32x4 *>(al) = *reinterpret_cast<const f32x4 *>(a.alpha + n);
+        *reinterpret_cast<f32x4 *>(al + 4) = *reinterpret_cast<const f32x4 *>(a.alpha + n + 4);
+        *reinterpret_cast<f32x4 *>(ze) = *reinterpret_cast<const f32x4 *>(a.zero + n);
+        *reinterpret_cast<f32x4 *>(ze + 4) = *reinterpret_cast<const f32x4 *>(a.zero + n + 4);
+        for (int i = 0; i < a.nr; ++i) {
+            const u32x4 g = *reinterpret_cast<const u32x4 *>(a.dY[i] + (size_t)m * a.N + n);
+            const float f = a.lam[i] * a.mult[i], inv = 1.0f / a.mult[i];
+            u32x4 o;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float lo = bf16_bits_to_float(g[w] & 0xFFFFu) * (f * al[2 * w]);
+                const float hi = bf16_bits_to_float(g[w] >> 16) * (f * al[2 * w + 1]);
+                o[w] = pack_bf16x2(lo, hi);
+                c += bf16_bits_to_float(o[w] & 0xFFFFu) * (a.bias[i] + ze[2 * w] * inv);
+                c += bf16_bits_to_float(o[w] >> 16) * (a.bias[i] + ze[2 * w + 1] * inv);
+            }
+            *reinterpret_cast<u32x4 *>(a.As[i] + (size_t)m * a.N + n) = o;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) a.cvec[m] = red[0] + red[1] + red[2] + red[3];
+}
+
+struct GtArgs {
+    const uint16_t *dY[3];
+    float lam[3];
+    uint16_t *GT;  // [N, M] bf16
+    int nr, M, N;
+};
+
+// GT[n, m] = bf16(sum_i lambda_i dY_i[m, n]) through a 64 x 64 LDS tile.
+__global__ __launch_bounds__(256) void bwd_gt_kernel(GtArgs a) {
+    __shared__ float tile[64][65];
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int m = m0 + rr, n = n0 + tx;
+        float s = 0.f;
+        if (m < a.M && n < a.N)
+            for (int i = 0; i < a.nr; ++i) s += a.lam[i] * bf16_bits_to_float(a.dY[i][(size_t)m * a.N + n]);
+        tile[rr][tx] = s;
+    }
+    __syncthreads();
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int n = n0 + rr, m = m0 + tx;
+        if (n < a.N && m < a.M) a.GT[(size_t)n * a.M + m] = (uint16_t)float_to_bf16_bits(tile[tx][rr]);
+    }
+}
+
+// out[c, r] = in[r, c] for a [rows, cols] matrix of T
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in, T *__restrict__ out, int rows,
+                                                        int cols) {
+    __shared__ T tile[64][64 + 4 / sizeof(T)];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int rr = ty; rr < 64; rr += 4)
+        if (r0 + rr < rows && c0 + tx < cols) tile[rr][tx] = in[(size_t)(r0 + rr) * cols + c0 + tx];
+    __syncthreads();
+    for (int rr = ty; rr < 64; rr += 4)
+        if (c0 + rr < cols && r0 + tx < rows) out[(size_t)(c0 + rr) * rows + r0 + tx] = tile[tx][rr];
+}
+
+// ============================================================================================
+// backward dX: dX[m, k] = sum_i sum_n As_i[m, n] * V_i[n, k] - c[m], V_i = the bf16 operand of slot i
+// Rows of the matrix-core product are k (from the transposed codes QT[K, N]), columns are tokens,
+// the contraction runs over n and, within each n tile, over the bit-widths.
+// ============================================================================================
+struct DxArgs {
+    const uint16_t *As[3];  // [M, N] bf16
+    const uint8_t *QT;      // [K, N] u8
+    const float *cvec;      // [M]
+    uint16_t *dX;           // [M, K] bf16
+    int M, N, K;
+    int nr;
+    int r[3];
+    int tiles_m, tiles_k;
+};
+
+constexpr int DX_BM = 256, DX_BK = 256;
+constexpr int DX_A_TILE = DX_BM * 128, DX_Q_TILE = DX_BK * 64;
+constexpr int DX_LDS = 2 * (DX_A_TILE + DX_Q_TILE);
+
+template <bool EP>
+__global__ __launch_bounds__(512) void dx_kernel(DxArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 2, wk = wave & 3;  // 2 waves along tokens x 4 along k
+    const int h = lane >> 5, l32 = lane & 31;
+
+    const uint32_t lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    constexpr int GROUP = 4;
+    const int width = GROUP * a.tiles_k;
+    const int first_m = (int)(lid / width) * GROUP;
+    const int gsz = min(a.tiles_m - first_m, GROUP);
+    const int tm = first_m + (int)(lid % width) % gsz;
+    const int tk = (int)(lid % width) / gsz;
+    const int m0 = tm * DX_BM, k0 = tk * DX_BK;
+
+    __amdgpu_buffer_rsrc_t rA[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+        rA[i] = make_rsrc(a.As[i < a.nr ? i : 0] + (size_t)m0 * a.N, (uint64_t)(a.M - m0) * a.N * 2);
+    const __amdgpu_buffer_rsrc_t rQ = make_rsrc(a.QT + (size_t)k0 * a.N, (uint64_t)(a.K - k0) * a.N);
+
+    uint32_t aoff[4], qoff[2];
+    int acol[4], qcol[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bf16_tile_lane<8>(wave, lane, i, (uint32_t)a.N * 2u, aoff[i], acol[i]);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) u8_tile_lane<8>(wave, lane, i, (uint32_t)a.N, qoff[i], qcol[i]);
+
+    auto issue = [&](int nt, int slot, int buf) {
+        const int n0 = nt * BKT;
+        uint8_t *as = smem + buf * DX_A_TILE;
+        uint8_t *qs = smem + 2 * DX_A_TILE + buf * DX_Q_TILE;
+        const __amdgpu_buffer_rsrc_t r = slot == 0 ? rA[0] : (slot == 1 ? rA[1] : rA[2]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t off = (n0 + acol[i] < a.N) ? aoff[i] + (uint32_t)n0 * 2u : kOOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)(as + (wave + i * 8) * 1024), 16, off, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t off = (n0 + qcol[i] < a.N) ? qoff[i] + (uint32_t)n0 : kOOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rQ, (lds_ptr)(qs + (wave + i * 8) * 1024), 16, off, 0, 0, 0);
+        }
+    };
+
+    // LDS fragment addresses: two 32-row blocks of k per wave, four 32-token blocks
+    uint32_t qa[2][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const int kl = wk * 64 + rb * 32 + l32;
+        qa[rb][0] = kl * 64 + ((h ^ ((kl >> 1) & 3)) << 4);
+        qa[rb][1] = kl * 64 + (((h + 2) ^ ((kl >> 1) & 3)) << 4);
+    }
+    uint32_t xa[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int cx = 2 * h + 4 * (t >> 1) + (t & 1);
+        xa[t] = (wm * 128 + l32) * 128 + ((cx ^ (l32 & 7)) << 4);
+    }
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[rb][j][v] = 0.f;
+
+    const int nnt = (a.N + BKT - 1) / BKT;
+    const int nst = nnt * a.nr;
+    issue(0, 0, 0);
+    int nt = 0, slot = 0;
+    for (int st = 0; st < nst; ++st) {
+        wait_vm0();
+        __syncthreads();
+        int nslot = slot + 1, nnt_next = nt;
+        if (nslot == a.nr) {
+            nslot = 0;
+            nnt_next = nt + 1;
+        }
+        if (st + 1 < nst) issue(nnt_next, nslot, (st + 1) & 1);
+        const uint8_t *as = smem + (st & 1) * DX_A_TILE;
+        const uint8_t *qs = smem + 2 * DX_A_TILE + (st & 1) * DX_Q_TILE;
+        const int r = a.r[slot];
+        const SliceParam sp = slice_param<EP>(r);
+        u32x4 raw[2][2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            raw[rb][0] = *reinterpret_cast<const u32x4 *>(qs + qa[rb][0]);
+            raw[rb][1] = *reinterpret_cast<const u32x4 *>(qs + qa[rb][1]);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            u32x4 wf[2];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                const uint32_t d0 = t < 2 ? raw[rb][0][2 * t] : raw[rb][1][2 * (t - 2)];
+                const uint32_t d1 = t < 2 ? raw[rb][0][2 * t + 1] : raw[rb][1][2 * (t - 2) + 1];
+                if (r == 8) {
+                    wf[rb] = codes_to_bf16_r8(d0, d1);
+                } else {
+                    wf[rb] = sliced_to_bf16<EP>(place_bytes<!EP>(d0, d1), sp.half2, sp.sh);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x4 xf = *reinterpret_cast<const u32x4 *>(as + xa[t] + j * 4096);
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) acc[rb][j] = mfma32(wf[rb], xf, acc[rb][j]);
+            }
+        }
+        slot = nslot;
+        nt = nnt_next;
+    }
+
+    // epilogue: rows of the product are k, columns tokens
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int m = m0 + wm * 128 + j * 32 + l32;
+        if (m >= a.M) continue;
+        const float c = a.cvec[m];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int k = k0 + wk * 64 + rb * 32 + 8 * g + 4 * h;
+                if (k >= a.K) continue;
+                u32x2 o = {pack_bf16x2(acc[rb][j][4 * g] - c, acc[rb][j][4 * g + 1] - c),
+                           pack_bf16x2(acc[rb][j][4 * g + 2] - c, acc[rb][j][4 * g + 3] - c)};
+                *reinterpret_cast<u32x2 *>(a.dX + (size_t)m * a.K + k) = o;
+            }
+    }
+}
+
+// ============================================================================================
+// backward dW: dW[n, k] (+)= sum_m GT[n, m] * XT[k, m]   (plain bf16 GEMM, fp32 out)
+// ============================================================================================
+struct DwArgs {
+    const uint16_t *GT;  // [N, M]
+    const uint16_t *XT;  // [K, M]
+    float *dW;           // [N, K]
+    int M, N, K;
+    int accumulate;
+    int tiles_n, tiles_k;
+};
+
+constexpr int DW_BN = 256, DW_BK = 256;
+constexpr int DW_TILE = 256 * 128;
+constexpr int DW_LDS = 4 * DW_TILE;
+
+__global__ __launch_bounds__(512) void dw_kernel(DwArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wn = wave >> 1, wk = wave & 1;  // 4 waves along n (64 rows each) x 2 along k (128 columns each)
+    const int h = lane >> 5, l32 = lane & 31;
+
+    const uint32_t lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    constexpr int GROUP = 4;
+    const int width = GROUP * a.tiles_k;
+    const int first_n = (int)(lid / width) * GROUP;
+    const int gsz = min(a.tiles_n - first_n, GROUP);
+    const int tn = first_n + (int)(lid % width) % gsz;
+    const int tk = (int)(lid % width) / gsz;
+    const int n0 = tn * DW_BN, k0 = tk * DW_BK;
+
+    const __amdgpu_buffer_rsrc_t rG = make_rsrc(a.GT + (size_t)n0 * a.M, (uint64_t)(a.N - n0) * a.M * 2);
+    const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.XT + (size_t)k0 * a.M, (uint64_t)(a.K - k0) * a.M * 2);
+
+    uint32_t off[4];
+    int col[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bf16_tile_lane<8>(wave, lane, i, (uint32_t)a.M * 2u, off[i], col[i]);
+
+    auto issue = [&](int mt, int buf) {
+        const int mm = mt * BKT;
+        uint8_t *gs = smem + buf * DW_TILE;
+        uint8_t *xs = smem + 2 * DW_TILE + buf * DW_TILE;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t o = (mm + col[i] < a.M) ? off[i] + (uint32_t)mm * 2u : kOOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rG, (lds_ptr)(gs + (wave + i * 8) * 1024), 16, o, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rX, (lds_ptr)(xs + (wave + i * 8) * 1024), 16, o, 0, 0, 0);
+        }
+    };
+
+    uint32_t ga[4], xa[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int cx = 2 * h + 4 * (t >> 1) + (t & 1);
+        ga[t] = (wn * 64 + l32) * 128 + ((cx ^ (l32 & 7)) << 4);
+        xa[t] = (wk * 128 + l32) * 128 + ((cx ^ (l32 & 7)) << 4);
+    }
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[rb][j][v] = 0.f;
+
+    const int nmt = (a.M + BKT - 1) / BKT;
+    issue(0, 0);
+    for (int mt = 0; mt < nmt; ++mt) {
+        wait_vm0();
+        __syncthreads();
+        if (mt + 1 < nmt) issue(mt + 1, (mt + 1) & 1);
+        const uint8_t *gs = smem + (mt & 1) * DW_TILE;
+        const uint8_t *xs = smem + 2 * DW_TILE + (mt & 1) * DW_TILE;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            u32x4 gf[2];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) gf[rb] = *reinterpret_cast<const u32x4 *>(gs + ga[t] + rb * 4096);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x4 xf = *reinterpret_cast<const u32x4 *>(xs + xa[t] + j * 4096);
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) acc[rb][j] = mfma32(gf[rb], xf, acc[rb][j]);
+            }
+        }
+    }
+
+    // rows of the product are n, columns k: 32 consecutive k per row across half a wave
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int n = n0 + wn * 64 + rb * 32 + 8 * g + 4 * h + e;
+                if (n >= a.N) continue;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int k = k0 + wk * 128 + j * 32 + l32;
+                    if (k >= a.K) continue;
+                    float *p = a.dW + (size_t)n * a.K + k;
+                    const float v = acc[rb][j][4 * g + e];
+                    *p = a.accumulate ? *p + v : v;
+                }
+            }
+}
+
+// ============================================================================================
+// host side
+// ============================================================================================
+static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+struct BwdWorkspace {
+    size_t cvec, as[3], gt, xt, qt, total;
+};
+
+static BwdWorkspace bwd_layout(int64_t M, int64_t N, int64_t K, int nr) {
+    BwdWorkspace w;
+    size_t o = 0;
+    w.cvec = o;
+    o += align256((size_t)M * 4);
+    for (int i = 0; i < 3; ++i) {
+        w.as[i] = o;
+        if (i < nr) o += align256((size_t)M * N * 2);
+    }
+    w.gt = o;
+    o += align256((size_t)M * N * 2);
+    w.xt = o;
+    o += align256((size_t)M * K * 2);
+    w.qt = o;
+    o += align256((size_t)N * K);
+    w.total = o;
+    return w;
+}
+
+static mq_status check_rs(const int *rs, int nr) {
+    if (!rs) return MQ_ERR_NULL;
+    if (nr < 1 || nr > 3) return MQ_ERR_BITS;
+    for (int i = 0; i < nr; ++i) {
+        if (rs[i] < 1 || rs[i] > 8) return MQ_ERR_BITS;
+        for (int j = 0; j < i; ++j)
+            if (rs[j] == rs[i]) return MQ_ERR_BITS;
+    }
+    return MQ_OK;
+}
+
+template <typename Kern>
+static bool allow_lds(Kern kern, int bytes) {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               bytes) == hipSuccess;
+}
+
+template <int NR, bool HAS8, bool EP>
+static mq_status launch_fwd(const FwdArgs &a, hipStream_t st) {
+    if (!allow_lds(fwd_kernel<NR, HAS8, EP>, FWD_LDS)) return MQ_ERR_DEVICE;
+    fwd_kernel<NR, HAS8, EP><<<dim3(a.tiles_m * a.tiles_n), dim3(512), FWD_LDS, st>>>(a);
+    return launch_status();
+}
+
+template <int NR, bool HAS8>
+static mq_status launch_fwd_ep(const FwdArgs &a, bool ep, hipStream_t st) {
+    return ep ? launch_fwd<NR, HAS8, true>(a, st) : launch_fwd<NR, HAS8, false>(a, st);
+}
+
+}  // namespace mq
+
+extern "C" size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int nr) {
+    using namespace mq;
+    if (M < 0 || N < 0 || K < 0 || nr < 1 || nr > 3) return 0;
+    if (op == MQ_OP_LINEAR_FWD) return align256((size_t)M * 4) + 256;
+    if (op == MQ_OP_LINEAR_BWD) return bwd_layout(M, N, K, nr).total + 256;
+    return 0;
+}
+
+extern "C" mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, const float *alpha,
+                                         const float *zero, int64_t M, int64_t N, int64_t K, const int *rs,
+                                         int nr, uint32_t flags, uint16_t *const *Y, void *ws, size_t ws_bytes,
+                                         void *hip_stream) {
+    using namespace mq;
+    if (M < 0 || N < 0 || K < 1) return MQ_ERR_SHAPE;
+    if (M > 0x7FFFFF00 || N > 0x7FFFFF00 || K > (1 << 22)) return MQ_ERR_SHAPE;
+    mq_status s = check_rs(rs, nr);
+    if (s != MQ_OK) return s;
+    if (K % 16 != 0 || N % 8 != 0) return MQ_ERR_ALIGN;
+    if (M == 0 || N == 0) return MQ_OK;
+    if (!X || !Q || !alpha || !zero || !Y) return MQ_ERR_NULL;
+    for (int i = 0; i < nr; ++i) {
+        if (!Y[i]) return MQ_ERR_NULL;
+        if (!aligned16(Y[i])) return MQ_ERR_ALIGN;
+    }
+    if (!aligned16(X) || !aligned16(Q) || !aligned16(alpha) || !aligned16(zero)) return MQ_ERR_ALIGN;
+    if (!ws || ws_bytes < mq_workspace_bytes(MQ_OP_LINEAR_FWD, M, N, K, nr) || !aligned16(ws))
+        return MQ_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    FwdArgs a;
+    a.X = X;
+    a.Q = Q;
+    a.alpha = alpha;
+    a.zero = zero;
+    a.rowsum = static_cast<float *>(ws);
+    a.M = (int)M;
+    a.N = (int)N;
+    a.K = (int)K;
+    // slot order: the r = 8 slot (if any) first
+    int has8 = 0, pos = 0;
+    for (int i = 0; i < 3; ++i) {
+        a.Y[i] = nullptr;
+        a.r[i] = 8;
+    }
+    for (int i = 0; i < nr; ++i)
+        if (rs[i] == 8) {
+            has8 = 1;
+            a.Y[0] = Y[i];
+            a.r[0] = 8;
+        }
+    pos = has8;
+    for (int i = 0; i < nr; ++i)
+        if (rs[i] != 8) {
+            a.Y[pos] = Y[i];
+            a.r[pos] = rs[i];
+            ++pos;
+        }
+    a.tiles_m = (int)cdiv(M, FWD_BM);
+    a.tiles_n = (int)cdiv(N, FWD_BN);
+
+    rowsum_kernel<<<dim3((unsigned)cdiv(M, 4)), dim3(256), 0, st>>>(X, (int)M, (int)K, static_cast<float *>(ws));
+    const bool ep = flags & MQ_FLAG_EXTRA_PRECISION;
+    if (nr == 1) return has8 ? launch_fwd_ep<1, true>(a, ep, st) : launch_fwd_ep<1, false>(a, ep, st);
+    if (nr == 2) return has8 ? launch_fwd_ep<2, true>(a, ep, st) : launch_fwd_ep<2, false>(a, ep, st);
+    return has8 ? launch_fwd_ep<3, true>(a, ep, st) : launch_fwd_ep<3, false>(a, ep, st);
+}
+
+extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero,
+                                   const uint16_t *const *dY, const float *lambda, int64_t M, int64_t N,
+                                   int64_t K, const int *rs, int nr, uint32_t flags, uint16_t *dX, float *dW,
+                                   void *ws, size_t ws_bytes, void *hip_stream) {
+    using namespace mq;
+    if (M < 0 || N < 0 || K < 1) return MQ_ERR_SHAPE;
+    if (M > (1 << 22) || N > (1 << 22) || K > (1 << 22)) return MQ_ERR_SHAPE;
+    mq_status s = check_rs(rs, nr);
+    if (s != MQ_OK) return s;
+    if (K % 16 != 0 || N % 16 != 0 || M % 8 != 0) return MQ_ERR_ALIGN;
+    if (M == 0 || N == 0) return MQ_OK;  // note: with M == 0 and no ACCUM flag dW is left untouched
+    if (!dY) return MQ_ERR_NULL;
+    for (int i = 0; i < nr; ++i) {
+        if (!dY[i]) return MQ_ERR_NULL;
+        if (!aligned16(dY[i])) return MQ_ERR_ALIGN;
+    }
+    if (dX && (!Q || !alpha || !zero)) return MQ_ERR_NULL;
+    if (dW && !X) return MQ_ERR_NULL;
+    if ((dX && !aligned16(dX)) || (dW && !aligned16(dW)) || (X && !aligned16(X)) || (Q && !aligned16(Q)) ||
+        (alpha && !aligned16(alpha)) || (zero && !aligned16(zero)))
+        return MQ_ERR_ALIGN;
+    if (!ws || ws_bytes < mq_workspace_bytes(MQ_OP_LINEAR_BWD, M, N, K, nr) || !aligned16(ws))
+        return MQ_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const BwdWorkspace lay = bwd_layout(M, N, K, nr);
+    uint8_t *base = static_cast<uint8_t *>(ws);
+    const bool ep = flags & MQ_FLAG_EXTRA_PRECISION;
+
+    if (dX) {
+        BwdPrepArgs p;
+        for (int i = 0; i < 3; ++i) {
+            const int j = i < nr ? i : 0;
+            p.dY[i] = dY[j];
+            p.As[i] = reinterpret_cast<uint16_t *>(base + lay.as[j]);
+            p.lam[i] = lambda ? lambda[j] : 1.0f;
+            p.mult[i] = rs[j] == 8 ? 1.0f : (float)(1 << (8 - rs[j]));
+            p.bias[i] = rs[j] == 8 ? 0.0f : 128.0f;
+        }
+        p.alpha = alpha;
+        p.zero = zero;
+        p.cvec = reinterpret_cast<float *>(base + lay.cvec);
+        p.nr = nr;
+        p.M = (int)M;
+        p.N = (int)N;
+        bwd_scale_kernel<<<dim3((unsigned)M), dim3(256), 0, st>>>(p);
+
+        uint8_t *QT = base + lay.qt;
+        transpose_kernel<uint8_t><<<dim3((unsigned)cdiv(K, 64), (unsigned)cdiv(N, 64)), dim3(256), 0, st>>>(
+            Q, QT, (int)N, (int)K);
+
+        DxArgs d;
+        for (int i = 0; i < 3; ++i) {
+            d.As[i] = p.As[i];
+            d.r[i] = rs[i < nr ? i : 0];
+        }
+        d.QT = QT;
+        d.cvec = p.cvec;
+        d.dX = dX;
+        d.M = (int)M;
+        d.N = (int)N;
+        d.K = (int)K;
+        d.nr = nr;
+        d.tiles_m = (int)cdiv(M, DX_BM);
+        d.tiles_k = (int)cdiv(K, DX_BK);
+        if (ep) {
+            if (!allow_lds(dx_kernel<true>, DX_LDS)) return MQ_ERR_DEVICE;
+            dx_kernel<true><<<dim3(d.tiles_m * d.tiles_k), dim3(512), DX_LDS, st>>>(d);
+        } else {
+            if (!allow_lds(dx_kernel<false>, DX_LDS)) return MQ_ERR_DEVICE;
+            dx_kernel<false><<<dim3(d.tiles_m * d.tiles_k), dim3(512), DX_LDS, st>>>(d);
+        }
+    }
+    if (dW) {
+        GtArgs g;
+        for (int i = 0; i < 3; ++i) {
+            const int j = i < nr ? i : 0;
+            g.dY[i] = dY[j];
+            g.lam[i] = lambda ? lambda[j] : 1.0f;
+        }
+        g.GT = reinterpret_cast<uint16_t *>(base + lay.gt);
+        g.nr = nr;
+        g.M = (int)M;
+        g.N = (int)N;
+        bwd_gt_kernel<<<dim3((unsigned)cdiv(N, 64), (unsigned)cdiv(M, 64)), dim3(256), 0, st>>>(g);
+        uint16_t *XT = reinterpret_cast<uint16_t *>(base + lay.xt);
+        transpose_kernel<uint16_t><<<dim3((unsigned)cdiv(K, 64), (unsigned)cdiv(M, 64)), dim3(256), 0, st>>>(
+            X, XT, (int)M, (int)K);
+        DwArgs w;
+        w.GT = g.GT;
+        w.XT = XT;
+        w.dW = dW;
+        w.M = (int)M;
+        w.N = (int)N;
+        w.K = (int)K;
+        w.accumulate = (flags & MQ_FLAG_ACCUM_DW) ? 1 : 0;
+        w.tiles_n = (int)cdiv(N, DW_BN);
+        w.tiles_k = (int)cdiv(K, DW_BK);
+        if (!allow_lds(dw_kernel, DW_LDS)) return MQ_ERR_DEVICE;
+        dw_kernel<<<dim3(w.tiles_n * w.tiles_k), dim3(512), DW_LDS, st>>>(w);
+    }
+    return launch_status();
+}
+
+extern "C" const char *mq_status_string(mq_status status) {
+    switch (status) {
+        case MQ_OK: return "ok";
+        case MQ_ERR_NULL: return "null pointer";
+        case MQ_ERR_SHAPE: return "bad shape";
+        case MQ_ERR_BITS: return "bad bit-width";
+        case MQ_ERR_ALIGN: return "bad alignment";
+        case MQ_ERR_WORKSPACE: return "workspace too small";
+        case MQ_ERR_CAPACITY: return "overflow list capacity exceeded";
+        case MQ_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}

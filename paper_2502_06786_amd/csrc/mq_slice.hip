@@ -1,0 +1,197 @@
+// mq_slice: the slicing operator S(q, r) of section 3.2 (round half up at bit level as appendix A
+// describes, clamp to 2^r - 1), optional packing to 8/r codes per byte, and the extra-precision
+// overflow set of the errata section as a CSR list.  Integer-only and HBM-bound:
+// 1 B read + r/8 B written per weight when packed.
+#include "mq_common.h"
+
+namespace mq {
+
+// Four int8 codes in a dword -> four r-bit codes in the same byte positions.
+// Works on the two 16-bit lanes that hold bytes (0, 2) and (1, 3), so q + half cannot overflow.
+__device__ __forceinline__ uint32_t slice4(uint32_t d, uint32_t half2, uint32_t s, uint32_t top2) {
+    uint32_t even = d & 0x00FF00FFu;
+    uint32_t odd = (d >> 8) & 0x00FF00FFu;
+    even = ((even + half2) >> s) & 0x01FF01FFu;  // a 16-bit lane holds at most 255 + 64 < 512
+    odd = ((odd + half2) >> s) & 0x01FF01FFu;
+    // per-lane min with the top code
+    const uint32_t e_lo = min(even & 0xFFFFu, top2 & 0xFFFFu), e_hi = min(even >> 16, top2 >> 16);
+    const uint32_t o_lo = min(odd & 0xFFFFu, top2 & 0xFFFFu), o_hi = min(odd >> 16, top2 >> 16);
+    return e_lo | (o_lo << 8) | (e_hi << 16) | (o_hi << 24);
+}
+
+__device__ __forceinline__ uint32_t slice1(uint32_t q, int r) {
+    const uint32_t s = 8 - r, half = (1u << s) >> 1, top = (1u << r) - 1;
+    return min((q + half) >> s, top);
+}
+
+// 16 codes per thread.  MODE 0: one code per byte; MODE 4 / 2: packed nibbles / crumbs.
+template <int MODE>
+__global__ __launch_bounds__(256) void slice_kernel(const uint8_t *__restrict__ Q, int64_t count, int r,
+                                                    uint8_t *__restrict__ out) {
+    const uint32_t s = 8 - r, half = (1u << s) >> 1, top = (1u << r) - 1;
+    const uint32_t half2 = half | (half << 16), top2 = top | (top << 16);
+    const int64_t chunks = count >> 4;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < chunks; c += stride) {
+        u32x4 d = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Q) + c);
+        u32x4 o;
+        o.x = slice4(d.x, half2, s, top2);
+        o.y = slice4(d.y, half2, s, top2);
+        o.z = slice4(d.z, half2, s, top2);
+        o.w = slice4(d.w, half2, s, top2);
+        if constexpr (MODE == 0) {
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(out) + c);
+        } else if constexpr (MODE == 4) {
+            // bytes (b0 b1 b2 b3) of codes < 16 -> two bytes (b0 | b1 << 4), (b2 | b3 << 4)
+            auto nib = [](uint32_t x) {
+                uint32_t y = (x | (x >> 4)) & 0x00FF00FFu;  // byte0 | byte1 << 4 in each 16-bit lane
+                return (y | (y >> 8)) & 0xFFFFu;
+            };
+            u32x2 p;
+            p.x = nib(o.x) | (nib(o.y) << 16);
+            p.y = nib(o.z) | (nib(o.w) << 16);
+            __builtin_nontemporal_store(p, reinterpret_cast<u32x2 *>(out) + c);
+        } else {
+            // bytes of codes < 4 -> one byte b0 | b1 << 2 | b2 << 4 | b3 << 6
+            auto crumb = [](uint32_t x) {
+                uint32_t y = (x | (x >> 6)) & 0x000F000Fu;  // (b0 | b1 << 2) in each 16-bit lane
+                return (y | (y >> 12)) & 0xFFu;
+            };
+            const uint32_t p = crumb(o.x) | (crumb(o.y) << 8) | (crumb(o.z) << 16) | (crumb(o.w) << 24);
+            __builtin_nontemporal_store(p, reinterpret_cast<uint32_t *>(out) + c);
+        }
+    }
+    // tail shorter than 16 codes: one thread, element by element (packing groups never straddle it
+    // because count is a multiple of 8 / r in the packed modes)
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const int64_t done = chunks << 4;
+        if constexpr (MODE == 0) {
+            for (int64_t i = done; i < count; ++i) out[i] = (uint8_t)slice1(Q[i], r);
+        } else {
+            constexpr int PER = 8 / MODE;
+            for (int64_t i = done; i < count; i += PER) {
+                uint32_t b = 0;
+                for (int j = 0; j < PER; ++j) b |= slice1(Q[i + j], r) << (MODE * j);
+                out[i / PER] = (uint8_t)b;
+            }
+        }
+    }
+}
+
+// ---- extra-precision overflow set -----------------------------------------------------------
+// Number of codes >= threshold among the four bytes of d.
+__device__ __forceinline__ int count_ge4(uint32_t d, uint32_t thr) {
+    return ((d & 0xFFu) >= thr) + (((d >> 8) & 0xFFu) >= thr) + (((d >> 16) & 0xFFu) >= thr) + ((d >> 24) >= thr);
+}
+
+// One block per row: row_ptr[n + 1] = number of codes >= thr in row n (row_ptr[0] = 0).
+__global__ __launch_bounds__(256) void overflow_count_kernel(const uint8_t *__restrict__ Q, int64_t K,
+                                                             uint32_t thr, int32_t *__restrict__ row_ptr) {
+    __shared__ int red[4];
+    const int64_t n = blockIdx.x;
+    const uint8_t *row = Q + n * K;
+    int cnt = 0;
+    for (int64_t k = threadIdx.x; k < K; k += 256) cnt += row[k] >= thr;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x / 64] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        row_ptr[n + 1] = red[0] + red[1] + red[2] + red[3];
+        if (n == 0) row_ptr[0] = 0;
+    }
+}
+
+// Single block, in place: row_ptr[1..N] counts -> inclusive prefix sums; *nnz = total.
+__global__ __launch_bounds__(1024) void overflow_scan_kernel(int32_t *__restrict__ row_ptr, int64_t N,
+                                                             int64_t *__restrict__ nnz) {
+    __shared__ int64_t part[1024];
+    const int64_t per = (N + 1023) / 1024;
+    const int64_t lo = 1 + threadIdx.x * per;
+    const int64_t hi = lo + per < N + 1 ? lo + per : N + 1;
+    int64_t sum = 0;
+    for (int64_t i = lo; i < hi; ++i) sum += row_ptr[i];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    // Hillis-Steele inclusive scan over the 1024 partial sums
+    for (int o = 1; o < 1024; o <<= 1) {
+        int64_t add = threadIdx.x >= (unsigned)o ? part[threadIdx.x - o] : 0;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    int64_t run = threadIdx.x ? part[threadIdx.x - 1] : 0;
+    for (int64_t i = lo; i < hi; ++i) {
+        run += row_ptr[i];
+        row_ptr[i] = (int32_t)run;
+    }
+    if (threadIdx.x == 1023) *nnz = part[1023];
+}
+
+// One block per row: columns with code >= thr, ascending, written at row_ptr[n] (bounded by capacity).
+__global__ __launch_bounds__(256) void overflow_fill_kernel(const uint8_t *__restrict__ Q, int64_t K,
+                                                            uint32_t thr, const int32_t *__restrict__ row_ptr,
+                                                            uint16_t *__restrict__ col_idx, int64_t capacity) {
+    __shared__ int wave_tot[4];
+    const int64_t n = blockIdx.x;
+    const uint8_t *row = Q + n * K;
+    int64_t base = row_ptr[n];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int64_t k0 = 0; k0 < K; k0 += 256) {
+        const int64_t k = k0 + threadIdx.x;
+        const bool hit = k < K && row[k] >= thr;
+        const uint64_t ballot = __ballot(hit);
+        if (lane == 0) wave_tot[wave] = __popcll(ballot);
+        __syncthreads();
+        int before = __popcll(ballot & ((1ull << lane) - 1ull));
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        const int total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+        if (hit && base + before < capacity) col_idx[base + before] = (uint16_t)k;
+        base += total;
+        __syncthreads();
+    }
+}
+
+}  // namespace mq
+
+extern "C" mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uint32_t flags, uint8_t *out,
+                              const mq_overflow *ovf, void *hip_stream) {
+    using namespace mq;
+    if (N < 0 || K < 0) return MQ_ERR_SHAPE;
+    if (r < 1 || r > 8) return MQ_ERR_BITS;
+    const bool packed = flags & MQ_FLAG_PACKED, ep = flags & MQ_FLAG_EXTRA_PRECISION;
+    if (packed && !(r == 8 || r == 4 || r == 2)) return MQ_ERR_BITS;
+    if (packed && (K % (8 / r)) != 0) return MQ_ERR_ALIGN;
+    if (ep) {
+        if (!ovf) return MQ_ERR_NULL;
+        if (N > 0 && (!ovf->row_ptr || !ovf->nnz || (ovf->capacity > 0 && !ovf->col_idx))) return MQ_ERR_NULL;
+        if (ovf->capacity < 0 || K > 65536 || N > 0x7FFFFFFE || (N > 0 && K > 0x7FFFFFFF / N))
+            return MQ_ERR_SHAPE;
+    }
+    if (N == 0 || K == 0) {
+        return MQ_OK;
+    }
+    if (!Q || !out) return MQ_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(out)) return MQ_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int64_t count = N * K;
+    const int64_t chunks = count >> 4;
+    int64_t blocks = cdiv(chunks > 0 ? chunks : 1, 256);
+    if (blocks > 256 * 32) blocks = 256 * 32;  // grid-stride beyond 32 blocks per CU
+    if (!packed || r == 8) {
+        slice_kernel<0><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, r, out);
+    } else if (r == 4) {
+        slice_kernel<4><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, r, out);
+    } else {
+        slice_kernel<2><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, r, out);
+    }
+    if (ep) {
+        const uint32_t half = (1u << (8 - r)) >> 1;
+        const uint32_t thr = r == 8 ? 256u : 256u - half;  // r = 8: nothing overflows
+        overflow_count_kernel<<<dim3((unsigned)N), dim3(256), 0, st>>>(Q, K, thr, ovf->row_ptr);
+        overflow_scan_kernel<<<dim3(1), dim3(1024), 0, st>>>(ovf->row_ptr, N, ovf->nnz);
+        overflow_fill_kernel<<<dim3((unsigned)N), dim3(256), 0, st>>>(Q, K, thr, ovf->row_ptr, ovf->col_idx,
+                                                                     ovf->capacity);
+    }
+    return launch_status();
+}

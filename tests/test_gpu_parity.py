@@ -1,0 +1,333 @@
+"""HIP path vs CPU oracle through the C ABI, at sizes the oracle finishes in seconds.
+
+Bars: bit-exact for codes, slices, packed bytes and overflow lists; rel-L2 <= 1e-2 against the
+fp64 oracle for Y, dX, dW, y (expected ~2e-3 from the bf16 output rounding; dW is fp32 and only
+sees the bf16 rounding of the summed gradient operand).
+"""
+import numpy as np
+import pytest
+import torch
+
+from tests.util import bf16_bits, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def mq():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2502_06786_amd as mq_
+
+    mq_.lib()
+    return mq_
+
+
+def dev(t):
+    return t.to("cuda")
+
+
+def _randn(seed, *shape, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    return torch.randn(*shape, generator=g) * scale
+
+
+# --------------------------------------------------------------------------
+# quantize
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("N,K", [(256, 256), (7, 100), (5, 2304), (3, 9216), (2, 36864), (3, 4100), (9, 3),
+                                 (1, 1), (130, 4608), (2, 70000)])
+def test_quantize_bit_exact(mq, oracle, N, K):
+    W = _randn(N * 1000 + K, N, K, scale=0.02)
+    if N > 2:
+        W[1] = 0.125            # constant row
+        W[2, 0] = 3.0           # outlier
+    Q, a, z = mq.mq_quantize_int8(dev(W))
+    qo, ao, zo = oracle.quantize_int8(W.numpy())
+    assert np.array_equal(a.cpu().numpy(), ao)
+    assert np.array_equal(z.cpu().numpy(), zo)
+    assert np.array_equal(Q.cpu().numpy(), qo)
+
+
+def test_quantize_config1_and_stride_and_clip(mq, oracle):
+    from paper_2502_06786_amd import synth
+    W = synth.weight(1, "gate")
+    Q, a, z = mq.mq_quantize_int8(dev(W))
+    qo, ao, zo = oracle.quantize_int8(W.numpy())
+    assert np.array_equal(Q.cpu().numpy(), qo) and np.array_equal(a.cpu().numpy(), ao)
+    # row stride: a [N, K] view of a wider buffer
+    big = dev(_randn(5, 40, 512, scale=0.02))
+    view = big[:, :256]
+    Q, a, z = mq.mq_quantize_int8(view)
+    qo, ao, zo = oracle.quantize_int8(view.cpu().contiguous().numpy())
+    assert np.array_equal(Q.cpu().numpy(), qo) and np.array_equal(z.cpu().numpy(), zo)
+    # clip factors (section 3.1.2)
+    g = torch.rand(40, generator=torch.Generator().manual_seed(1)) * 0.5 + 0.5
+    b = torch.rand(40, generator=torch.Generator().manual_seed(2)) * 0.5 + 0.5
+    Wc = big[:, 256:].contiguous()
+    Q, a, z = mq.mq_quantize_int8(Wc, dev(g), dev(b))
+    qo, ao, zo = oracle.quantize_int8(Wc.cpu().numpy(), g.numpy(), b.numpy())
+    assert np.array_equal(Q.cpu().numpy(), qo) and np.array_equal(a.cpu().numpy(), ao)
+    assert np.array_equal(z.cpu().numpy(), zo)
+
+
+# --------------------------------------------------------------------------
+# slice / pack / overflow list
+# --------------------------------------------------------------------------
+def test_slice_all_codes_all_r(mq, oracle):
+    q = torch.arange(256, dtype=torch.int32).repeat(5).to(torch.uint8).reshape(5, 256)
+    for r in range(1, 9):
+        got = mq.mq_slice(dev(q), r).cpu().numpy()
+        assert np.array_equal(got, oracle.slice_codes(q.numpy(), r)), r
+
+
+@pytest.mark.parametrize("N,K", [(256, 256), (3, 40), (1, 8), (33, 1000), (257, 4104)])
+def test_slice_packed_and_ragged(mq, oracle, N, K):
+    g = torch.Generator().manual_seed(N + K)
+    q = torch.randint(0, 256, (N, K), generator=g, dtype=torch.int32).to(torch.uint8)
+    for r in (8, 4, 2):
+        got = mq.mq_slice(dev(q), r, packed=True).cpu().numpy()
+        assert np.array_equal(got, oracle.pack(oracle.slice_codes(q.numpy(), r), r)), r
+    for r in (3, 6):
+        got = mq.mq_slice(dev(q), r).cpu().numpy()
+        assert np.array_equal(got, oracle.slice_codes(q.numpy(), r)), r
+
+
+@pytest.mark.parametrize("r", [2, 4, 3, 6, 8])
+def test_slice_extra_precision_overflow_list(mq, oracle, r):
+    g = torch.Generator().manual_seed(r)
+    N, K = 70, 1000
+    q = torch.randint(0, 256, (N, K), generator=g, dtype=torch.int32).to(torch.uint8)
+    q[5] = 0          # empty row
+    q[6] = 255        # full row
+    packed = r in (8, 4, 2)
+    out, ovf = mq.mq_slice(dev(q), r, packed=packed, extra_precision=True)
+    torch.cuda.synchronize()
+    codes = oracle.slice_codes(q.numpy(), r)
+    want = oracle.pack(codes, r) if packed else codes
+    assert np.array_equal(out.cpu().numpy(), want)          # dense plane == plain slice
+    rp, ci = oracle.overflow_csr(q.numpy(), r)
+    nnz = int(ovf.nnz.item())
+    assert nnz == ci.size
+    assert np.array_equal(ovf.row_ptr.cpu().numpy(), rp)
+    assert np.array_equal(ovf.col_idx.cpu().numpy().view(np.uint16)[:nnz], ci)
+
+
+def test_slice_overflow_capacity(mq, oracle):
+    g = torch.Generator().manual_seed(77)
+    q = torch.randint(0, 256, (20, 512), generator=g, dtype=torch.int32).to(torch.uint8)
+    rp, ci = oracle.overflow_csr(q.numpy(), 2)
+    cap = ci.size // 2
+    ovf = mq.Overflow(20, cap)
+    ovf.col_idx = torch.full((cap + 64,), -1, dtype=torch.int16, device="cuda")  # guard region after capacity
+    mq.mq_slice(dev(q), 2, extra_precision=True, ovf=ovf)
+    torch.cuda.synchronize()
+    assert int(ovf.nnz.item()) == ci.size > cap                  # the caller sees the shortfall
+    got = ovf.col_idx.cpu().numpy().view(np.uint16)
+    assert np.array_equal(got[:cap], ci[:cap])
+    assert np.all(got[cap:] == 0xFFFF)                            # nothing written past capacity
+
+
+# --------------------------------------------------------------------------
+# fused multi-precision forward
+# --------------------------------------------------------------------------
+def _quantized(mq, oracle, W):
+    Q, a, z = mq.mq_quantize_int8(dev(W))
+    qo, ao, zo = oracle.quantize_int8(W.numpy())
+    assert np.array_equal(Q.cpu().numpy(), qo)
+    return Q, a, z, qo, ao, zo
+
+
+FWD_SHAPES = [(16, 256, 256), (300, 264, 208), (1, 8, 16), (257, 136, 1040), (520, 392, 64)]
+RS_SETS = [(8, 4, 2), (2,), (8,), (4, 2), (2, 8), (6, 3), (8, 6, 3), (7, 5, 1)]
+
+
+@pytest.mark.parametrize("M,N,K", FWD_SHAPES)
+def test_fwd_multi_shapes(mq, oracle, M, N, K):
+    W = _randn(M + N + K, N, K, scale=0.02)
+    X = _randn(M * 3 + 1, M, K).to(torch.bfloat16)
+    Q, a, z, qo, ao, zo = _quantized(mq, oracle, W)
+    for ep in (False, True):
+        Ys = mq.mq_linear_fwd_multi(dev(X), Q, a, z, (8, 4, 2), extra_precision=ep)
+        for r, Y in zip((8, 4, 2), Ys):
+            want = oracle.linear_fwd(bf16_bits(X), qo, ao, zo, r, ep=ep)
+            assert rel_l2(Y.float().cpu().numpy(), want) <= TOL, (r, ep)
+
+
+@pytest.mark.parametrize("rs", RS_SETS)
+def test_fwd_multi_bit_width_sets(mq, oracle, rs):
+    M, N, K = 200, 136, 336
+    W = _randn(11, N, K, scale=0.02)
+    W[:, 5] *= 6.0                                  # a heavy column so the top bucket is populated
+    X = _randn(12, M, K).to(torch.bfloat16)
+    Q, a, z, qo, ao, zo = _quantized(mq, oracle, W)
+    for ep in (False, True):
+        Ys = mq.mq_linear_fwd_multi(dev(X), Q, a, z, rs, extra_precision=ep)
+        assert len(Ys) == len(rs)
+        for r, Y in zip(rs, Ys):
+            want = oracle.linear_fwd(bf16_bits(X), qo, ao, zo, r, ep=ep)
+            assert rel_l2(Y.float().cpu().numpy(), want) <= TOL, (rs, r, ep)
+
+
+def test_fwd_uniform_codes_hit_every_bucket(mq, oracle):
+    # codes uniform on 0..255 (all buckets incl. the clamped top one), alpha/z arbitrary
+    from paper_2502_06786_amd import synth
+    M, N, K = 64, 128, 512
+    q = synth.uniform_codes(3, N, K)
+    a = (torch.rand(N, generator=torch.Generator().manual_seed(4)) * 1e-3 + 1e-4)
+    z = torch.rand(N, generator=torch.Generator().manual_seed(5)) * 255
+    X = _randn(6, M, K).to(torch.bfloat16)
+    for ep in (False, True):
+        Ys = mq.mq_linear_fwd_multi(dev(X), dev(q), dev(a), dev(z), (8, 4, 2), extra_precision=ep)
+        for r, Y in zip((8, 4, 2), Ys):
+            want = oracle.linear_fwd(bf16_bits(X), q.numpy(), a.numpy(), z.numpy(), r, ep=ep)
+            assert rel_l2(Y.float().cpu().numpy(), want) <= TOL, (r, ep)
+
+
+def test_fwd_exact_small_integers(mq, oracle):
+    # alpha = 1, z = 0, X small integers: every product and sum is exact in fp32 and the outputs are
+    # integers below 2^8 * ... representable in bf16 only if small, so compare before rounding matters:
+    # one-hot X rows select single codes -> Y must equal the sliced value exactly.
+    N, K = 64, 64
+    q = torch.arange(N * K, dtype=torch.int32).remainder(256).to(torch.uint8).reshape(N, K)
+    a = torch.ones(N)
+    z = torch.zeros(N)
+    X = torch.eye(K).to(torch.bfloat16)
+    Ys = mq.mq_linear_fwd_multi(dev(X), dev(q), dev(a), dev(z), (8, 4, 2))
+    for r, Y in zip((8, 4, 2), Ys):
+        want = oracle.slice_values(q.numpy(), r).astype(np.float64).T     # Y[k, n] = S(q[n, k])
+        assert np.array_equal(Y.float().cpu().numpy().astype(np.float64), want), r
+    Ys = mq.mq_linear_fwd_multi(dev(X), dev(q), dev(a), dev(z), (4, 2), extra_precision=True)
+    for r, Y in zip((4, 2), Ys):
+        want = oracle.slice_values(q.numpy(), r, ep=True).astype(np.float64).T
+        assert np.array_equal(Y.float().cpu().numpy().astype(np.float64), want), r
+
+
+# --------------------------------------------------------------------------
+# STE backward
+# --------------------------------------------------------------------------
+BWD_SHAPES = [(16, 256, 256), (264, 272, 208), (8, 16, 16), (520, 400, 320)]
+
+
+@pytest.mark.parametrize("M,N,K", BWD_SHAPES)
+def test_bwd_shapes(mq, oracle, M, N, K):
+    W = _randn(M + N + K + 1, N, K, scale=0.02)
+    X = _randn(M * 5 + 1, M, K).to(torch.bfloat16)
+    dYs = [_randn(100 + i, M, N, scale=1e-3).to(torch.bfloat16) for i in range(3)]
+    lambdas = (0.1, 0.1, 1.0)
+    rs = (8, 4, 2)
+    Q, a, z, qo, ao, zo = _quantized(mq, oracle, W)
+    for ep in (False, True):
+        dX, dW = mq.mq_linear_bwd(dev(X), Q, a, z, [dev(d) for d in dYs], lambdas, rs, extra_precision=ep)
+        want_dx = oracle.linear_bwd_dx(qo, ao, zo, [bf16_bits(d) for d in dYs], lambdas, rs, ep=ep)
+        want_dw = oracle.linear_bwd_dw(bf16_bits(X), [bf16_bits(d) for d in dYs], lambdas)
+        assert rel_l2(dX.float().cpu().numpy(), want_dx) <= TOL, ("dX", ep)
+        assert rel_l2(dW.cpu().numpy(), want_dw) <= TOL, ("dW", ep)
+
+
+@pytest.mark.parametrize("rs,lambdas", [((2,), None), ((8,), (0.5,)), ((4, 2), (0.4, 1.0)), ((6, 3), None),
+                                        ((2, 8, 4), (1.0, 0.2, 0.2))])
+def test_bwd_bit_width_sets_and_accumulate(mq, oracle, rs, lambdas):
+    M, N, K = 136, 144, 176
+    W = _randn(21, N, K, scale=0.02)
+    X = _randn(22, M, K).to(torch.bfloat16)
+    dYs = [_randn(200 + i, M, N, scale=1e-3).to(torch.bfloat16) for i in range(len(rs))]
+    Q, a, z, qo, ao, zo = _quantized(mq, oracle, W)
+    dX, dW = mq.mq_linear_bwd(dev(X), Q, a, z, [dev(d) for d in dYs], lambdas, rs)
+    want_dx = oracle.linear_bwd_dx(qo, ao, zo, [bf16_bits(d) for d in dYs], lambdas, rs)
+    want_dw = oracle.linear_bwd_dw(bf16_bits(X), [bf16_bits(d) for d in dYs], lambdas)
+    assert rel_l2(dX.float().cpu().numpy(), want_dx) <= TOL
+    assert rel_l2(dW.cpu().numpy(), want_dw) <= TOL
+    # accumulate into an existing dW; skip dX
+    base = dev(_randn(23, N, K, scale=1e-2))
+    dW2 = base.clone()
+    none, dW2 = mq.mq_linear_bwd(dev(X), Q, a, z, [dev(d) for d in dYs], lambdas, rs, need_dX=False, dW=dW2,
+                                 accumulate_dW=True)
+    assert none is None
+    assert rel_l2((dW2 - base).cpu().numpy(), want_dw) <= TOL
+    # dX only
+    dX3, none = mq.mq_linear_bwd(dev(X), Q, a, z, [dev(d) for d in dYs], lambdas, rs, need_dW=False)
+    assert none is None and torch.equal(dX3, dX)
+
+
+# --------------------------------------------------------------------------
+# decode GEMV
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("N,K", [(256, 256), (100, 512), (16, 64), (1000, 1344), (4096, 4096), (40, 14336)])
+@pytest.mark.parametrize("r", [2, 4, 8])
+def test_gemv_plain(mq, oracle, N, K, r):
+    W = _randn(N + K + r, N, K, scale=0.02)
+    Q, a, z, qo, ao, zo = _quantized(mq, oracle, W)
+    packed = mq.mq_slice(Q, r, packed=True)
+    a16, z16 = a.to(torch.bfloat16), z.to(torch.bfloat16)
+    for B in (1, 3, 4, 16):
+        x = _randn(B * 7 + r, B, K).to(torch.bfloat16)
+        y = mq.mq_gemv_sliced(dev(x), packed, a16, z16, r, K)
+        want = oracle.gemv_sliced(bf16_bits(x), packed.cpu().numpy(), bf16_bits(a16), bf16_bits(z16), r, K)
+        assert rel_l2(y.float().cpu().numpy(), want) <= TOL, (B,)
+
+
+@pytest.mark.parametrize("r,frac", [(2, 0.05), (4, 0.02), (2, 0.125)])
+def test_gemv_extra_precision(mq, oracle, r, frac):
+    from paper_2502_06786_amd import synth
+    N, K = 300, 1024
+    q = synth.uniform_codes(9, N, K) if frac == 0.125 else synth.planted_overflow_codes(9, N, K, r, frac)
+    a = (torch.rand(N, generator=torch.Generator().manual_seed(4)) * 1e-3 + 1e-4).to(torch.bfloat16)
+    z = (torch.rand(N, generator=torch.Generator().manual_seed(5)) * 255).to(torch.bfloat16)
+    packed, ovf = mq.mq_slice(dev(q), r, packed=True, extra_precision=True)
+    torch.cuda.synchronize()
+    rp, ci = oracle.overflow_csr(q.numpy(), r)
+    assert int(ovf.nnz.item()) == ci.size and abs(ci.size / q.numel() - frac) < 0.01
+    for B in (1, 4, 16):
+        x = _randn(B + r, B, K).to(torch.bfloat16)
+        y = mq.mq_gemv_sliced(dev(x), packed, dev(a), dev(z), r, K, ovf=ovf)
+        want = oracle.gemv_sliced(bf16_bits(x), packed.cpu().numpy(), bf16_bits(a), bf16_bits(z), r, K, ovf=(rp, ci))
+        assert rel_l2(y.float().cpu().numpy(), want) <= TOL, (B,)
+        plain = oracle.gemv_sliced(bf16_bits(x), packed.cpu().numpy(), bf16_bits(a), bf16_bits(z), r, K)
+        # the overflow term itself (a few % of y) is there, up to the bf16 rounding of y
+        assert rel_l2(y.float().cpu().numpy() - plain, want - plain) <= 0.25
+
+
+def test_gemv_one_hot_exact(mq, oracle):
+    # alpha = 1, z = 0, one-hot activations: y[b, n] is exactly the sliced value of code [n, b].
+    N, K = 64, 256
+    q = torch.arange(N * K, dtype=torch.int32).mul(7).remainder(256).to(torch.uint8).reshape(N, K)
+    a = torch.ones(N).to(torch.bfloat16)
+    z = torch.zeros(N).to(torch.bfloat16)
+    for r in (2, 4, 8):
+        packed = mq.mq_slice(dev(q), r, packed=True)
+        for k0 in (0, 100, 240):
+            x = torch.zeros(16, K)
+            x[torch.arange(16), k0 + torch.arange(16)] = 1.0
+            y = mq.mq_gemv_sliced(dev(x.to(torch.bfloat16)), packed, dev(a), dev(z), r, K)
+            want = oracle.slice_values(q.numpy(), r)[:, k0:k0 + 16].T.astype(np.float64)
+            assert np.array_equal(y.float().cpu().numpy().astype(np.float64), want), (r, k0)
+
+
+# --------------------------------------------------------------------------
+# argument checking (host side, nothing is launched)
+# --------------------------------------------------------------------------
+def test_error_codes(mq):
+    Q = torch.zeros(8, 64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(mq.MqError) as e:
+        mq.mq_slice(Q, 9)
+    assert e.value.status == 3
+    with pytest.raises(mq.MqError) as e:
+        mq.mq_slice(Q, 3, packed=True)
+    assert e.value.status == 3
+    X = torch.zeros(4, 64, dtype=torch.bfloat16, device="cuda")
+    a = torch.ones(8, device="cuda")
+    with pytest.raises(mq.MqError) as e:
+        mq.mq_linear_fwd_multi(X, Q, a, a, (8, 8))
+    assert e.value.status == 3
+    with pytest.raises(mq.MqError) as e:
+        mq.mq_linear_fwd_multi(X, Q, a, a, (8, 4, 2), ws=torch.zeros(1, dtype=torch.uint8, device="cuda"))
+    assert e.value.status in (4, 5)
+    with pytest.raises(mq.MqError) as e:
+        mq.mq_gemv_sliced(torch.zeros(17, 64, dtype=torch.bfloat16, device="cuda"), Q, a.bfloat16(), a.bfloat16(), 8, 64)
+    assert e.value.status == 2
+    # empty problems are no-ops
+    assert mq.mq_linear_fwd_multi(X[:0], Q, a, a, (8,))[0].shape == (0, 8)
+    assert mq.mq_slice(Q[:0], 4).shape == (0, 64)
