@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the nested quantized linear hot path on one MI355X.
+
+One step = one pass of the whole hot path over the Gemma-2-2B-shaped MLP (d_model 2304, ffn 9216,
+4096 tokens; seeded synthetic weights and activations already resident in HBM): for each of the
+three linears (gate, up, down) quantize the fp32 master weight to int8 codes, slice and pack the
+r = 4 and r = 2 planes (r = 2 also with the extra-precision overflow list), run the fused
+r = 8/4/2 forward and the straight-through backward (dX, dW), round alpha/z to bf16 and run the
+decode GEMV at B = 1, 4, 16 on the int4 and int2 planes.
+
+`value` is the forward + backward matrix-core work of the step (6 MNK + 8 MNK flops per linear)
+divided by the wall time of the WHOLE step, so the bandwidth-bound operations count against it.
+Per-operation figures from HIP events recorded inside the timed region are reported next to it,
+and `roofline` prices the fused forward kernel against the bf16 MFMA peak.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gemv-sweep", action="store_true")
+    return ap.parse_args()
+
+
+class Linear:
+    """Device buffers of one linear of the MLP; everything is allocated before the timed region."""
+
+    def __init__(self, mq, torch, synth, name, M, rs, lambdas):
+        dev = "cuda"
+        case = synth.linear_case(2, name)
+        self.name, self.M, self.N, self.K, self.rs, self.lambdas = name, M, case.N, case.K, rs, lambdas
+        N, K = self.N, self.K
+        self.W = case.W.to(dev)
+        self.X = case.X.to(dev)
+        self.dY = [d.to(dev) for d in case.dY]
+        self.Q = torch.empty(N, K, dtype=torch.uint8, device=dev)
+        self.alpha = torch.empty(N, dtype=torch.float32, device=dev)
+        self.zero = torch.empty(N, dtype=torch.float32, device=dev)
+        self.alpha16 = torch.empty(N, dtype=torch.bfloat16, device=dev)
+        self.zero16 = torch.empty(N, dtype=torch.bfloat16, device=dev)
+        self.p4 = torch.empty(N, K // 2, dtype=torch.uint8, device=dev)
+        self.p2 = torch.empty(N, K // 4, dtype=torch.uint8, device=dev)
+        self.ovf2 = mq.Overflow(N, N * K // 8, dev)   # room for 12.5 % overflow
+        self.Y = [torch.empty(M, N, dtype=torch.bfloat16, device=dev) for _ in rs]
+        self.dX = torch.empty(M, K, dtype=torch.bfloat16, device=dev)
+        self.dW = torch.empty(N, K, dtype=torch.float32, device=dev)
+        self.ws_f = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD, M, N, K, len(rs)), dtype=torch.uint8, device=dev)
+        self.ws_b = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, M, N, K, len(rs)), dtype=torch.uint8, device=dev)
+        self.xdec = {B: synth.activations(2, f"dec{B}:" + name, B, K).to(dev) for B in (1, 4, 16)}
+        self.ydec = {B: torch.empty(B, N, dtype=torch.bfloat16, device=dev) for B in (1, 4, 16)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no collectives are part of the hot path).", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2502_06786_amd as mq
+    from paper_2502_06786_amd import synth
+
+    mq.lib()  # fails loudly when libmq.so is missing
+    torch.cuda.set_device(0)
+    rs, lambdas = (8, 4, 2), synth.LAMBDAS[2]
+    _, M = synth.mlp_shapes(2)
+    layers = [Linear(mq, torch, synth, name, M, rs, lambdas) for name in ("gate", "up", "down")]
+
+    ops = ["quantize", "slice", "fwd", "bwd", "gemv"]
+    records = {op: [] for op in ops}   # (start event, end event) pairs inside the timed region
+
+    def timed(op, fn, rec):
+        if not rec:
+            fn()
+            return
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        records[op].append((a, b))
+
+    def step(rec):
+        for L in layers:
+            timed("quantize", lambda: mq.mq_quantize_int8(L.W, Q=L.Q, alpha=L.alpha, zero=L.zero), rec)
+
+            def do_slice():
+                mq.mq_slice(L.Q, 4, packed=True, out=L.p4)
+                mq.mq_slice(L.Q, 2, packed=True, extra_precision=True, out=L.p2, ovf=L.ovf2)
+                mq.mq_params_to_bf16(L.alpha, L.zero, L.alpha16, L.zero16)
+            timed("slice", do_slice, rec)
+            timed("fwd", lambda: mq.mq_linear_fwd_multi(L.X, L.Q, L.alpha, L.zero, rs, Y=L.Y, ws=L.ws_f), rec)
+            timed("bwd", lambda: mq.mq_linear_bwd(L.X, L.Q, L.alpha, L.zero, L.dY, lambdas, rs, dX=L.dX, dW=L.dW,
+                                                  ws=L.ws_b), rec)
+
+            def do_gemv():
+                for B in (1, 4, 16):
+                    mq.mq_gemv_sliced(L.xdec[B], L.p4, L.alpha16, L.zero16, 4, L.K, y=L.ydec[B])
+                    mq.mq_gemv_sliced(L.xdec[B], L.p2, L.alpha16, L.zero16, 2, L.K, y=L.ydec[B])
+            timed("gemv", do_gemv, rec)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    mnk = sum(L.M * L.N * L.K for L in layers)
+    flops_fwd, flops_bwd = 6.0 * mnk, 8.0 * mnk
+    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+
+    op_ms = {op: sum(a.elapsed_time(b) for a, b in records[op]) / args.steps for op in ops}   # ms per step
+    nk = sum(L.N * L.K for L in layers)
+    gemv_bytes = sum(sum(L.N * L.K * r // 8 + 4 * L.N + 2 * B * L.K + 2 * B * L.N for r in (4, 2)) for B in (1, 4, 16)
+                     for L in layers)
+    per_op = {
+        "fwd_TFLOPs": flops_fwd / (op_ms["fwd"] * 1e-3) / 1e12,
+        "bwd_TFLOPs": flops_bwd / (op_ms["bwd"] * 1e-3) / 1e12,
+        "quantize_GBs": 5.0 * nk / (op_ms["quantize"] * 1e-3) / 1e9,
+        "slice_GBs": (2.0 + 0.5 + 0.25) * nk / (op_ms["slice"] * 1e-3) / 1e9,
+        "gemv_GBs": gemv_bytes / (op_ms["gemv"] * 1e-3) / 1e9,
+        "ms": {k: round(v, 4) for k, v in op_ms.items()},
+    }
+
+    # Roofline of the dominant kernel, the fused r = 8/4/2 forward (one launch per linear): events
+    # bracket the mq_linear_fwd_multi call, i.e. the kernel plus its few-microsecond row-sum pre-pass.
+    fwd_launches = len(records["fwd"])
+    fwd_avg_ms = sum(a.elapsed_time(b) for a, b in records["fwd"]) / fwd_launches
+    achieved = (flops_fwd / len(layers)) / (fwd_avg_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "fwd_kernel<3,true,false>", "achieved": round(achieved, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": None, "avg_launch_ms": round(fwd_avg_ms, 4)}
+
+    out = {
+        "metric": "fused r=8/4/2 quant-linear TFLOP/s (fwd 6MNK + STE bwd 8MNK over the whole hot-path step)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: Gemma-2-2B-shaped MLP, d_model 2304, ffn 9216, 4096 tokens, "
+                               "gate/up/down; quantize + slice/pack + fused r=8/4/2 fwd + STE bwd + decode GEMV "
+                               "B=1/4/16 (int4, int2)", "tokens": M, "rs": list(rs), "seed": synth.config_seed(2)},
+        "per_op": per_op,
+        "roofline": roofline,
+    }
+    if not args.no_gemv_sweep:
+        out["gemv_roofline"] = gemv_sweep(torch, mq, synth)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(torch, synth, rs, lambdas)
+    print(json.dumps(out))
+
+
+def gemv_sweep(torch, mq, synth):
+    """Decode GEMV on the 7B-shaped matrices of configs[3]: each shape gets enough independent copies to
+    exceed the 256 MB last-level cache, and one stream-ordered sweep over all copies is timed."""
+    res = {}
+    best = None
+    for (N, K) in synth.DECODE_SHAPES:
+        g = torch.Generator().manual_seed(N * 7 + K)
+        for r in (2, 4):
+            kb = K * r // 8
+            copies = max(8, int(640e6 // (N * kb)) + 1)
+            planes = [torch.randint(0, 256, (N, kb), generator=g, dtype=torch.int32).to(torch.uint8).cuda()
+                      for _ in range(2)]
+            planes = planes + [planes[i % 2].clone() for i in range(copies - 2)]
+            a16 = (torch.rand(N, generator=g) * 1e-3 + 1e-4).to(torch.bfloat16).cuda()
+            z16 = (torch.rand(N, generator=g) * 255).to(torch.bfloat16).cuda()
+            for B in (1, 4, 16):
+                x = synth.activations(4, f"x{B}:{N}x{K}", B, K).cuda()
+                y = torch.empty(B, N, dtype=torch.bfloat16, device="cuda")
+                for p in planes[:2]:
+                    mq.mq_gemv_sliced(x, p, a16, z16, r, K, y=y)
+                torch.cuda.synchronize()
+                times = []
+                for _ in range(5):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for p in planes:
+                        mq.mq_gemv_sliced(x, p, a16, z16, r, K, y=y)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    times.append(e0.elapsed_time(e1) / len(planes))
+                ms = sorted(times)[len(times) // 2]
+                nbytes = N * kb + 4 * N + 2 * B * K + 2 * B * N
+                gbs = nbytes / (ms * 1e-3) / 1e9
+                res[f"int{r}_{N}x{K}_B{B}"] = {"us": round(ms * 1e3, 2), "GBs": round(gbs, 1),
+                                                "frac": round(gbs / PEAK_HBM_GBS, 4)}
+                if r == 2 and (best is None or gbs > best[1]):
+                    best = (f"int{r}_{N}x{K}_B{B}", gbs)
+            del planes
+    res["bound"] = "hbm"
+    res["peak"] = PEAK_HBM_GBS
+    res["unit"] = "GB/s"
+    res["best_int2"] = {"case": best[0], "achieved": round(best[1], 1), "frac": round(best[1] / PEAK_HBM_GBS, 4)}
+    res["note"] = "time per call from a stream-ordered sweep over independent copies (launch gaps included)"
+    return res
+
+
+def cpu_baseline(torch, synth, rs, lambdas):
+    """The CPU oracle as it stands on a bounded slab of the gate linear: forward for 2048 of the 9216
+    output channels, dX for 512 of the 4096 tokens, dW for 1024 of the 9216 weight rows."""
+    import numpy as np
+    import oracle
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+    case = synth.linear_case(2, "gate")
+    Wn = case.W.numpy()
+    nf, md, nw = 2048, 512, 1024
+    t0 = time.perf_counter()
+    q, a, z = oracle.quantize_int8(Wn)
+    for r in (4, 2):
+        oracle.pack(oracle.slice_codes(q, r), r)
+    t_q = time.perf_counter() - t0
+    xb = bits(case.X)
+    t0 = time.perf_counter()
+    for r in rs:
+        oracle.linear_fwd(xb, q[:nf], a[:nf], z[:nf], r)
+    dyb = [bits(d[:md]) for d in case.dY]
+    oracle.linear_bwd_dx(q, a, z, dyb, lambdas, rs)
+    dyw = [bits(d[:, :nw]) for d in case.dY]
+    oracle.linear_bwd_dw(xb, dyw, lambdas)
+    t_mm = time.perf_counter() - t0
+    flops = 6.0 * case.M * nf * case.K + 6.0 * md * case.N * case.K + 2.0 * case.M * nw * case.K
+    return {"value": round(flops / t_mm / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"gate linear slab: fwd r=8/4/2 on {nf}/{case.N} channels, dX on {md}/{case.M} tokens, "
+                      f"dW on {nw}/{case.N} rows ({flops / 1e9:.0f} GFLOP in {t_mm:.1f} s); quantize+slice+pack of "
+                      f"the full {case.N}x{case.K} matrix took {t_q:.2f} s"}
+
+
+if __name__ == "__main__":
+    main()

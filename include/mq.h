@@ -93,6 +93,14 @@ mq_status mq_quantize_int8(const float *W, int64_t N, int64_t K, int64_t ldw,
                            uint8_t *Q, float *alpha, float *zero, void *hip_stream);
 
 /*
+ * Per-channel scale and zero-point rounded to bf16 (nearest even) for the decode path, which keeps
+ * them in bf16 next to the packed low-bit plane.  alpha, zero [N] fp32 -> alpha_bf16, zero_bf16 [N].
+ * (The paper fixes no storage type for them; the decode GEMV consumes exactly these arrays.)
+ */
+mq_status mq_params_to_bf16(const float *alpha, const float *zero, int64_t N, uint16_t *alpha_bf16,
+                            uint16_t *zero_bf16, void *hip_stream);
+
+/*
  * Slicing operator S(q, r) of section 3.2 (slicing equation; appendix A for
  * the rounding):  code = min((q + half) >> s, 2^r - 1), S = code << s.
  *   Q    [N, K] uint8

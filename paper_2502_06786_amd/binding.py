@@ -22,7 +22,7 @@ MQ_OP_LINEAR_FWD = 0
 MQ_OP_LINEAR_BWD = 1
 
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
-           "mq_workspace_bytes", "mq_status_string"]
+           "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string"]
 
 
 class MqError(RuntimeError):
@@ -53,7 +53,8 @@ def _load() -> ctypes.CDLL:
     lib.mq_workspace_bytes.restype = sz
     lib.mq_status_string.argtypes = [ci]
     lib.mq_status_string.restype = ctypes.c_char_p
-    for name in EXPORTS[:5]:
+    lib.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
+    for name in EXPORTS[:6]:
         getattr(lib, name).restype = ci
     return lib
 
@@ -121,6 +122,17 @@ def mq_quantize_int8(W, gamma=None, beta=None, Q=None, alpha=None, zero=None):
                                _ptr(zero, torch.float32), _stream())
     _check(st, "mq_quantize_int8")
     return Q, alpha, zero
+
+
+def mq_params_to_bf16(alpha, zero, alpha_bf16=None, zero_bf16=None):
+    """fp32 [N] scale and zero-point -> bf16 copies for the decode GEMV."""
+    N = alpha.numel()
+    alpha_bf16 = torch.empty(N, dtype=torch.bfloat16, device=alpha.device) if alpha_bf16 is None else alpha_bf16
+    zero_bf16 = torch.empty(N, dtype=torch.bfloat16, device=alpha.device) if zero_bf16 is None else zero_bf16
+    st = _lib.mq_params_to_bf16(_ptr(alpha, torch.float32), _ptr(zero, torch.float32), N,
+                                _ptr(alpha_bf16, torch.bfloat16), _ptr(zero_bf16, torch.bfloat16), _stream())
+    _check(st, "mq_params_to_bf16")
+    return alpha_bf16, zero_bf16
 
 
 def mq_slice(Q, r: int, packed: bool = False, extra_precision: bool = False, out=None, ovf: Overflow | None = None,

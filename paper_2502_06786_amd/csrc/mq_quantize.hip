@@ -144,7 +144,30 @@ __global__ __launch_bounds__(256) void quantize_rows_generic_kernel(const float 
     for (int64_t k = threadIdx.x; k < K; k += 256) Q[n * K + k] = (uint8_t)quant1(w[k], a, z);
 }
 
+// fp32 -> bf16 (round to nearest even) of the per-channel scale and zero-point for the decode path
+__global__ __launch_bounds__(256) void params_to_bf16_kernel(const float *__restrict__ alpha,
+                                                             const float *__restrict__ zero, int64_t N,
+                                                             uint16_t *__restrict__ alpha_bf16,
+                                                             uint16_t *__restrict__ zero_bf16) {
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n < N) {
+        alpha_bf16[n] = (uint16_t)float_to_bf16_bits(alpha[n]);
+        zero_bf16[n] = (uint16_t)float_to_bf16_bits(zero[n]);
+    }
+}
+
 }  // namespace mq
+
+extern "C" mq_status mq_params_to_bf16(const float *alpha, const float *zero, int64_t N, uint16_t *alpha_bf16,
+                                       uint16_t *zero_bf16, void *hip_stream) {
+    using namespace mq;
+    if (N < 0 || N > 0x7FFFFFFF) return MQ_ERR_SHAPE;
+    if (N == 0) return MQ_OK;
+    if (!alpha || !zero || !alpha_bf16 || !zero_bf16) return MQ_ERR_NULL;
+    params_to_bf16_kernel<<<dim3((unsigned)cdiv(N, 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(
+        alpha, zero, N, alpha_bf16, zero_bf16);
+    return launch_status();
+}
 
 extern "C" mq_status mq_quantize_int8(const float *W, int64_t N, int64_t K, int64_t ldw,
                                       const float *gamma, const float *beta, uint8_t *Q,
