@@ -18,6 +18,8 @@
 // Backward (identity STE): dX reuses the same in-register slicing on a transposed copy of the
 // codes, with one pre-scaled gradient operand per bit-width accumulated into a single accumulator;
 // dW is a plain bf16 GEMM of the lambda-weighted gradient sum against X.
+#include <type_traits>
+
 #include "mq_common.h"
 
 namespace mq {
@@ -44,9 +46,10 @@ __device__ __forceinline__ f32x16 mfma32(const u32x4 &a, const u32x4 &b, const f
 
 // ---- LDS tiles ------------------------------------------------------------------------------
 // bf16 tile: ROWS x 64 elements, 128-byte rows of eight 16-byte chunks; chunk c of row r is stored
-// at chunk position c ^ (r & 7).  u8 tile: ROWS x 64 bytes, four chunks per row; chunk c of row r
-// at position c ^ ((r >> 1) & 3).  Both make the 16-byte fragment reads of 32 consecutive rows hit
-// distinct banks.  A direct-to-LDS load writes lane l of a wave at base + 16 l, so the swizzle is
+// at chunk position c ^ ((r >> 1) & 7).  u8 tile: ROWS x 64 bytes, four chunks per row; chunk c of
+// row r at position c ^ ((r >> 2) & 3).  The LDS has 64 four-byte banks and serves a 16-byte read
+// sixteen lanes at a time, so sixteen consecutive rows must land on sixteen distinct 16-byte bank
+// groups of a 256-byte window; both swizzles do that (measured: same rate as a contiguous read).  A direct-to-LDS load writes lane l of a wave at base + 16 l, so the swizzle is
 // applied by choosing which global chunk each lane fetches.
 
 // Per-lane byte offset (row * ld_bytes + chunk * 16) of instruction `inst` of this wave for a bf16
@@ -55,7 +58,7 @@ template <int NWAVES>
 __device__ __forceinline__ void bf16_tile_lane(int wave, int lane, int inst, uint32_t ld_bytes,
                                                uint32_t &voff, int &col) {
     const int slot = (wave + inst * NWAVES) * 64 + lane;
-    const int row = slot >> 3, p = slot & 7, c = p ^ (row & 7);
+    const int row = slot >> 3, p = slot & 7, c = p ^ ((row >> 1) & 7);
     voff = (uint32_t)row * ld_bytes + (uint32_t)c * 16u;
     col = c * 8;
 }
@@ -63,7 +66,7 @@ template <int NWAVES>
 __device__ __forceinline__ void u8_tile_lane(int wave, int lane, int inst, uint32_t ld_bytes,
                                              uint32_t &voff, int &col) {
     const int slot = (wave + inst * NWAVES) * 64 + lane;
-    const int row = slot >> 2, p = slot & 3, c = p ^ ((row >> 1) & 3);
+    const int row = slot >> 2, p = slot & 3, c = p ^ ((row >> 2) & 3);
     voff = (uint32_t)row * ld_bytes + (uint32_t)c * 16u;
     col = c * 16;
 }
@@ -142,16 +145,33 @@ struct FwdArgs {
     int tiles_m, tiles_n;
 };
 
-constexpr int FWD_BM = 256, FWD_BN = 128;
-constexpr int FWD_X_TILE = FWD_BM * 128, FWD_Q_TILE = FWD_BN * 64;
-constexpr int FWD_LDS = 2 * (FWD_X_TILE + FWD_Q_TILE);
+constexpr int FWD_BN = 128;
+constexpr int FWD_Q_TILE = FWD_BN * 64;
+constexpr int FWD_STAGES = 4;
+// 32-token blocks per wave: the accumulators (16 NR MB registers) must leave room for the operands
+constexpr int fwd_mb(int nr) { return nr == 3 ? 5 : 6; }
+constexpr int fwd_lds(int mb, int nr) {
+    const int stages = FWD_STAGES * (mb * 32 * 128 + FWD_Q_TILE), staging = nr * mb * 32 * (FWD_BN * 2 + 8);
+    return stages > staging ? stages : staging;
+}
 
-template <int NR, bool HAS8, bool EP>
-__global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
+// One workgroup = 4 waves (one per SIMD, so each may use the whole 512-entry register file) on a
+// (32 MB)-token x 128-channel tile; wave w owns channels [32 w, 32 w + 32) for all tokens, i.e.
+// MB x NR accumulator blocks of 32 x 32.  The converted code operand of a wave is then reused by
+// MB MFMAs per bit-width, which keeps the VALU slicing work at a fraction of the MFMA time.
+// LDS holds four stages of 64 k: stage kt is computed while stage kt + 1 is resident (the operands
+// of the next 16-wide k step are fetched into registers behind the MFMAs of the current one, also
+// across the stage boundary) and stages kt + 2, kt + 3 are in flight, so a load has two full
+// iterations to arrive.
+template <int NR, bool HAS8, bool EP, int MB>
+__global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    constexpr int BM = 32 * MB;
+    constexpr int X_TILE = BM * 128;
+    constexpr int STAGE = X_TILE + FWD_Q_TILE;
+    constexpr int LPS = MB + 2;  // direct-to-LDS loads per wave and stage
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave >> 2, wn = wave & 3;  // 2 waves along tokens x 4 along channels
     const int h = lane >> 5, l32 = lane & 31;
 
     // XCD-aware tile order: each XCD walks groups of 4 token tiles across the channel tiles
@@ -162,118 +182,228 @@ __global__ __launch_bounds__(512) void fwd_kernel(FwdArgs a) {
     const int gsz = min(a.tiles_m - first_m, GROUP);
     const int tm = first_m + (int)(lid % width) % gsz;
     const int tn = (int)(lid % width) / gsz;
-    const int m0 = tm * FWD_BM, n0 = tn * FWD_BN;
+    const int m0 = tm * BM, n0 = tn * FWD_BN;
 
     const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.X + (size_t)m0 * a.K, (uint64_t)(a.M - m0) * a.K * 2);
     const __amdgpu_buffer_rsrc_t rQ = make_rsrc(a.Q + (size_t)n0 * a.K, (uint64_t)(a.N - n0) * a.K);
 
-    // global -> LDS lane offsets (constant over the K loop)
-    uint32_t xoff[4];
-    int xcol[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) bf16_tile_lane<8>(wave, lane, i, (uint32_t)a.K * 2u, xoff[i], xcol[i]);
-    uint32_t qoff;
-    int qcol;
-    u8_tile_lane<8>(wave, lane, 0, (uint32_t)a.K, qoff, qcol);
+    // global -> LDS: lane offsets of the wave's first X / Q instruction; instruction i is 32 (X) or
+    // 64 (Q) rows further down with the same chunk
+    uint32_t xoff0, qoff0;
+    int xcol, qcol;
+    bf16_tile_lane<4>(wave, lane, 0, (uint32_t)a.K * 2u, xoff0, xcol);
+    u8_tile_lane<4>(wave, lane, 0, (uint32_t)a.K, qoff0, qcol);
+    const uint32_t xstep = 32u * (uint32_t)a.K * 2u, qstep = 64u * (uint32_t)a.K;
 
-    auto issue = [&](int kt, int buf) {
+    // Stage kt -> LDS buffer kt % 4, as MB + 2 loads per wave (MB of X, then 2 of Q).  Branch-free:
+    // a stage past the end of K (or a chunk past K in the last stage) is requested at an
+    // out-of-range offset, which the buffer unit answers with zeros without touching memory, so
+    // the number of loads in flight is the same in every iteration.
+    auto issue_one = [&](int kt, int i) {
         const int k0 = kt * BKT;
-        uint8_t *xs = smem + buf * FWD_X_TILE;
-        uint8_t *qs = smem + 2 * FWD_X_TILE + buf * FWD_Q_TILE;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t off = (k0 + xcol[i] < a.K) ? xoff[i] + (uint32_t)k0 * 2u : kOOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rX, (lds_ptr)(xs + (wave + i * 8) * 1024), 16, off, 0, 0, 0);
+        uint8_t *xs = smem + (kt & 3) * STAGE;
+        if (i < MB) {
+            // (an out-of-range base stays out of range: kOOB + i * xstep < 2^32 for every legal K)
+            const uint32_t xb = (k0 + xcol < a.K) ? xoff0 + (uint32_t)k0 * 2u : kOOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rX, (lds_ptr)(xs + (wave + i * 4) * 1024), 16,
+                                                     xb + (uint32_t)i * xstep, 0, 0, 0);
+        } else {
+            const uint32_t qb = (k0 + qcol < a.K) ? qoff0 + (uint32_t)k0 : kOOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rQ, (lds_ptr)(xs + X_TILE + (wave + (i - MB) * 4) * 1024), 16,
+                                                     qb + (uint32_t)(i - MB) * qstep, 0, 0, 0);
         }
-        const uint32_t off = (k0 + qcol < a.K) ? qoff + (uint32_t)k0 : kOOB;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rQ, (lds_ptr)(qs + wave * 1024), 16, off, 0, 0, 0);
+    };
+    auto issue = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < MB + 2; ++i) issue_one(kt, i);
     };
 
-    // LDS fragment addresses
-    const int nl = wn * 32 + l32;
-    const uint32_t qa0 = nl * 64 + ((h ^ ((nl >> 1) & 3)) << 4);
-    const uint32_t qa1 = nl * 64 + (((h + 2) ^ ((nl >> 1) & 3)) << 4);
+    // LDS fragment addresses (byte offsets inside a stage)
+    const int nl = wave * 32 + l32;
+    const uint32_t qa0 = X_TILE + nl * 64 + ((h ^ ((nl >> 2) & 3)) << 4);
+    const uint32_t qa1 = X_TILE + nl * 64 + (((h + 2) ^ ((nl >> 2) & 3)) << 4);
     uint32_t xa[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int cx = 2 * h + 4 * (t >> 1) + (t & 1);
-        xa[t] = (wm * 128 + l32) * 128 + ((cx ^ (l32 & 7)) << 4);
+        xa[t] = l32 * 128 + ((cx ^ ((l32 >> 1) & 7)) << 4);
     }
 
     SliceParam sp[NR];
 #pragma unroll
     for (int i = 0; i < NR; ++i) sp[i] = slice_param<EP>(a.r[i]);
 
-    f32x16 acc[NR][4];
+    // Dword w (two consecutive k) of the code operand of slot i, from the 8 code bytes (d0, d1).
+    auto convert_piece = [&](int i, int w, uint32_t d0, uint32_t d1) -> uint32_t {
+        const uint32_t d = w < 2 ? d0 : d1;
+        if (HAS8 && i == 0) {
+            const float lo = (w & 1) ? (float)((d >> 16) & 0xFFu) : (float)(d & 0xFFu);
+            const float hi = (w & 1) ? (float)(d >> 24) : (float)((d >> 8) & 0xFFu);
+            return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+        }
+        if constexpr (EP) {
+            const uint32_t placed = __builtin_amdgcn_perm(0u, d, (w & 1) ? 0x0C030C02u : 0x0C010C00u);
+            return (((placed + sp[i].half2) >> sp[i].sh) & 0x00FF00FFu) | kMagic128;
+        } else {
+            const uint32_t placed = __builtin_amdgcn_perm(0u, d, (w & 1) ? 0x030C020Cu : 0x010C000Cu);
+            u16x2 t = __builtin_elementwise_add_sat(__builtin_bit_cast(u16x2, placed),
+                                                    __builtin_bit_cast(u16x2, sp[i].half2));
+            const unsigned short s16 = (unsigned short)sp[i].sh;
+            t = t >> u16x2{s16, s16};
+            return __builtin_bit_cast(uint32_t, t) | kMagic128;
+        }
+    };
+
+    f32x16 acc[NR][MB];
 #pragma unroll
     for (int i = 0; i < NR; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < MB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int nkt = (a.K + BKT - 1) / BKT;
-    issue(0, 0);
-    for (int kt = 0; kt < nkt; ++kt) {
-        wait_vm0();
-        __syncthreads();
-        if (kt + 1 < nkt) issue(kt + 1, (kt + 1) & 1);
-        const uint8_t *xs = smem + (kt & 1) * FWD_X_TILE;
-        const uint8_t *qs = smem + 2 * FWD_X_TILE + (kt & 1) * FWD_Q_TILE;
-        const u32x4 raw0 = *reinterpret_cast<const u32x4 *>(qs + qa0);
-        const u32x4 raw1 = *reinterpret_cast<const u32x4 *>(qs + qa1);
+    issue(0);
+    issue(1);
+    issue(2);
+    // stage 0 must have landed before the first operand fetch; stages 1 and 2 may stay in flight
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPS) : "memory");
+    __syncthreads();
+
+    u32x4 xf[MB];      // activation operands of the current k step (refilled as soon as they are consumed)
+    u32x4 raw[2];      // 32 code bytes of this lane's channel: four k steps of one stage
+    u32x4 wf[NR];      // code operands of the current k step
+    raw[0] = *reinterpret_cast<const u32x4 *>(smem + qa0);
+    raw[1] = *reinterpret_cast<const u32x4 *>(smem + qa1);
+#pragma unroll
+    for (int j = 0; j < MB; ++j) xf[j] = *reinterpret_cast<const u32x4 *>(smem + xa[0] + j * 4096);
+#pragma unroll
+    for (int i = 0; i < NR; ++i)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) wf[i][w] = convert_piece(i, w, raw[0][0], raw[0][1]);
+
+    // One stage of 64 k: four 16-wide steps of NR * MB MFMAs.  A wave issues in order, so whatever
+    // is queued behind an MFMA that waits for the matrix pipe waits with it; the other work of a
+    // step is therefore cut into one small group per MFMA, fenced so that the compiler keeps it
+    // there:  group q < MB requests operand block q of step t + 1 from LDS (it then has the rest
+    // of the step to arrive), groups 1 .. 4 NR each produce one dword of the next code operands,
+    // the last groups of step 0 issue the global loads of stage kt + 3, and step 2 fetches the
+    // code bytes of the next stage.  MORE (compile time): there is a next stage.
+    auto tile = [&](auto more_tag, int kt) {
+        constexpr bool MORE = decltype(more_tag)::value;
+        constexpr int NM = NR * MB;
+        static_assert(4 * NR + 1 <= NM, "not enough MFMAs to hide the operand work");
+        constexpr int LPG = (LPS + NM - 1) / NM;  // global loads per group in step 0
+        const uint8_t *cur = smem + (kt & 3) * STAGE;
+        const uint8_t *nxt = smem + ((kt + 1) & 3) * STAGE;
+        u32x4 rawn[2];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const uint32_t d0 = t < 2 ? raw0[2 * t] : raw1[2 * (t - 2)];
-            const uint32_t d1 = t < 2 ? raw0[2 * t + 1] : raw1[2 * (t - 2) + 1];
-            u32x4 wf[NR];
-            const u32x4 placed = place_bytes<!EP>(d0, d1);
+            const bool pre = t < 3 || MORE;  // is there a next step
+            const uint8_t *src = t < 3 ? cur + xa[(t + 1) & 3] : nxt + xa[0];
+            // code bytes of the next step
+            uint32_t d0 = t == 3 ? rawn[0][0] : (t + 1 < 2 ? raw[0][2 * (t + 1)] : raw[1][2 * (t + 1 - 2)]);
+            uint32_t d1 = t == 3 ? rawn[0][1] : (t + 1 < 2 ? raw[0][2 * (t + 1) + 1] : raw[1][2 * (t + 1 - 2) + 1]);
+            // pin the conversions of this step to this step (the optimizer would otherwise collect
+            // them across the loop back-edge)
+            if (pre) asm volatile("" : "+v"(d0), "+v"(d1));
+            u32x4 xfn[MB];
+            u32x4 wfn[NR];
 #pragma unroll
-            for (int i = 0; i < NR; ++i) {
-                if (HAS8 && i == 0) {
-                    wf[i] = codes_to_bf16_r8(d0, d1);
-                } else {
-                    wf[i] = sliced_to_bf16<EP>(placed, sp[i].half2, sp[i].sh);
+            for (int q = 0; q < NM; ++q) {
+                const int j = q / NR, i = q % NR;
+                acc[i][j] = mfma32(wf[i], xf[j], acc[i][j]);
+                if (pre && q < MB) xfn[q] = *reinterpret_cast<const u32x4 *>(src + q * 4096);
+                if (pre && q >= 1 && q - 1 < 4 * NR) {
+                    uint32_t piece = convert_piece((q - 1) / 4, (q - 1) % 4, d0, d1);
+                    asm volatile("" : "+v"(piece));  // keeps the conversion inside this group
+                    wfn[(q - 1) / 4][(q - 1) % 4] = piece;
                 }
+                if (MORE && t == 2 && q >= NM - 2) rawn[q - (NM - 2)] = *reinterpret_cast<const u32x4 *>(nxt + (q == NM - 2 ? qa0 : qa1));
+                if (MORE && t == 0) {
+#pragma unroll
+                    for (int u = 0; u < LPG; ++u) {
+                        const int ld = (NM - 1 - q) * LPG + u;  // the last groups carry the loads
+                        if (ld < LPS) issue_one(kt + 3, ld);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
+            if (pre) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const u32x4 xf = *reinterpret_cast<const u32x4 *>(xs + xa[t] + j * 4096);
+                for (int i = 0; i < NR; ++i) wf[i] = wfn[i];
 #pragma unroll
-                for (int i = 0; i < NR; ++i) acc[i][j] = mfma32(wf[i], xf, acc[i][j]);
+                for (int j = 0; j < MB; ++j) xf[j] = xfn[j];
             }
         }
+        if (MORE) {
+            raw[0] = rawn[0];
+            raw[1] = rawn[1];
+        }
+    };
+
+    for (int kt = 0; kt + 1 < nkt; ++kt) {
+        // Stage kt + 1 must be resident for the operand prefetch at the end of this iteration; the
+        // loads of stage kt + 2 may stay in flight.  After the barrier every wave is done with
+        // stage kt - 1, whose buffer stage kt + 3 reuses.
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");
+        __syncthreads();
+        tile(std::true_type{}, kt);
     }
+    tile(std::false_type{}, nkt - 1);
+    wait_vm0();  // zero-fill loads of dead stages must not land in the staging area below
 
     // ---- epilogue ---------------------------------------------------------------------------
-    // accumulator v = 4 g + e of a lane holds row (channel) 8 g + 4 h + e, column (token) l32
-    float rs[4];
+    // accumulator v = 4 g + e of a lane holds row (channel) 8 g + 4 h + e, column (token) l32.
+    // A lane therefore owns only 4 consecutive channels of a token; the tile is first assembled in
+    // LDS ([token][channel] bf16, rows padded by 8 bytes so that both the 8-byte writes and the
+    // read-back are bank-conflict free) and then stored as whole 256-byte rows.
+    constexpr int OS = FWD_BN * 2 + 8;  // staging row stride in bytes
+    constexpr int OT = BM * OS;         // one bit-width
+    __syncthreads();                    // every wave is done with the operand stages
+    float rs[MB];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int m = m0 + wm * 128 + j * 32 + l32;
+    for (int j = 0; j < MB; ++j) {
+        const int m = m0 + j * 32 + l32;
         rs[j] = m < a.M ? a.rowsum[m] : 0.f;
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wn * 32 + 8 * g + 4 * h;
-        if (n >= a.N) continue;
-        const f32x4 al = *reinterpret_cast<const f32x4 *>(a.alpha + n);
-        const f32x4 ze = *reinterpret_cast<const f32x4 *>(a.zero + n);
+        const int nloc = wave * 32 + 8 * g + 4 * h;
+        f32x4 al = {0.f, 0.f, 0.f, 0.f}, ze = {0.f, 0.f, 0.f, 0.f};
+        if (n0 + nloc < a.N) {
+            al = *reinterpret_cast<const f32x4 *>(a.alpha + n0 + nloc);
+            ze = *reinterpret_cast<const f32x4 *>(a.zero + n0 + nloc);
+        }
 #pragma unroll
         for (int i = 0; i < NR; ++i) {
             const bool is8 = HAS8 && i == 0;
             const float mult = is8 ? 1.0f : (float)(1 << (8 - a.r[i]));
             const float bias = is8 ? 0.0f : 128.0f * mult;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int m = m0 + wm * 128 + j * 32 + l32;
-                if (m >= a.M) continue;
+            for (int j = 0; j < MB; ++j) {
                 float y[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    y[e] = al[e] * (mult * acc[i][j][4 * g + e] - (bias + ze[e]) * rs[j]);
-                u32x2 o = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
-                *reinterpret_cast<u32x2 *>(a.Y[i] + (size_t)m * a.N + n) = o;
+                for (int e = 0; e < 4; ++e) y[e] = al[e] * (mult * acc[i][j][4 * g + e] - (bias + ze[e]) * rs[j]);
+                const u32x2 o = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+                *reinterpret_cast<u32x2 *>(smem + i * OT + (j * 32 + l32) * OS + nloc * 2) = o;
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+#pragma unroll
+        for (int it = 0; it < BM * 16 / 256; ++it) {
+            const int c = it * 256 + threadIdx.x;
+            const int row = c >> 4, ch = c & 15;
+            const int m = m0 + row, n = n0 + ch * 8;
+            if (m < a.M && n < a.N) {
+                const uint8_t *src = smem + i * OT + row * OS + ch * 16;
+                const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
+                const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
+                __builtin_nontemporal_store(u32x4{lo.x, lo.y, hi.x, hi.y},
+                                            reinterpret_cast<u32x4 *>(a.Y[i] + (size_t)m * a.N + n));
             }
         }
     }
@@ -459,14 +589,14 @@ __global__ __launch_bounds__(512) void dx_kernel(DxArgs a) {
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
         const int kl = wk * 64 + rb * 32 + l32;
-        qa[rb][0] = kl * 64 + ((h ^ ((kl >> 1) & 3)) << 4);
-        qa[rb][1] = kl * 64 + (((h + 2) ^ ((kl >> 1) & 3)) << 4);
+        qa[rb][0] = kl * 64 + ((h ^ ((kl >> 2) & 3)) << 4);
+        qa[rb][1] = kl * 64 + (((h + 2) ^ ((kl >> 2) & 3)) << 4);
     }
     uint32_t xa[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int cx = 2 * h + 4 * (t >> 1) + (t & 1);
-        xa[t] = (wm * 128 + l32) * 128 + ((cx ^ (l32 & 7)) << 4);
+        xa[t] = (wm * 128 + l32) * 128 + ((cx ^ ((l32 >> 1) & 7)) << 4);
     }
 
     f32x16 acc[2][4];
@@ -599,8 +729,8 @@ __global__ __launch_bounds__(512) void dw_kernel(DwArgs a) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int cx = 2 * h + 4 * (t >> 1) + (t & 1);
-        ga[t] = (wn * 64 + l32) * 128 + ((cx ^ (l32 & 7)) << 4);
-        xa[t] = (wk * 128 + l32) * 128 + ((cx ^ (l32 & 7)) << 4);
+        ga[t] = (wn * 64 + l32) * 128 + ((cx ^ ((l32 >> 1) & 7)) << 4);
+        xa[t] = (wk * 128 + l32) * 128 + ((cx ^ ((l32 >> 1) & 7)) << 4);
     }
 
     f32x16 acc[2][4];
@@ -699,9 +829,12 @@ static bool allow_lds(Kern kern, int bytes) {
 }
 
 template <int NR, bool HAS8, bool EP>
-static mq_status launch_fwd(const FwdArgs &a, hipStream_t st) {
-    if (!allow_lds(fwd_kernel<NR, HAS8, EP>, FWD_LDS)) return MQ_ERR_DEVICE;
-    fwd_kernel<NR, HAS8, EP><<<dim3(a.tiles_m * a.tiles_n), dim3(512), FWD_LDS, st>>>(a);
+static mq_status launch_fwd(FwdArgs a, hipStream_t st) {
+    constexpr int MB = fwd_mb(NR);
+    a.tiles_m = (int)cdiv(a.M, 32 * MB);
+    a.tiles_n = (int)cdiv(a.N, FWD_BN);
+    if (!allow_lds(fwd_kernel<NR, HAS8, EP, MB>, fwd_lds(MB, NR))) return MQ_ERR_DEVICE;
+    fwd_kernel<NR, HAS8, EP, MB><<<dim3(a.tiles_m * a.tiles_n), dim3(256), fwd_lds(MB, NR), st>>>(a);
     return launch_status();
 }
 
@@ -769,8 +902,6 @@ extern "C" mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, co
             a.r[pos] = rs[i];
             ++pos;
         }
-    a.tiles_m = (int)cdiv(M, FWD_BM);
-    a.tiles_n = (int)cdiv(N, FWD_BN);
 
     rowsum_kernel<<<dim3((unsigned)cdiv(M, 4)), dim3(256), 0, st>>>(X, (int)M, (int)K, static_cast<float *>(ws));
     const bool ep = flags & MQ_FLAG_EXTRA_PRECISION;
