@@ -42,116 +42,132 @@ __device__ __forceinline__ uint32_t pair_hi(uint32_t first, uint32_t second) {
     return __builtin_amdgcn_perm(second, first, 0x07060302u);
 }
 
+// Eight (R = 2), four (R = 4) or two (R = 8) MFMAs on the 16 bytes `d` a lane holds of one weight
+// row, against the activations x0/x1 of the same k range; `acc_c` gathers the products with the
+// constant operand c (row 0 = ones, for int2 row 1 = the field offsets).
+template <int R, int RG>
+__device__ __forceinline__ void gemv_segment(const u32x4 (&wt)[RG], const u32x4 *xs, int i, f32x4 (&acc)[RG],
+                                             f32x4 &acc_c) {
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const u32x4 ones = {kOne2, kOne2, kOne2, kOne2};
+    if constexpr (R == 2) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const u32x4 x0 = xs[2 * w], x1 = xs[2 * w + 1];
+            // codes j and j + 8 of the dword share a register; pair the activations the same way
+            const u32x4 xb0 = {pair_lo(x0.x, x1.x), pair_hi(x0.x, x1.x), pair_lo(x0.y, x1.y), pair_hi(x0.y, x1.y)};
+            const u32x4 xb1 = {pair_lo(x0.z, x1.z), pair_hi(x0.z, x1.z), pair_lo(x0.w, x1.w), pair_hi(x0.w, x1.w)};
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) {
+                const uint32_t d = wt[rg][w], d6 = d >> 6, d12 = d >> 12;
+                const u32x4 a0 = {(d & 0x00030003u) | kB128, (d & 0x000C000Cu) | kB32, (d & 0x00300030u) | kB8,
+                                  (d6 & 0x00030003u) | kB128};
+                const u32x4 a1 = {(d6 & 0x000C000Cu) | kB32, (d6 & 0x00300030u) | kB8, (d12 & 0x00030003u) | kB128,
+                                  (d12 & 0x000C000Cu) | kB32};
+                acc[rg] = mfma16(a0, xb0, acc[rg]);
+                acc[rg] = mfma16(a1, xb1, acc[rg]);
+            }
+            const u32x4 c0 = i == 0 ? ones : (i == 1 ? u32x4{kB128, kB32, kB8, kB128} : zero4);
+            const u32x4 c1 = i == 0 ? ones : (i == 1 ? u32x4{kB32, kB8, kB128, kB32} : zero4);
+            acc_c = mfma16(c0, xb0, acc_c);
+            acc_c = mfma16(c1, xb1, acc_c);
+        }
+    } else if constexpr (R == 4) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const u32x4 x0 = xs[w];
+            // codes j and j + 4 of the dword share a register
+            const u32x4 xb = {pair_lo(x0.x, x0.z), pair_hi(x0.x, x0.z), pair_lo(x0.y, x0.w), pair_hi(x0.y, x0.w)};
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) {
+                const uint32_t d = wt[rg][w];
+                const u32x4 a0 = {(d & 0x000F000Fu) | kB128, ((d >> 4) & 0x000F000Fu) | kB128,
+                                  ((d >> 8) & 0x000F000Fu) | kB128, ((d >> 12) & 0x000F000Fu) | kB128};
+                acc[rg] = mfma16(a0, xb, acc[rg]);
+            }
+            acc_c = mfma16(i == 0 ? ones : zero4, xb, acc_c);
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const u32x4 xb = xs[u];
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) {
+                const uint32_t d0 = wt[rg][2 * u], d1 = wt[rg][2 * u + 1];
+                auto two = [](uint32_t lo, uint32_t hi) {  // two small integers -> packed bf16 (exact)
+                    return __builtin_amdgcn_perm(__float_as_uint((float)hi), __float_as_uint((float)lo), 0x07060302u);
+                };
+                const u32x4 a0 = {two(d0 & 0xFFu, (d0 >> 8) & 0xFFu), two((d0 >> 16) & 0xFFu, d0 >> 24),
+                                  two(d1 & 0xFFu, (d1 >> 8) & 0xFFu), two((d1 >> 16) & 0xFFu, d1 >> 24)};
+                acc[rg] = mfma16(a0, xb, acc[rg]);
+            }
+            acc_c = mfma16(i == 0 ? ones : zero4, xb, acc_c);
+        }
+    }
+}
+
 // One workgroup = NW waves on one block of 16 * RG weight rows; the waves interleave over the
 // 64-byte row segments and their partial sums meet in LDS.  Lane (i, g) = (lane % 16, lane / 16)
 // owns weight row i of each of the RG row groups and bytes [16 g, 16 g + 16) of every segment,
-// and batch entry b = i of the activations for the same k range.
-template <int R, int RG>
-__global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
+// and batch entry b = i of the activations for the same k range.  A wave requests the weights and
+// activations of IT segments at once before it computes, so that a whole small matrix is in
+// flight after one round trip to memory.
+template <int R, int RG, int IT>
+__global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int NW = blockDim.x >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int n0 = blockIdx.x * (16 * RG);
-    constexpr int KPB = 8 / R;          // codes per byte
-    constexpr int SLOTS = RG + 1;       // accumulators per lane: RG row groups + the constant operand
+    constexpr int KPB = 8 / R;             // codes per byte
+    constexpr int SLOTS = RG + 1;          // accumulators per lane: RG row groups + the constant operand
+    constexpr int XV = R == 2 ? 8 : (R == 4 ? 4 : 2);  // 16-byte activation loads per lane and segment
+
+    // epilogue parameters of this thread's first output, requested before anything else so that
+    // their latency is hidden behind the weight stream
+    constexpr int OUTS = 16 * RG * 16;  // outputs of the workgroup: (b, row) = (t / (16 RG), t % (16 RG))
+    uint16_t e_alpha = 0, e_zero = 0;
+    if (threadIdx.x < OUTS && n0 + (int)(threadIdx.x % (16 * RG)) < a.N) {
+        e_alpha = a.alpha[n0 + threadIdx.x % (16 * RG)];
+        e_zero = a.zero[n0 + threadIdx.x % (16 * RG)];
+    }
 
     f32x4 acc[RG];
 #pragma unroll
     for (int rg = 0; rg < RG; ++rg) acc[rg] = f32x4{0.f, 0.f, 0.f, 0.f};
     f32x4 acc_c = {0.f, 0.f, 0.f, 0.f};  // row 0: sum_k x, row 1 (int2): sum_k x * offset_k
 
-    const int iters = (a.KB + 63) >> 6;
+    const int segs = (a.KB + 63) >> 6;
     const bool xlive = i < a.B;
     const uint16_t *xrow = a.x + (size_t)(xlive ? i : 0) * a.K;
 
-    for (int it = wave; it < iters; it += NW) {
-        const int off = it * 64 + g * 16;  // byte offset inside the packed row
-        const bool inside = off < a.KB;
-        u32x4 wt[RG];
+    for (int s0 = wave; s0 < segs; s0 += NW * IT) {
+        u32x4 wt[IT][RG];
+        u32x4 xs[IT][XV];
 #pragma unroll
-        for (int rg = 0; rg < RG; ++rg) {
-            const int row = n0 + rg * 16 + i;
-            wt[rg] = u32x4{0u, 0u, 0u, 0u};
-            if (inside && row < a.N)
-                wt[rg] = __builtin_nontemporal_load(
-                    reinterpret_cast<const u32x4 *>(a.packed + (size_t)row * a.KB + off));
-        }
-        const int kx = off * KPB;  // first k of this lane's 16 bytes
-        const bool xl = inside && xlive;
-
-        if constexpr (R == 2) {
+        for (int it = 0; it < IT; ++it) {
+            const int off = (s0 + it * NW) * 64 + g * 16;  // byte offset inside the packed row
+            const bool inside = off < a.KB;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                u32x4 x0 = {0u, 0u, 0u, 0u}, x1 = {0u, 0u, 0u, 0u};
-                if (xl) {
-                    x0 = *reinterpret_cast<const u32x4 *>(xrow + kx + 16 * w);
-                    x1 = *reinterpret_cast<const u32x4 *>(xrow + kx + 16 * w + 8);
-                }
-                // codes j and j + 8 of the dword share a register; pair the activations the same way
-                const u32x4 xb0 = {pair_lo(x0.x, x1.x), pair_hi(x0.x, x1.x), pair_lo(x0.y, x1.y), pair_hi(x0.y, x1.y)};
-                const u32x4 xb1 = {pair_lo(x0.z, x1.z), pair_hi(x0.z, x1.z), pair_lo(x0.w, x1.w), pair_hi(x0.w, x1.w)};
-#pragma unroll
-                for (int rg = 0; rg < RG; ++rg) {
-                    const uint32_t d = wt[rg][w], d6 = d >> 6, d12 = d >> 12;
-                    const u32x4 a0 = {(d & 0x00030003u) | kB128, (d & 0x000C000Cu) | kB32,
-                                      (d & 0x00300030u) | kB8, (d6 & 0x00030003u) | kB128};
-                    const u32x4 a1 = {(d6 & 0x000C000Cu) | kB32, (d6 & 0x00300030u) | kB8,
-                                      (d12 & 0x00030003u) | kB128, (d12 & 0x000C000Cu) | kB32};
-                    acc[rg] = mfma16(a0, xb0, acc[rg]);
-                    acc[rg] = mfma16(a1, xb1, acc[rg]);
-                }
-                // constant operand: row 0 = ones, row 1 = the offsets of the fields above
-                u32x4 c0 = {0u, 0u, 0u, 0u}, c1 = {0u, 0u, 0u, 0u};
-                if (i == 0) {
-                    c0 = u32x4{kOne2, kOne2, kOne2, kOne2};
-                    c1 = c0;
-                } else if (i == 1) {
-                    c0 = u32x4{kB128, kB32, kB8, kB128};
-                    c1 = u32x4{kB32, kB8, kB128, kB32};
-                }
-                acc_c = mfma16(c0, xb0, acc_c);
-                acc_c = mfma16(c1, xb1, acc_c);
-            }
-        } else if constexpr (R == 4) {
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                u32x4 x0 = {0u, 0u, 0u, 0u};
-                if (xl) x0 = *reinterpret_cast<const u32x4 *>(xrow + kx + 8 * w);
-                // codes j and j + 4 of the dword share a register
-                const u32x4 xb = {pair_lo(x0.x, x0.z), pair_hi(x0.x, x0.z), pair_lo(x0.y, x0.w), pair_hi(x0.y, x0.w)};
-#pragma unroll
-                for (int rg = 0; rg < RG; ++rg) {
-                    const uint32_t d = wt[rg][w];
-                    const u32x4 a0 = {(d & 0x000F000Fu) | kB128, ((d >> 4) & 0x000F000Fu) | kB128,
-                                      ((d >> 8) & 0x000F000Fu) | kB128, ((d >> 12) & 0x000F000Fu) | kB128};
-                    acc[rg] = mfma16(a0, xb, acc[rg]);
-                }
-                u32x4 c0 = {0u, 0u, 0u, 0u};
-                if (i == 0) c0 = u32x4{kOne2, kOne2, kOne2, kOne2};
-                acc_c = mfma16(c0, xb, acc_c);
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                u32x4 xb = {0u, 0u, 0u, 0u};
-                if (xl) xb = *reinterpret_cast<const u32x4 *>(xrow + kx + 8 * u);
-#pragma unroll
-                for (int rg = 0; rg < RG; ++rg) {
-                    const uint32_t d0 = wt[rg][2 * u], d1 = wt[rg][2 * u + 1];
-                    auto two = [](uint32_t lo, uint32_t hi) {  // two small integers -> packed bf16 (exact)
-                        return __builtin_amdgcn_perm(__float_as_uint((float)hi), __float_as_uint((float)lo), 0x07060302u);
-                    };
-                    const u32x4 a0 = {two(d0 & 0xFFu, (d0 >> 8) & 0xFFu), two((d0 >> 16) & 0xFFu, d0 >> 24),
-                                      two(d1 & 0xFFu, (d1 >> 8) & 0xFFu), two((d1 >> 16) & 0xFFu, d1 >> 24)};
-                    acc[rg] = mfma16(a0, xb, acc[rg]);
-                }
-                u32x4 c0 = {0u, 0u, 0u, 0u};
-                if (i == 0) c0 = u32x4{kOne2, kOne2, kOne2, kOne2};
-                acc_c = mfma16(c0, xb, acc_c);
+            for (int rg = 0; rg < RG; ++rg) {
+                const int row = n0 + rg * 16 + i;
+                wt[it][rg] = u32x4{0u, 0u, 0u, 0u};
+                if (inside && row < a.N)
+                    wt[it][rg] = __builtin_nontemporal_load(
+                        reinterpret_cast<const u32x4 *>(a.packed + (size_t)row * a.KB + off));
             }
         }
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            const int off = (s0 + it * NW) * 64 + g * 16;
+            const bool xl = off < a.KB && xlive;
+            const u32x4 *xp = reinterpret_cast<const u32x4 *>(xrow + off * KPB);
+#pragma unroll
+            for (int v = 0; v < XV; ++v) xs[it][v] = xl ? xp[v] : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int it = 0; it < IT; ++it) gemv_segment<R, RG>(wt[it], xs[it], i, acc, acc_c);
     }
 
     // ---- cross-wave reduction in LDS --------------------------------------------------------
@@ -207,11 +223,14 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
     // matrix-core output layout: lane = column b + 16 * (row / 4), component = row % 4
     const float *tot = reinterpret_cast<const float *>(total);
     constexpr float kScale = (float)(1 << (8 - R));
-    for (int t = threadIdx.x; t < 16 * RG * 16; t += blockDim.x) {
-        const int b = t / (16 * RG), r = t % (16 * RG);
-        const int row = n0 + r;
-        if (b >= a.B || row >= a.N) continue;
-        const int rg = r >> 4, ri = r & 15;
+    for (int t = threadIdx.x; t < OUTS; t += blockDim.x) {
+        const int b = t / (16 * RG), er = t % (16 * RG), erow = n0 + er;
+        if (b >= a.B || erow >= a.N) continue;
+        if (t != (int)threadIdx.x) {  // only workgroups with fewer threads than outputs come here
+            e_alpha = a.alpha[erow];
+            e_zero = a.zero[erow];
+        }
+        const int rg = er >> 4, ri = er & 15;
         float dot = tot[(rg * 64 + b + 16 * (ri >> 2)) * 4 + (ri & 3)];
         const float xsum = tot[(RG * 64 + b) * 4 + 0];
         float offset;
@@ -223,18 +242,18 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
             offset = 0.0f;
         }
         dot -= offset;
-        if (a.row_ptr) dot += ovf[r * 16 + b];
-        const float al = bf16_bits_to_float(a.alpha[row]), z = bf16_bits_to_float(a.zero[row]);
+        if (a.row_ptr) dot += ovf[er * 16 + b];
+        const float al = bf16_bits_to_float(e_alpha), z = bf16_bits_to_float(e_zero);
         const float yv = al * (kScale * dot - z * xsum);
-        a.y[(size_t)b * a.N + row] = (uint16_t)float_to_bf16_bits(yv);
+        a.y[(size_t)b * a.N + erow] = (uint16_t)float_to_bf16_bits(yv);
     }
 }
 
-template <int R, int RG>
+template <int R, int RG, int IT>
 static void launch_gemv(const GemvArgs &a, int nw, hipStream_t st) {
     const int blocks = (int)cdiv(a.N, 16 * RG);
     const size_t lds = (size_t)(nw + 1) * (RG + 1) * 64 * 16 + (size_t)16 * RG * 16 * 4;
-    gemv_kernel<R, RG><<<dim3(blocks), dim3(64 * nw), lds, st>>>(a);
+    gemv_kernel<R, RG, IT><<<dim3(blocks), dim3(64 * nw), lds, st>>>(a);
 }
 
 }  // namespace mq
@@ -266,22 +285,28 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
     a.K = (int)K;
     a.KB = (int)kb;
 
-    // rows per workgroup: as many as still leave two workgroups per compute unit
-    int rg = 4;
-    while (rg > 1 && cdiv(N, 16 * rg) < 512) rg >>= 1;
-    // waves per workgroup: each should see at least two 64-byte segments of its rows
-    const int64_t iters = cdiv(kb, 64);
-    int nw = 8;
-    while (nw > 1 && iters < 2 * nw) nw >>= 1;
+    // Rows per workgroup (16 RG): each activation value is fetched once per workgroup, so a larger
+    // batch wants more rows behind every fetch; small batches keep RG = 1 for more workgroups.
+    const int rg = B <= 2 ? 1 : (B <= 8 ? 2 : 4);
+    // Waves per workgroup split the 64-byte segments of the rows; each wave takes up to IT of them
+    // per round trip to memory.
+    const int64_t segs = cdiv(kb, 64);
+    int nw = 16;
+    while (nw > 1 && segs < nw) nw >>= 1;
+    int it = segs >= 2 * nw ? 2 : 1;
+    if (r == 2 && rg == 4) it = 1;  // 64 int2 weights per lane and segment: registers allow one segment
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-#define MQ_GEMV_CASE(R_, RG_)                    \
-    if (r == R_ && rg == RG_) {                  \
-        launch_gemv<R_, RG_>(a, nw, st);         \
-        return launch_status();                  \
+#define MQ_GEMV_CASE(R_, RG_, IT_)                 \
+    if (r == R_ && rg == RG_ && it == IT_) {       \
+        launch_gemv<R_, RG_, IT_>(a, nw, st);      \
+        return launch_status();                    \
     }
-    MQ_GEMV_CASE(2, 1) MQ_GEMV_CASE(2, 2) MQ_GEMV_CASE(2, 4)
-    MQ_GEMV_CASE(4, 1) MQ_GEMV_CASE(4, 2) MQ_GEMV_CASE(4, 4)
-    MQ_GEMV_CASE(8, 1) MQ_GEMV_CASE(8, 2) MQ_GEMV_CASE(8, 4)
+    MQ_GEMV_CASE(2, 1, 1) MQ_GEMV_CASE(2, 2, 1) MQ_GEMV_CASE(2, 4, 1)
+    MQ_GEMV_CASE(2, 1, 2) MQ_GEMV_CASE(2, 2, 2)
+    MQ_GEMV_CASE(4, 1, 1) MQ_GEMV_CASE(4, 2, 1) MQ_GEMV_CASE(4, 4, 1)
+    MQ_GEMV_CASE(4, 1, 2) MQ_GEMV_CASE(4, 2, 2) MQ_GEMV_CASE(4, 4, 2)
+    MQ_GEMV_CASE(8, 1, 1) MQ_GEMV_CASE(8, 2, 1) MQ_GEMV_CASE(8, 4, 1)
+    MQ_GEMV_CASE(8, 1, 2) MQ_GEMV_CASE(8, 2, 2) MQ_GEMV_CASE(8, 4, 2)
 #undef MQ_GEMV_CASE
     return MQ_ERR_BITS;
 }
