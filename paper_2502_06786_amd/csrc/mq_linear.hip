@@ -523,26 +523,45 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in
 // the contraction runs over n and, within each n tile, over the bit-widths.
 // ============================================================================================
 struct DxArgs {
-    const uint16_t *As[3];  // [M, N] bf16
+    const uint16_t *As[3];  // [M, N] bf16, slot order (the r = 8 slot first when HAS8)
     const uint8_t *QT;      // [K, N] u8
     const float *cvec;      // [M]
     uint16_t *dX;           // [M, K] bf16
     int M, N, K;
-    int nr;
-    int r[3];
+    int r[3];               // bit-width per slot
     int tiles_m, tiles_k;
 };
 
-constexpr int DX_BM = 256, DX_BK = 256;
+constexpr int DX_MB = 5;                        // 32-token blocks per wave
+constexpr int DX_RB = 2;                        // 32-row blocks of k per wave
+constexpr int DX_BM = 32 * DX_MB;               // tokens per workgroup
+constexpr int DX_BK = 4 * 32 * DX_RB;           // k rows per workgroup (4 waves)
 constexpr int DX_A_TILE = DX_BM * 128, DX_Q_TILE = DX_BK * 64;
-constexpr int DX_LDS = 2 * (DX_A_TILE + DX_Q_TILE);
+constexpr int DX_STAGE = DX_A_TILE + DX_Q_TILE;
+constexpr int DX_OS = DX_BK * 2 + 8;            // row stride of the output staging tile
+constexpr int dx_lds() {
+    const int stages = 4 * DX_STAGE, staging = DX_BM * DX_OS;
+    return stages > staging ? stages : staging;
+}
 
-template <bool EP>
-__global__ __launch_bounds__(512) void dx_kernel(DxArgs a) {
+// Same pipeline as the forward kernel (one wave per SIMD, four LDS stages, one small fenced group
+// of operand work per MFMA), with the roles changed: a stage is one 64-wide tile of n for ONE
+// bit-width, i.e. the gradient operand As_slot[tokens, n tile] and the transposed codes
+// QT[k rows, n tile]; the NRS bit-widths of an n tile follow each other and all accumulate into the
+// same accumulators.  Wave w owns k rows [64 w, 64 w + 64) for all 160 tokens of the tile.  The
+// stage loop is unrolled over the bit-widths so that the kind of code conversion is a compile-time
+// property of each copy of the stage body.
+template <int NRS, bool HAS8, bool EP>
+__global__ __launch_bounds__(256) void dx_kernel(DxArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    constexpr int MB = DX_MB, RB = DX_RB;
+    constexpr int QL = DX_BK / 64;       // direct-to-LDS loads per wave and stage for the codes (16 rows each)
+    constexpr int LPS = MB + QL;         // loads per wave and stage
+    constexpr int NM = RB * MB;          // MFMAs per 16-wide step
+    static_assert(4 * RB + 1 <= NM && LPS <= NM, "not enough MFMAs to hide the operand work");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave >> 2, wk = wave & 3;  // 2 waves along tokens x 4 along k
     const int h = lane >> 5, l32 = lane & 31;
 
     const uint32_t lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
@@ -554,123 +573,231 @@ __global__ __launch_bounds__(512) void dx_kernel(DxArgs a) {
     const int tk = (int)(lid % width) / gsz;
     const int m0 = tm * DX_BM, k0 = tk * DX_BK;
 
-    __amdgpu_buffer_rsrc_t rA[3];
+    __amdgpu_buffer_rsrc_t rA[NRS];
 #pragma unroll
-    for (int i = 0; i < 3; ++i)
-        rA[i] = make_rsrc(a.As[i < a.nr ? i : 0] + (size_t)m0 * a.N, (uint64_t)(a.M - m0) * a.N * 2);
+    for (int i = 0; i < NRS; ++i) rA[i] = make_rsrc(a.As[i] + (size_t)m0 * a.N, (uint64_t)(a.M - m0) * a.N * 2);
     const __amdgpu_buffer_rsrc_t rQ = make_rsrc(a.QT + (size_t)k0 * a.N, (uint64_t)(a.K - k0) * a.N);
 
-    uint32_t aoff[4], qoff[2];
-    int acol[4], qcol[2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) bf16_tile_lane<8>(wave, lane, i, (uint32_t)a.N * 2u, aoff[i], acol[i]);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) u8_tile_lane<8>(wave, lane, i, (uint32_t)a.N, qoff[i], qcol[i]);
+    uint32_t aoff0, qoff0;
+    int acol, qcol;
+    bf16_tile_lane<4>(wave, lane, 0, (uint32_t)a.N * 2u, aoff0, acol);
+    u8_tile_lane<4>(wave, lane, 0, (uint32_t)a.N, qoff0, qcol);
+    const uint32_t astep = 32u * (uint32_t)a.N * 2u, qstep = 64u * (uint32_t)a.N;
 
-    auto issue = [&](int nt, int slot, int buf) {
+    // load i of stage (n tile nt, bit-width slot) into LDS buffer `buf`; out-of-range requests
+    // (a tile past N) are answered with zeros, so the loads in flight are the same every stage
+    auto issue_one = [&](int nt, auto slot_tag, int buf, int i) {
+        constexpr int SLOT = decltype(slot_tag)::value;
         const int n0 = nt * BKT;
-        uint8_t *as = smem + buf * DX_A_TILE;
-        uint8_t *qs = smem + 2 * DX_A_TILE + buf * DX_Q_TILE;
-        const __amdgpu_buffer_rsrc_t r = slot == 0 ? rA[0] : (slot == 1 ? rA[1] : rA[2]);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t off = (n0 + acol[i] < a.N) ? aoff[i] + (uint32_t)n0 * 2u : kOOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)(as + (wave + i * 8) * 1024), 16, off, 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const uint32_t off = (n0 + qcol[i] < a.N) ? qoff[i] + (uint32_t)n0 : kOOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rQ, (lds_ptr)(qs + (wave + i * 8) * 1024), 16, off, 0, 0, 0);
+        uint8_t *as = smem + buf * DX_STAGE;
+        if (i < MB) {
+            const uint32_t ab = (n0 + acol < a.N) ? aoff0 + (uint32_t)n0 * 2u : kOOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rA[SLOT], (lds_ptr)(as + (wave + i * 4) * 1024), 16,
+                                                     ab + (uint32_t)i * astep, 0, 0, 0);
+        } else {
+            const uint32_t qb = (n0 + qcol < a.N) ? qoff0 + (uint32_t)n0 : kOOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rQ, (lds_ptr)(as + DX_A_TILE + (wave + (i - MB) * 4) * 1024), 16,
+                                                     qb + (uint32_t)(i - MB) * qstep, 0, 0, 0);
         }
     };
 
-    // LDS fragment addresses: two 32-row blocks of k per wave, four 32-token blocks
-    uint32_t qa[2][2];
+    // LDS fragment addresses (byte offsets inside a stage)
+    uint32_t qa[RB][2];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        const int kl = wk * 64 + rb * 32 + l32;
-        qa[rb][0] = kl * 64 + ((h ^ ((kl >> 2) & 3)) << 4);
-        qa[rb][1] = kl * 64 + (((h + 2) ^ ((kl >> 2) & 3)) << 4);
+    for (int rb = 0; rb < RB; ++rb) {
+        const int kl = wave * (32 * RB) + rb * 32 + l32;
+        qa[rb][0] = DX_A_TILE + kl * 64 + ((h ^ ((kl >> 2) & 3)) << 4);
+        qa[rb][1] = DX_A_TILE + kl * 64 + (((h + 2) ^ ((kl >> 2) & 3)) << 4);
     }
     uint32_t xa[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int cx = 2 * h + 4 * (t >> 1) + (t & 1);
-        xa[t] = (wm * 128 + l32) * 128 + ((cx ^ ((l32 >> 1) & 7)) << 4);
+        xa[t] = l32 * 128 + ((cx ^ ((l32 >> 1) & 7)) << 4);
     }
 
-    f32x16 acc[2][4];
+    SliceParam sp[NRS];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int i = 0; i < NRS; ++i) sp[i] = slice_param<EP>(a.r[i]);
+
+    // dword w (two consecutive n) of the code operand of bit-width SLOT from 8 code bytes (d0, d1)
+    auto convert_piece = [&](auto slot_tag, int w, uint32_t d0, uint32_t d1) -> uint32_t {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        const uint32_t d = w < 2 ? d0 : d1;
+        if constexpr (HAS8 && SLOT == 0) {
+            const float lo = (w & 1) ? (float)((d >> 16) & 0xFFu) : (float)(d & 0xFFu);
+            const float hi = (w & 1) ? (float)(d >> 24) : (float)((d >> 8) & 0xFFu);
+            return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+        } else if constexpr (EP) {
+            const uint32_t placed = __builtin_amdgcn_perm(0u, d, (w & 1) ? 0x0C030C02u : 0x0C010C00u);
+            return (((placed + sp[SLOT].half2) >> sp[SLOT].sh) & 0x00FF00FFu) | kMagic128;
+        } else {
+            const uint32_t placed = __builtin_amdgcn_perm(0u, d, (w & 1) ? 0x030C020Cu : 0x010C000Cu);
+            u16x2 t = __builtin_elementwise_add_sat(__builtin_bit_cast(u16x2, placed),
+                                                    __builtin_bit_cast(u16x2, sp[SLOT].half2));
+            const unsigned short s16 = (unsigned short)sp[SLOT].sh;
+            t = t >> u16x2{s16, s16};
+            return __builtin_bit_cast(uint32_t, t) | kMagic128;
+        }
+    };
+
+    f32x16 acc[RB][MB];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int j = 0; j < MB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[rb][j][v] = 0.f;
 
     const int nnt = (a.N + BKT - 1) / BKT;
-    const int nst = nnt * a.nr;
-    issue(0, 0, 0);
-    int nt = 0, slot = 0;
-    for (int st = 0; st < nst; ++st) {
-        wait_vm0();
-        __syncthreads();
-        int nslot = slot + 1, nnt_next = nt;
-        if (nslot == a.nr) {
-            nslot = 0;
-            nnt_next = nt + 1;
-        }
-        if (st + 1 < nst) issue(nnt_next, nslot, (st + 1) & 1);
-        const uint8_t *as = smem + (st & 1) * DX_A_TILE;
-        const uint8_t *qs = smem + 2 * DX_A_TILE + (st & 1) * DX_Q_TILE;
-        const int r = a.r[slot];
-        const SliceParam sp = slice_param<EP>(r);
-        u32x4 raw[2][2];
+    // prologue: stages 0, 1, 2 (n tile st / NRS, bit-width st % NRS)
+    {
+        auto issue_stage = [&](auto st_tag) {
+            constexpr int ST = decltype(st_tag)::value;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            raw[rb][0] = *reinterpret_cast<const u32x4 *>(qs + qa[rb][0]);
-            raw[rb][1] = *reinterpret_cast<const u32x4 *>(qs + qa[rb][1]);
-        }
+            for (int i = 0; i < LPS; ++i) issue_one(ST / NRS, std::integral_constant<int, ST % NRS>{}, ST & 3, i);
+        };
+        issue_stage(std::integral_constant<int, 0>{});
+        issue_stage(std::integral_constant<int, 1>{});
+        issue_stage(std::integral_constant<int, 2>{});
+    }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPS) : "memory");
+    __syncthreads();
+
+    u32x4 xf[MB];         // gradient operands of the current step
+    u32x4 raw[RB][2];     // 32 code bytes per k row of this lane: four steps of one stage
+    u32x4 wf[RB];         // code operands of the current step
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        raw[rb][0] = *reinterpret_cast<const u32x4 *>(smem + qa[rb][0]);
+        raw[rb][1] = *reinterpret_cast<const u32x4 *>(smem + qa[rb][1]);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) wf[rb][w] = convert_piece(std::integral_constant<int, 0>{}, w, raw[rb][0][0], raw[rb][0][1]);
+    }
+#pragma unroll
+    for (int j = 0; j < MB; ++j) xf[j] = *reinterpret_cast<const u32x4 *>(smem + xa[0] + j * 4096);
+
+    // One stage: four 16-wide steps.  st = index of this stage, nt3 / the slot of stage st + 3 are
+    // what the loads issued in step 0 fetch.
+    auto tile = [&](auto slot_tag, auto more_tag, int st, int nt) {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        constexpr bool MORE = decltype(more_tag)::value;
+        constexpr int NEXT = (SLOT + 1) % NRS;
+        const uint8_t *cur = smem + (st & 3) * DX_STAGE;
+        const uint8_t *nxt = smem + ((st + 1) & 3) * DX_STAGE;
+        u32x4 rawn[RB][2];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            u32x4 wf[2];
+            const bool pre = t < 3 || MORE;
+            const uint8_t *src = t < 3 ? cur + xa[(t + 1) & 3] : nxt + xa[0];
+            uint32_t d0[RB], d1[RB];
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-                const uint32_t d0 = t < 2 ? raw[rb][0][2 * t] : raw[rb][1][2 * (t - 2)];
-                const uint32_t d1 = t < 2 ? raw[rb][0][2 * t + 1] : raw[rb][1][2 * (t - 2) + 1];
-                if (r == 8) {
-                    wf[rb] = codes_to_bf16_r8(d0, d1);
-                } else {
-                    wf[rb] = sliced_to_bf16<EP>(place_bytes<!EP>(d0, d1), sp.half2, sp.sh);
-                }
+            for (int rb = 0; rb < RB; ++rb) {
+                d0[rb] = t == 3 ? rawn[rb][0][0] : (t + 1 < 2 ? raw[rb][0][2 * (t + 1)] : raw[rb][1][2 * (t + 1 - 2)]);
+                d1[rb] = t == 3 ? rawn[rb][0][1] : (t + 1 < 2 ? raw[rb][0][2 * (t + 1) + 1] : raw[rb][1][2 * (t + 1 - 2) + 1]);
+                if (pre) asm volatile("" : "+v"(d0[rb]), "+v"(d1[rb]));  // pins the conversions to this step
             }
+            u32x4 xfn[MB];
+            u32x4 wfn[RB];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const u32x4 xf = *reinterpret_cast<const u32x4 *>(as + xa[t] + j * 4096);
+            for (int q = 0; q < NM; ++q) {
+                const int j = q / RB, rb = q % RB;
+                acc[rb][j] = mfma32(wf[rb], xf[j], acc[rb][j]);
+                if (pre && q < MB) xfn[q] = *reinterpret_cast<const u32x4 *>(src + q * 4096);
+                if (pre && q >= 1 && q - 1 < 4 * RB) {
+                    const int prb = (q - 1) / 4, pw = (q - 1) % 4;
+                    uint32_t piece = t < 3 ? convert_piece(std::integral_constant<int, SLOT>{}, pw, d0[prb], d1[prb])
+                                           : convert_piece(std::integral_constant<int, NEXT>{}, pw, d0[prb], d1[prb]);
+                    asm volatile("" : "+v"(piece));  // keeps the conversion inside this group
+                    wfn[prb][pw] = piece;
+                }
+                if (MORE && t == 2 && q >= NM - 2 * RB) {
+                    const int e = q - (NM - 2 * RB);
+                    rawn[e / 2][e % 2] = *reinterpret_cast<const u32x4 *>(nxt + qa[e / 2][e % 2]);
+                }
+                if (MORE && t == 0 && NM - 1 - q < LPS)
+                    issue_one(nt + (SLOT + 3) / NRS, std::integral_constant<int, (SLOT + 3) % NRS>{}, (st + 3) & 3, NM - 1 - q);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (pre) {
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb) acc[rb][j] = mfma32(wf[rb], xf, acc[rb][j]);
+                for (int rb = 0; rb < RB; ++rb) wf[rb] = wfn[rb];
+#pragma unroll
+                for (int j = 0; j < MB; ++j) xf[j] = xfn[j];
             }
         }
-        slot = nslot;
-        nt = nnt_next;
-    }
+        if (MORE) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                raw[rb][0] = rawn[rb][0];
+                raw[rb][1] = rawn[rb][1];
+            }
+        }
+    };
+    auto stage = [&](auto slot_tag, auto more_tag, int st, int nt) {
+        // stage st + 1 must be resident (operand prefetch at the end of this stage); the loads of
+        // stage st + 2 may stay in flight; after the barrier the buffer of stage st - 1 is free
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");
+        __syncthreads();
+        tile(slot_tag, more_tag, st, nt);
+    };
 
-    // epilogue: rows of the product are k, columns tokens
+    int st = 0;
+    for (int nt = 0; nt + 1 < nnt; ++nt) {
+        stage(std::integral_constant<int, 0>{}, std::true_type{}, st++, nt);
+        if constexpr (NRS > 1) stage(std::integral_constant<int, 1>{}, std::true_type{}, st++, nt);
+        if constexpr (NRS > 2) stage(std::integral_constant<int, 2>{}, std::true_type{}, st++, nt);
+    }
+    {
+        const int nt = nnt - 1;
+        if constexpr (NRS == 1) {
+            stage(std::integral_constant<int, 0>{}, std::false_type{}, st++, nt);
+        } else if constexpr (NRS == 2) {
+            stage(std::integral_constant<int, 0>{}, std::true_type{}, st++, nt);
+            stage(std::integral_constant<int, 1>{}, std::false_type{}, st++, nt);
+        } else {
+            stage(std::integral_constant<int, 0>{}, std::true_type{}, st++, nt);
+            stage(std::integral_constant<int, 1>{}, std::true_type{}, st++, nt);
+            stage(std::integral_constant<int, 2>{}, std::false_type{}, st++, nt);
+        }
+    }
+    wait_vm0();  // zero-fill loads of dead stages must not land in the staging area below
+
+    // ---- epilogue: rows of the product are k, columns tokens; dX = acc - c[m] --------------------
+    // assembled in LDS as [token][k] bf16 (rows padded by 8 bytes) and stored as whole 512-byte rows
+    __syncthreads();
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int m = m0 + wm * 128 + j * 32 + l32;
-        if (m >= a.M) continue;
-        const float c = a.cvec[m];
+    for (int j = 0; j < MB; ++j) {
+        const int m = m0 + j * 32 + l32;
+        const float c = m < a.M ? a.cvec[m] : 0.f;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int k = k0 + wk * 64 + rb * 32 + 8 * g + 4 * h;
-                if (k >= a.K) continue;
-                u32x2 o = {pack_bf16x2(acc[rb][j][4 * g] - c, acc[rb][j][4 * g + 1] - c),
-                           pack_bf16x2(acc[rb][j][4 * g + 2] - c, acc[rb][j][4 * g + 3] - c)};
-                *reinterpret_cast<u32x2 *>(a.dX + (size_t)m * a.K + k) = o;
+                const int kloc = wave * (32 * RB) + rb * 32 + 8 * g + 4 * h;
+                const u32x2 o = {pack_bf16x2(acc[rb][j][4 * g] - c, acc[rb][j][4 * g + 1] - c),
+                                 pack_bf16x2(acc[rb][j][4 * g + 2] - c, acc[rb][j][4 * g + 3] - c)};
+                *reinterpret_cast<u32x2 *>(smem + (j * 32 + l32) * DX_OS + kloc * 2) = o;
             }
     }
+    __syncthreads();
+    constexpr int CPR = DX_BK / 8;  // 16-byte chunks per row
+#pragma unroll
+    for (int it = 0; it < DX_BM * CPR / 256; ++it) {
+        const int c = it * 256 + threadIdx.x;
+        const int row = c / CPR, ch = c % CPR;
+        const int m = m0 + row, k = k0 + ch * 8;
+        if (m < a.M && k < a.K) {
+            const uint8_t *src = smem + row * DX_OS + ch * 16;
+            const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
+            const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
+            __builtin_nontemporal_store(u32x4{lo.x, lo.y, hi.x, hi.y},
+                                        reinterpret_cast<u32x4 *>(a.dX + (size_t)m * a.K + k));
+        }
+    }
+#else
+    (void)a;
+#endif
 }
 
 // ============================================================================================
@@ -843,6 +970,25 @@ static mq_status launch_fwd_ep(const FwdArgs &a, bool ep, hipStream_t st) {
     return ep ? launch_fwd<NR, HAS8, true>(a, st) : launch_fwd<NR, HAS8, false>(a, st);
 }
 
+template <int NRS, bool HAS8, bool EP>
+static mq_status launch_dx_one(const DxArgs &d, hipStream_t st) {
+    if (!allow_lds(dx_kernel<NRS, HAS8, EP>, dx_lds())) return MQ_ERR_DEVICE;
+    dx_kernel<NRS, HAS8, EP><<<dim3(d.tiles_m * d.tiles_k), dim3(256), dx_lds(), st>>>(d);
+    return launch_status();
+}
+
+template <int NRS>
+static mq_status launch_dx_nrs(const DxArgs &d, bool has8, bool ep, hipStream_t st) {
+    if (has8) return ep ? launch_dx_one<NRS, true, true>(d, st) : launch_dx_one<NRS, true, false>(d, st);
+    return ep ? launch_dx_one<NRS, false, true>(d, st) : launch_dx_one<NRS, false, false>(d, st);
+}
+
+static mq_status launch_dx(const DxArgs &d, int nr, bool has8, bool ep, hipStream_t st) {
+    if (nr == 1) return launch_dx_nrs<1>(d, has8, ep, st);
+    if (nr == 2) return launch_dx_nrs<2>(d, has8, ep, st);
+    return launch_dx_nrs<3>(d, has8, ep, st);
+}
+
 }  // namespace mq
 
 extern "C" size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int nr) {
@@ -960,10 +1106,20 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
         transpose_kernel<uint8_t><<<dim3((unsigned)cdiv(K, 64), (unsigned)cdiv(N, 64)), dim3(256), 0, st>>>(
             Q, QT, (int)N, (int)K);
 
+        // slot order of the kernel: the r = 8 bit-width (if any) first
         DxArgs d;
+        int order[3] = {0, 0, 0}, has8 = 0, pos = 0;
+        for (int i = 0; i < nr; ++i)
+            if (rs[i] == 8) {
+                has8 = 1;
+                order[pos++] = i;
+            }
+        for (int i = 0; i < nr; ++i)
+            if (rs[i] != 8) order[pos++] = i;
         for (int i = 0; i < 3; ++i) {
-            d.As[i] = p.As[i];
-            d.r[i] = rs[i < nr ? i : 0];
+            const int j = order[i < nr ? i : 0];
+            d.As[i] = p.As[j];
+            d.r[i] = rs[j];
         }
         d.QT = QT;
         d.cvec = p.cvec;
@@ -971,16 +1127,10 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
         d.M = (int)M;
         d.N = (int)N;
         d.K = (int)K;
-        d.nr = nr;
         d.tiles_m = (int)cdiv(M, DX_BM);
         d.tiles_k = (int)cdiv(K, DX_BK);
-        if (ep) {
-            if (!allow_lds(dx_kernel<true>, DX_LDS)) return MQ_ERR_DEVICE;
-            dx_kernel<true><<<dim3(d.tiles_m * d.tiles_k), dim3(512), DX_LDS, st>>>(d);
-        } else {
-            if (!allow_lds(dx_kernel<false>, DX_LDS)) return MQ_ERR_DEVICE;
-            dx_kernel<false><<<dim3(d.tiles_m * d.tiles_k), dim3(512), DX_LDS, st>>>(d);
-        }
+        const mq_status ds = launch_dx(d, nr, has8 != 0, ep, st);
+        if (ds != MQ_OK) return ds;
     }
     if (dW) {
         GtArgs g;
