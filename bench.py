@@ -27,6 +27,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM-side bytes per launch of the fused forward kernel on this workload (average of the three
+# linears), from the FETCH_SIZE / WRITE_SIZE counter passes summarised in
+# profiles/hot_path_step_gemma2b_mlp_hbm_traffic.txt (FETCH_SIZE scaled by 2.00, WRITE_SIZE by 1.00).
+FWD_TRAFFIC_BYTES = (355604 + 166014) * 1024
 
 
 def parse():
@@ -36,6 +40,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gemv-sweep", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three 256 MiB device-to-device copies before the timed region: a kernel of "
+                         "known traffic against which hardware byte counters of a profiling run are scaled")
     return ap.parse_args()
 
 
@@ -115,6 +122,14 @@ def main():
                     mq.mq_gemv_sliced(L.xdec[B], L.p2, L.alpha16, L.zero16, 2, L.K, y=L.ydec[B])
             timed("gemv", do_gemv, rec)
 
+    if args.copy_calibration:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -147,9 +162,11 @@ def main():
     fwd_launches = len(records["fwd"])
     fwd_avg_ms = sum(a.elapsed_time(b) for a, b in records["fwd"]) / fwd_launches
     achieved = (flops_fwd / len(layers)) / (fwd_avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "fwd_kernel<3,true,false>", "achieved": round(achieved, 2),
+    roofline = {"bound": "mfma", "kernel": "mq::fwd_kernel<3, true, false, 5>", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": None, "avg_launch_ms": round(fwd_avg_ms, 4)}
+                "traffic": FWD_TRAFFIC_BYTES, "algorithmic_bytes": int(sum(L.N * L.K + 2 * L.M * L.K + 6 * L.M * L.N
+                                                                         for L in layers) / len(layers)),
+                "avg_launch_ms": round(fwd_avg_ms, 4)}
 
     out = {
         "metric": "fused r=8/4/2 quant-linear TFLOP/s (fwd 6MNK + STE bwd 8MNK over the whole hot-path step)",
