@@ -8,6 +8,8 @@
 // that sits at mantissa bit p of a bf16 whose exponent is 2^(7-p) reads as 2^(7-p) + code, so one
 // AND-OR per two codes does the unpack; the constant 2^(7-p) offsets are summed by one extra
 // matrix-core product with a constant operand and subtracted in the epilogue.
+#include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 
 #include "mq_common.h"
@@ -25,6 +27,8 @@ struct GemvArgs {
     int B, N, K;
     int KB;  // bytes per packed row
 };
+
+__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 constexpr uint32_t kB128 = 0x43004300u, kB32 = 0x42004200u, kB8 = 0x41004100u;  // (128,128) (32,32) (8,8)
 
@@ -59,24 +63,83 @@ __device__ __forceinline__ float wave_sum(float v) {
            __int_as_float(__builtin_amdgcn_readlane(bits, 32)) + __int_as_float(__builtin_amdgcn_readlane(bits, 48));
 }
 
-// The MFMAs of one 64-byte row segment: the 16 bytes a lane holds of each of its RG weight rows
-// against the activations of the same k range, read from LDS (xs[v * xstride] = v-th operand of
-// the lane's k range, already in the element order of the unpacked codes).
+// One workgroup = KS * RW waves.  Wave (ks, rw) = (wave % KS, wave / KS) streams block rw of
+// 16 * RG weight rows and takes every KS-th 64-byte segment of those rows; the KS partial sums of a
+// row block meet in LDS.  Lane (i, g) = (lane % 16, lane / 16) owns weight row i of each of the RG
+// row groups and bytes [16 g, 16 g + 16) of a segment, and batch entry b = i of the activations
+// for the same k range.  A workgroup walks over groups of RW row blocks (grid-stride), so that the
+// whole grid is resident at once and no second, mostly empty round of workgroups is needed.
+//
+// Activations: x is brought into LDS by direct global->LDS loads (asynchronous, all in flight at
+// once) as 1 KB blocks of 512 consecutive k of one batch entry; 16-byte slot L of the block of
+// batch entry b is kept at slot L ^ b, so that the 16 lanes of a matrix-core operand read (16
+// batch entries, same k) hit 16 different bank groups.  A second, LDS-local pass pairs the values
+// the way the unpacked codes are paired and takes sum_k x and (int2) sum_k x * offset_k, which is
+// what removes the 128 / 32 / 8 offsets of the unpack and applies the zero-point.  When all of x
+// fits it is staged once per workgroup; otherwise in chunks, per group of row blocks.
+//
+// Weights stream through a register ring that keeps D - 1 segments per wave in flight behind the
+// one being computed.  Few rows -> large KS (the whole matrix is in flight after one round trip);
+// many rows -> KS = 1 and every wave streams its own rows.
+//
+// Lanes are never masked in the hot loop: rows past N re-read row N - 1 and batch entries past B
+// re-read whatever LDS holds for them; both only feed outputs that are not stored (a column of the
+// product depends on its own batch entry only).  A lane whose 16 bytes lie past the end of the row
+// re-reads the row's last 16 bytes; any bit pattern unpacks to finite numbers, and those meet
+// activations that were staged as zeros.
+constexpr int kSumBytes = 1024;  // [0, 32): per-half-wave parts of sum_k x; [32, 64): of sum_k x * offset_k
+constexpr uint32_t kOOB = 0x80000000u;
+typedef __attribute__((address_space(3))) void *lds_ptr;
+
+// The operands of one 64-byte segment: XV 16-byte slots per lane; slot L = sb * 4 XV + g * XV + v of
+// the block, kept at L ^ b.
+// (v & mask) | magic.  The fused v_and_or_b32 takes at most one scalar operand and no literals, so it
+// is only selected when the masks already live in scalar registers and the exponent patterns in
+// vector registers (see unpack_consts); with literal constants the compiler emits two instructions.
+// (Plain C on purpose: hazards around instructions inside inline assembly are not tracked.)
+__device__ __forceinline__ uint32_t and_or(uint32_t v, uint32_t mask_s, uint32_t magic_v) {
+    return (v & mask_s) | magic_v;
+}
+
+// Constants of the unpack, pinned in registers once per kernel.
+struct UnpackConsts {
+    uint32_t m0, m1, m2;     // scalar: field masks
+    uint32_t e128, e32, e8;  // vector: (128,128), (32,32), (8,8) as bf16 pairs
+};
+template <int R>
+__device__ __forceinline__ UnpackConsts unpack_consts() {
+    UnpackConsts c;
+    c.m0 = R == 2 ? 0x00030003u : 0x000F000Fu;
+    c.m1 = 0x000C000Cu;
+    c.m2 = 0x00300030u;
+    c.e128 = kB128;
+    c.e32 = kB32;
+    c.e8 = kB8;
+    asm volatile("" : "+s"(c.m0), "+s"(c.m1), "+s"(c.m2));
+    asm volatile("" : "+v"(c.e128), "+v"(c.e32), "+v"(c.e8));
+    return c;
+}
+
+// The operands of one 64-byte segment: XV 16-byte slots per lane; slot L = sb * 4 XV + g * XV + v of
+// the block, kept at L ^ b.
 template <int R, int RG>
-__device__ __forceinline__ void gemv_segment(const u32x4 (&wt)[RG], const u32x4 *xs, int xstride, f32x4 (&acc)[RG]) {
+__device__ __forceinline__ void gemv_segment(const u32x4 (&wt)[RG], const uint8_t *blk, uint32_t slot0,
+                                             const UnpackConsts &uc, f32x4 (&acc)[RG]) {
+    // slot0 = (sb * 4 XV + g * XV) ^ b, shifted to bytes; v < XV only touches bits that b may flip too
+    auto operand = [&](int v) { return *reinterpret_cast<const u32x4 *>(blk + (slot0 ^ (uint32_t)(v << 4))); };
     if constexpr (R == 2) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const u32x4 xb0 = xs[(2 * w) * xstride], xb1 = xs[(2 * w + 1) * xstride];
+            const u32x4 xb0 = operand(2 * w), xb1 = operand(2 * w + 1);
 #pragma unroll
             for (int rg = 0; rg < RG; ++rg) {
                 // codes j and j + 8 of a dword share a register; fields at bits 0-1, 2-3, 4-5 of a
-                // 16-bit lane read as 128 + c, 32 + c, 8 + c under the exponents below
+                // 16-bit lane read as 128 + c, 32 + c, 8 + c under the exponents of e128, e32, e8
                 const uint32_t d = wt[rg][w], d6 = d >> 6, d12 = d >> 12;
-                const u32x4 a0 = {(d & 0x00030003u) | kB128, (d & 0x000C000Cu) | kB32, (d & 0x00300030u) | kB8,
-                                  (d6 & 0x00030003u) | kB128};
-                const u32x4 a1 = {(d6 & 0x000C000Cu) | kB32, (d6 & 0x00300030u) | kB8, (d12 & 0x00030003u) | kB128,
-                                  (d12 & 0x000C000Cu) | kB32};
+                const u32x4 a0 = {and_or(d, uc.m0, uc.e128), and_or(d, uc.m1, uc.e32), and_or(d, uc.m2, uc.e8),
+                                  and_or(d6, uc.m0, uc.e128)};
+                const u32x4 a1 = {and_or(d6, uc.m1, uc.e32), and_or(d6, uc.m2, uc.e8), and_or(d12, uc.m0, uc.e128),
+                                  and_or(d12, uc.m1, uc.e32)};
                 acc[rg] = mfma16(a0, xb0, acc[rg]);
                 acc[rg] = mfma16(a1, xb1, acc[rg]);
             }
@@ -84,19 +147,19 @@ __device__ __forceinline__ void gemv_segment(const u32x4 (&wt)[RG], const u32x4 
     } else if constexpr (R == 4) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const u32x4 xb = xs[w * xstride];
+            const u32x4 xb = operand(w);
 #pragma unroll
             for (int rg = 0; rg < RG; ++rg) {
                 const uint32_t d = wt[rg][w];  // codes j and j + 4 of the dword share a register
-                const u32x4 a0 = {(d & 0x000F000Fu) | kB128, ((d >> 4) & 0x000F000Fu) | kB128,
-                                  ((d >> 8) & 0x000F000Fu) | kB128, ((d >> 12) & 0x000F000Fu) | kB128};
+                const u32x4 a0 = {and_or(d, uc.m0, uc.e128), and_or(d >> 4, uc.m0, uc.e128),
+                                  and_or(d >> 8, uc.m0, uc.e128), and_or(d >> 12, uc.m0, uc.e128)};
                 acc[rg] = mfma16(a0, xb, acc[rg]);
             }
         }
     } else {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const u32x4 xb = xs[u * xstride];
+            const u32x4 xb = operand(u);
 #pragma unroll
             for (int rg = 0; rg < RG; ++rg) {
                 const uint32_t d0 = wt[rg][2 * u], d1 = wt[rg][2 * u + 1];
@@ -111,223 +174,304 @@ __device__ __forceinline__ void gemv_segment(const u32x4 (&wt)[RG], const u32x4 
     }
 }
 
-// One workgroup = KS * RW waves.  Wave (ks, rw) = (wave % KS, wave / KS) streams block rw of
-// 16 * RG weight rows and takes every KS-th 64-byte segment of those rows; the KS partial sums of a
-// row block meet in LDS.  Lane (i, g) = (lane % 16, lane / 16) owns weight row i of each of the RG
-// row groups and bytes [16 g, 16 g + 16) of a segment, and batch entry b = i of the activations
-// for the same k range.
-//
-// The activations are staged in LDS once per workgroup, already paired the way the unpacked codes
-// are (in chunks of at most kXChunk bytes when B * K is large) and shared by all its waves; while
-// they sit there, sum_k x and (int2) sum_k x * offset_k are taken once per workgroup, which is
-// what removes the 128 / 32 / 8 offsets of the unpack and applies the zero-point.  The weights
-// stream through a register ring that keeps D - 1 segments per wave in flight behind the one
-// being computed.  Few rows -> large KS (the whole matrix is in flight after one round trip);
-// many rows -> KS = 1 and every wave streams its own rows.
-//
-// Lanes are never masked in the hot loop: rows past N re-read row N - 1 and batch entries past B
-// re-read entry i % bp; both only feed outputs that are not stored.  A lane whose 16 bytes lie
-// past the end of the row re-reads the row's last 16 bytes; any bit pattern unpacks to finite
-// numbers, and those meet activations that were staged as zeros.
-constexpr int kXChunk = 65536;
-constexpr int kSumBytes = 2048;  // per-wave partial sums of x: [2][16 batch entries][16 waves] floats, in front of the staging area
-
+// CB = 512-k blocks of x per chunk.  LDS: [sums][area A][x], where area A starts with the 2 KB per
+// wave through which weight lines are transposed and also takes the reduction data once the main
+// loop is over.  single != 0: all of x is staged once per workgroup and stays (area A then is as
+// large as the reduction data); single == 0: x is restaged (in one or more chunks) for every group
+// of row blocks and the reduction data may run over it.
 template <int R, int RG, int D, bool EP>
-__global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int chunk_segs, int KS) {
-    extern __shared__ __attribute__((aligned(16))) float lds[];
+__global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, int KS, int ngroups, int x_off,
+                                                    int single_flag) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int NW = blockDim.x >> 6;
     const int RW = NW / KS;
     const int ks = wave % KS, rw = wave / KS;
     const int i = lane & 15, g = lane >> 4;
     constexpr int ROWS = 16 * RG;          // rows of one row block
-    const int nb = blockIdx.x * RW * ROWS; // first row of the workgroup
-    const int n0 = nb + rw * ROWS;         // first row of this wave
     constexpr int KPB = 8 / R;             // codes per byte
     constexpr int XV = R == 2 ? 8 : (R == 4 ? 4 : 2);  // 16-byte activation operands per lane and segment
     constexpr int SEGK = 64 * KPB;         // k values per segment
-    constexpr int UNITK = R == 2 ? 16 : 8; // k values one staging step handles
-    constexpr int UPS = SEGK / UNITK;      // staging steps per segment and batch entry
+    constexpr int SSPB = 512 / (2 * SEGK); // 128-byte weight lines (two segments) per 512-k block of x
 
-    float *sums = lds;  // [b * 16 + wave]: part of sum_k x[b, k]; [256 + b * 16 + wave]: part of sum_k x[b, k] * offset_k
-    u32x4 *xl = reinterpret_cast<u32x4 *>(reinterpret_cast<uint8_t *>(lds) + kSumBytes);
-    for (int t = threadIdx.x; t < 512; t += blockDim.x) sums[t] = 0.f;
+    float *sums = reinterpret_cast<float *>(lds);
+    uint8_t *area = lds + kSumBytes;
+    uint8_t *xbuf = area + x_off;
+    const int segs = (a.KB + 127) >> 7;  // 128-byte lines per row
+    const int chunk_segs = CB * SSPB;
+    const bool single = single_flag != 0;
+    const int bb = i & (bp - 1), b15 = bb & 15;
+    const uint8_t *xlane = xbuf + bb * 1024;
+    const uint32_t lane_slot = (uint32_t)((g * XV) ^ b15);
 
-    f32x4 acc[RG];
-    u32x4 w[D][RG];
-    const uint8_t *rp[RG];
-#pragma unroll
-    for (int rg = 0; rg < RG; ++rg) {
-        acc[rg] = f32x4{0.f, 0.f, 0.f, 0.f};
-        rp[rg] = a.packed + (size_t)min(n0 + rg * 16 + i, a.N - 1) * a.KB;
-#pragma unroll
-        for (int d = 0; d < D; ++d) w[d][rg] = u32x4{0u, 0u, 0u, 0u};
-    }
-    int off = ks * 64 + g * 16;  // byte offset, inside the packed row, of the next segment to request
-    // Unconditional (an offset past the row is clamped into it), so that the number of loads in
-    // flight is known at compile time and a use only waits for its own load.
-    const int off_last = a.KB - 16;
-    auto fetch_next = [&](u32x4 (&dst)[RG]) {
-        const int o = min(off, off_last);
-#pragma unroll
-        for (int rg = 0; rg < RG; ++rg)
-            dst[rg] = *reinterpret_cast<const u32x4 *>(rp[rg] + o);  // (plain loads: non-temporal ones measured slower here)
-        off += KS * 64;
-    };
-    const int segs = (a.KB + 63) >> 6;
-    const u32x4 *xlane = xl + g * bp + (i & (bp - 1));
-    const int step = KS * D;  // segments one turn of the ring covers (all KS waves of a row block)
+    // Weights are fetched as whole 128-byte lines: lane (li, lc) = (lane / 8, lane % 8) takes 16-byte
+    // piece lc of the line of row li (first load) and row li + 8 (second load) of a 16-row group, so
+    // that eight neighbouring lanes cover one line.  The matrix core wants lane (i, g) to hold piece
+    // 4 * sgm + g of row i for segment sgm of the line: the pieces change lanes through a 2 KB LDS
+    // tile per wave, [row][piece ^ (row / 2 % 8)], which both the writes and the reads hit without
+    // bank conflicts.  LDS operations of one wave execute in order, so the tile needs no barrier.
+    const int li = lane >> 3, lc = lane & 7;
+    uint8_t *tb = area + wave * 2048;
+    const uint32_t wslot0 = (uint32_t)(8 * li + (lc ^ ((li >> 1) & 7))) << 4;
+    const uint32_t wslot1 = (uint32_t)(8 * (li + 8) + (lc ^ (((li + 8) >> 1) & 7))) << 4;
+    const uint32_t rslot0 = (uint32_t)(8 * i + (g ^ ((i >> 1) & 7))) << 4;
+    const uint32_t rslot1 = (uint32_t)(8 * i + ((4 + g) ^ ((i >> 1) & 7))) << 4;
 
-    // The code below is kept small on purpose: a decode GEMV runs for a few microseconds, and
-    // instruction fetch of a cold kernel is a visible part of that.
-#pragma unroll
-    for (int d = 0; d + 1 < D; ++d) fetch_next(w[d]);
+    const uint64_t xbytes = (uint64_t)a.B * a.K * 2;
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(a.x), 0, (int)(xbytes > 0x7FFFFFFFull ? 0x7FFFFFFFull : xbytes), 0x00020000);
 
-    int s = ks;
-    for (int c0 = 0; c0 < segs; c0 += chunk_segs) {
-        const int c1 = min(c0 + chunk_segs, segs);
-        const int units_per_row = (c1 - c0) * UPS;
-        if (c0 > 0) __syncthreads();  // the previous chunk of x has been consumed
-        // ---- stage x[:, c0 * SEGK : c1 * SEGK) in operand order: (ls, v, g, b) ------------------
-        for (int t = threadIdx.x; t < units_per_row * a.B; t += blockDim.x) {
-            const int b = t / units_per_row, un = t % units_per_row;
-            const int k = c0 * SEGK + un * UNITK;
-            const int ls = un / UPS, in = un % UPS;
-            u32x4 x0 = {0u, 0u, 0u, 0u}, x1 = {0u, 0u, 0u, 0u};
-            if (k < a.K) {  // a partial last segment is completed with zeros
-                const uint16_t *src = a.x + (size_t)b * a.K + k;
-                x0 = *reinterpret_cast<const u32x4 *>(src);
-                if constexpr (R == 2) x1 = *reinterpret_cast<const u32x4 *>(src + 8);
-            }
-            if constexpr (R == 2) {
-                const int gg = in >> 2, ww = in & 3;  // k = seg * 256 + gg * 64 + ww * 16
-                // codes j and j + 8 of a dword share a register: pair the activations the same way
-                xl[((ls * XV + 2 * ww) * 4 + gg) * bp + b] =
-                    u32x4{pair_lo(x0.x, x1.x), pair_hi(x0.x, x1.x), pair_lo(x0.y, x1.y), pair_hi(x0.y, x1.y)};
-                xl[((ls * XV + 2 * ww + 1) * 4 + gg) * bp + b] =
-                    u32x4{pair_lo(x0.z, x1.z), pair_hi(x0.z, x1.z), pair_lo(x0.w, x1.w), pair_hi(x0.w, x1.w)};
-            } else {
-                const int gg = in / XV, vv = in % XV;  // k = seg * SEGK + gg * (SEGK / 4) + vv * 8
-                if constexpr (R == 4)  // codes j and j + 4 of a dword share a register
-                    x0 = u32x4{pair_lo(x0.x, x0.z), pair_hi(x0.x, x0.z), pair_lo(x0.y, x0.w), pair_hi(x0.y, x0.w)};
-                xl[((ls * XV + vv) * 4 + gg) * bp + b] = x0;
+    // chunk c of x -> LDS: block j = (kb, b) by wave j % NW
+    auto issue_x = [&](int c) {
+        for (int j = wave; j < CB * bp; j += NW) {
+            const int kb = j / bp, b = j % bp;
+            if (b < a.B) {
+                const int k = (c * CB + kb) * 512 + ((lane ^ (b & 15)) << 3);
+                const uint32_t vo = k < a.K ? ((uint32_t)b * (uint32_t)a.K + (uint32_t)k) * 2u : kOOB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(xbuf + j * 1024), 16, vo, 0, 0, 0);
             }
         }
-        __syncthreads();
-        // ---- this wave's share of sum_k x and sum_k x * offset_k of the chunk, in a fixed order ----
-        {
-            const int Q = (c1 - c0) * XV * 4, per = (Q + NW - 1) / NW;
-            const int qlo = wave * per, qhi = min(qlo + per, Q);
-            for (int b = 0; b < a.B; ++b) {
-                float s1 = 0.f, s2 = 0.f;
-                for (int q = qlo + lane; q < qhi; q += 64) {
-                    const u32x4 v = xl[q * bp + b];
-                    const bool odd = (q >> 2) & 1;  // operand index v within the segment
+    };
+    // LDS-local pass over the staged chunk: pair the activations like the codes, accumulate the sums
+    float s1 = 0.f, s2 = 0.f;
+    auto pair_pass = [&](bool with_sums) {
+        const int hw = wave * 2 + (lane >> 5), u = lane & 31;
+        for (int j = hw; j < CB * bp; j += 2 * NW) {
+            const int b = j % bp;
+            if (b >= a.B) continue;
+            uint8_t *blk = xbuf + j * 1024;
+            if constexpr (R == 2) {
+                u32x4 *p0 = reinterpret_cast<u32x4 *>(blk + (((2 * u) ^ (b & 15)) << 4));
+                u32x4 *p1 = reinterpret_cast<u32x4 *>(blk + (((2 * u + 1) ^ (b & 15)) << 4));
+                const u32x4 x0 = *p0, x1 = *p1;
+                // codes j and j + 8 of a dword share a register: pair the activations the same way
+                const u32x4 o0 = {pair_lo(x0.x, x1.x), pair_hi(x0.x, x1.x), pair_lo(x0.y, x1.y), pair_hi(x0.y, x1.y)};
+                const u32x4 o1 = {pair_lo(x0.z, x1.z), pair_hi(x0.z, x1.z), pair_lo(x0.w, x1.w), pair_hi(x0.w, x1.w)};
+                *p0 = o0;
+                *p1 = o1;
+                if (with_sums) {
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj) {
-                        const float e = __uint_as_float(v[jj] << 16) + __uint_as_float(v[jj] & 0xFFFF0000u);
-                        s1 += e;
-                        if constexpr (R == 2) {
-                            const int cls = ((odd ? 4 : 0) + jj) % 3;  // field position inside the 16-bit lane
-                            s2 += e * (cls == 0 ? 128.f : (cls == 1 ? 32.f : 8.f));
-                        }
+                        const float e0 = __uint_as_float(o0[jj] << 16) + __uint_as_float(o0[jj] & 0xFFFF0000u);
+                        const float e1 = __uint_as_float(o1[jj] << 16) + __uint_as_float(o1[jj] & 0xFFFF0000u);
+                        s1 += e0 + e1;
+                        // field position inside the 16-bit lane: 0, 1, 2, 0 then 1, 2, 0, 1
+                        s2 += e0 * (jj % 3 == 0 ? 128.f : (jj % 3 == 1 ? 32.f : 8.f));
+                        s2 += e1 * ((jj + 4) % 3 == 0 ? 128.f : ((jj + 4) % 3 == 1 ? 32.f : 8.f));
                     }
                 }
-                s1 = wave_sum(s1);
-                if constexpr (R == 2) s2 = wave_sum(s2);
-                if (lane == 0) {
-                    sums[b * 16 + wave] += s1;
-                    sums[256 + b * 16 + wave] += s2;
+            } else {
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    u32x4 *p = reinterpret_cast<u32x4 *>(blk + (((u + 32 * half) ^ (b & 15)) << 4));
+                    u32x4 x0 = *p;
+                    if constexpr (R == 4) {  // codes j and j + 4 of a dword share a register
+                        x0 = u32x4{pair_lo(x0.x, x0.z), pair_hi(x0.x, x0.z), pair_lo(x0.y, x0.w), pair_hi(x0.y, x0.w)};
+                        *p = x0;
+                    }
+                    if (with_sums) {
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj)
+                            s1 += __uint_as_float(x0[jj] << 16) + __uint_as_float(x0[jj] & 0xFFFF0000u);
+                    }
                 }
             }
         }
-        // ---- the wave's segments of this chunk --------------------------------------------------
-        // The load of the segment D - 1 ahead is unconditional (so that the number in flight stays
-        // known and a use waits for its own load only); the arithmetic of a segment past the end
-        // is skipped by a wave-uniform branch.  The ring is unrolled D times: moving registers
-        // whose loads are still in flight would force a wait for them.
-        for (; s < c1; s += step) {
-#pragma unroll
-            for (int d = 0; d < D; ++d) {
-                fetch_next(w[(d + D - 1) % D]);
-                if (s + d * KS < c1) gemv_segment<R, RG>(w[d], xlane + (s + d * KS - c0) * XV * 4 * bp, 4 * bp, acc);
-            }
-        }
-    }
-    __syncthreads();  // the staging area is reused by the reduction below
+    };
+    // sum over a half-wave, left in its lane 0 (lanes 0 and 32 of the wave)
+    auto half_wave_sum = [&](float v) {
+        auto dpp_add = [](float x, auto ctrl) {
+            const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, 0xF, 0xF, true);
+            return x + __int_as_float(moved);
+        };
+        v = dpp_add(v, std::integral_constant<int, 0xB1>{});
+        v = dpp_add(v, std::integral_constant<int, 0x4E>{});
+        v = dpp_add(v, std::integral_constant<int, 0x141>{});
+        v = dpp_add(v, std::integral_constant<int, 0x140>{});
+        const int bits = __float_as_int(v);
+        const float lo = __int_as_float(__builtin_amdgcn_readlane(bits, 0)) + __int_as_float(__builtin_amdgcn_readlane(bits, 16));
+        const float hi = __int_as_float(__builtin_amdgcn_readlane(bits, 32)) + __int_as_float(__builtin_amdgcn_readlane(bits, 48));
+        return lane < 32 ? lo : hi;
+    };
 
-    // ---- reduction over the KS waves of a row block, in LDS ------------------------------------
-    // part[wave][rg][lane] (float4), then ovf[row][b]; the sum is left in part[rw * KS][..]
-    f32x4 *part = reinterpret_cast<f32x4 *>(xl);
-    float *ovf = reinterpret_cast<float *>(part + NW * RG * 64);
-#pragma unroll
-    for (int rg = 0; rg < RG; ++rg) part[(wave * RG + rg) * 64 + lane] = acc[rg];
-
-    // ---- extra precision: sum of x over each row's overflow columns ---------------------------
-    if constexpr (EP) {
-        for (int r = wave; r < RW * ROWS; r += NW) {
-            const int row = nb + r;
-            float sx[16];
-#pragma unroll
-            for (int b = 0; b < 16; ++b) sx[b] = 0.f;
-            if (row < a.N) {
-                const int lo = a.row_ptr[row], hi = a.row_ptr[row + 1];
-                for (int p = lo + lane; p < hi; p += 64) {
-                    const int col = a.col_idx[p];
-#pragma unroll
-                    for (int b = 0; b < 16; ++b)
-                        if (b < a.B) sx[b] += bf16_bits_to_float(a.x[(size_t)b * a.K + col]);
-                }
+    auto stage = [&](int c, bool with_sums) {
+        issue_x(c);
+        wait_all_loads();
+        __syncthreads();
+        pair_pass(with_sums);
+        if (with_sums) {  // running totals; complete after the last chunk's pass
+            const float t1 = half_wave_sum(s1), t2 = R == 2 ? half_wave_sum(s2) : 0.f;
+            if ((lane & 31) == 0) {
+                sums[wave * 2 + (lane >> 5)] = t1;
+                sums[32 + wave * 2 + (lane >> 5)] = t2;
             }
-#pragma unroll
-            for (int b = 0; b < 16; ++b) {
-                if (b < a.B) {
-#pragma unroll
-                    for (int o = 32; o > 0; o >>= 1) sx[b] += __shfl_xor(sx[b], o, 64);
-                }
-                if (lane == 0) ovf[r * 16 + b] = sx[b];
-            }
-        }
-    }
-    __syncthreads();
-    if (KS > 1) {
-        for (int t = threadIdx.x; t < RW * RG * 64; t += blockDim.x) {
-            const int q = t / (RG * 64), e = t % (RG * 64);
-            f32x4 *base = part + (size_t)q * KS * RG * 64 + e;
-            f32x4 sum = base[0];
-            for (int kk = 1; kk < KS; ++kk) {
-                const f32x4 pv = base[kk * RG * 64];
-                sum.x += pv.x;
-                sum.y += pv.y;
-                sum.z += pv.z;
-                sum.w += pv.w;
-            }
-            base[0] = sum;
         }
         __syncthreads();
-    }
-
-    // ---- epilogue: y[b, n] = alpha_n * (2^s * (codes.x [+ overflow]) - z_n * sum_k x) -----------
-    // matrix-core output layout: lane = column b + 16 * (row / 4), component = row % 4
-    constexpr float kScale = (float)(1 << (8 - R));
-    for (int t = threadIdx.x; t < RW * ROWS * 16; t += blockDim.x) {
-        const int b = t / (RW * ROWS), r = t % (RW * ROWS), row = nb + r;
-        if (b >= a.B || row >= a.N) continue;
-        const int q = r / ROWS, er = r % ROWS, rg = er >> 4, ri = er & 15;
-        const float *tot = reinterpret_cast<const float *>(part + (size_t)q * KS * RG * 64);
-        float dot = tot[(rg * 64 + b + 16 * (ri >> 2)) * 4 + (ri & 3)];
-        float xsum = 0.f, xoff = 0.f;
-        for (int wv = 0; wv < NW; ++wv) {
-            xsum += sums[b * 16 + wv];
-            xoff += sums[256 + b * 16 + wv];
+    };
+    const UnpackConsts uc = unpack_consts<R>();
+    bool first = true;
+    for (int grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
+        const int nb = grp * RW * ROWS;  // first row of the group
+        const int n0 = nb + rw * ROWS;   // first row of this wave
+        f32x4 acc[RG];
+        u32x4 w[D][2][RG];  // [ring slot][first / second load][row group]
+        const int n0c = min(n0, a.N - 1);
+        const uint8_t *wbase = a.packed + (size_t)n0c * a.KB;  // wave-uniform
+        uint32_t roff[RG][2];
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) {
+            acc[rg] = f32x4{0.f, 0.f, 0.f, 0.f};
+            roff[rg][0] = (uint32_t)(min(n0 + rg * 16 + li, a.N - 1) - n0c) * (uint32_t)a.KB;
+            roff[rg][1] = (uint32_t)(min(n0 + rg * 16 + li + 8, a.N - 1) - n0c) * (uint32_t)a.KB;
+#pragma unroll
+            for (int d = 0; d < D; ++d) w[d][0][rg] = w[d][1][rg] = u32x4{0u, 0u, 0u, 0u};
         }
-        if constexpr (R == 2) dot -= xoff;
-        if constexpr (R == 4) dot -= 128.0f * xsum;
-        if constexpr (EP) dot += ovf[r * 16 + b];
-        const float al = bf16_bits_to_float(a.alpha[row]), z = bf16_bits_to_float(a.zero[row]);
-        const float yv = al * (kScale * dot - z * xsum);
-        a.y[(size_t)b * a.N + row] = (uint16_t)float_to_bf16_bits(yv);
+        // alpha and z of the rows this lane will write: requested now and used after the main loop,
+        // except for int2, whose unpack leaves no registers to hold them that long
+        constexpr bool kEarlyParams = R != 2;
+        float pal[RG][4], pze[RG][4];
+        auto load_params = [&]() {
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    const int row = min(n0 + rg * 16 + 4 * g + cc, a.N - 1);
+                    pal[rg][cc] = bf16_bits_to_float(a.alpha[row]);
+                    pze[rg][cc] = bf16_bits_to_float(a.zero[row]);
+                }
+        };
+        if constexpr (kEarlyParams) load_params();
+        int off = ks * 128 + lc * 16;  // byte offset, inside the packed row, of the next piece to request
+        // Unconditional (an offset past the row is clamped into it), so that the number of loads in
+        // flight is known at compile time and a use only waits for its own load.
+        const int off_last = a.KB - 16;
+        auto fetch_next = [&](u32x4 (&dst)[2][RG]) {
+            const uint32_t o = (uint32_t)min(off, off_last);
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) {
+                dst[0][rg] = *reinterpret_cast<const u32x4 *>(wbase + (roff[rg][0] + o));
+                dst[1][rg] = *reinterpret_cast<const u32x4 *>(wbase + (roff[rg][1] + o));
+            }
+            off += KS * 128;
+        };
+        // one 128-byte line of each of the wave's 16 RG rows: transpose through LDS, then two segments
+        auto compute_line = [&](const u32x4 (&raw)[2][RG], int sr) {
+            u32x4 wt0[RG], wt1[RG];
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) {
+                *reinterpret_cast<u32x4 *>(tb + wslot0) = raw[0][rg];
+                *reinterpret_cast<u32x4 *>(tb + wslot1) = raw[1][rg];
+                wt0[rg] = *reinterpret_cast<const u32x4 *>(tb + rslot0);
+                wt1[rg] = *reinterpret_cast<const u32x4 *>(tb + rslot1);
+            }
+            const uint8_t *blk = xlane + (sr / SSPB) * bp * 1024;
+            const uint32_t sb = (uint32_t)(sr % SSPB) * 2u;  // first segment of the line inside the x block
+            gemv_segment<R, RG>(wt0, blk, ((sb * 4 * XV) ^ lane_slot) << 4, uc, acc);
+            __builtin_amdgcn_sched_barrier(0);  // keeps the operand reads of the second segment out of the first
+            gemv_segment<R, RG>(wt1, blk, (((sb + 1) * 4 * XV) ^ lane_slot) << 4, uc, acc);
+        };
+        const int step = KS * D;  // lines one turn of the ring covers (all KS waves of a row block)
+#pragma unroll
+        for (int d = 0; d + 1 < D; ++d) fetch_next(w[d]);
+
+        int s = ks;
+        for (int c0 = 0, c = 0; c0 < segs; c0 += chunk_segs, ++c) {
+            const int c1 = min(c0 + chunk_segs, segs);
+            if (first || !single) {
+                if (c > 0 || !first) __syncthreads();  // the x area (or the reduction data over it) has been consumed
+                stage(c, first);
+            }
+            // The load of the line D - 1 ahead is unconditional; the arithmetic of a line past the
+            // end is skipped by a wave-uniform branch.  The ring is unrolled D times: moving
+            // registers whose loads are still in flight would force a wait for them.
+            for (; s < c1; s += step) {
+#pragma unroll
+                for (int d = 0; d < D; ++d) {
+                    fetch_next(w[(d + D - 1) % D]);
+                    if (s + d * KS < c1) compute_line(w[d], s + d * KS - c0);
+                }
+            }
+        }
+        first = false;
+
+        // ---- after the main loop ------------------------------------------------------------------
+        // Wave ks == 0 of a row block ends up with the sums of its rows in the matrix-core output
+        // layout (lane = batch entry b + 16 * (row / 4), component = row % 4) and writes them out
+        // itself.  With KS == 1 and no overflow list nothing is shared between waves here, so they
+        // run on without a barrier; otherwise partial sums and overflow sums meet in LDS.
+        f32x4 *part = reinterpret_cast<f32x4 *>(area);                    // [wave][rg][lane], over the tiles
+        float *ovf = reinterpret_cast<float *>(area + NW * 2048);         // [row of the group][b]
+        const bool shared = EP || KS > 1;
+        if (KS > 1) {
+            __syncthreads();  // every wave is done with its transposition tile
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) part[(wave * RG + rg) * 64 + lane] = acc[rg];
+        }
+        // extra precision: sum of x over each row's overflow columns, rows dealt out to all waves
+        if constexpr (EP) {
+            for (int r = wave; r < RW * ROWS; r += NW) {
+                const int row = nb + r;
+                float sx[16];
+#pragma unroll
+                for (int b = 0; b < 16; ++b) sx[b] = 0.f;
+                if (row < a.N) {
+                    const int lo = a.row_ptr[row], hi = a.row_ptr[row + 1];
+                    for (int p = lo + lane; p < hi; p += 64) {
+                        const int col = a.col_idx[p];
+#pragma unroll
+                        for (int b = 0; b < 16; ++b)
+                            if (b < a.B) sx[b] += bf16_bits_to_float(a.x[(size_t)b * a.K + col]);
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < 16; ++b) {
+                    if (b < a.B) sx[b] = wave_sum(sx[b]);
+                    if (lane == 0) ovf[r * 16 + b] = sx[b];
+                }
+            }
+        }
+        if (shared) __syncthreads();
+        if (ks == 0) {
+            if constexpr (!kEarlyParams) load_params();
+            if (KS > 1) {
+#pragma unroll
+                for (int rg = 0; rg < RG; ++rg)
+                    for (int kk = 1; kk < KS; ++kk) {
+                        const f32x4 pv = part[((wave + kk) * RG + rg) * 64 + lane];
+                        acc[rg].x += pv.x;
+                        acc[rg].y += pv.y;
+                        acc[rg].z += pv.z;
+                        acc[rg].w += pv.w;
+                    }
+            }
+            // y[b, n] = alpha_n * (2^s * (codes.x [+ overflow]) - z_n * sum_k x)
+            constexpr float kScale = (float)(1 << (8 - R));
+            const int b = lane & 15;
+            if (b < a.B) {
+                float xsum = 0.f, xoff = 0.f;
+                for (int hw = b; hw < 2 * NW; hw += bp) {  // the half-waves that staged batch entry b
+                    xsum += sums[hw];
+                    xoff += sums[32 + hw];
+                }
+#pragma unroll
+                for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) {
+                        const int rl = rg * 16 + 4 * g + cc, row = n0 + rl;
+                        if (row < a.N) {
+                            float dot = acc[rg][cc];
+                            if constexpr (R == 2) dot -= xoff;
+                            if constexpr (R == 4) dot -= 128.0f * xsum;
+                            if constexpr (EP) dot += ovf[(rw * ROWS + rl) * 16 + b];
+                            const float yv = pal[rg][cc] * (kScale * dot - pze[rg][cc] * xsum);
+                            a.y[(size_t)b * a.N + row] = (uint16_t)float_to_bf16_bits(yv);
+                        }
+                    }
+            }
+        }
+        // the next group's tiles, overflow sums or (restaged) x area start behind a barrier
+        if (shared && single && grp + (int)gridDim.x < ngroups) __syncthreads();
     }
 }
 
@@ -335,32 +479,46 @@ template <int R, int RG, int D>
 static mq_status launch_gemv(const GemvArgs &a, int nw, int ks, hipStream_t st) {
     int bp = 1;
     while (bp < a.B) bp <<= 1;
-    const int segk = 64 * (8 / R), segs = (a.KB + 63) / 64;
-    const int seg_bytes = segk * 2 * bp;  // staged activations of one segment
-    // Segments of x per staging chunk.  Everything at once when it fits 128 KB; otherwise chunks of
-    // about kXChunk bytes that are a multiple of KS * D segments, so that the register ring of
-    // every wave is in the same phase at each chunk boundary.
-    // Segments of x per staging chunk.  Everything at once when it fits 128 KB; otherwise chunks of
-    // about kXChunk bytes that are a multiple of KS * D segments, so that the register ring of
-    // every wave is in the same phase at each chunk boundary.
-    int chunk_segs = segs;
-    if ((size_t)segs * seg_bytes > 131072) {
-        while (ks > 1 && ks * D * seg_bytes > 131072) ks >>= 1;
+    constexpr int SSPB = 512 / (2 * 64 * (8 / R));  // 128-byte weight lines per 512-k block of x
+    const int lines = (a.KB + 127) / 128;
+    const int blocks_all = (lines + SSPB - 1) / SSPB;  // 512-k blocks that cover K
+    // area A: the 2 KB transposition tiles of the waves (reused for the K-split partial sums, which
+    // need RG <= 2 KB per wave), then the overflow sums of the group's rows
+    static_assert(RG <= 2, "partial sums are laid over the transposition tiles");
+    auto area_bytes = [&](int nw_, int ks_) { return (size_t)nw_ * 2048 + (size_t)(nw_ / ks_) * 16 * RG * 16 * 4; };
+    constexpr size_t kLdsMax = 160 * 1024 - kSumBytes;
+    // all of x at once when it fits behind the reduction data; otherwise chunks that are a multiple of
+    // KS * D lines, so that the register ring of every wave is in the same phase at each chunk
+    // boundary, restaged for every group of row blocks, with the reduction data laid over them
+    int CB = blocks_all, single = 1;
+    size_t x_off = area_bytes(nw, ks);
+    size_t lds = kSumBytes + x_off + (size_t)blocks_all * bp * 1024;
+    if (lds > kLdsMax + kSumBytes) {
+        single = 0;
+        const int cap_blocks = (int)std::min<size_t>(131072, kLdsMax - area_bytes(nw, 1)) / (bp * 1024);
+        while (ks > 1 && ks * D > cap_blocks * SSPB) ks >>= 1;
         const int step = ks * D;
-        chunk_segs = kXChunk / seg_bytes / step * step;
-        if (chunk_segs < step) chunk_segs = step;
+        CB = cap_blocks * SSPB / step * step / SSPB;
+        if (CB < 1) return MQ_ERR_SHAPE;  // (cannot happen: D <= 4, cap_blocks >= 5)
+        x_off = area_bytes(nw, ks);
+        lds = kSumBytes + x_off + (size_t)CB * bp * 1024;
     }
-    if (nw < ks) nw = ks;
     const int rw = nw / ks;
-    const int blocks = (int)cdiv(a.N, 16 * RG * rw);
-    const size_t xbytes = (size_t)chunk_segs * seg_bytes;
-    const size_t red = (size_t)nw * RG * 64 * 16 + (size_t)rw * 16 * RG * 16 * 4;
-    const size_t lds = kSumBytes + (xbytes > red ? xbytes : red);
+    const int ngroups = (int)cdiv(a.N, 16 * RG * rw);
+    // resident workgroups: 16 waves and 160 KB of LDS per compute unit, 256 compute units
+    int wpc = 16;
+#ifdef MQ_GEMV_TUNE
+    if (const char *e = getenv("MQ_GEMV_WPC")) wpc = atoi(e);
+#endif
+    const int per_cu = std::max(1, std::min(wpc / nw, (int)((160 * 1024) / lds)));
+    const int capacity = 256 * per_cu;
+    const int rounds = (ngroups + capacity - 1) / capacity;
+    const int grid = (ngroups + rounds - 1) / rounds;
     auto go = [&](auto kern) -> mq_status {
         if (lds > 65536 && hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return MQ_ERR_DEVICE;
-        kern<<<dim3(blocks), dim3(64 * nw), lds, st>>>(a, bp, chunk_segs, ks);
+        kern<<<dim3(grid), dim3(64 * nw), lds, st>>>(a, bp, CB, ks, ngroups, (int)x_off, single);
         return launch_status();
     };
     return a.row_ptr ? go(gemv_kernel<R, RG, D, true>) : go(gemv_kernel<R, RG, D, false>);
@@ -375,6 +533,7 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
     if (r != 8 && r != 4 && r != 2) return MQ_ERR_BITS;
     if (B < 1 || B > 16 || N < 0 || K < 1 || N > 0x7FFFFFF0 || K > 0x7FFFFFF0) return MQ_ERR_SHAPE;
     if (ovf && K > 65536) return MQ_ERR_SHAPE;
+    if (B * K > (1ll << 29)) return MQ_ERR_SHAPE;  // 32-bit byte offsets into x
     const int64_t kb = K * r / 8;
     if ((K * r) % 128 != 0) return MQ_ERR_ALIGN;  // packed rows are whole 16-byte units
     if (N == 0) return MQ_OK;
@@ -395,23 +554,29 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
     a.K = (int)K;
     a.KB = (int)kb;
 
-    // Rows per workgroup (16 RG): each activation value is fetched once per workgroup, so a larger
-    // batch wants more rows behind every fetch; small batches keep RG = 1 for more workgroups.
-    const int rg = B <= 2 ? 1 : (B <= 8 ? 2 : 4);
-    // K-split: enough waves in total (about 16 per compute unit) when there are few row blocks,
+    // Rows per wave (16 RG): every activation operand read from LDS serves RG matrix-core products, so
+    // larger batches take two row groups; batches of one or two keep RG = 1 for more waves.
+    const int rg = B <= 2 ? 1 : 2;
+    // K-split: about 2048 waves in total (8 per compute unit measured best across the decode shapes:
+    // enough loads in flight, and the whole grid resident at once) when there are few row blocks,
     // none when the rows alone provide them.  Workgroups have 8 waves (KS of them per row block),
     // or KS when that is larger.
-    const int64_t segs = cdiv(kb, 64);
+    const int64_t segs = cdiv(kb, 128);  // 128-byte lines per row
     const int64_t row_blocks = cdiv(N, 16 * rg);
     int ks = 1;
-    while (ks < 16 && row_blocks * ks < 4096 && 2 * ks <= segs) ks <<= 1;
-    const int nw = ks > 8 ? ks : 8;
+    while (ks < 16 && row_blocks * ks * 2 <= 2560 && 2 * ks <= segs) ks <<= 1;
+    int nw = ks > 8 ? ks : 8;
+#ifdef MQ_GEMV_TUNE
+    if (const char *e = getenv("MQ_GEMV_KS")) ks = atoi(e);
+    if (const char *e = getenv("MQ_GEMV_NW")) nw = atoi(e);
+    if (nw < ks) nw = ks;
+#endif
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 #define MQ_GEMV_CASE(R_, RG_, D_) \
     if (r == R_ && rg == RG_) return launch_gemv<R_, RG_, D_>(a, nw, ks, st);
-    MQ_GEMV_CASE(2, 1, 4) MQ_GEMV_CASE(2, 2, 3) MQ_GEMV_CASE(2, 4, 2)
-    MQ_GEMV_CASE(4, 1, 4) MQ_GEMV_CASE(4, 2, 3) MQ_GEMV_CASE(4, 4, 2)
-    MQ_GEMV_CASE(8, 1, 4) MQ_GEMV_CASE(8, 2, 3) MQ_GEMV_CASE(8, 4, 2)
+    MQ_GEMV_CASE(2, 1, 3) MQ_GEMV_CASE(2, 2, 2)
+    MQ_GEMV_CASE(4, 1, 4) MQ_GEMV_CASE(4, 2, 2)
+    MQ_GEMV_CASE(8, 1, 4) MQ_GEMV_CASE(8, 2, 2)
 #undef MQ_GEMV_CASE
     return MQ_ERR_BITS;
 }
