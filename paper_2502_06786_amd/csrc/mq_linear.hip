@@ -18,6 +18,7 @@
 // Backward (identity STE): dX reuses the same in-register slicing on a transposed copy of the
 // codes, with one pre-scaled gradient operand per bit-width accumulated into a single accumulator;
 // dW is a plain bf16 GEMM of the lambda-weighted gradient sum against X.
+#include <algorithm>
 #include <type_traits>
 
 #include "mq_common.h"
@@ -428,93 +429,127 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict_
 }
 
 // ============================================================================================
-// backward: helpers that prepare the operands
+// backward, preparation (HBM-bound): one pass over the nr gradient tensors produces
+//   As_i[m, n] = bf16(lambda_i * alpha_n * 2^s_i * dY_i[m, n])     (operand of the dX contraction)
+//   c[m]       = sum_i sum_n As_i[m, n] * (bias_i + z_n / 2^s_i)   (what the 128 + code form and z add to dX[m, :])
+//   GT[n, m]   = bf16(sum_i lambda_i * dY_i[m, n])                  (transposed operand of the dW GEMM)
 // ============================================================================================
-struct BwdPrepArgs {
+struct PrepArgs {
     const uint16_t *dY[3];
-    uint16_t *As[3];  // lambda_i * alpha_n * 2^s_i * dY_i, bf16 [M, N]
+    uint16_t *As[3];     // null pointers when dX is not wanted
     const float *alpha, *zero;
-    float *cvec;      // [M]
     float lam[3];
-    float mult[3];    // 2^s_i (1 for the r = 8 slot)
-    float bias[3];    // 128 for sliced slots, 0 for the r = 8 slot
+    float mult[3];       // 2^s_i
+    float bias[3];       // 128 for sliced slots, 0 for the r = 8 slot
+    float *cpart;        // [nsplit][M] partial sums of c over column ranges, or null
+    uint16_t *GT;        // [N, M] or null
     int nr, M, N;
+    int cols_per_split;  // multiple of 64
 };
 
-// One workgroup per token row: scale the gradients by lambda_i * alpha_n * 2^s_i (rounded to bf16,
-// the operand the matrix core will see) and reduce c[m] = sum_i sum_n As_i[m,n] * (bias_i + z_n / 2^s_i),
-// the constant that the 128 + code representation and the zero-point contribute to dX[m, :].
-__global__ __launch_bounds__(256) void bwd_scale_kernel(BwdPrepArgs a) {
-    __shared__ float red[4];
-    const int m = blockIdx.x;
+constexpr int PREP_ROWS = 32;
+constexpr int PREP_MAX_SPLIT = 16;
+
+// Workgroup (strip, split) walks 32 token rows across one range of columns in 32 x 64 tiles: thread
+// (r, ch) = (t / 8, t % 8) owns eight consecutive columns of row r, so a row segment is one 128-byte
+// line per gradient tensor.  The summed gradient tile is turned through LDS and leaves as 64-byte
+// row segments of GT.
+__global__ __launch_bounds__(256) void bwd_prep_kernel(PrepArgs a) {
+    __shared__ uint16_t tile[64][PREP_ROWS + 2];
+    const int t = threadIdx.x, r = t >> 3, ch = t & 7;
+    const int m0 = blockIdx.x * PREP_ROWS, m = m0 + r;
+    const int nbeg = blockIdx.y * a.cols_per_split, nend = min(nbeg + a.cols_per_split, a.N);
+    const bool want_as = a.As[0] != nullptr;
     float c = 0.f;
-    for (int ch = threadIdx.x; ch < a.N / 8; ch += 256) {
-        const int n = ch * 8;
-        float al[8], ze[8];
-        *reinterpret_cast<f32x4 *>(al) = *reinterpret_cast<const f32x4 *>(a.alpha + n);
-        *reinterpret_cast<f32x4 *>(al + 4) = *reinterpret_cast<const f32x4 *>(a.alpha + n + 4);
-        *reinterpret_cast<f32x4 *>(ze) = *reinterpret_cast<const f32x4 *>(a.zero + n);
-        *reinterpret_cast<f32x4 *>(ze + 4) = *reinterpret_cast<const f32x4 *>(a.zero + n + 4);
-        for (int i = 0; i < a.nr; ++i) {
-            const u32x4 g = *reinterpret_cast<const u32x4 *>(a.dY[i] + (size_t)m * a.N + n);
-            const float f = a.lam[i] * a.mult[i], inv = 1.0f / a.mult[i];
-            u32x4 o;
+    for (int n0 = nbeg; n0 < nend; n0 += 64) {
+        const int n = n0 + ch * 8;
+        float g[8];
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float lo = bf16_bits_to_float(g[w] & 0xFFFFu) * (f * al[2 * w]);
-                const float hi = bf16_bits_to_float(g[w] >> 16) * (f * al[2 * w + 1]);
-                o[w] = pack_bf16x2(lo, hi);
-                c += bf16_bits_to_float(o[w] & 0xFFFFu) * (a.bias[i] + ze[2 * w] * inv);
-                c += bf16_bits_to_float(o[w] >> 16) * (a.bias[i] + ze[2 * w + 1] * inv);
+        for (int j = 0; j < 8; ++j) g[j] = 0.f;
+        if (m < a.M && n < a.N) {
+            float al[8], ze[8];
+            if (want_as) {
+                *reinterpret_cast<f32x4 *>(al) = *reinterpret_cast<const f32x4 *>(a.alpha + n);
+                *reinterpret_cast<f32x4 *>(al + 4) = *reinterpret_cast<const f32x4 *>(a.alpha + n + 4);
+                *reinterpret_cast<f32x4 *>(ze) = *reinterpret_cast<const f32x4 *>(a.zero + n);
+                *reinterpret_cast<f32x4 *>(ze + 4) = *reinterpret_cast<const f32x4 *>(a.zero + n + 4);
             }
-            *reinterpret_cast<u32x4 *>(a.As[i] + (size_t)m * a.N + n) = o;
+            u32x4 dy[3];
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+                if (i < a.nr) dy[i] = *reinterpret_cast<const u32x4 *>(a.dY[i] + (size_t)m * a.N + n);
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                if (i >= a.nr) break;
+                const float f = a.lam[i] * a.mult[i], inv = 1.0f / a.mult[i];
+                u32x4 o;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float dlo = bf16_bits_to_float(dy[i][w] & 0xFFFFu), dhi = bf16_bits_to_float(dy[i][w] >> 16);
+                    g[2 * w] += a.lam[i] * dlo;
+                    g[2 * w + 1] += a.lam[i] * dhi;
+                    if (want_as) {
+                        o[w] = pack_bf16x2(dlo * (f * al[2 * w]), dhi * (f * al[2 * w + 1]));
+                        c += bf16_bits_to_float(o[w] & 0xFFFFu) * (a.bias[i] + ze[2 * w] * inv);
+                        c += bf16_bits_to_float(o[w] >> 16) * (a.bias[i] + ze[2 * w + 1] * inv);
+                    }
+                }
+                if (want_as) *reinterpret_cast<u32x4 *>(a.As[i] + (size_t)m * a.N + n) = o;
+            }
+        }
+        if (a.GT) {
+            __syncthreads();  // the previous tile has been written out
+#pragma unroll
+            for (int j = 0; j < 8; ++j) tile[ch * 8 + j][r] = (uint16_t)float_to_bf16_bits(g[j]);
+            __syncthreads();
+            const int nn = t >> 2, part = t & 3;  // 64 rows of GT, four 16-byte pieces each
+            if (n0 + nn < a.N && m0 + part * 8 < a.M) {
+                const uint32_t *src = reinterpret_cast<const uint32_t *>(&tile[nn][part * 8]);
+                *reinterpret_cast<u32x4 *>(a.GT + (size_t)(n0 + nn) * a.M + m0 + part * 8) =
+                    u32x4{src[0], src[1], src[2], src[3]};
+            }
         }
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = c;
-    __syncthreads();
-    if (threadIdx.x == 0) a.cvec[m] = red[0] + red[1] + red[2] + red[3];
-}
-
-struct GtArgs {
-    const uint16_t *dY[3];
-    float lam[3];
-    uint16_t *GT;  // [N, M] bf16
-    int nr, M, N;
-};
-
-// GT[n, m] = bf16(sum_i lambda_i dY_i[m, n]) through a 64 x 64 LDS tile.
-__global__ __launch_bounds__(256) void bwd_gt_kernel(GtArgs a) {
-    __shared__ float tile[64][65];
-    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int rr = ty; rr < 64; rr += 4) {
-        const int m = m0 + rr, n = n0 + tx;
-        float s = 0.f;
-        if (m < a.M && n < a.N)
-            for (int i = 0; i < a.nr; ++i) s += a.lam[i] * bf16_bits_to_float(a.dY[i][(size_t)m * a.N + n]);
-        tile[rr][tx] = s;
-    }
-    __syncthreads();
-    for (int rr = ty; rr < 64; rr += 4) {
-        const int n = n0 + rr, m = m0 + tx;
-        if (n < a.N && m < a.M) a.GT[(size_t)n * a.M + m] = (uint16_t)float_to_bf16_bits(tile[tx][rr]);
+    if (a.cpart) {
+        c += __shfl_xor(c, 1, 64);
+        c += __shfl_xor(c, 2, 64);
+        c += __shfl_xor(c, 4, 64);
+        if (ch == 0 && m < a.M) a.cpart[(size_t)blockIdx.y * a.M + m] = c;
     }
 }
 
-// out[c, r] = in[r, c] for a [rows, cols] matrix of T
+// out[c, r] = in[r, c] for a [rows, cols] matrix of 1- or 2-byte elements; rows and cols are
+// multiples of 16 bytes' worth of elements.  64 x (64 bytes) tiles, 16-byte global accesses on both
+// sides, the turn happens in LDS.
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in, T *__restrict__ out, int rows,
                                                         int cols) {
-    __shared__ T tile[64][64 + 4 / sizeof(T)];
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int rr = ty; rr < 64; rr += 4)
-        if (r0 + rr < rows && c0 + tx < cols) tile[rr][tx] = in[(size_t)(r0 + rr) * cols + c0 + tx];
+    constexpr int E = 16 / sizeof(T);  // elements per 16 bytes
+    constexpr int TC = 4 * E;          // tile columns (64 bytes)
+    constexpr int S = 64 + 4 / sizeof(T);  // padded row of the turned tile (a multiple of 4 bytes)
+    __shared__ T tile[TC][S];
+    const int t = threadIdx.x;
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * TC;
+    {
+        const int r = t >> 2, chunk = t & 3;
+        if (r0 + r < rows && c0 + chunk * E < cols) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(in + (size_t)(r0 + r) * cols + c0 + chunk * E);
+            T e[E];
+            __builtin_memcpy(e, &v, 16);
+#pragma unroll
+            for (int j = 0; j < E; ++j) tile[chunk * E + j][r] = e[j];
+        }
+    }
     __syncthreads();
-    for (int rr = ty; rr < 64; rr += 4)
-        if (c0 + rr < cols && r0 + tx < rows) out[(size_t)(c0 + rr) * rows + r0 + tx] = tile[tx][rr];
+    {
+        constexpr int PIECES = 64 / E;  // 16-byte pieces per row of the turned tile
+        const int c = t / PIECES, piece = t % PIECES;
+        if (c < TC && c0 + c < cols && r0 + piece * E < rows) {
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(&tile[c][piece * E]);
+            *reinterpret_cast<u32x4 *>(out + (size_t)(c0 + c) * rows + r0 + piece * E) =
+                u32x4{src[0], src[1], src[2], src[3]};
+        }
+    }
 }
 
 // ============================================================================================
@@ -525,7 +560,8 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in
 struct DxArgs {
     const uint16_t *As[3];  // [M, N] bf16, slot order (the r = 8 slot first when HAS8)
     const uint8_t *QT;      // [K, N] u8
-    const float *cvec;      // [M]
+    const float *cvec;      // [nsplit][M]: partial sums of c[m] over column ranges
+    int nsplit;
     uint16_t *dX;           // [M, K] bf16
     int M, N, K;
     int r[3];               // bit-width per slot
@@ -769,7 +805,9 @@ __global__ __launch_bounds__(256) void dx_kernel(DxArgs a) {
 #pragma unroll
     for (int j = 0; j < MB; ++j) {
         const int m = m0 + j * 32 + l32;
-        const float c = m < a.M ? a.cvec[m] : 0.f;
+        float c = 0.f;
+        if (m < a.M)
+            for (int sp = 0; sp < a.nsplit; ++sp) c += a.cvec[(size_t)sp * a.M + m];
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -923,7 +961,7 @@ static BwdWorkspace bwd_layout(int64_t M, int64_t N, int64_t K, int nr) {
     BwdWorkspace w;
     size_t o = 0;
     w.cvec = o;
-    o += align256((size_t)M * 4);
+    o += align256((size_t)PREP_MAX_SPLIT * M * 4);
     for (int i = 0; i < 3; ++i) {
         w.as[i] = o;
         if (i < nr) o += align256((size_t)M * N * 2);
@@ -1084,24 +1122,31 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
     uint8_t *base = static_cast<uint8_t *>(ws);
     const bool ep = flags & MQ_FLAG_EXTRA_PRECISION;
 
-    if (dX) {
-        BwdPrepArgs p;
-        for (int i = 0; i < 3; ++i) {
-            const int j = i < nr ? i : 0;
-            p.dY[i] = dY[j];
-            p.As[i] = reinterpret_cast<uint16_t *>(base + lay.as[j]);
-            p.lam[i] = lambda ? lambda[j] : 1.0f;
-            p.mult[i] = rs[j] == 8 ? 1.0f : (float)(1 << (8 - rs[j]));
-            p.bias[i] = rs[j] == 8 ? 0.0f : 128.0f;
-        }
-        p.alpha = alpha;
-        p.zero = zero;
-        p.cvec = reinterpret_cast<float *>(base + lay.cvec);
-        p.nr = nr;
-        p.M = (int)M;
-        p.N = (int)N;
-        bwd_scale_kernel<<<dim3((unsigned)M), dim3(256), 0, st>>>(p);
+    // one pass over the gradients: scaled operands + c for dX, transposed sum for dW
+    PrepArgs p;
+    for (int i = 0; i < 3; ++i) {
+        const int j = i < nr ? i : 0;
+        p.dY[i] = dY[j];
+        p.As[i] = dX ? reinterpret_cast<uint16_t *>(base + lay.as[j]) : nullptr;
+        p.lam[i] = lambda ? lambda[j] : 1.0f;
+        p.mult[i] = rs[j] == 8 ? 1.0f : (float)(1 << (8 - rs[j]));
+        p.bias[i] = rs[j] == 8 ? 0.0f : 128.0f;
+    }
+    p.alpha = alpha;
+    p.zero = zero;
+    p.cpart = dX ? reinterpret_cast<float *>(base + lay.cvec) : nullptr;
+    p.GT = dW ? reinterpret_cast<uint16_t *>(base + lay.gt) : nullptr;
+    p.nr = nr;
+    p.M = (int)M;
+    p.N = (int)N;
+    // column ranges so that about a thousand workgroups exist; c[m] is summed over them in the dX epilogue
+    const int64_t strips = cdiv(M, PREP_ROWS);
+    int nsplit = (int)std::min<int64_t>(std::min<int64_t>(PREP_MAX_SPLIT, cdiv(N, 64)), std::max<int64_t>(1, cdiv(1024, strips)));
+    p.cols_per_split = (int)(cdiv(cdiv(N, nsplit), 64) * 64);
+    nsplit = (int)cdiv(N, p.cols_per_split);
+    bwd_prep_kernel<<<dim3((unsigned)strips, (unsigned)nsplit), dim3(256), 0, st>>>(p);
 
+    if (dX) {
         uint8_t *QT = base + lay.qt;
         transpose_kernel<uint8_t><<<dim3((unsigned)cdiv(K, 64), (unsigned)cdiv(N, 64)), dim3(256), 0, st>>>(
             Q, QT, (int)N, (int)K);
@@ -1122,7 +1167,8 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
             d.r[i] = rs[j];
         }
         d.QT = QT;
-        d.cvec = p.cvec;
+        d.cvec = p.cpart;
+        d.nsplit = nsplit;
         d.dX = dX;
         d.M = (int)M;
         d.N = (int)N;
@@ -1133,22 +1179,11 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
         if (ds != MQ_OK) return ds;
     }
     if (dW) {
-        GtArgs g;
-        for (int i = 0; i < 3; ++i) {
-            const int j = i < nr ? i : 0;
-            g.dY[i] = dY[j];
-            g.lam[i] = lambda ? lambda[j] : 1.0f;
-        }
-        g.GT = reinterpret_cast<uint16_t *>(base + lay.gt);
-        g.nr = nr;
-        g.M = (int)M;
-        g.N = (int)N;
-        bwd_gt_kernel<<<dim3((unsigned)cdiv(N, 64), (unsigned)cdiv(M, 64)), dim3(256), 0, st>>>(g);
         uint16_t *XT = reinterpret_cast<uint16_t *>(base + lay.xt);
-        transpose_kernel<uint16_t><<<dim3((unsigned)cdiv(K, 64), (unsigned)cdiv(M, 64)), dim3(256), 0, st>>>(
+        transpose_kernel<uint16_t><<<dim3((unsigned)cdiv(K, 32), (unsigned)cdiv(M, 64)), dim3(256), 0, st>>>(
             X, XT, (int)M, (int)K);
         DwArgs w;
-        w.GT = g.GT;
+        w.GT = p.GT;
         w.XT = XT;
         w.dW = dW;
         w.M = (int)M;
