@@ -290,6 +290,25 @@ def test_gemv_extra_precision(mq, oracle, r, frac):
         assert rel_l2(y.float().cpu().numpy() - plain, want - plain) <= 0.25
 
 
+@pytest.mark.parametrize("r,B", [(2, 1), (4, 3), (8, 16)])
+def test_gemv_many_rows(mq, oracle, r, B):
+    """More groups of row blocks than workgroups are resident at once (every workgroup walks over several
+    groups), a row count that is not a multiple of 16, and a single 128-byte weight line per row."""
+    from paper_2502_06786_amd import synth
+    N, K = 66001 if B == 1 else 131075, 128 * 8 // r
+    q = synth.uniform_codes(31 + r, N, K)
+    a = (torch.rand(N, generator=torch.Generator().manual_seed(6)) * 1e-3 + 1e-4).to(torch.bfloat16)
+    z = (torch.rand(N, generator=torch.Generator().manual_seed(7)) * 255).to(torch.bfloat16)
+    packed = mq.mq_slice(dev(q), r, packed=True)
+    x = _randn(B + r, B, K).to(torch.bfloat16)
+    y = mq.mq_gemv_sliced(dev(x), packed, dev(a), dev(z), r, K)
+    want = oracle.gemv_sliced(bf16_bits(x), packed.cpu().numpy(), bf16_bits(a), bf16_bits(z), r, K)
+    assert rel_l2(y.float().cpu().numpy(), want) <= TOL
+    # every row, not just the norm: a group that was skipped or written twice shows up here
+    err = np.abs(y.float().cpu().numpy().astype(np.float64) - want)
+    assert np.all(err <= 2.0 ** -7 * np.abs(want) + 1e-4 * np.abs(want).max())
+
+
 def test_gemv_one_hot_exact(mq, oracle):
     # alpha = 1, z = 0, one-hot activations: y[b, n] is exactly the sliced value of code [n, b].
     N, K = 64, 256
