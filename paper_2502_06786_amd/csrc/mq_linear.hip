@@ -850,15 +850,30 @@ struct DwArgs {
     int tiles_n, tiles_k;
 };
 
-constexpr int DW_BN = 256, DW_BK = 256;
-constexpr int DW_TILE = 256 * 128;
-constexpr int DW_LDS = 4 * DW_TILE;
+constexpr int DW_RB = 2;                   // 32-row blocks of n per wave
+constexpr int DW_MB = 6;                   // 32-column blocks of k per wave
+constexpr int DW_BN = 4 * 32 * DW_RB;      // rows of n per workgroup (4 waves)
+constexpr int DW_BK = 32 * DW_MB;          // columns of k per workgroup
+constexpr int DW_BM = 32;                  // contraction elements (tokens) per stage: 64-byte rows
+constexpr int DW_A_TILE = DW_BN * 64, DW_B_TILE = DW_BK * 64;
+constexpr int DW_STAGE = DW_A_TILE + DW_B_TILE;
+constexpr int DW_NST = 5;                  // LDS stages
+constexpr int DW_LDS = DW_NST * DW_STAGE;
 
-__global__ __launch_bounds__(512) void dw_kernel(DwArgs a) {
+// Same pipeline as the forward and dX kernels (one wave per SIMD, direct-to-LDS stages, one small
+// fenced group of operand work per MFMA), without any code conversion: both operands are bf16 rows
+// with the contraction index (tokens) contiguous.  Wave w owns rows [64 w, 64 w + 64) of the n tile
+// for all 192 k columns: 12 accumulators, 8 operand reads per 12 MFMAs.  Stages are 32 tokens deep
+// (64-byte rows) so that five of them fit: three stages of loads stay in flight.
+__global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    constexpr int RB = DW_RB, MB = DW_MB, NM = RB * MB;
+    constexpr int AL = DW_BN / 64, BL = DW_BK / 64;  // direct-to-LDS loads per wave and stage (16 rows each)
+    constexpr int LPS = AL + BL;
+    static_assert(RB + MB <= NM && LPS <= NM, "not enough MFMAs to hide the operand work");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wn = wave >> 1, wk = wave & 1;  // 4 waves along n (64 rows each) x 2 along k (128 columns each)
     const int h = lane >> 5, l32 = lane & 31;
 
     const uint32_t lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
@@ -873,79 +888,122 @@ __global__ __launch_bounds__(512) void dw_kernel(DwArgs a) {
     const __amdgpu_buffer_rsrc_t rG = make_rsrc(a.GT + (size_t)n0 * a.M, (uint64_t)(a.N - n0) * a.M * 2);
     const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.XT + (size_t)k0 * a.M, (uint64_t)(a.K - k0) * a.M * 2);
 
-    uint32_t off[4];
-    int col[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) bf16_tile_lane<8>(wave, lane, i, (uint32_t)a.M * 2u, off[i], col[i]);
+    uint32_t off0;
+    int colb;  // byte column of this lane's 16-byte piece inside a 64-byte row
+    u8_tile_lane<4>(wave, lane, 0, (uint32_t)a.M * 2u, off0, colb);
+    const uint32_t rstep = 64u * (uint32_t)a.M * 2u;  // 64 rows further down
 
-    auto issue = [&](int mt, int buf) {
-        const int mm = mt * BKT;
-        uint8_t *gs = smem + buf * DW_TILE;
-        uint8_t *xs = smem + 2 * DW_TILE + buf * DW_TILE;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t o = (mm + col[i] < a.M) ? off[i] + (uint32_t)mm * 2u : kOOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rG, (lds_ptr)(gs + (wave + i * 8) * 1024), 16, o, 0, 0, 0);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rX, (lds_ptr)(xs + (wave + i * 8) * 1024), 16, o, 0, 0, 0);
-        }
+    // load i of the stage of token tile mt into LDS buffer `buf`; a tile past M is requested at an
+    // out-of-range offset and answered with zeros, so the loads in flight are the same every stage
+    auto issue_one = [&](int mt, int buf, int i) {
+        const int mm = mt * DW_BM;
+        uint8_t *base = smem + buf * DW_STAGE;
+        const uint32_t o = (mm + colb / 2 < a.M) ? off0 + (uint32_t)mm * 2u : kOOB;
+        if (i < AL)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rG, (lds_ptr)(base + (wave + i * 4) * 1024), 16,
+                                                     o + (uint32_t)i * rstep, 0, 0, 0);
+        else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rX, (lds_ptr)(base + DW_A_TILE + (wave + (i - AL) * 4) * 1024), 16,
+                                                     o + (uint32_t)(i - AL) * rstep, 0, 0, 0);
     };
 
-    uint32_t ga[4], xa[4];
+    // LDS fragment offsets inside a stage for the two 16-token steps of a stage
+    uint32_t ab[2], bb[2];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int cx = 2 * h + 4 * (t >> 1) + (t & 1);
-        ga[t] = (wn * 64 + l32) * 128 + ((cx ^ ((l32 >> 1) & 7)) << 4);
-        xa[t] = (wk * 128 + l32) * 128 + ((cx ^ ((l32 >> 1) & 7)) << 4);
+    for (int t = 0; t < 2; ++t) {
+        const uint32_t chunk = (uint32_t)((2 * t + h) ^ ((l32 >> 2) & 3)) << 4;
+        ab[t] = (uint32_t)(wave * 64 + l32) * 64u + chunk;
+        bb[t] = (uint32_t)DW_A_TILE + (uint32_t)l32 * 64u + chunk;
     }
 
-    f32x16 acc[2][4];
+    f32x16 acc[RB][MB];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < MB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[rb][j][v] = 0.f;
 
-    const int nmt = (a.M + BKT - 1) / BKT;
-    issue(0, 0);
-    for (int mt = 0; mt < nmt; ++mt) {
-        wait_vm0();
-        __syncthreads();
-        if (mt + 1 < nmt) issue(mt + 1, (mt + 1) & 1);
-        const uint8_t *gs = smem + (mt & 1) * DW_TILE;
-        const uint8_t *xs = smem + 2 * DW_TILE + (mt & 1) * DW_TILE;
+    const int nmt = (a.M + DW_BM - 1) / DW_BM;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            u32x4 gf[2];
+    for (int st = 0; st < DW_NST - 1; ++st)
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) gf[rb] = *reinterpret_cast<const u32x4 *>(gs + ga[t] + rb * 4096);
+        for (int i = 0; i < LPS; ++i) issue_one(st, st, i);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DW_NST - 2) * LPS) : "memory");
+    __syncthreads();
+
+    u32x4 af[RB], bf[MB];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const u32x4 xf = *reinterpret_cast<const u32x4 *>(xs + xa[t] + j * 4096);
+    for (int rb = 0; rb < RB; ++rb) af[rb] = *reinterpret_cast<const u32x4 *>(smem + ab[0] + rb * 2048);
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb) acc[rb][j] = mfma32(gf[rb], xf, acc[rb][j]);
+    for (int j = 0; j < MB; ++j) bf[j] = *reinterpret_cast<const u32x4 *>(smem + bb[0] + j * 2048);
+
+    // one stage: two 16-token steps; cb = LDS buffer of this stage
+    auto tile = [&](auto more_tag, int mt, int cb) {
+        constexpr bool MORE = decltype(more_tag)::value;
+        const int nb = cb + 1 == DW_NST ? 0 : cb + 1;   // buffer of the next stage
+        const int ib = cb == 0 ? DW_NST - 1 : cb - 1;   // buffer of stage mt + NST - 1 (= the one of stage mt - 1)
+        const uint8_t *cur = smem + cb * DW_STAGE;
+        const uint8_t *nxt = smem + nb * DW_STAGE;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const bool pre = t == 0 || MORE;
+            const uint8_t *src = t == 0 ? cur : nxt;
+            const int tn_ = t == 0 ? 1 : 0;
+            u32x4 afn[RB], bfn[MB];
+#pragma unroll
+            for (int q = 0; q < NM; ++q) {
+                const int rb = q % RB, j = q / RB;
+                acc[rb][j] = mfma32(af[rb], bf[j], acc[rb][j]);
+                if (pre && q < RB) afn[q] = *reinterpret_cast<const u32x4 *>(src + ab[tn_] + q * 2048);
+                if (pre && q >= RB && q < RB + MB)
+                    bfn[q - RB] = *reinterpret_cast<const u32x4 *>(src + bb[tn_] + (q - RB) * 2048);
+                if (MORE && t == 0 && q >= NM - LPS) issue_one(mt + DW_NST - 1, ib, q - (NM - LPS));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (pre) {
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) af[rb] = afn[rb];
+#pragma unroll
+                for (int j = 0; j < MB; ++j) bf[j] = bfn[j];
             }
         }
-    }
+    };
 
-    // rows of the product are n, columns k: 32 consecutive k per row across half a wave
+    int cb = 0;
+    for (int mt = 0; mt + 1 < nmt; ++mt) {
+        // stage mt + 1 must be resident (operand prefetch at the end of this stage); the loads of
+        // stages mt + 2 and mt + 3 may stay in flight; after the barrier the buffer of stage mt - 1
+        // is free for stage mt + 4
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DW_NST - 3) * LPS) : "memory");
+        __syncthreads();
+        tile(std::true_type{}, mt, cb);
+        cb = cb + 1 == DW_NST ? 0 : cb + 1;
+    }
+    tile(std::false_type{}, nmt - 1, cb);
+    wait_vm0();  // zero-fill loads of dead stages must have landed before the workgroup ends
+
+    // rows of the product are n, columns k: 32 consecutive k (one 128-byte line) per row and half-wave
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int g = 0; g < 4; ++g)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int n = n0 + wn * 64 + rb * 32 + 8 * g + 4 * h + e;
+                const int n = n0 + wave * 64 + rb * 32 + 8 * g + 4 * h + e;
                 if (n >= a.N) continue;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int k = k0 + wk * 128 + j * 32 + l32;
+                for (int j = 0; j < MB; ++j) {
+                    const int k = k0 + j * 32 + l32;
                     if (k >= a.K) continue;
                     float *p = a.dW + (size_t)n * a.K + k;
                     const float v = acc[rb][j][4 * g + e];
                     *p = a.accumulate ? *p + v : v;
                 }
             }
+#else
+    (void)a;
+#endif
 }
 
 // ============================================================================================
@@ -1193,7 +1251,7 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
         w.tiles_n = (int)cdiv(N, DW_BN);
         w.tiles_k = (int)cdiv(K, DW_BK);
         if (!allow_lds(dw_kernel, DW_LDS)) return MQ_ERR_DEVICE;
-        dw_kernel<<<dim3(w.tiles_n * w.tiles_k), dim3(512), DW_LDS, st>>>(w);
+        dw_kernel<<<dim3(w.tiles_n * w.tiles_k), dim3(256), DW_LDS, st>>>(w);
     }
     return launch_status();
 }
