@@ -91,7 +91,15 @@ __global__ __launch_bounds__(256) void overflow_count_kernel(const uint8_t *__re
     const int64_t n = blockIdx.x;
     const uint8_t *row = Q + n * K;
     int cnt = 0;
-    for (int64_t k = threadIdx.x; k < K; k += 256) cnt += row[k] >= thr;
+    if ((K & 15) == 0) {  // rows are whole 16-byte chunks (Q itself is 16-byte aligned)
+        const u32x4 *row16 = reinterpret_cast<const u32x4 *>(row);
+        for (int64_t c = threadIdx.x; c < (K >> 4); c += 256) {
+            const u32x4 d = row16[c];
+            cnt += count_ge4(d.x, thr) + count_ge4(d.y, thr) + count_ge4(d.z, thr) + count_ge4(d.w, thr);
+        }
+    } else {
+        for (int64_t k = threadIdx.x; k < K; k += 256) cnt += row[k] >= thr;
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x / 64] = cnt;
@@ -152,6 +160,51 @@ __global__ __launch_bounds__(256) void overflow_fill_kernel(const uint8_t *__res
     }
 }
 
+// Same result for rows that are whole 16-byte chunks: a thread takes 16 consecutive columns, the
+// position of its first hit comes from a prefix sum over the hit counts of the threads before it.
+__global__ __launch_bounds__(256) void overflow_fill16_kernel(const uint8_t *__restrict__ Q, int64_t K,
+                                                              uint32_t thr, const int32_t *__restrict__ row_ptr,
+                                                              uint16_t *__restrict__ col_idx, int64_t capacity) {
+    __shared__ int wave_tot[4];
+    const int64_t n = blockIdx.x;
+    const u32x4 *row16 = reinterpret_cast<const u32x4 *>(Q + n * K);
+    int64_t base = row_ptr[n];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t chunks = K >> 4;
+    for (int64_t c0 = 0; c0 < chunks; c0 += 256) {
+        const int64_t c = c0 + threadIdx.x;
+        uint32_t hits = 0;  // bit j: column 16 c + j overflows
+        if (c < chunks) {
+            const u32x4 d = row16[c];
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) hits |= (uint32_t)(((d[w] >> (8 * b)) & 0xFFu) >= thr) << (4 * w + b);
+        }
+        const int cnt = __popc(hits);
+        int incl = cnt;  // inclusive prefix sum over the lanes of the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        int before = incl - cnt;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        const int total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+        int64_t pos = base + before;
+        while (hits) {
+            const int j = __ffs(hits) - 1;
+            hits &= hits - 1;
+            if (pos < capacity) col_idx[pos] = (uint16_t)(c * 16 + j);
+            ++pos;
+        }
+        base += total;
+        __syncthreads();
+    }
+}
+
 }  // namespace mq
 
 extern "C" mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uint32_t flags, uint8_t *out,
@@ -190,8 +243,12 @@ extern "C" mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uin
         const uint32_t thr = r == 8 ? 256u : 256u - half;  // r = 8: nothing overflows
         overflow_count_kernel<<<dim3((unsigned)N), dim3(256), 0, st>>>(Q, K, thr, ovf->row_ptr);
         overflow_scan_kernel<<<dim3(1), dim3(1024), 0, st>>>(ovf->row_ptr, N, ovf->nnz);
-        overflow_fill_kernel<<<dim3((unsigned)N), dim3(256), 0, st>>>(Q, K, thr, ovf->row_ptr, ovf->col_idx,
-                                                                     ovf->capacity);
+        if ((K & 15) == 0)
+            overflow_fill16_kernel<<<dim3((unsigned)N), dim3(256), 0, st>>>(Q, K, thr, ovf->row_ptr, ovf->col_idx,
+                                                                           ovf->capacity);
+        else
+            overflow_fill_kernel<<<dim3((unsigned)N), dim3(256), 0, st>>>(Q, K, thr, ovf->row_ptr, ovf->col_idx,
+                                                                         ovf->capacity);
     }
     return launch_status();
 }
