@@ -371,26 +371,33 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
             __builtin_amdgcn_sched_barrier(0);  // keeps the operand reads of the second segment out of the first
             gemv_segment<R, RG>(wt1, blk, (((sb + 1) * 4 * XV) ^ lane_slot) << 4, uc, acc);
         };
-        const int step = KS * D;  // lines one turn of the ring covers (all KS waves of a row block)
 #pragma unroll
         for (int d = 0; d + 1 < D; ++d) fetch_next(w[d]);
 
-        int s = ks;
-        for (int c0 = 0, c = 0; c0 < segs; c0 += chunk_segs, ++c) {
-            const int c1 = min(c0 + chunk_segs, segs);
-            if (first || !single) {
-                if (c > 0 || !first) __syncthreads();  // the x area (or the reduction data over it) has been consumed
-                stage(c, first);
-            }
-            // The load of the line D - 1 ahead is unconditional; the arithmetic of a line past the
-            // end is skipped by a wave-uniform branch.  The ring is unrolled D times: moving
-            // registers whose loads are still in flight would force a wait for them.
-            for (; s < c1; s += step) {
+        // Line sb + ks is this wave's line in the current step; sb is the same for all waves of the
+        // workgroup, so the switch to the next chunk of x (a barrier) happens in the same step for
+        // all of them: chunk boundaries are multiples of KS.  The load of the line D - 1 steps ahead
+        // is unconditional; the arithmetic of a line past the end is skipped by a wave-uniform
+        // branch.  The ring is unrolled D times: moving registers whose loads are still in flight
+        // would force a wait for them.
+        int c = 0, c0 = 0, c1 = min(chunk_segs, segs);
+        if (first || !single) {
+            if (!first) __syncthreads();  // the previous group is done with the x area
+            stage(0, first);
+        }
+        for (int sb = 0; sb < segs;) {
 #pragma unroll
-                for (int d = 0; d < D; ++d) {
-                    fetch_next(w[(d + D - 1) % D]);
-                    if (s + d * KS < c1) compute_line(w[d], s + d * KS - c0);
+            for (int d = 0; d < D; ++d) {
+                if (sb >= c1 && c1 < segs) {  // (only when x does not fit: restaged per group, chunk by chunk)
+                    __syncthreads();          // the chunk has been consumed
+                    ++c;
+                    c0 = c1;
+                    c1 = min(c0 + chunk_segs, segs);
+                    stage(c, first);
                 }
+                fetch_next(w[(d + D - 1) % D]);
+                if (sb + ks < c1) compute_line(w[d], sb + ks - c0);
+                sb += KS;
             }
         }
         first = false;
@@ -495,11 +502,18 @@ static mq_status launch_gemv(const GemvArgs &a, int nw, int ks, hipStream_t st) 
     size_t lds = kSumBytes + x_off + (size_t)blocks_all * bp * 1024;
     if (lds > kLdsMax + kSumBytes) {
         single = 0;
-        const int cap_blocks = (int)std::min<size_t>(131072, kLdsMax - area_bytes(nw, 1)) / (bp * 1024);
-        while (ks > 1 && ks * D > cap_blocks * SSPB) ks >>= 1;
-        const int step = ks * D;
-        CB = cap_blocks * SSPB / step * step / SSPB;
-        if (CB < 1) return MQ_ERR_SHAPE;  // (cannot happen: D <= 4, cap_blocks >= 5)
+        // chunks of whole 512-k blocks whose line count is a multiple of KS; eight waves per workgroup
+        // (more row-block groups, a smaller area A), the largest KS whose chunk still fits
+        nw = 8;
+        if (ks > nw) ks = nw;
+        int cap_blocks = 0;
+        for (;; ks >>= 1) {
+            cap_blocks = (int)(std::min<size_t>(131072, kLdsMax - area_bytes(nw, ks)) / (bp * 1024));
+            if (ks == 1 || cap_blocks * SSPB >= ks) break;
+        }
+        const int unit = std::max(ks, SSPB);  // (both are powers of two)
+        CB = cap_blocks * SSPB / unit * unit / SSPB;
+        if (CB < 1) return MQ_ERR_SHAPE;  // (cannot happen: at KS = 1 at least seven 16 KB blocks fit)
         x_off = area_bytes(nw, ks);
         lds = kSumBytes + x_off + (size_t)CB * bp * 1024;
     }
