@@ -569,8 +569,11 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
     a.KB = (int)kb;
 
     // Rows per wave (16 RG): every activation operand read from LDS serves RG matrix-core products, so
-    // larger batches take two row groups; batches of one or two keep RG = 1 for more waves.
-    const int rg = B <= 2 ? 1 : 2;
+    // larger batches and tall matrices take two row groups; short ones keep RG = 1 for more waves.
+    int rg = (B > 2 || N >= 8192) ? 2 : 1;
+#ifdef MQ_GEMV_TUNE
+    if (const char *e = getenv("MQ_GEMV_RG")) rg = atoi(e);
+#endif
     // K-split: about 2048 waves in total (8 per compute unit measured best across the decode shapes:
     // enough loads in flight, and the whole grid resident at once) when there are few row blocks,
     // none when the rows alone provide them.  Workgroups have 8 waves (KS of them per row block),
@@ -578,7 +581,7 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
     const int64_t segs = cdiv(kb, 128);  // 128-byte lines per row
     const int64_t row_blocks = cdiv(N, 16 * rg);
     int ks = 1;
-    while (ks < 16 && row_blocks * ks * 2 <= 2560 && 2 * ks <= segs) ks <<= 1;
+    while (ks < 16 && row_blocks * ks * 2 <= 2048 && 2 * ks <= segs) ks <<= 1;
     int nw = ks > 8 ? ks : 8;
 #ifdef MQ_GEMV_TUNE
     if (const char *e = getenv("MQ_GEMV_KS")) ks = atoi(e);
