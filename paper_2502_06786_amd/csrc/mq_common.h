@@ -23,16 +23,15 @@ union Frag8 {  // eight bf16 = one MFMA operand register quad
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
 
-// fp32 -> bf16, round to nearest even (inputs are finite).
-__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
+// fp32 -> bf16, round to nearest even, two at a time: gfx950 converts a pair in one instruction
+// (v_cvt_pk_bf16_f32), which the compiler selects for this vector conversion.
+typedef __bf16 bf16pair_t __attribute__((ext_vector_type(2)));
+typedef float f32pair_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32pair_t{lo, hi}, bf16pair_t));
 }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
-}
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) { return pack_bf16x2(f, 0.0f) & 0xFFFFu; }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
