@@ -162,7 +162,7 @@ def main():
     fwd_launches = len(records["fwd"])
     fwd_avg_ms = sum(a.elapsed_time(b) for a, b in records["fwd"]) / fwd_launches
     achieved = (flops_fwd / len(layers)) / (fwd_avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "mq::fwd_kernel<3, true, false, 5>", "achieved": round(achieved, 2),
+    roofline = {"bound": "mfma", "kernel": "mq::fwd_kernel<3, true, false, MB> (MB = 4 for gate and up, 5 for down)", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": FWD_TRAFFIC_BYTES, "algorithmic_bytes": int(sum(L.N * L.K + 2 * L.M * L.K + 6 * L.M * L.N
                                                                          for L in layers) / len(layers)),

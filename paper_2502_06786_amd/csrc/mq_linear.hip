@@ -293,7 +293,8 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
     auto tile = [&](auto more_tag, int kt) {
         constexpr bool MORE = decltype(more_tag)::value;
         constexpr int NM = NR * MB;
-        static_assert(4 * NR + 1 <= NM, "not enough MFMAs to hide the operand work");
+        static_assert(4 * NR <= NM, "not enough MFMAs to hide the operand work");
+        constexpr int CQ = 4 * NR + 1 <= NM ? 1 : 0;  // first group that carries a conversion
         constexpr int LPG = (LPS + NM - 1) / NM;  // global loads per group in step 0
         const uint8_t *cur = smem + (kt & 3) * STAGE;
         const uint8_t *nxt = smem + ((kt + 1) & 3) * STAGE;
@@ -315,10 +316,10 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
                 const int j = q / NR, i = q % NR;
                 acc[i][j] = mfma32(wf[i], xf[j], acc[i][j]);
                 if (pre && q < MB) xfn[q] = *reinterpret_cast<const u32x4 *>(src + q * 4096);
-                if (pre && q >= 1 && q - 1 < 4 * NR) {
-                    uint32_t piece = convert_piece((q - 1) / 4, (q - 1) % 4, d0, d1);
+                if (pre && q >= CQ && q - CQ < 4 * NR) {
+                    uint32_t piece = convert_piece((q - CQ) / 4, (q - CQ) % 4, d0, d1);
                     asm volatile("" : "+v"(piece));  // keeps the conversion inside this group
-                    wfn[(q - 1) / 4][(q - 1) % 4] = piece;
+                    wfn[(q - CQ) / 4][(q - CQ) % 4] = piece;
                 }
                 if (MORE && t == 2 && q >= NM - 2) rawn[q - (NM - 2)] = *reinterpret_cast<const u32x4 *>(nxt + (q == NM - 2 ? qa0 : qa1));
                 if (MORE && t == 0) {
@@ -1051,14 +1052,29 @@ static bool allow_lds(Kern kern, int bytes) {
                                bytes) == hipSuccess;
 }
 
-template <int NR, bool HAS8, bool EP>
-static mq_status launch_fwd(FwdArgs a, hipStream_t st) {
-    constexpr int MB = fwd_mb(NR);
+template <int NR, bool HAS8, bool EP, int MB>
+static mq_status launch_fwd_mb(FwdArgs a, hipStream_t st) {
     a.tiles_m = (int)cdiv(a.M, 32 * MB);
     a.tiles_n = (int)cdiv(a.N, FWD_BN);
     if (!allow_lds(fwd_kernel<NR, HAS8, EP, MB>, fwd_lds(MB, NR))) return MQ_ERR_DEVICE;
     fwd_kernel<NR, HAS8, EP, MB><<<dim3(a.tiles_m * a.tiles_n), dim3(256), fwd_lds(MB, NR), st>>>(a);
     return launch_status();
+}
+
+// Token-tile height: the tallest tile amortises the code conversion and the epilogue best, but the
+// number of tiles rarely divides evenly over the 256 compute units; one block less can save a whole
+// round of workgroups.  Cost of a choice = rounds x (main loop + epilogue) in matrix-core cycles
+// (32 per MFMA; prologue and epilogue constants measured on the Gemma-2-2B shapes).
+template <int NR, bool HAS8, bool EP>
+static mq_status launch_fwd(const FwdArgs &a, hipStream_t st) {
+    constexpr int HI = fwd_mb(NR), LO = HI - 1;
+    auto cost = [&](int mb) {
+        const int64_t tiles = cdiv(a.M, 32 * mb) * cdiv(a.N, FWD_BN);
+        const int64_t rounds = cdiv(tiles, 256);
+        const int64_t per_tile = cdiv(a.K, BKT) * NR * mb * 128 + 3000 + 890 * NR * mb;
+        return rounds * per_tile;
+    };
+    return cost(LO) < cost(HI) ? launch_fwd_mb<NR, HAS8, EP, LO>(a, st) : launch_fwd_mb<NR, HAS8, EP, HI>(a, st);
 }
 
 template <int NR, bool HAS8>
