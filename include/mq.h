@@ -169,7 +169,9 @@ mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const float *alpha,
  *   ovf     host struct or NULL (= plain slice); row_ptr/col_idx as written by mq_slice
  *           with nnz <= capacity
  *   y       [B, N] bf16 out
- * K must be a multiple of 128.  N == 0 is a no-op.
+ * A packed row must be a whole number of 16-byte units (K*r a multiple of 128 bits, else
+ * MQ_ERR_ALIGN); B*K <= 2^29 and, with an overflow list, K <= 65536 (else MQ_ERR_SHAPE).
+ * N == 0 is a no-op.
  */
 mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                          const uint16_t *zero_bf16, const mq_overflow *ovf,
