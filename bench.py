@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gemv-sweep", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the measured-ceiling probes")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 256 MiB device-to-device copies before the timed region: a kernel of "
                          "known traffic against which hardware byte counters of a profiling run are scaled")
@@ -179,11 +180,67 @@ def main():
         "per_op": per_op,
         "roofline": roofline,
     }
+    if not args.no_probes:
+        peaks = measured_peaks(torch, mq)
+        out["measured_peaks"] = peaks
+        roofline["frac_of_measured"] = round(achieved / peaks["mfma_bf16_normal_operands_TFLOPs"], 4)
     if not args.no_gemv_sweep:
         out["gemv_roofline"] = gemv_sweep(torch, mq, synth)
+        if not args.no_probes:
+            best = out["gemv_roofline"]["best_int2"]
+            best["frac_of_measured_read"] = round(best["achieved"] / peaks["hbm_read_85MB_GBs"], 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, synth, rs, lambdas)
     print(json.dumps(out))
+
+
+def measured_peaks(torch, mq):
+    """What this GPU sustains on kernels that only multiply or only read (library probes): the matrix-core
+    loop fed with N(0,1) bf16 operands (the bit patterns set the power drawn, hence the clock) and with a
+    constant, a 1 GiB read, and reads of decode-sized 85 MB buffers (eight copies in turn)."""
+    def timed(fn, reps=3):
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            n = fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(n / (e0.elapsed_time(e1) * 1e-3))
+        return sorted(ts)[len(ts) // 2]
+
+    g = torch.Generator().manual_seed(1234)
+    normal = torch.randn(32768, generator=g).to(torch.bfloat16).cuda()
+    const = torch.full((32768,), 128.0, dtype=torch.bfloat16, device="cuda")
+    sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    mq.mq_probe_mfma(normal, 2000, sink)
+    res = {
+        "mfma_bf16_normal_operands_TFLOPs": round(timed(lambda: mq.mq_probe_mfma(normal, 30000, sink)) / 1e12, 1),
+        "mfma_bf16_constant_operands_TFLOPs": round(timed(lambda: mq.mq_probe_mfma(const, 30000, sink)) / 1e12, 1),
+    }
+    big = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+    isink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    mq.mq_probe_read(big, isink)
+    res["hbm_read_1GiB_GBs"] = round(timed(lambda: mq.mq_probe_read(big, isink)) / 1e9, 1)
+    nb = 36864 * 2304
+    parts = [big[i * (128 << 20): i * (128 << 20) + nb] for i in range(8)]
+
+    def decode_sized():
+        for p in parts:
+            mq.mq_probe_read(p, isink)
+        return 8 * nb
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        decode_sized()
+
+    def replay():
+        graph.replay()
+        return 8 * nb
+    replay()
+    res["hbm_read_85MB_GBs"] = round(timed(replay, reps=5) / 1e9, 1)
+    res["note"] = ("library probes mq_probe_mfma (1024 waves, 12 accumulators each, ~10 ms) and mq_probe_read; "
+                   "published peaks: 2500 TFLOP/s, 8000 GB/s")
+    return res
 
 
 def gemv_sweep(torch, mq, synth):

@@ -177,6 +177,21 @@ mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_
                          const uint16_t *zero_bf16, const mq_overflow *ovf,
                          int64_t B, int64_t N, int64_t K, int r, uint16_t *y, void *hip_stream);
 
+/*
+ * Measurement helpers (they compute nothing of the method): ceilings of this GPU as measured by
+ * kernels that only multiply or only read, to put next to the published peaks.
+ *
+ * mq_probe_mfma: 256 workgroups of one wave per SIMD run `iters` rounds of 12 independent
+ *   32x32x16 bf16 matrix-core products per wave = 256 * 4 * iters * 12 * 32768 flops.
+ *   operands_bf16  device, 32768 bf16 values (64 KB) the products are fed with: their bit patterns
+ *                  set the power the loop draws, hence the clock it sustains
+ *   sink           device [65536] float, overwritten
+ * mq_probe_read: reads `bytes` (a multiple of 16) from src once with 16-byte loads.
+ *   sink           device [1] uint32, practically never written
+ */
+mq_status mq_probe_mfma(const uint16_t *operands_bf16, int64_t iters, float *sink, void *hip_stream);
+mq_status mq_probe_read(const void *src, int64_t bytes, uint32_t *sink, void *hip_stream);
+
 /* Bytes of workspace `op` needs at these sizes (0 on invalid arguments). */
 size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int nr);
 

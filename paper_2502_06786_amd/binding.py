@@ -22,7 +22,7 @@ MQ_OP_LINEAR_FWD = 0
 MQ_OP_LINEAR_BWD = 1
 
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
-           "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string"]
+           "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string", "mq_probe_mfma", "mq_probe_read"]
 
 
 class MqError(RuntimeError):
@@ -54,8 +54,11 @@ def _load() -> ctypes.CDLL:
     lib.mq_status_string.argtypes = [ci]
     lib.mq_status_string.restype = ctypes.c_char_p
     lib.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
-    for name in EXPORTS[:6]:
-        getattr(lib, name).restype = ci
+    lib.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
+    lib.mq_probe_read.argtypes = [vp, i64, vp, vp]
+    for name in EXPORTS:
+        if name not in ("mq_workspace_bytes", "mq_status_string"):
+            getattr(lib, name).restype = ci
     return lib
 
 
@@ -133,6 +136,24 @@ def mq_params_to_bf16(alpha, zero, alpha_bf16=None, zero_bf16=None):
                                 _ptr(alpha_bf16, torch.bfloat16), _ptr(zero_bf16, torch.bfloat16), _stream())
     _check(st, "mq_params_to_bf16")
     return alpha_bf16, zero_bf16
+
+
+def mq_probe_mfma(operands, iters: int, sink=None):
+    """Measurement helper: `iters` rounds of 12 bf16 32x32x16 products per wave on 1024 waves, fed with the
+    32768 bf16 values of `operands`.  Returns the flop count of the launch."""
+    assert operands.numel() >= 32768
+    sink = torch.empty(65536, dtype=torch.float32, device=operands.device) if sink is None else sink
+    st = _lib.mq_probe_mfma(_ptr(operands, torch.bfloat16), int(iters), _ptr(sink, torch.float32), _stream())
+    _check(st, "mq_probe_mfma")
+    return 256 * 4 * int(iters) * 12 * 32 * 32 * 16 * 2
+
+
+def mq_probe_read(src, sink=None):
+    """Measurement helper: one kernel that reads every byte of `src` (uint8, a multiple of 16 bytes) once."""
+    sink = torch.zeros(1, dtype=torch.int32, device=src.device) if sink is None else sink
+    st = _lib.mq_probe_read(_ptr(src, torch.uint8), src.numel(), _ptr(sink, torch.int32), _stream())
+    _check(st, "mq_probe_read")
+    return src.numel()
 
 
 def mq_slice(Q, r: int, packed: bool = False, extra_precision: bool = False, out=None, ovf: Overflow | None = None,

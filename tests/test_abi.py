@@ -1,0 +1,133 @@
+"""The C-ABI library without a GPU: it loads, exports every function include/mq.h declares, and its
+host-side argument checks answer with the documented status codes before anything is launched.
+
+Only calls that return before the first launch are made here (bad sizes, bad bit-widths, null
+pointers, sizes of zero); compute calls live in the GPU tests.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mq.h")
+LIB = os.path.join(ROOT, "paper_2502_06786_amd", "libmq.so")
+
+OK, NULL, SHAPE, BITS, ALIGN, WORKSPACE, CAPACITY, DEVICE = range(8)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"\b(mq_[a-z0-9_]+)\s*\(", text)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.fail(f"{LIB} is not built (python -c 'import __graft_entry__ as g; g.build()')")
+    lib_ = ctypes.CDLL(LIB)
+    vp, i64, ci, u32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t
+    lib_.mq_quantize_int8.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
+    lib_.mq_slice.argtypes = [vp, i64, i64, ci, u32, vp, vp, vp]
+    lib_.mq_linear_fwd_multi.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, sz, vp]
+    lib_.mq_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
+    lib_.mq_gemv_sliced.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
+    lib_.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
+    lib_.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
+    lib_.mq_probe_read.argtypes = [vp, i64, vp, vp]
+    lib_.mq_workspace_bytes.argtypes = [ci, i64, i64, i64, ci]
+    lib_.mq_workspace_bytes.restype = sz
+    lib_.mq_status_string.argtypes = [ci]
+    lib_.mq_status_string.restype = ctypes.c_char_p
+    return lib_
+
+
+def test_header_declares_the_five_calls():
+    names = set(declared_functions())
+    assert {"mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced"} <= names
+
+
+def test_library_exports_every_declared_function(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_binding_names_match_the_header():
+    # (the binding module itself needs torch and loads the library on import)
+    from paper_2502_06786_amd import binding
+    assert sorted(binding.EXPORTS) == sorted(set(declared_functions()))
+    for name in binding.EXPORTS:
+        public = "status_string" if name == "mq_status_string" else name
+        assert callable(getattr(binding, public)), name
+
+
+def test_status_strings(lib):
+    seen = {lib.mq_status_string(c).decode() for c in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+    assert lib.mq_status_string(99).decode() == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    f = lib.mq_workspace_bytes
+    M, N, K = 4096, 9216, 2304
+    fwd, bwd = f(0, M, N, K, 3), f(1, M, N, K, 3)
+    assert fwd >= 4 * M
+    # three scaled gradient copies + transposed gradient sum + X^T + Q^T
+    assert bwd >= 3 * M * N * 2 + M * N * 2 + M * K * 2 + N * K
+    assert f(1, M, N, K, 1) < bwd
+    assert f(0, -1, N, K, 3) == 0 and f(1, M, N, K, 4) == 0 and f(1, M, N, K, 0) == 0
+
+
+def test_slice_argument_checks(lib):
+    assert lib.mq_slice(None, 4, 64, 9, 0, None, None, None) == BITS
+    assert lib.mq_slice(None, 4, 64, 0, 0, None, None, None) == BITS
+    assert lib.mq_slice(None, -1, 64, 4, 0, None, None, None) == SHAPE
+    assert lib.mq_slice(None, 4, 64, 3, 2, None, None, None) == BITS       # packed 3-bit planes are not built
+    assert lib.mq_slice(None, 4, 63, 2, 2, None, None, None) == ALIGN      # K not a whole number of bytes
+    assert lib.mq_slice(None, 4, 64, 2, 1, None, None, None) == NULL       # extra precision without a list
+    assert lib.mq_slice(None, 0, 64, 4, 0, None, None, None) == OK         # empty input: nothing to do
+    assert lib.mq_slice(None, 4, 64, 4, 0, None, None, None) == NULL
+
+
+def test_quantize_argument_checks(lib):
+    assert lib.mq_quantize_int8(None, 4, 64, 64, None, None, None, None, None, None) == NULL
+    assert lib.mq_quantize_int8(None, -4, 64, 64, None, None, None, None, None, None) == SHAPE
+    assert lib.mq_quantize_int8(None, 4, 64, 32, None, None, None, None, None, None) == SHAPE   # ldw < K
+    assert lib.mq_quantize_int8(None, 0, 64, 64, None, None, None, None, None, None) == OK
+
+
+def test_linear_argument_checks(lib):
+    ci = ctypes.c_int
+    rs = (ci * 3)(8, 4, 2)
+    dup = (ci * 2)(4, 4)
+    bad = (ci * 1)(9)
+    fwd, bwd = lib.mq_linear_fwd_multi, lib.mq_linear_bwd
+    assert fwd(None, None, None, None, 16, 256, 256, rs, 4, 0, None, None, 0, None) == BITS
+    assert fwd(None, None, None, None, 16, 256, 256, dup, 2, 0, None, None, 0, None) == BITS
+    assert fwd(None, None, None, None, 16, 256, 256, bad, 1, 0, None, None, 0, None) == BITS
+    assert fwd(None, None, None, None, 16, 256, 256, None, 3, 0, None, None, 0, None) == NULL
+    assert fwd(None, None, None, None, -1, 256, 256, rs, 3, 0, None, None, 0, None) == SHAPE
+    assert fwd(None, None, None, None, 16, 256, 250, rs, 3, 0, None, None, 0, None) == ALIGN
+    assert bwd(None, None, None, None, None, None, 16, 256, 256, rs, 0, 0, None, None, None, 0, None) == BITS
+    assert bwd(None, None, None, None, None, None, 16, 256, 250, rs, 3, 0, None, None, None, 0, None) == ALIGN
+    assert bwd(None, None, None, None, None, None, 12, 256, 256, rs, 3, 0, None, None, None, 0, None) == ALIGN
+    assert bwd(None, None, None, None, None, None, 16, 256, 256, rs, 3, 0, None, None, None, 0, None) == NULL
+    assert bwd(None, None, None, None, None, None, 0, 256, 256, rs, 3, 0, None, None, None, 0, None) == OK
+
+
+def test_gemv_argument_checks(lib):
+    g = lib.mq_gemv_sliced
+    assert g(None, None, None, None, None, 1, 64, 256, 3, None, None) == BITS
+    assert g(None, None, None, None, None, 17, 64, 256, 2, None, None) == SHAPE
+    assert g(None, None, None, None, None, 0, 64, 256, 2, None, None) == SHAPE
+    assert g(None, None, None, None, None, 1, 64, 100, 2, None, None) == ALIGN   # 200 bits per row
+    assert g(None, None, None, None, None, 16, 64, 1 << 26, 2, None, None) == SHAPE  # B * K beyond 2^29
+    assert g(None, None, None, None, None, 1, 0, 256, 2, None, None) == OK
+    assert g(None, None, None, None, None, 1, 64, 256, 2, None, None) == NULL
+
+
+def test_probe_argument_checks(lib):
+    assert lib.mq_probe_mfma(None, 10, None, None) == NULL
+    assert lib.mq_probe_read(None, 1024, None, None) == NULL

@@ -325,6 +325,18 @@ def test_gemv_one_hot_exact(mq, oracle):
             assert np.array_equal(y.float().cpu().numpy().astype(np.float64), want), (r, k0)
 
 
+def test_measurement_probes_run(mq):
+    ops = torch.randn(32768, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
+    sink = torch.zeros(65536, dtype=torch.float32, device="cuda")
+    flops = mq.mq_probe_mfma(ops, 8, sink)
+    assert flops == 256 * 4 * 8 * 12 * 32768
+    torch.cuda.synchronize()
+    assert torch.isfinite(sink).all() and sink.abs().sum() > 0
+    src = torch.arange(1 << 20, dtype=torch.int32).to(torch.uint8).cuda()
+    assert mq.mq_probe_read(src) == src.numel()
+    torch.cuda.synchronize()
+
+
 # --------------------------------------------------------------------------
 # argument checking (host side, nothing is launched)
 # --------------------------------------------------------------------------
