@@ -295,9 +295,13 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
         return lane < 32 ? lo : hi;
     };
 
-    auto stage = [&](int c, bool with_sums) {
-        issue_x(c);
-        wait_all_loads();
+    // `ring` = weight loads that were requested after the activations and may stay in flight (loads
+    // return in order, so waiting for all but the newest `ring` is waiting for the activations)
+    auto stage = [&](int c, bool with_sums, auto ring) {
+        if constexpr (decltype(ring)::value == 0)
+            wait_all_loads();
+        else
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(ring)::value) : "memory");
         __syncthreads();
         pair_pass(with_sums);
         if (with_sums) {  // running totals; complete after the last chunk's pass
@@ -327,9 +331,9 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
 #pragma unroll
             for (int d = 0; d < D; ++d) w[d][0][rg] = w[d][1][rg] = u32x4{0u, 0u, 0u, 0u};
         }
-        // alpha and z of the rows this lane will write: requested now and used after the main loop,
-        // except for int2, whose unpack leaves no registers to hold them that long
-        constexpr bool kEarlyParams = R != 2;
+        // alpha and z of the rows this lane will write: requested now and used after the main loop
+        // (later where the registers to hold them that long are missing)
+        constexpr bool kEarlyParams = !(EP && R == 2);
         float pal[RG][4], pze[RG][4];
         auto load_params = [&]() {
 #pragma unroll
@@ -371,6 +375,13 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
             __builtin_amdgcn_sched_barrier(0);  // keeps the operand reads of the second segment out of the first
             gemv_segment<R, RG>(wt1, blk, (((sb + 1) * 4 * XV) ^ lane_slot) << 4, uc, acc);
         };
+        // The activations of the first chunk are requested before the weights of the ring: they come
+        // from L2 and are paired while the first weight lines are still on their way from HBM.
+        const bool stage_first = first || !single;
+        if (stage_first) {
+            if (!first) __syncthreads();  // the previous group is done with the x area
+            issue_x(0);
+        }
 #pragma unroll
         for (int d = 0; d + 1 < D; ++d) fetch_next(w[d]);
 
@@ -381,10 +392,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
         // branch.  The ring is unrolled D times: moving registers whose loads are still in flight
         // would force a wait for them.
         int c = 0, c0 = 0, c1 = min(chunk_segs, segs);
-        if (first || !single) {
-            if (!first) __syncthreads();  // the previous group is done with the x area
-            stage(0, first);
-        }
+        if (stage_first) stage(0, first, std::integral_constant<int, (D - 1) * 2 * RG>{});
         for (int sb = 0; sb < segs;) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
@@ -393,7 +401,8 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                     ++c;
                     c0 = c1;
                     c1 = min(c0 + chunk_segs, segs);
-                    stage(c, first);
+                    issue_x(c);
+                    stage(c, first, std::integral_constant<int, 0>{});
                 }
                 fetch_next(w[(d + D - 1) % D]);
                 if (sb + ks < c1) compute_line(w[d], sb + ks - c0);
