@@ -94,9 +94,9 @@ def slice_values(q, r: int, ep: bool = False):
 def pack(codes, r: int):
     codes = _c(codes, np.uint8)
     N, K = codes.shape
-    per = 8 // r
-    assert r in (8, 4, 2) and K % per == 0
-    out = np.empty((N, K // per), np.uint8)
+    assert 1 <= r <= 8 and (K * r) % 8 == 0
+    assert int(codes.max(initial=0)) < (1 << r)
+    out = np.empty((N, K * r // 8), np.uint8)
     _load().mqo_pack(_p(codes), _i64(N), _i64(K), ctypes.c_int(r), _p(out))
     return out
 

@@ -112,26 +112,38 @@ void mqo_slice_values(const uint8_t *Q, int64_t count, int r, int ep, uint16_t *
 }
 
 /* ------------------------------------------------------------------------
- * Packing (format is this repository's; the paper gives none): r in {8,4,2},
- * 8/r codes per byte, element k of a row lives in byte k / (8/r) at bit
- * offset r * (k mod 8/r).  K must be a multiple of 8/r.
+ * Packing (format is this repository's; the paper gives none).  A row is a
+ * little-endian bit stream of r bits per code: code k occupies stream bits
+ * [r k, r k + r), least significant bit first, and stream bit t is bit t mod 8
+ * of byte t / 8.  For r in {8, 4, 2} this is "8/r codes per byte, element k in
+ * byte k / (8/r) at bit offset r (k mod 8/r)"; r = 6 and r = 3 (the
+ * interpolated bit-widths of section 4.2) put 4 resp. 8 codes into 3 bytes.
+ * K r must be a multiple of 8.
  * ---------------------------------------------------------------------- */
 void mqo_pack(const uint8_t *code, int64_t N, int64_t K, int r, uint8_t *out) {
-    int per = 8 / r;
-    int64_t kb = K / per;
+    int64_t kb = K * r / 8;
     memset(out, 0, (size_t)(N * kb));
     for (int64_t n = 0; n < N; ++n)
         for (int64_t k = 0; k < K; ++k)
-            out[n * kb + k / per] |= (uint8_t)(code[n * K + k] << (r * (k % per)));
+            for (int j = 0; j < r; ++j) {
+                int64_t t = k * r + j;
+                if ((code[n * K + k] >> j) & 1) out[n * kb + t / 8] |= (uint8_t)(1u << (t % 8));
+            }
+}
+
+static int stream_code(const uint8_t *row, int64_t k, int r) {
+    int c = 0;
+    for (int j = 0; j < r; ++j) {
+        int64_t t = k * r + j;
+        c |= ((row[t / 8] >> (t % 8)) & 1) << j;
+    }
+    return c;
 }
 
 void mqo_unpack(const uint8_t *packed, int64_t N, int64_t K, int r, uint8_t *code) {
-    int per = 8 / r;
-    int64_t kb = K / per;
-    int mask = (1 << r) - 1;
+    int64_t kb = K * r / 8;
     for (int64_t n = 0; n < N; ++n)
-        for (int64_t k = 0; k < K; ++k)
-            code[n * K + k] = (uint8_t)((packed[n * kb + k / per] >> (r * (k % per))) & mask);
+        for (int64_t k = 0; k < K; ++k) code[n * K + k] = (uint8_t)stream_code(packed + n * kb, k, r);
 }
 
 /* ------------------------------------------------------------------------
@@ -308,17 +320,14 @@ void mqo_linear_bwd_dw_sampled(const uint16_t *X, const uint16_t *const *dY, con
 void mqo_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                      const uint16_t *zero_bf16, const int32_t *row_ptr, const uint16_t *col_idx,
                      int64_t B, int64_t N, int64_t K, int r, double *y) {
-    int per = 8 / r;
-    int64_t kb = K / per;
-    int mask = (1 << r) - 1;
+    int64_t kb = K * r / 8;
     int s = 8 - r;
 #pragma omp parallel for schedule(static)
     for (int64_t n = 0; n < N; ++n) {
         double a = bf16_bits_to_f64(alpha_bf16[n]);
         double z = bf16_bits_to_f64(zero_bf16[n]);
         int *S = (int *)malloc((size_t)K * sizeof(int));
-        for (int64_t k = 0; k < K; ++k)
-            S[k] = ((packed[n * kb + k / per] >> (r * (k % per))) & mask) << s;
+        for (int64_t k = 0; k < K; ++k) S[k] = stream_code(packed + n * kb, k, r) << s;
         if (row_ptr)
             for (int32_t p = row_ptr[n]; p < row_ptr[n + 1]; ++p) S[col_idx[p]] += 1 << s;
         for (int64_t b = 0; b < B; ++b) {

@@ -208,15 +208,25 @@ def test_pack_hand_examples(oracle):
     assert oracle.pack(codes2, 2).tolist() == [[0b11100100, 0b00011011]]
     codes8 = np.array([[7, 200]], np.uint8)
     assert oracle.pack(codes8, 8).tolist() == [[7, 200]]
+    # bit stream, r = 6: 4 codes in 3 bytes.  1 | 2 << 6 | 3 << 12 | 63 << 18 = 0xFC3081
+    codes6 = np.array([[1, 2, 3, 63]], np.uint8)
+    assert oracle.pack(codes6, 6).tolist() == [[0x81, 0x30, 0xFC]]
+    # r = 3: 8 codes in 3 bytes.  sum_k c_k << 3k for c = 1,2,3,4,5,6,7,0 = 0x1F58D1
+    codes3 = np.array([[1, 2, 3, 4, 5, 6, 7, 0]], np.uint8)
+    assert oracle.pack(codes3, 3).tolist() == [[0xD1, 0x58, 0x1F]]
 
 
 def test_pack_roundtrip(oracle):
     rng = np.random.default_rng(5)
-    for r in (8, 4, 2):
+    for r in (8, 4, 2, 6, 3, 1, 5, 7):
         codes = rng.integers(0, 2 ** r, (9, 64), dtype=np.uint8)
         p = oracle.pack(codes, r)
         assert p.shape == (9, 64 * r // 8)
         assert np.array_equal(oracle.unpack(p, 64, r), codes)
+        # the row read as one little-endian integer is sum_k code_k 2^(r k)
+        for n in (0, 8):
+            want = sum(int(c) << (r * k) for k, c in enumerate(codes[n]))
+            assert int.from_bytes(p[n].tobytes(), "little") == want
 
 
 def test_overflow_csr(oracle):
