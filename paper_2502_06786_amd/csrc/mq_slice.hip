@@ -2,6 +2,8 @@
 // describes, clamp to 2^r - 1), optional packing to 8/r codes per byte, and the extra-precision
 // overflow set of the errata section as a CSR list.  Integer-only and HBM-bound:
 // 1 B read + r/8 B written per weight when packed.
+#include <algorithm>
+
 #include "mq_common.h"
 
 namespace mq {
@@ -73,6 +75,60 @@ __global__ __launch_bounds__(256) void slice_kernel(const uint8_t *__restrict__ 
                 uint32_t b = 0;
                 for (int j = 0; j < PER; ++j) b |= slice1(Q[i + j], r) << (MODE * j);
                 out[i / PER] = (uint8_t)b;
+            }
+        }
+    }
+}
+
+// Packed r-bit planes for bit-widths that do not divide 8 (r = 6, 3: the interpolated bit-widths of
+// section 4.2): a little-endian bit stream, code k at stream bits [r k, r k + r).  32 codes per
+// thread become exactly R dwords.
+template <int R>
+__global__ __launch_bounds__(256) void slice_stream_kernel(const uint8_t *__restrict__ Q, int64_t count,
+                                                           uint8_t *__restrict__ out) {
+    constexpr uint32_t s = 8 - R, half = (1u << s) >> 1, top = (1u << R) - 1;
+    constexpr uint32_t half2 = half | (half << 16), top2 = top | (top << 16);
+    const int64_t groups = count >> 5;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < groups; c += stride) {
+        const u32x4 d0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Q) + 2 * c);
+        const u32x4 d1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Q) + 2 * c + 1);
+        uint32_t codes[8];  // four codes per dword, one per byte
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            codes[w] = slice4(d0[w], half2, s, top2);
+            codes[4 + w] = slice4(d1[w], half2, s, top2);
+        }
+        uint32_t *dst = reinterpret_cast<uint32_t *>(out) + c * R;
+        uint64_t acc = 0;
+        int have = 0, word = 0;  // (compile-time after unrolling)
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const uint64_t code = (codes[k >> 2] >> (8 * (k & 3))) & 0xFFu;
+            acc |= code << have;
+            have += R;
+            if (have >= 32) {
+                __builtin_nontemporal_store((uint32_t)acc, dst + word);
+                ++word;
+                acc >>= 32;
+                have -= 32;
+            }
+        }
+    }
+    // tail shorter than 32 codes (a whole number of bytes, since count * R is a multiple of 8): one
+    // thread, bit by bit
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const int64_t done = groups << 5;
+        uint32_t acc = 0;
+        int have = 0;
+        int64_t byte = done * R / 8;
+        for (int64_t i = done; i < count; ++i) {
+            acc |= slice1(Q[i], R) << have;
+            have += R;
+            while (have >= 8) {
+                out[byte++] = (uint8_t)acc;
+                acc >>= 8;
+                have -= 8;
             }
         }
     }
@@ -213,8 +269,8 @@ extern "C" mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uin
     if (N < 0 || K < 0) return MQ_ERR_SHAPE;
     if (r < 1 || r > 8) return MQ_ERR_BITS;
     const bool packed = flags & MQ_FLAG_PACKED, ep = flags & MQ_FLAG_EXTRA_PRECISION;
-    if (packed && !(r == 8 || r == 4 || r == 2)) return MQ_ERR_BITS;
-    if (packed && (K % (8 / r)) != 0) return MQ_ERR_ALIGN;
+    if (packed && !(r == 8 || r == 6 || r == 4 || r == 3 || r == 2)) return MQ_ERR_BITS;
+    if (packed && ((K * r) % 8) != 0) return MQ_ERR_ALIGN;  // rows are whole bytes
     if (ep) {
         if (!ovf) return MQ_ERR_NULL;
         if (N > 0 && (!ovf->row_ptr || !ovf->nnz || (ovf->capacity > 0 && !ovf->col_idx))) return MQ_ERR_NULL;
@@ -231,7 +287,14 @@ extern "C" mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uin
     const int64_t chunks = count >> 4;
     int64_t blocks = cdiv(chunks > 0 ? chunks : 1, 256);
     if (blocks > 256 * 32) blocks = 256 * 32;  // grid-stride beyond 32 blocks per CU
-    if (!packed || r == 8) {
+    if (packed && (r == 6 || r == 3)) {
+        int64_t sblocks = cdiv(std::max<int64_t>(count >> 5, 1), 256);
+        if (sblocks > 256 * 32) sblocks = 256 * 32;
+        if (r == 6)
+            slice_stream_kernel<6><<<dim3((unsigned)sblocks), dim3(256), 0, st>>>(Q, count, out);
+        else
+            slice_stream_kernel<3><<<dim3((unsigned)sblocks), dim3(256), 0, st>>>(Q, count, out);
+    } else if (!packed || r == 8) {
         slice_kernel<0><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, r, out);
     } else if (r == 4) {
         slice_kernel<4><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, r, out);

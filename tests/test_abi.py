@@ -84,7 +84,8 @@ def test_slice_argument_checks(lib):
     assert lib.mq_slice(None, 4, 64, 9, 0, None, None, None) == BITS
     assert lib.mq_slice(None, 4, 64, 0, 0, None, None, None) == BITS
     assert lib.mq_slice(None, -1, 64, 4, 0, None, None, None) == SHAPE
-    assert lib.mq_slice(None, 4, 64, 3, 2, None, None, None) == BITS       # packed 3-bit planes are not built
+    assert lib.mq_slice(None, 4, 64, 5, 2, None, None, None) == BITS       # packed 5-bit planes are not built
+    assert lib.mq_slice(None, 4, 62, 6, 2, None, None, None) == ALIGN      # 372 bits per row
     assert lib.mq_slice(None, 4, 63, 2, 2, None, None, None) == ALIGN      # K not a whole number of bytes
     assert lib.mq_slice(None, 4, 64, 2, 1, None, None, None) == NULL       # extra precision without a list
     assert lib.mq_slice(None, 0, 64, 4, 0, None, None, None) == OK         # empty input: nothing to do
