@@ -250,7 +250,7 @@ def gemv_sweep(torch, mq, synth):
     best = None
     for (N, K) in synth.DECODE_SHAPES:
         g = torch.Generator().manual_seed(N * 7 + K)
-        for r in (2, 4):
+        for r in (2, 4, 3, 6):
             kb = K * r // 8
             copies = max(8, int(640e6 // (N * kb)) + 1)
             planes = [torch.randint(0, 256, (N, kb), generator=g, dtype=torch.int32).to(torch.uint8).cuda()

@@ -106,9 +106,13 @@ mq_status mq_params_to_bf16(const float *alpha, const float *zero, int64_t N, ui
  *   Q    [N, K] uint8
  *   r    1..8 (r = 8 is the identity)
  *   out  without MQ_FLAG_PACKED: [N, K] uint8, the codes (NOT shifted back up);
- *        with MQ_FLAG_PACKED (r in {8, 4, 2}, K a multiple of 8/r):
- *        [N, K*r/8] bytes, element k of a row in byte k/(8/r) at bit offset
- *        r * (k mod 8/r).  The packing order is this library's definition.
+ *        with MQ_FLAG_PACKED (r in {8, 6, 4, 3, 2}, K*r a multiple of 8):
+ *        [N, K*r/8] bytes, each row a little-endian bit stream of r bits per
+ *        code: code k at stream bits [r*k, r*k + r), stream bit t = bit t mod 8
+ *        of byte t / 8 (for r in {8, 4, 2}: element k in byte k/(8/r) at bit
+ *        offset r * (k mod 8/r); r = 6 and r = 3, the interpolated bit-widths
+ *        of section 4.2, put 4 resp. 8 codes into 3 bytes).  The packing order
+ *        is this library's definition.
  *   ovf  required iff MQ_FLAG_EXTRA_PRECISION (errata section): the dense plane
  *        written to `out` is the clamped one (bit-identical to the plain
  *        slice) and the weights whose unclamped code is 2^r are listed in *ovf.
@@ -164,13 +168,13 @@ mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const float *alpha,
  *     y[b,n] = alpha_n * (2^s * (sum_k code[n,k] x[b,k] + sum_{k in O_n} x[b,k])
  *                         - z_n * sum_k x[b,k])
  *   x       [B, K] bf16, 1 <= B <= 16
- *   packed  [N, K*r/8] as written by mq_slice with MQ_FLAG_PACKED, r in {8, 4, 2}
+ *   packed  [N, K*r/8] as written by mq_slice with MQ_FLAG_PACKED, r in {8, 6, 4, 3, 2}
  *   alpha_bf16, zero_bf16  [N] bf16
  *   ovf     host struct or NULL (= plain slice); row_ptr/col_idx as written by mq_slice
  *           with nnz <= capacity
  *   y       [B, N] bf16 out
- * A packed row must be a whole number of 16-byte units (K*r a multiple of 128 bits, else
- * MQ_ERR_ALIGN); B*K <= 2^29 and, with an overflow list, K <= 65536 (else MQ_ERR_SHAPE).
+ * A packed row must be a whole number of 16-byte units (K*r a multiple of 128 bits; for
+ * r = 6 and r = 3 of 12-byte units, K*r a multiple of 96 bits; else MQ_ERR_ALIGN); B*K <= 2^29 and, with an overflow list, K <= 65536 (else MQ_ERR_SHAPE).
  * N == 0 is a no-op.
  */
 mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,

@@ -101,6 +101,18 @@ __device__ __forceinline__ uint32_t and_or(uint32_t v, uint32_t mask_s, uint32_t
     return (v & mask_s) | magic_v;
 }
 
+// Geometry per bit-width.  A weight "line" is what eight neighbouring lanes fetch of one row in one
+// load: 128 bytes (16 per lane) for r = 8, 4, 2, and 96 bytes (12 per lane) for the bit streams of
+// r = 6 and r = 3, whose codes straddle any power-of-two boundary but fill 12 bytes exactly
+// (16 resp. 32 codes).  A lane's piece unpacks to XV matrix-core operands of 8 codes each.
+constexpr int line_bytes(int r) { return (r == 6 || r == 3) ? 96 : 128; }
+constexpr int piece_bytes(int r) { return line_bytes(r) / 8; }
+constexpr int line_codes(int r) { return line_bytes(r) * 8 / r; }            // k values per line
+constexpr int operands_per_piece(int r) { return line_codes(r) / 8 / 8; }    // XV
+struct __attribute__((packed, aligned(4))) Piece12 {
+    uint32_t a, b, c;
+};
+
 // Constants of the unpack, pinned in registers once per kernel.
 struct UnpackConsts {
     uint32_t m0, m1, m2;     // scalar: field masks
@@ -109,8 +121,8 @@ struct UnpackConsts {
 template <int R>
 __device__ __forceinline__ UnpackConsts unpack_consts() {
     UnpackConsts c;
-    c.m0 = R == 2 ? 0x00030003u : 0x000F000Fu;
-    c.m1 = 0x000C000Cu;
+    c.m0 = R == 2 ? 0x00030003u : (R == 4 ? 0x000F000Fu : (R == 6 ? 0x0000003Fu : 0x00000007u));
+    c.m1 = R == 2 ? 0x000C000Cu : (R == 6 ? 0x003F0000u : 0x00070000u);
     c.m2 = 0x00300030u;
     c.e128 = kB128;
     c.e32 = kB32;
@@ -156,6 +168,31 @@ __device__ __forceinline__ void gemv_segment(const u32x4 (&wt)[RG], const uint8_
                 acc[rg] = mfma16(a0, xb, acc[rg]);
             }
         }
+    } else if constexpr (R == 6 || R == 3) {
+        // bit stream: code j of the 96-bit piece sits at bits [R j, R j + R); operand v takes codes
+        // 8 v .. 8 v + 7 in their natural order, two per register (low half, high half), each read
+        // as 128 + code under the exponent of e128
+        constexpr int XVP = operands_per_piece(R);
+#pragma unroll
+        for (int v = 0; v < XVP; ++v) {
+            const u32x4 xb = operand(v);
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) {
+                const u32x4 d = wt[rg];
+                auto field_at = [&](int j, int pos) -> uint32_t {  // code j moved to bit `pos`, unmasked
+                    const int bit = R * j, idx = bit >> 5, sh = bit & 31;
+                    if (sh + R > 32) return __builtin_amdgcn_alignbit(d[(idx + 1) & 3], d[idx], (uint32_t)(sh - pos));
+                    return sh >= pos ? d[idx] >> (sh - pos) : d[idx] << (pos - sh);
+                };
+                u32x4 a0;
+#pragma unroll
+                for (int p2 = 0; p2 < 4; ++p2) {
+                    const int j = 8 * v + 2 * p2;
+                    a0[p2] = and_or(field_at(j + 1, 16), uc.m1, and_or(field_at(j, 0), uc.m0, uc.e128));
+                }
+                acc[rg] = mfma16(a0, xb, acc[rg]);
+            }
+        }
     } else {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -190,15 +227,14 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
     const int ks = wave % KS, rw = wave / KS;
     const int i = lane & 15, g = lane >> 4;
     constexpr int ROWS = 16 * RG;          // rows of one row block
-    constexpr int KPB = 8 / R;             // codes per byte
-    constexpr int XV = R == 2 ? 8 : (R == 4 ? 4 : 2);  // 16-byte activation operands per lane and segment
-    constexpr int SEGK = 64 * KPB;         // k values per segment
-    constexpr int SSPB = 512 / (2 * SEGK); // 128-byte weight lines (two segments) per 512-k block of x
+    constexpr int LINEB = line_bytes(R), PIECE = piece_bytes(R);
+    constexpr int XV = operands_per_piece(R);     // 16-byte activation operands per lane and segment
+    constexpr int SSPB = 512 / line_codes(R);     // weight lines (two segments each) per 512-k block of x
 
     float *sums = reinterpret_cast<float *>(lds);
     uint8_t *area = lds + kSumBytes;
     uint8_t *xbuf = area + x_off;
-    const int segs = (a.KB + 127) >> 7;  // 128-byte lines per row
+    const int segs = (a.KB + LINEB - 1) / LINEB;  // weight lines per row
     const int chunk_segs = CB * SSPB;
     const bool single = single_flag != 0;
     const int bb = i & (bp - 1), b15 = bb & 15;
@@ -346,18 +382,25 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                 }
         };
         if constexpr (kEarlyParams) load_params();
-        int off = ks * 128 + lc * 16;  // byte offset, inside the packed row, of the next piece to request
+        int off = ks * LINEB + lc * PIECE;  // byte offset, inside the packed row, of the next piece to request
         // Unconditional (an offset past the row is clamped into it), so that the number of loads in
         // flight is known at compile time and a use only waits for its own load.
-        const int off_last = a.KB - 16;
+        const int off_last = a.KB - PIECE;
         auto fetch_next = [&](u32x4 (&dst)[2][RG]) {
             const uint32_t o = (uint32_t)min(off, off_last);
 #pragma unroll
             for (int rg = 0; rg < RG; ++rg) {
-                dst[0][rg] = *reinterpret_cast<const u32x4 *>(wbase + (roff[rg][0] + o));
-                dst[1][rg] = *reinterpret_cast<const u32x4 *>(wbase + (roff[rg][1] + o));
+                if constexpr (PIECE == 16) {
+                    dst[0][rg] = *reinterpret_cast<const u32x4 *>(wbase + (roff[rg][0] + o));
+                    dst[1][rg] = *reinterpret_cast<const u32x4 *>(wbase + (roff[rg][1] + o));
+                } else {  // 12-byte pieces, 4-byte aligned
+                    const Piece12 p0 = *reinterpret_cast<const Piece12 *>(wbase + (roff[rg][0] + o));
+                    const Piece12 p1 = *reinterpret_cast<const Piece12 *>(wbase + (roff[rg][1] + o));
+                    dst[0][rg] = u32x4{p0.a, p0.b, p0.c, 0u};
+                    dst[1][rg] = u32x4{p1.a, p1.b, p1.c, 0u};
+                }
             }
-            off += KS * 128;
+            off += KS * LINEB;
         };
         // one 128-byte line of each of the wave's 16 RG rows: transpose through LDS, then two segments
         auto compute_line = [&](const u32x4 (&raw)[2][RG], int sr) {
@@ -478,7 +521,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                         if (row < a.N) {
                             float dot = acc[rg][cc];
                             if constexpr (R == 2) dot -= xoff;
-                            if constexpr (R == 4) dot -= 128.0f * xsum;
+                            if constexpr (R == 4 || R == 6 || R == 3) dot -= 128.0f * xsum;
                             if constexpr (EP) dot += ovf[(rw * ROWS + rl) * 16 + b];
                             const float yv = pal[rg][cc] * (kScale * dot - pze[rg][cc] * xsum);
                             a.y[(size_t)b * a.N + row] = (uint16_t)float_to_bf16_bits(yv);
@@ -495,8 +538,8 @@ template <int R, int RG, int D>
 static mq_status launch_gemv(const GemvArgs &a, int nw, int ks, hipStream_t st) {
     int bp = 1;
     while (bp < a.B) bp <<= 1;
-    constexpr int SSPB = 512 / (2 * 64 * (8 / R));  // 128-byte weight lines per 512-k block of x
-    const int lines = (a.KB + 127) / 128;
+    constexpr int SSPB = 512 / line_codes(R);  // weight lines per 512-k block of x
+    const int lines = (a.KB + line_bytes(R) - 1) / line_bytes(R);
     const int blocks_all = (lines + SSPB - 1) / SSPB;  // 512-k blocks that cover K
     // area A: the 2 KB transposition tiles of the waves (reused for the K-split partial sums, which
     // need RG <= 2 KB per wave), then the overflow sums of the group's rows
@@ -553,12 +596,13 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
                                     const uint16_t *zero_bf16, const mq_overflow *ovf, int64_t B, int64_t N,
                                     int64_t K, int r, uint16_t *y, void *hip_stream) {
     using namespace mq;
-    if (r != 8 && r != 4 && r != 2) return MQ_ERR_BITS;
+    if (r != 8 && r != 6 && r != 4 && r != 3 && r != 2) return MQ_ERR_BITS;
     if (B < 1 || B > 16 || N < 0 || K < 1 || N > 0x7FFFFFF0 || K > 0x7FFFFFF0) return MQ_ERR_SHAPE;
     if (ovf && K > 65536) return MQ_ERR_SHAPE;
     if (B * K > (1ll << 29)) return MQ_ERR_SHAPE;  // 32-bit byte offsets into x
     const int64_t kb = K * r / 8;
-    if ((K * r) % 128 != 0) return MQ_ERR_ALIGN;  // packed rows are whole 16-byte units
+    // packed rows are whole 16-byte units (12-byte units for the bit streams of r = 6 and r = 3)
+    if ((K * r) % (8 * piece_bytes(r)) != 0) return MQ_ERR_ALIGN;
     if (N == 0) return MQ_OK;
     if (!x || !packed || !alpha_bf16 || !zero_bf16 || !y) return MQ_ERR_NULL;
     if (ovf && (!ovf->row_ptr || !ovf->col_idx)) return MQ_ERR_NULL;
@@ -587,7 +631,7 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
     // enough loads in flight, and the whole grid resident at once) when there are few row blocks,
     // none when the rows alone provide them.  Workgroups have 8 waves (KS of them per row block),
     // or KS when that is larger.
-    const int64_t segs = cdiv(kb, 128);  // 128-byte lines per row
+    const int64_t segs = cdiv(kb, line_bytes(r));  // weight lines per row
     const int64_t row_blocks = cdiv(N, 16 * rg);
     int ks = 1;
     while (ks < 16 && row_blocks * ks * 2 <= 2048 && 2 * ks <= segs) ks <<= 1;
@@ -603,6 +647,8 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
     MQ_GEMV_CASE(2, 1, 3) MQ_GEMV_CASE(2, 2, 2)
     MQ_GEMV_CASE(4, 1, 4) MQ_GEMV_CASE(4, 2, 2)
     MQ_GEMV_CASE(8, 1, 4) MQ_GEMV_CASE(8, 2, 2)
+    MQ_GEMV_CASE(6, 1, 4) MQ_GEMV_CASE(6, 2, 2)
+    MQ_GEMV_CASE(3, 1, 4) MQ_GEMV_CASE(3, 2, 2)
 #undef MQ_GEMV_CASE
     return MQ_ERR_BITS;
 }

@@ -120,7 +120,8 @@ def test_linear_argument_checks(lib):
 
 def test_gemv_argument_checks(lib):
     g = lib.mq_gemv_sliced
-    assert g(None, None, None, None, None, 1, 64, 256, 3, None, None) == BITS
+    assert g(None, None, None, None, None, 1, 64, 256, 5, None, None) == BITS
+    assert g(None, None, None, None, None, 1, 64, 200, 6, None, None) == ALIGN   # 1200 bits: not whole 12-byte units
     assert g(None, None, None, None, None, 17, 64, 256, 2, None, None) == SHAPE
     assert g(None, None, None, None, None, 0, 64, 256, 2, None, None) == SHAPE
     assert g(None, None, None, None, None, 1, 64, 100, 2, None, None) == ALIGN   # 200 bits per row

@@ -100,7 +100,7 @@ def test_decode_gemv_7b_shapes(mq, oracle, N, K):
     Q, alpha, zero = mq.mq_quantize_int8(W.cuda())
     a16, z16 = mq.mq_params_to_bf16(alpha, zero)
     ab, zb = bf16_bits(a16), bf16_bits(z16)
-    for r in (4, 2):
+    for r in (4, 2, 6, 3):   # 6 and 3: the interpolated bit-widths, stored as bit streams
         packed = mq.mq_slice(Q, r, packed=True)
         pk = packed.cpu().numpy()
         assert np.array_equal(pk, oracle.pack(oracle.slice_codes(Q.cpu().numpy(), r), r))

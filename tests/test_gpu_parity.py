@@ -256,7 +256,7 @@ def test_bwd_bit_width_sets_and_accumulate(mq, oracle, rs, lambdas):
 # decode GEMV
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("N,K", [(256, 256), (100, 512), (16, 64), (1000, 1344), (4096, 4096), (40, 14336)])
-@pytest.mark.parametrize("r", [2, 4, 8])
+@pytest.mark.parametrize("r", [2, 4, 8, 6, 3])
 def test_gemv_plain(mq, oracle, N, K, r):
     W = _randn(N + K + r, N, K, scale=0.02)
     Q, a, z, qo, ao, zo = _quantized(mq, oracle, W)
@@ -269,7 +269,7 @@ def test_gemv_plain(mq, oracle, N, K, r):
         assert rel_l2(y.float().cpu().numpy(), want) <= TOL, (B,)
 
 
-@pytest.mark.parametrize("r,frac", [(2, 0.05), (4, 0.02), (2, 0.125)])
+@pytest.mark.parametrize("r,frac", [(2, 0.05), (4, 0.02), (2, 0.125), (6, 0.02), (3, 0.03)])
 def test_gemv_extra_precision(mq, oracle, r, frac):
     from paper_2502_06786_amd import synth
     N, K = 300, 1024
@@ -286,8 +286,9 @@ def test_gemv_extra_precision(mq, oracle, r, frac):
         want = oracle.gemv_sliced(bf16_bits(x), packed.cpu().numpy(), bf16_bits(a), bf16_bits(z), r, K, ovf=(rp, ci))
         assert rel_l2(y.float().cpu().numpy(), want) <= TOL, (B,)
         plain = oracle.gemv_sliced(bf16_bits(x), packed.cpu().numpy(), bf16_bits(a), bf16_bits(z), r, K)
-        # the overflow term itself (a few % of y) is there, up to the bf16 rounding of y
-        assert rel_l2(y.float().cpu().numpy() - plain, want - plain) <= 0.25
+        # the overflow term itself (a few % of y; four times smaller at r = 6, where one step is 4
+        # instead of 16 or 64) is there, up to the bf16 rounding of y
+        assert rel_l2(y.float().cpu().numpy() - plain, want - plain) <= (0.25 if r <= 4 else 0.6)
 
 
 @pytest.mark.parametrize("r,B", [(2, 1), (4, 3), (8, 16)])
@@ -315,7 +316,7 @@ def test_gemv_one_hot_exact(mq, oracle):
     q = torch.arange(N * K, dtype=torch.int32).mul(7).remainder(256).to(torch.uint8).reshape(N, K)
     a = torch.ones(N).to(torch.bfloat16)
     z = torch.zeros(N).to(torch.bfloat16)
-    for r in (2, 4, 8):
+    for r in (2, 4, 8, 6, 3):
         packed = mq.mq_slice(dev(q), r, packed=True)
         for k0 in (0, 100, 240):
             x = torch.zeros(16, K)
@@ -346,7 +347,7 @@ def test_error_codes(mq):
         mq.mq_slice(Q, 9)
     assert e.value.status == 3
     with pytest.raises(mq.MqError) as e:
-        mq.mq_slice(Q, 3, packed=True)
+        mq.mq_slice(Q, 5, packed=True)
     assert e.value.status == 3
     X = torch.zeros(4, 64, dtype=torch.bfloat16, device="cuda")
     a = torch.ones(8, device="cuda")
