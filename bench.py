@@ -303,8 +303,9 @@ def gemv_sweep(torch, mq, synth):
 
 
 def cpu_baseline(torch, synth, rs, lambdas):
-    """The CPU oracle as it stands on a bounded slab of the gate linear: forward for 2048 of the 9216
-    output channels, dX for 512 of the 4096 tokens, dW for 1024 of the 9216 weight rows."""
+    """The CPU oracle as it stands on a bounded slab of the gate linear (about 10-15 s of host work):
+    forward for 6144 of the 9216 output channels, dX for 1536 of the 4096 tokens, dW for 3072 of the
+    9216 weight rows."""
     import numpy as np
     import oracle
 
@@ -313,7 +314,7 @@ def cpu_baseline(torch, synth, rs, lambdas):
 
     case = synth.linear_case(2, "gate")
     Wn = case.W.numpy()
-    nf, md, nw = 2048, 512, 1024
+    nf, md, nw = 6144, 1536, 3072
     t0 = time.perf_counter()
     q, a, z = oracle.quantize_int8(Wn)
     for r in (4, 2):
