@@ -189,6 +189,8 @@ def main():
         if not args.no_probes:
             best = out["gemv_roofline"]["best_int2"]
             best["frac_of_measured_read"] = round(best["achieved"] / peaks["hbm_read_85MB_GBs"], 4)
+    if not args.no_gemv_sweep:
+        out["extra_precision_gemv"] = ep_gemv(torch, mq, synth)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, synth, rs, lambdas)
     print(json.dumps(out))
@@ -299,6 +301,60 @@ def gemv_sweep(torch, mq, synth):
     res["best_int2"] = {"case": best[0], "achieved": round(best[1], 1), "frac": round(best[1] / PEAK_HBM_GBS, 4)}
     res["note"] = ("time per call from a HIP-graph replay of one stream-ordered sweep over independent copies of the "
                    "matrix (more than the 256 MB last-level cache holds); gaps between kernels included")
+    return res
+
+
+def ep_gemv(torch, mq, synth):
+    """Configuration 5: int2 decode GEMV on the 27B-shaped gate matrix (36864 x 4608) with codes planted at the
+    paper's overflow density (about 5 % at r = 2, Table 7): the plain int2 plane, the plane plus the sparse
+    overflow list, and the dense 3-bit extra-precision plane.  Seven copies of each plane in turn (more than
+    the last-level cache holds), HIP-graph replay, time per call."""
+    N, K, r = 36864, 4608, 2
+    q = synth.planted_overflow_codes(55, N, K, r, 0.05).cuda()
+    plain, ovf = mq.mq_slice(q, r, packed=True, extra_precision=True, capacity=N * K // 8)
+    dense = mq.mq_slice(q, r, packed=True, extra_precision=True, dense_ep=True)
+    torch.cuda.synchronize()
+    nnz = int(ovf.nnz.item())
+    f = nnz / (N * K)
+    del q
+    g = torch.Generator().manual_seed(5)
+    a16 = (torch.rand(N, generator=g) * 1e-3 + 1e-4).to(torch.bfloat16).cuda()
+    z16 = (torch.rand(N, generator=g) * 255).to(torch.bfloat16).cuda()
+    plains = [plain] + [plain.clone() for _ in range(6)]
+    denses = [dense] + [dense.clone() for _ in range(6)]
+    res = {"shape": f"{N}x{K}", "overflow_fraction": round(f, 4), "avg_bits_paper_accounting": round(r + f, 3),
+           "stored_bits_list": round(r + 16 * f + 32.0 / K, 3), "stored_bits_dense": 3.0}
+    for B in (1, 4, 16):
+        x = synth.activations(5, f"ep{B}", B, K).cuda()
+        y = torch.empty(B, N, dtype=torch.bfloat16, device="cuda")
+        variants = {
+            "plain_int2": (lambda p: mq.mq_gemv_sliced(x, p, a16, z16, r, K, y=y), plains, N * K // 4),
+            "int2_plus_list": (lambda p: mq.mq_gemv_sliced(x, p, a16, z16, r, K, y=y, ovf=ovf), plains,
+                               N * K // 4 + 2 * nnz + 4 * (N + 1)),
+            "dense_3bit": (lambda p: mq.mq_gemv_sliced_dense_ep(x, p, a16, z16, r, K, y=y), denses, N * K * 3 // 8),
+        }
+        for name, (fn, planes, wbytes) in variants.items():
+            fn(planes[0])
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for p in planes:
+                    fn(p)
+            graph.replay()
+            torch.cuda.synchronize()
+            times = []
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                graph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1) / len(planes))
+            del graph
+            ms = sorted(times)[1]
+            nbytes = wbytes + 4 * N + 2 * B * K + 2 * B * N
+            res[f"{name}_B{B}"] = {"us": round(ms * 1e3, 2), "GBs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                   "frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
     return res
 
 

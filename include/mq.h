@@ -51,7 +51,9 @@ typedef enum {
 enum {
     MQ_FLAG_EXTRA_PRECISION = 1, /* errata section: slice without the clamp (2^r + 1 levels) */
     MQ_FLAG_PACKED = 2,          /* mq_slice: write 8/r codes per byte instead of one        */
-    MQ_FLAG_ACCUM_DW = 4         /* mq_linear_bwd: dW += instead of dW =                     */
+    MQ_FLAG_ACCUM_DW = 4,        /* mq_linear_bwd: dW += instead of dW =                     */
+    MQ_FLAG_EP_DENSE = 8         /* mq_slice, with the two flags above: one plane of r + 1 bits
+                                    per code that keeps code 2^r, instead of plane + list     */
 };
 
 enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1 };
@@ -117,6 +119,11 @@ mq_status mq_params_to_bf16(const float *alpha, const float *zero, int64_t N, ui
  *        written to `out` is the clamped one (bit-identical to the plain
  *        slice) and the weights whose unclamped code is 2^r are listed in *ovf.
  *        `ovf` itself is a host struct holding device pointers.  Needs K <= 65536.
+ *        With MQ_FLAG_EP_DENSE as well (and MQ_FLAG_PACKED): no list; `out` is
+ *        [N, K*(r+1)/8], the same bit-stream format with r + 1 bits per code,
+ *        holding the unclamped codes 0 .. 2^r (r + 1 in {2, 3, 4, 6, 8}); this is
+ *        the layout of choice where the overflow bucket is dense (about 5 % of
+ *        the weights at r = 2 in the paper's Table 7) and ovf may be NULL.
  */
 mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uint32_t flags,
                    uint8_t *out, const mq_overflow *ovf, void *hip_stream);
@@ -180,6 +187,16 @@ mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const float *alpha,
 mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                          const uint16_t *zero_bf16, const mq_overflow *ovf,
                          int64_t B, int64_t N, int64_t K, int r, uint16_t *y, void *hip_stream);
+
+/*
+ * The same GEMV on a dense extra-precision plane (mq_slice with MQ_FLAG_EXTRA_PRECISION |
+ * MQ_FLAG_PACKED | MQ_FLAG_EP_DENSE): codes 0 .. 2^r stored with r + 1 bits, one code step
+ * still 2^(8-r) (errata section: int2 with the extra bucket has the levels 0, 64, 128, 192, 256).
+ *   packed  [N, K*(r+1)/8], r + 1 in {2, 3, 4, 6, 8}; alignment as for a plain (r+1)-bit plane
+ */
+mq_status mq_gemv_sliced_dense_ep(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
+                                  const uint16_t *zero_bf16, int64_t B, int64_t N, int64_t K, int r,
+                                  uint16_t *y, void *hip_stream);
 
 /*
  * Measurement helpers (they compute nothing of the method): ceilings of this GPU as measured by

@@ -239,8 +239,10 @@ def linear_bwd_dw_sampled(X_bf16, dYs_bf16, lambdas, ns, ks):
     return out
 
 
-def gemv_sliced(x_bf16, packed, alpha_bf16, zero_bf16, r: int, K: int, ovf=None):
-    """y = x . What_r^T from a packed plane with bf16 alpha, z; ovf = (row_ptr, col_idx) or None."""
+def gemv_sliced(x_bf16, packed, alpha_bf16, zero_bf16, r: int, K: int, ovf=None, shift: int = -1):
+    """y = x . What_r^T from a packed plane with bf16 alpha, z; ovf = (row_ptr, col_idx) or None.
+    shift: s of the grid the stored codes live on (default 8 - r); a dense extra-precision plane of the
+    rv-bit slice is read with r = rv + 1, shift = 8 - rv."""
     x = _c(x_bf16, np.uint16)
     B = x.shape[0]
     assert x.shape[1] == K
@@ -255,5 +257,5 @@ def gemv_sliced(x_bf16, packed, alpha_bf16, zero_bf16, r: int, K: int, ovf=None)
         ci = _c(ovf[1], np.uint16)
     y = np.empty((B, N), np.float64)
     _load().mqo_gemv_sliced(_p(x), _p(packed), _p(a), _p(z), _p(rp), _p(ci), _i64(B), _i64(N), _i64(K),
-                            ctypes.c_int(r), _p(y))
+                            ctypes.c_int(r), ctypes.c_int(shift), _p(y))
     return y

@@ -315,13 +315,15 @@ void mqo_linear_bwd_dw_sampled(const uint16_t *X, const uint16_t *const *dY, con
  *     y[b,n] = sum_k x[b,k] * alpha_n * (S[n,k] - z_n)
  * where S = code << (8-r) is read back from the packed plane, alpha and z
  * are bf16, and, when an overflow list is given (extra precision), S gains
- * one more 2^(8-r) at every listed column.
+ * one more 2^(8-r) at every listed column.  `shift` < 0 means s = 8 - r; a
+ * dense extra-precision plane (codes 0 .. 2^rv stored with r = rv + 1 bits,
+ * errata section) is read with shift = 8 - rv.
  * ---------------------------------------------------------------------- */
 void mqo_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                      const uint16_t *zero_bf16, const int32_t *row_ptr, const uint16_t *col_idx,
-                     int64_t B, int64_t N, int64_t K, int r, double *y) {
+                     int64_t B, int64_t N, int64_t K, int r, int shift, double *y) {
     int64_t kb = K * r / 8;
-    int s = 8 - r;
+    int s = shift < 0 ? 8 - r : shift;
 #pragma omp parallel for schedule(static)
     for (int64_t n = 0; n < N; ++n) {
         double a = bf16_bits_to_f64(alpha_bf16[n]);

@@ -22,7 +22,8 @@ MQ_OP_LINEAR_FWD = 0
 MQ_OP_LINEAR_BWD = 1
 
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
-           "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string", "mq_probe_mfma", "mq_probe_read"]
+           "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string", "mq_probe_mfma", "mq_probe_read",
+           "mq_gemv_sliced_dense_ep"]
 
 
 class MqError(RuntimeError):
@@ -54,6 +55,7 @@ def _load() -> ctypes.CDLL:
     lib.mq_status_string.argtypes = [ci]
     lib.mq_status_string.restype = ctypes.c_char_p
     lib.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
+    lib.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
     lib.mq_probe_read.argtypes = [vp, i64, vp, vp]
     for name in EXPORTS:
@@ -67,6 +69,9 @@ _lib = _load()
 
 def lib() -> ctypes.CDLL:
     return _lib
+
+
+MQ_FLAG_EP_DENSE = 8
 
 
 def status_string(status: int) -> str:
@@ -138,6 +143,20 @@ def mq_params_to_bf16(alpha, zero, alpha_bf16=None, zero_bf16=None):
     return alpha_bf16, zero_bf16
 
 
+def mq_gemv_sliced_dense_ep(x, packed, alpha_bf16, zero_bf16, r: int, K: int, y=None):
+    """x bf16 [B, K], packed uint8 [N, K*(r+1)/8] holding the unclamped extra-precision codes -> y bf16 [B, N]."""
+    B = x.shape[0]
+    N = packed.shape[0]
+    if x.shape[1] != K or packed.shape[1] != K * (r + 1) // 8:
+        raise ValueError("shape mismatch")
+    if y is None:
+        y = torch.empty(B, N, dtype=torch.bfloat16, device=x.device)
+    st = _lib.mq_gemv_sliced_dense_ep(_ptr(x, torch.bfloat16), _ptr(packed, torch.uint8), _ptr(alpha_bf16, torch.bfloat16),
+                                      _ptr(zero_bf16, torch.bfloat16), B, N, K, r, _ptr(y, torch.bfloat16), _stream())
+    _check(st, "mq_gemv_sliced_dense_ep")
+    return y
+
+
 def mq_probe_mfma(operands, iters: int, sink=None):
     """Measurement helper: `iters` rounds of 12 bf16 32x32x16 products per wave on 1024 waves, fed with the
     32768 bf16 values of `operands`.  Returns the flop count of the launch."""
@@ -157,13 +176,19 @@ def mq_probe_read(src, sink=None):
 
 
 def mq_slice(Q, r: int, packed: bool = False, extra_precision: bool = False, out=None, ovf: Overflow | None = None,
-             capacity: int | None = None):
-    """Slice int8 codes to r bits.  Returns `out`, or (out, Overflow) with extra_precision."""
+             capacity: int | None = None, dense_ep: bool = False):
+    """Slice int8 codes to r bits.  Returns `out`, or (out, Overflow) with extra_precision; with dense_ep (and
+    packed, extra_precision) a single plane of r + 1 bits per code."""
     N, K = Q.shape
     flags = (MQ_FLAG_PACKED if packed else 0) | (MQ_FLAG_EXTRA_PRECISION if extra_precision else 0)
+    flags |= MQ_FLAG_EP_DENSE if dense_ep else 0
     if out is None:
-        cols = K * r // 8 if packed else K
+        cols = K * (r + 1 if dense_ep else r) // 8 if packed else K
         out = torch.empty(N, cols, dtype=torch.uint8, device=Q.device)
+    if dense_ep:
+        st = _lib.mq_slice(_ptr(Q, torch.uint8), N, K, r, flags, _ptr(out, torch.uint8), None, _stream())
+        _check(st, "mq_slice")
+        return out
     c_ovf = None
     if extra_precision:
         if ovf is None:

@@ -25,7 +25,8 @@ struct GemvArgs {
     const uint16_t *col_idx;  // overflow columns
     uint16_t *y;              // [B, N] bf16
     int B, N, K;
-    int KB;  // bytes per packed row
+    int KB;       // bytes per packed row
+    float scale;  // 2^s: one step of the stored codes on the int8 grid
 };
 
 __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -505,7 +506,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                     }
             }
             // y[b, n] = alpha_n * (2^s * (codes.x [+ overflow]) - z_n * sum_k x)
-            constexpr float kScale = (float)(1 << (8 - R));
+            const float kScale = a.scale;
             const int b = lane & 15;
             if (b < a.B) {
                 float xsum = 0.f, xoff = 0.f;
@@ -592,9 +593,10 @@ static mq_status launch_gemv(const GemvArgs &a, int nw, int ks, hipStream_t st) 
 
 }  // namespace mq
 
-extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
-                                    const uint16_t *zero_bf16, const mq_overflow *ovf, int64_t B, int64_t N,
-                                    int64_t K, int r, uint16_t *y, void *hip_stream) {
+// r = bits per stored code, shift = s of the grid the codes live on (8 - r for a plain plane)
+static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
+                               const uint16_t *zero_bf16, const mq_overflow *ovf, int64_t B, int64_t N, int64_t K,
+                               int r, int shift, uint16_t *y, void *hip_stream) {
     using namespace mq;
     if (r != 8 && r != 6 && r != 4 && r != 3 && r != 2) return MQ_ERR_BITS;
     if (B < 1 || B > 16 || N < 0 || K < 1 || N > 0x7FFFFFF0 || K > 0x7FFFFFF0) return MQ_ERR_SHAPE;
@@ -620,6 +622,7 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
     a.N = (int)N;
     a.K = (int)K;
     a.KB = (int)kb;
+    a.scale = (float)(1 << shift);
 
     // Rows per wave (16 RG): every activation operand read from LDS serves RG matrix-core products, so
     // larger batches and tall matrices take two row groups; short ones keep RG = 1 for more waves.
@@ -651,4 +654,19 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
     MQ_GEMV_CASE(3, 1, 4) MQ_GEMV_CASE(3, 2, 2)
 #undef MQ_GEMV_CASE
     return MQ_ERR_BITS;
+}
+
+extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
+                                    const uint16_t *zero_bf16, const mq_overflow *ovf, int64_t B, int64_t N,
+                                    int64_t K, int r, uint16_t *y, void *hip_stream) {
+    if (r < 1 || r > 8) return MQ_ERR_BITS;
+    return gemv_dispatch(x, packed, alpha_bf16, zero_bf16, ovf, B, N, K, r, 8 - r, y, hip_stream);
+}
+
+extern "C" mq_status mq_gemv_sliced_dense_ep(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
+                                             const uint16_t *zero_bf16, int64_t B, int64_t N, int64_t K, int r,
+                                             uint16_t *y, void *hip_stream) {
+    if (r < 1 || r > 7) return MQ_ERR_BITS;
+    // codes 0 .. 2^r of the r-bit extra-precision slice, stored with r + 1 bits, one step = 2^(8 - r)
+    return gemv_dispatch(x, packed, alpha_bf16, zero_bf16, nullptr, B, N, K, r + 1, 8 - r, y, hip_stream);
 }

@@ -21,16 +21,18 @@ __device__ __forceinline__ uint32_t slice4(uint32_t d, uint32_t half2, uint32_t 
     return e_lo | (o_lo << 8) | (e_hi << 16) | (o_hi << 24);
 }
 
-__device__ __forceinline__ uint32_t slice1(uint32_t q, int r) {
-    const uint32_t s = 8 - r, half = (1u << s) >> 1, top = (1u << r) - 1;
+__device__ __forceinline__ uint32_t slice1(uint32_t q, uint32_t s, uint32_t top) {
+    const uint32_t half = (1u << s) >> 1;
     return min((q + half) >> s, top);
 }
 
 // 16 codes per thread.  MODE 0: one code per byte; MODE 4 / 2: packed nibbles / crumbs.
+// s = 8 - r, top = the largest code (2^r - 1, or 2^r when the clamp is dropped for a dense
+// extra-precision plane, which is then packed one bit wider than r).
 template <int MODE>
-__global__ __launch_bounds__(256) void slice_kernel(const uint8_t *__restrict__ Q, int64_t count, int r,
-                                                    uint8_t *__restrict__ out) {
-    const uint32_t s = 8 - r, half = (1u << s) >> 1, top = (1u << r) - 1;
+__global__ __launch_bounds__(256) void slice_kernel(const uint8_t *__restrict__ Q, int64_t count, uint32_t s,
+                                                    uint32_t top, uint8_t *__restrict__ out) {
+    const uint32_t half = (1u << s) >> 1;
     const uint32_t half2 = half | (half << 16), top2 = top | (top << 16);
     const int64_t chunks = count >> 4;
     const int64_t stride = (int64_t)gridDim.x * 256;
@@ -68,12 +70,12 @@ __global__ __launch_bounds__(256) void slice_kernel(const uint8_t *__restrict__ 
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         const int64_t done = chunks << 4;
         if constexpr (MODE == 0) {
-            for (int64_t i = done; i < count; ++i) out[i] = (uint8_t)slice1(Q[i], r);
+            for (int64_t i = done; i < count; ++i) out[i] = (uint8_t)slice1(Q[i], s, top);
         } else {
             constexpr int PER = 8 / MODE;
             for (int64_t i = done; i < count; i += PER) {
                 uint32_t b = 0;
-                for (int j = 0; j < PER; ++j) b |= slice1(Q[i + j], r) << (MODE * j);
+                for (int j = 0; j < PER; ++j) b |= slice1(Q[i + j], s, top) << (MODE * j);
                 out[i / PER] = (uint8_t)b;
             }
         }
@@ -84,10 +86,10 @@ __global__ __launch_bounds__(256) void slice_kernel(const uint8_t *__restrict__ 
 // section 4.2): a little-endian bit stream, code k at stream bits [r k, r k + r).  32 codes per
 // thread become exactly R dwords.
 template <int R>
-__global__ __launch_bounds__(256) void slice_stream_kernel(const uint8_t *__restrict__ Q, int64_t count,
-                                                           uint8_t *__restrict__ out) {
-    constexpr uint32_t s = 8 - R, half = (1u << s) >> 1, top = (1u << R) - 1;
-    constexpr uint32_t half2 = half | (half << 16), top2 = top | (top << 16);
+__global__ __launch_bounds__(256) void slice_stream_kernel(const uint8_t *__restrict__ Q, int64_t count, uint32_t s,
+                                                           uint32_t top, uint8_t *__restrict__ out) {
+    const uint32_t half = (1u << s) >> 1;
+    const uint32_t half2 = half | (half << 16), top2 = top | (top << 16);
     const int64_t groups = count >> 5;
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < groups; c += stride) {
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(256) void slice_stream_kernel(const uint8_t *__rest
         int have = 0;
         int64_t byte = done * R / 8;
         for (int64_t i = done; i < count; ++i) {
-            acc |= slice1(Q[i], R) << have;
+            acc |= slice1(Q[i], s, top) << have;
             have += R;
             while (have >= 8) {
                 out[byte++] = (uint8_t)acc;
@@ -269,9 +271,12 @@ extern "C" mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uin
     if (N < 0 || K < 0) return MQ_ERR_SHAPE;
     if (r < 1 || r > 8) return MQ_ERR_BITS;
     const bool packed = flags & MQ_FLAG_PACKED, ep = flags & MQ_FLAG_EXTRA_PRECISION;
-    if (packed && !(r == 8 || r == 6 || r == 4 || r == 3 || r == 2)) return MQ_ERR_BITS;
-    if (packed && ((K * r) % 8) != 0) return MQ_ERR_ALIGN;  // rows are whole bytes
-    if (ep) {
+    const bool dense_ep = flags & MQ_FLAG_EP_DENSE;
+    if (dense_ep && !(packed && ep)) return MQ_ERR_BITS;
+    const int rp = dense_ep ? r + 1 : r;  // bits per stored code
+    if (packed && !(rp == 8 || rp == 6 || rp == 4 || rp == 3 || rp == 2)) return MQ_ERR_BITS;
+    if (packed && ((K * rp) % 8) != 0) return MQ_ERR_ALIGN;  // rows are whole bytes
+    if (ep && !dense_ep) {
         if (!ovf) return MQ_ERR_NULL;
         if (N > 0 && (!ovf->row_ptr || !ovf->nnz || (ovf->capacity > 0 && !ovf->col_idx))) return MQ_ERR_NULL;
         if (ovf->capacity < 0 || K > 65536 || N > 0x7FFFFFFE || (N > 0 && K > 0x7FFFFFFF / N))
@@ -287,21 +292,23 @@ extern "C" mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uin
     const int64_t chunks = count >> 4;
     int64_t blocks = cdiv(chunks > 0 ? chunks : 1, 256);
     if (blocks > 256 * 32) blocks = 256 * 32;  // grid-stride beyond 32 blocks per CU
-    if (packed && (r == 6 || r == 3)) {
+    const uint32_t sh = (uint32_t)(8 - r);
+    const uint32_t top = dense_ep ? (1u << r) : (1u << r) - 1;  // a dense extra-precision plane keeps code 2^r
+    if (packed && (rp == 6 || rp == 3)) {
         int64_t sblocks = cdiv(std::max<int64_t>(count >> 5, 1), 256);
         if (sblocks > 256 * 32) sblocks = 256 * 32;
-        if (r == 6)
-            slice_stream_kernel<6><<<dim3((unsigned)sblocks), dim3(256), 0, st>>>(Q, count, out);
+        if (rp == 6)
+            slice_stream_kernel<6><<<dim3((unsigned)sblocks), dim3(256), 0, st>>>(Q, count, sh, top, out);
         else
-            slice_stream_kernel<3><<<dim3((unsigned)sblocks), dim3(256), 0, st>>>(Q, count, out);
-    } else if (!packed || r == 8) {
-        slice_kernel<0><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, r, out);
-    } else if (r == 4) {
-        slice_kernel<4><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, r, out);
+            slice_stream_kernel<3><<<dim3((unsigned)sblocks), dim3(256), 0, st>>>(Q, count, sh, top, out);
+    } else if (!packed || rp == 8) {
+        slice_kernel<0><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, sh, top, out);
+    } else if (rp == 4) {
+        slice_kernel<4><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, sh, top, out);
     } else {
-        slice_kernel<2><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, r, out);
+        slice_kernel<2><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(Q, count, sh, top, out);
     }
-    if (ep) {
+    if (ep && !dense_ep) {
         const uint32_t half = (1u << (8 - r)) >> 1;
         const uint32_t thr = r == 8 ? 256u : 256u - half;  // r = 8: nothing overflows
         overflow_count_kernel<<<dim3((unsigned)N), dim3(256), 0, st>>>(Q, K, thr, ovf->row_ptr);

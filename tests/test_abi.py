@@ -35,6 +35,7 @@ def lib():
     lib_.mq_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_gemv_sliced.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
+    lib_.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
     lib_.mq_probe_read.argtypes = [vp, i64, vp, vp]
     lib_.mq_workspace_bytes.argtypes = [ci, i64, i64, i64, ci]
@@ -128,6 +129,18 @@ def test_gemv_argument_checks(lib):
     assert g(None, None, None, None, None, 16, 64, 1 << 26, 2, None, None) == SHAPE  # B * K beyond 2^29
     assert g(None, None, None, None, None, 1, 0, 256, 2, None, None) == OK
     assert g(None, None, None, None, None, 1, 64, 256, 2, None, None) == NULL
+
+
+def test_dense_extra_precision_argument_checks(lib):
+    g = lib.mq_gemv_sliced_dense_ep
+    assert g(None, None, None, None, 1, 64, 256, 4, None, None) == BITS     # 5 bits per code are not built
+    assert g(None, None, None, None, 1, 64, 256, 8, None, None) == BITS
+    assert g(None, None, None, None, 1, 64, 100, 2, None, None) == ALIGN    # 300 bits per row
+    assert g(None, None, None, None, 1, 64, 256, 2, None, None) == NULL
+    s = lib.mq_slice
+    assert s(None, 4, 64, 2, 8, None, None, None) == BITS                   # dense needs packed + extra precision
+    assert s(None, 4, 64, 4, 11, None, None, None) == BITS                  # 5 bits per code
+    assert s(None, 4, 64, 2, 11, None, None, None) == NULL                  # fine up to the pointers (no list needed)
 
 
 def test_probe_argument_checks(lib):

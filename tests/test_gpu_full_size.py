@@ -135,6 +135,9 @@ def test_extra_precision_gemv_27b_shape(mq, oracle, name):
         assert np.array_equal(ovf.col_idx.cpu().numpy().view(np.uint16)[:ci.size], ci)
         pk = packed.cpu().numpy()
         print(f"  {label}: overflow fraction {ci.size / qn.size:.4f}", flush=True)
+        dense = mq.mq_slice(codes, 2, packed=True, extra_precision=True, dense_ep=True)
+        dn = dense.cpu().numpy()
+        assert np.array_equal(dn[:1024], oracle.pack(oracle.slice_codes(qn[:1024], 2, ep=True), 3))
         for B in synth.DECODE_BATCHES:
             x = synth.activations(5, f"x{B}:" + name, B, K)
             for use_ovf in (False, True):
@@ -142,3 +145,6 @@ def test_extra_precision_gemv_27b_shape(mq, oracle, name):
                 want = oracle.gemv_sliced(bf16_bits(x), pk, ab, zb, 2, K, ovf=(rp, ci) if use_ovf else None)
                 err = rel_l2(y.float().cpu().numpy(), want)
                 assert err <= TOL, (label, B, use_ovf, err)
+                if use_ovf:   # the dense 3-bit plane holds the same weights
+                    yd = mq.mq_gemv_sliced_dense_ep(x.cuda(), dense, a16, z16, 2, K)
+                    assert rel_l2(yd.float().cpu().numpy(), want) <= TOL, (label, B, "dense")

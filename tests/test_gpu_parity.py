@@ -291,6 +291,29 @@ def test_gemv_extra_precision(mq, oracle, r, frac):
         assert rel_l2(y.float().cpu().numpy() - plain, want - plain) <= (0.25 if r <= 4 else 0.6)
 
 
+@pytest.mark.parametrize("r", [2, 3, 5, 1, 7])
+def test_dense_extra_precision_plane_and_gemv(mq, oracle, r):
+    """One plane of r + 1 bits per code holding the unclamped extra-precision codes, and the GEMV that reads it."""
+    from paper_2502_06786_amd import synth
+    N, K = 200, 1536
+    q = synth.uniform_codes(40 + r, N, K) if r != 2 else synth.planted_overflow_codes(41, N, K, 2, 0.05)
+    a = (torch.rand(N, generator=torch.Generator().manual_seed(8)) * 1e-3 + 1e-4).to(torch.bfloat16)
+    z = (torch.rand(N, generator=torch.Generator().manual_seed(9)) * 255).to(torch.bfloat16)
+    dense = mq.mq_slice(dev(q), r, packed=True, extra_precision=True, dense_ep=True)
+    want_plane = oracle.pack(oracle.slice_codes(q.numpy(), r, ep=True), r + 1)
+    assert np.array_equal(dense.cpu().numpy(), want_plane)
+    rp, ci = oracle.overflow_csr(q.numpy(), r)
+    plain = oracle.pack(oracle.slice_codes(q.numpy(), r), r) if r in (2, 3) else None
+    for B in (1, 4, 16):
+        x = _randn(B + r, B, K).to(torch.bfloat16)
+        y = mq.mq_gemv_sliced_dense_ep(dev(x), dense, dev(a), dev(z), r, K)
+        want = oracle.gemv_sliced(bf16_bits(x), want_plane, bf16_bits(a), bf16_bits(z), r + 1, K, shift=8 - r)
+        assert rel_l2(y.float().cpu().numpy(), want) <= TOL, (B,)
+        if plain is not None:   # the same weights as clamped plane + list
+            same = oracle.gemv_sliced(bf16_bits(x), plain, bf16_bits(a), bf16_bits(z), r, K, ovf=(rp, ci))
+            assert np.array_equal(want, same)
+
+
 @pytest.mark.parametrize("r,B", [(2, 1), (4, 3), (8, 16)])
 def test_gemv_many_rows(mq, oracle, r, B):
     """More groups of row blocks than workgroups are resident at once (every workgroup walks over several

@@ -433,3 +433,29 @@ def test_gemv_one_hot_and_ep_difference(oracle):
         xf = x.to(torch.float64).numpy()
         want = np.stack([[a32[n] * 2.0 ** s * xf[b, ci[rp[n]:rp[n + 1]]].sum() for n in range(N)] for b in range(3)])
         np.testing.assert_allclose(d, want, rtol=1e-9, atol=1e-12)
+
+
+def test_gemv_dense_extra_precision_plane(oracle):
+    """The dense extra-precision plane (unclamped codes, one bit wider) and the clamped plane + overflow list are
+    two storage forms of the same weights: both routes through the oracle give the same y, and a one-hot
+    activation reads back the extra-precision level set of the errata section (0, 64, 128, 192, 256 at r = 2)."""
+    rng = np.random.default_rng(21)
+    N, K = 12, 64
+    q = rng.integers(0, 256, (N, K), dtype=np.uint8)
+    q[0, :5] = [0, 40, 100, 170, 240]                  # levels 0, 64, 128, 192, 256
+    ones = np.full(N, 0x3F80, np.uint16)               # alpha = 1.0 in bf16
+    zeros = np.zeros(N, np.uint16)
+    for rv in (2, 3, 5):
+        dense = oracle.pack(oracle.slice_codes(q, rv, ep=True), rv + 1)
+        plain = oracle.pack(oracle.slice_codes(q, rv), rv)
+        rp, ci = oracle.overflow_csr(q, rv)
+        x = rng.standard_normal((3, K)).astype(np.float32)
+        xb = (x.view(np.uint32) >> 16).astype(np.uint16)
+        y_dense = oracle.gemv_sliced(xb, dense, ones, zeros, rv + 1, K, shift=8 - rv)
+        y_list = oracle.gemv_sliced(xb, plain, ones, zeros, rv, K, ovf=(rp, ci))
+        assert np.array_equal(y_dense, y_list)
+    onehot = np.zeros((5, K), np.uint16)
+    onehot[np.arange(5), np.arange(5)] = 0x3F80
+    dense = oracle.pack(oracle.slice_codes(q, 2, ep=True), 3)
+    y = oracle.gemv_sliced(onehot, dense, ones, zeros, 3, K, shift=6)
+    assert y[np.arange(5), 0].tolist() == [0.0, 64.0, 128.0, 192.0, 256.0]
