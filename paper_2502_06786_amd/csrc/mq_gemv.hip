@@ -468,27 +468,103 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
 #pragma unroll
             for (int rg = 0; rg < RG; ++rg) part[(wave * RG + rg) * 64 + lane] = acc[rg];
         }
-        // extra precision: sum of x over each row's overflow columns, rows dealt out to all waves
+        // Extra precision: ovf[row][b] = sum of x[b, k] over the row's overflow columns.  A wave takes a
+        // contiguous range of the group's rows, whose list entries are contiguous too, and walks
+        // them 64 at a time (coalesced 2-byte loads).  Lane l keeps, per batch entry b, the sum of
+        // what it gathered for the row being walked; the wave-wide reduction happens once per row,
+        // where the row ends.  The row pointers of the range sit in one register (lane j: the
+        // pointer of the j-th row).  x is gathered from its staged copy in LDS when all of it is
+        // resident, from global memory otherwise.
         if constexpr (EP) {
-            for (int r = wave; r < RW * ROWS; r += NW) {
-                const int row = nb + r;
-                float sx[16];
-#pragma unroll
-                for (int b = 0; b < 16; ++b) sx[b] = 0.f;
-                if (row < a.N) {
-                    const int lo = a.row_ptr[row], hi = a.row_ptr[row + 1];
-                    for (int p = lo + lane; p < hi; p += 64) {
-                        const int col = a.col_idx[p];
-#pragma unroll
-                        for (int b = 0; b < 16; ++b)
-                            if (b < a.B) sx[b] += bf16_bits_to_float(a.x[(size_t)b * a.K + col]);
+            const int rpw = RW * ROWS / NW;  // rows per wave: 16 RG / KS >= 1
+            float *mine = ovf + wave * rpw * 16;
+            for (int t = lane; t < rpw * 16; t += 64) mine[t] = 0.f;
+            const int ra = nb + wave * rpw;
+            const int nrows = min(rpw, a.N - ra);  // wave-uniform
+            if (nrows > 0) {
+                const int myrp = lane <= nrows ? a.row_ptr[ra + lane] : 0x7FFFFFFF;
+                const int e1 = __builtin_amdgcn_readlane(myrp, nrows);
+                // x[b, k] as staged: block k / 512 of entry b, 16-byte slot (k % 512) / 8 kept at
+                // slot ^ b, and inside the slot (or the pair of slots, int2) the order the pairing
+                // pass left: elements j and j + 8 (int2) or j and j + 4 (int4) share a dword
+                auto staged = [&](int b, int k) -> float {
+                    const int j = k & 511;
+                    int slot, dw, half;
+                    if constexpr (R == 2) {
+                        const int e16 = j & 15, e8 = e16 & 7;
+                        slot = ((j >> 4) << 1) + (e8 >> 2);
+                        dw = e8 & 3;
+                        half = e16 >> 3;
+                    } else if constexpr (R == 4) {
+                        const int e8 = j & 7;
+                        slot = j >> 3;
+                        dw = e8 & 3;
+                        half = e8 >> 2;
+                    } else {
+                        slot = j >> 3;
+                        dw = (j & 7) >> 1;
+                        half = j & 1;
                     }
-                }
+                    const uint8_t *q = xbuf + ((k >> 9) * bp + b) * 1024 + ((slot ^ (b & 15)) << 4) + dw * 4 + half * 2;
+                    return bf16_bits_to_float(*reinterpret_cast<const uint16_t *>(q));
+                };
+                float accb[16];
 #pragma unroll
-                for (int b = 0; b < 16; ++b) {
-                    if (b < a.B) sx[b] = wave_sum(sx[b]);
-                    if (lane == 0) ovf[r * 16 + b] = sx[b];
-                }
+                for (int b = 0; b < 16; ++b) accb[b] = 0.f;
+                int cur = 0;  // row (relative to ra) being walked
+                auto flush = [&]() {
+#pragma unroll
+                    for (int b = 0; b < 16; ++b) {
+                        if (b < a.B) {
+                            const float t = wave_sum(accb[b]);
+                            if (lane == 0) mine[cur * 16 + b] = t;
+                            accb[b] = 0.f;
+                        }
+                    }
+                };
+                auto walk = [&](auto from_lds, int bstart, int col) {  // one batch of 64 entries
+                    const int p = bstart + lane;
+                    while (true) {
+                        const int lo = __builtin_amdgcn_readlane(myrp, cur);
+                        const int hi = __builtin_amdgcn_readlane(myrp, cur + 1);  // cur < nrows: a valid lane
+                        const bool inrow = p >= lo && p < hi;
+                        if (hi > bstart) {  // (an empty or finished row has nothing in this batch)
+#pragma unroll
+                            for (int b = 0; b < 16; ++b) {
+                                if (b < a.B) {
+                                    float v;
+                                    if constexpr (decltype(from_lds)::value)
+                                        v = staged(b, col);
+                                    else
+                                        v = bf16_bits_to_float(a.x[(size_t)b * a.K + col]);
+                                    accb[b] += inrow ? v : 0.f;
+                                }
+                            }
+                        }
+                        if (hi >= bstart + 64 || cur + 1 >= nrows) break;  // the row goes on (or was the last one)
+                        flush();
+                        ++cur;
+                    }
+                };
+                constexpr int U = 8;  // batches whose column indices are requested ahead
+                auto walk_all = [&](auto from_lds) {
+                    for (int base = __builtin_amdgcn_readlane(myrp, 0); base < e1; base += 64 * U) {
+                        int colu[U];
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const int p = base + 64 * u + lane;
+                            colu[u] = p < e1 ? (int)a.col_idx[p] : 0;
+                        }
+#pragma unroll
+                        for (int u = 0; u < U; ++u)
+                            if (base + 64 * u < e1) walk(from_lds, base + 64 * u, colu[u]);
+                    }
+                };
+                if (single)
+                    walk_all(std::true_type{});
+                else
+                    walk_all(std::false_type{});
+                if (e1 > __builtin_amdgcn_readlane(myrp, 0)) flush();  // the row the walk ended in
             }
         }
         if (shared) __syncthreads();
