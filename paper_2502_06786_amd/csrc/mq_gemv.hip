@@ -370,7 +370,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
         }
         // alpha and z of the rows this lane will write: requested now and used after the main loop
         // (later where the registers to hold them that long are missing)
-        constexpr bool kEarlyParams = !(EP && R == 2);
+        constexpr bool kEarlyParams = !EP;
         float pal[RG][4], pze[RG][4];
         auto load_params = [&]() {
 #pragma unroll
@@ -463,18 +463,16 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
         f32x4 *part = reinterpret_cast<f32x4 *>(area);                    // [wave][rg][lane], over the tiles
         float *ovf = reinterpret_cast<float *>(area + NW * 2048);         // [row of the group][b]
         const bool shared = EP || KS > 1;
-        if (KS > 1) {
-            __syncthreads();  // every wave is done with its transposition tile
-#pragma unroll
-            for (int rg = 0; rg < RG; ++rg) part[(wave * RG + rg) * 64 + lane] = acc[rg];
-        }
         // Extra precision: ovf[row][b] = sum of x[b, k] over the row's overflow columns.  A wave takes a
         // contiguous range of the group's rows, whose list entries are contiguous too, and walks
-        // them 64 at a time (coalesced 2-byte loads).  Lane l keeps, per batch entry b, the sum of
-        // what it gathered for the row being walked; the wave-wide reduction happens once per row,
-        // where the row ends.  The row pointers of the range sit in one register (lane j: the
-        // pointer of the j-th row).  x is gathered from its staged copy in LDS when all of it is
-        // resident, from global memory otherwise.
+        // them 64 at a time.  Column indices are fetched in chunks of 8 batches (coalesced 2-byte
+        // loads) and parked in the wave's own LDS tile, free now (the K-split partial sums move into
+        // the tiles only afterwards), while the previous chunk is walked.
+        // Lane l keeps, per batch entry b, the sum of what it gathered for the row being walked;
+        // the wave-wide reduction happens once per row, where the row ends.  The row pointers of
+        // the range sit in one register (lane j: the pointer of the j-th row).  x is gathered from
+        // its staged copy in LDS when all of it is resident, from global memory otherwise.  The
+        // walk exists once per padded batch size so that its loops over b carry no branches.
         if constexpr (EP) {
             const int rpw = RW * ROWS / NW;  // rows per wave: 16 RG / KS >= 1
             float *mine = ovf + wave * rpw * 16;
@@ -483,11 +481,11 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
             const int nrows = min(rpw, a.N - ra);  // wave-uniform
             if (nrows > 0) {
                 const int myrp = lane <= nrows ? a.row_ptr[ra + lane] : 0x7FFFFFFF;
-                const int e1 = __builtin_amdgcn_readlane(myrp, nrows);
+                const int e0 = __builtin_amdgcn_readlane(myrp, 0), e1 = __builtin_amdgcn_readlane(myrp, nrows);
                 // x[b, k] as staged: block k / 512 of entry b, 16-byte slot (k % 512) / 8 kept at
                 // slot ^ b, and inside the slot (or the pair of slots, int2) the order the pairing
                 // pass left: elements j and j + 8 (int2) or j and j + 4 (int4) share a dword
-                auto staged = [&](int b, int k) -> float {
+                auto staged_offset = [&](int k) -> uint32_t {  // without the parts that depend on b
                     const int j = k & 511;
                     int slot, dw, half;
                     if constexpr (R == 2) {
@@ -505,67 +503,94 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                         dw = (j & 7) >> 1;
                         half = j & 1;
                     }
-                    const uint8_t *q = xbuf + ((k >> 9) * bp + b) * 1024 + ((slot ^ (b & 15)) << 4) + dw * 4 + half * 2;
-                    return bf16_bits_to_float(*reinterpret_cast<const uint16_t *>(q));
+                    return (uint32_t)(((k >> 9) * bp) * 1024 + (slot << 4) + dw * 4 + half * 2);
                 };
-                float accb[16];
+                uint16_t *ring = reinterpret_cast<uint16_t *>(tb);  // two chunks of 8 x 64 column indices
+                auto walk = [&](auto bp_tag, auto from_lds) {
+                    constexpr int BPC = decltype(bp_tag)::value;
+                    float accb[BPC];
 #pragma unroll
-                for (int b = 0; b < 16; ++b) accb[b] = 0.f;
-                int cur = 0;  // row (relative to ra) being walked
-                auto flush = [&]() {
+                    for (int b = 0; b < BPC; ++b) accb[b] = 0.f;
+                    int cur = 0;  // row (relative to ra) being walked
+                    auto flush = [&]() {
 #pragma unroll
-                    for (int b = 0; b < 16; ++b) {
-                        if (b < a.B) {
+                        for (int b = 0; b < BPC; ++b) {
                             const float t = wave_sum(accb[b]);
                             if (lane == 0) mine[cur * 16 + b] = t;
                             accb[b] = 0.f;
                         }
-                    }
-                };
-                auto walk = [&](auto from_lds, int bstart, int col) {  // one batch of 64 entries
-                    const int p = bstart + lane;
-                    while (true) {
-                        const int lo = __builtin_amdgcn_readlane(myrp, cur);
-                        const int hi = __builtin_amdgcn_readlane(myrp, cur + 1);  // cur < nrows: a valid lane
-                        const bool inrow = p >= lo && p < hi;
-                        if (hi > bstart) {  // (an empty or finished row has nothing in this batch)
+                    };
+                    int colu[8];
+                    auto request = [&](int base) {
 #pragma unroll
-                            for (int b = 0; b < 16; ++b) {
-                                if (b < a.B) {
-                                    float v;
-                                    if constexpr (decltype(from_lds)::value)
-                                        v = staged(b, col);
-                                    else
-                                        v = bf16_bits_to_float(a.x[(size_t)b * a.K + col]);
-                                    accb[b] += inrow ? v : 0.f;
-                                }
-                            }
-                        }
-                        if (hi >= bstart + 64 || cur + 1 >= nrows) break;  // the row goes on (or was the last one)
-                        flush();
-                        ++cur;
-                    }
-                };
-                constexpr int U = 8;  // batches whose column indices are requested ahead
-                auto walk_all = [&](auto from_lds) {
-                    for (int base = __builtin_amdgcn_readlane(myrp, 0); base < e1; base += 64 * U) {
-                        int colu[U];
-#pragma unroll
-                        for (int u = 0; u < U; ++u) {
+                        for (int u = 0; u < 8; ++u) {
                             const int p = base + 64 * u + lane;
                             colu[u] = p < e1 ? (int)a.col_idx[p] : 0;
                         }
+                    };
+                    auto park = [&](int buf) {
 #pragma unroll
-                        for (int u = 0; u < U; ++u)
-                            if (base + 64 * u < e1) walk(from_lds, base + 64 * u, colu[u]);
+                        for (int u = 0; u < 8; ++u) ring[buf * 512 + u * 64 + lane] = (uint16_t)colu[u];
+                    };
+                    request(e0);
+                    park(0);
+                    int buf = 0;
+                    for (int base = e0; base < e1; base += 512, buf ^= 1) {
+                        if (base + 512 < e1) request(base + 512);
+                        for (int u = 0; u < 8 && base + 64 * u < e1; ++u) {
+                            const int bstart = base + 64 * u, p = bstart + lane;
+                            const int col = ring[buf * 512 + u * 64 + lane];
+                            const uint32_t so = staged_offset(col);
+                            while (true) {
+                                const int lo = __builtin_amdgcn_readlane(myrp, cur);
+                                const int hi = __builtin_amdgcn_readlane(myrp, cur + 1);  // cur < nrows: a valid lane
+                                const bool inrow = p >= lo && p < hi;
+                                if (hi > bstart) {  // (an empty or finished row has nothing in this batch)
+                                    constexpr int HB = BPC < 8 ? BPC : 8;  // gathers in flight
+#pragma unroll
+                                    for (int b0 = 0; b0 < BPC; b0 += HB) {
+                                        float v[HB];
+#pragma unroll
+                                        for (int bb = 0; bb < HB; ++bb) {
+                                            const int b = b0 + bb;
+                                            if constexpr (decltype(from_lds)::value) {
+                                                // (entries b >= B read whatever LDS holds; their sums are never used)
+                                                const uint8_t *q = xbuf + b * 1024 + (so ^ (uint32_t)((b & 15) << 4));
+                                                v[bb] = bf16_bits_to_float(*reinterpret_cast<const uint16_t *>(q));
+                                            } else {
+                                                v[bb] = bf16_bits_to_float(a.x[(size_t)min(b, a.B - 1) * a.K + col]);
+                                            }
+                                        }
+#pragma unroll
+                                        for (int bb = 0; bb < HB; ++bb) accb[b0 + bb] += inrow ? v[bb] : 0.f;
+                                    }
+                                }
+                                if (hi >= bstart + 64 || cur + 1 >= nrows) break;  // the row goes on (or was the last)
+                                flush();
+                                ++cur;
+                            }
+                        }
+                        if (base + 512 < e1) park(buf ^ 1);
                     }
+                    if (e1 > e0) flush();  // the row the walk ended in
+                };
+                auto walk_bp = [&](auto from_lds) {
+                    if (bp == 1) walk(std::integral_constant<int, 1>{}, from_lds);
+                    else if (bp == 2) walk(std::integral_constant<int, 2>{}, from_lds);
+                    else if (bp == 4) walk(std::integral_constant<int, 4>{}, from_lds);
+                    else if (bp == 8) walk(std::integral_constant<int, 8>{}, from_lds);
+                    else walk(std::integral_constant<int, 16>{}, from_lds);
                 };
                 if (single)
-                    walk_all(std::true_type{});
+                    walk_bp(std::true_type{});
                 else
-                    walk_all(std::false_type{});
-                if (e1 > __builtin_amdgcn_readlane(myrp, 0)) flush();  // the row the walk ended in
+                    walk_bp(std::false_type{});
             }
+        }
+        if (KS > 1) {
+            __syncthreads();  // every wave is done with its transposition tile
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) part[(wave * RG + rg) * 64 + lane] = acc[rg];
         }
         if (shared) __syncthreads();
         if (ks == 0) {
@@ -702,7 +727,7 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
 
     // Rows per wave (16 RG): every activation operand read from LDS serves RG matrix-core products, so
     // larger batches and tall matrices take two row groups; short ones keep RG = 1 for more waves.
-    int rg = (B > 2 || N >= 8192) ? 2 : 1;
+    int rg = (B > 2 || (N >= 8192 && !ovf)) ? 2 : 1;  // (a list is walked by the waves of a group: more groups)
 #ifdef MQ_GEMV_TUNE
     if (const char *e = getenv("MQ_GEMV_RG")) rg = atoi(e);
 #endif
