@@ -114,6 +114,20 @@ struct __attribute__((packed, aligned(4))) Piece12 {
     uint32_t a, b, c;
 };
 
+// Order in which the 32 codes of a 3-bit piece (12 bytes) enter its four matrix-core operands:
+// kOrder3[8 v + 2 p + h] = code that operand v holds in half h of register p.  Codes that sit at the
+// same position of the two 16-bit halves of a dword once each half is shifted by its own amount
+// share a register (one packed shift serves two registers: the codes at bits 0-2 read as 128 + c,
+// the next ones at bits 3-5 as 16 + c); the six codes that straddle a half or lie alone go last.
+__device__ constexpr uint8_t kOrder3[32] = {0, 6, 1, 7, 2, 8, 3, 9,          11, 16, 12, 17, 13, 18, 14, 19,
+                                            22, 27, 23, 28, 24, 29, 25, 30,  15, 20, 4, 5, 10, 21, 26, 31};
+// kPlace3[code] = 8 v + 2 p + h, the inverse
+__device__ constexpr uint8_t kPlace3[32] = {0, 2, 4, 6, 26, 27, 1, 3, 5, 7, 28, 8, 10, 12, 14, 24,
+                                            9, 11, 13, 15, 25, 29, 16, 18, 20, 22, 30, 17, 19, 21, 23, 31};
+// offset under which element (v, p) of the 3-bit order reads: 16 for the registers fed from bits 3-5
+__host__ __device__ constexpr float offset3(int v, int p) { return (v < 3 && (p & 1)) ? 16.f : 128.f; }
+constexpr uint32_t kB16 = 0x41804180u;  // (16, 16)
+
 // Constants of the unpack, pinned in registers once per kernel.
 struct UnpackConsts {
     uint32_t m0, m1, m2;     // scalar: field masks
@@ -122,11 +136,11 @@ struct UnpackConsts {
 template <int R>
 __device__ __forceinline__ UnpackConsts unpack_consts() {
     UnpackConsts c;
-    c.m0 = R == 2 ? 0x00030003u : (R == 4 ? 0x000F000Fu : (R == 6 ? 0x0000003Fu : 0x00000007u));
-    c.m1 = R == 2 ? 0x000C000Cu : (R == 6 ? 0x003F0000u : 0x00070000u);
-    c.m2 = 0x00300030u;
+    c.m0 = R == 2 ? 0x00030003u : (R == 4 ? 0x000F000Fu : (R == 6 ? 0x0000003Fu : 0x00070007u));
+    c.m1 = R == 2 ? 0x000C000Cu : (R == 6 ? 0x003F0000u : 0x00380038u);
+    c.m2 = R == 3 ? 0x00070000u : 0x00300030u;
     c.e128 = kB128;
-    c.e32 = kB32;
+    c.e32 = R == 3 ? kB16 : kB32;
     c.e8 = kB8;
     asm volatile("" : "+s"(c.m0), "+s"(c.m1), "+s"(c.m2));
     asm volatile("" : "+v"(c.e128), "+v"(c.e32), "+v"(c.e8));
@@ -169,8 +183,41 @@ __device__ __forceinline__ void gemv_segment(const u32x4 (&wt)[RG], const uint8_
                 acc[rg] = mfma16(a0, xb, acc[rg]);
             }
         }
-    } else if constexpr (R == 6 || R == 3) {
-        // bit stream: code j of the 96-bit piece sits at bits [R j, R j + R); operand v takes codes
+    } else if constexpr (R == 3) {
+        // 32 codes in 96 bits, operands in the order of kOrder3 (see there)
+        u32x4 xb[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) xb[v] = operand(v);
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) {
+            u32x4 ops[4];
+            const uint32_t d0 = wt[rg].x, d1 = wt[rg].y, d2 = wt[rg].z;
+            auto halves = [](uint32_t d, int lo, int hi) {  // each 16-bit half shifted right by its own amount
+                const u16x2 t = __builtin_bit_cast(u16x2, d) >> u16x2{(unsigned short)lo, (unsigned short)hi};
+                return __builtin_bit_cast(uint32_t, t);
+            };
+            const uint32_t a0 = halves(d0, 0, 2), a1 = halves(d0, 6, 8);
+            ops[0] = u32x4{and_or(a0, uc.m0, uc.e128), and_or(a0, uc.m1, uc.e32), and_or(a1, uc.m0, uc.e128),
+                               and_or(a1, uc.m1, uc.e32)};
+            const uint32_t b0 = halves(d1, 1, 0), b1 = halves(d1, 7, 6);
+            ops[1] = u32x4{and_or(b0, uc.m0, uc.e128), and_or(b0, uc.m1, uc.e32), and_or(b1, uc.m0, uc.e128),
+                               and_or(b1, uc.m1, uc.e32)};
+            const uint32_t c0 = halves(d2, 2, 1), c1 = halves(d2, 8, 7);
+            ops[2] = u32x4{and_or(c0, uc.m0, uc.e128), and_or(c0, uc.m1, uc.e32), and_or(c1, uc.m0, uc.e128),
+                               and_or(c1, uc.m1, uc.e32)};
+            // (15, 20): bits 13-15 and 28-30 of d1; (4, 5): bits 12-14 and 15-17 of d0;
+            // (10, 21): bits 30-32 and 63-65 of the piece; (26, 31): bits 14-16 and 29-31 of d2
+            const uint32_t lo7 = uc.m0 & 0xFFFFu;  // 0x7 in the low half only
+            ops[3] = u32x4{and_or(halves(d1, 13, 12), uc.m0, uc.e128),
+                               and_or(d0 << 1, uc.m2, and_or(d0 >> 12, lo7, uc.e128)),
+                               and_or(__builtin_amdgcn_alignbit(d2, d1, 15), uc.m2,
+                                      and_or(__builtin_amdgcn_alignbit(d1, d0, 30), lo7, uc.e128)),
+                               and_or(d2 >> 13, uc.m2, and_or(d2 >> 14, lo7, uc.e128))};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[rg] = mfma16(ops[v], xb[v], acc[rg]);
+        }
+    } else if constexpr (R == 6) {
+        // bit stream: code j of the 96-bit piece sits at bits [6 j, 6 j + 6); operand v takes codes
         // 8 v .. 8 v + 7 in their natural order, two per register (low half, high half), each read
         // as 128 + code under the exponent of e128
         constexpr int XVP = operands_per_piece(R);
@@ -298,6 +345,31 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                         s2 += e1 * ((jj + 4) % 3 == 0 ? 128.f : ((jj + 4) % 3 == 1 ? 32.f : 8.f));
                     }
                 }
+            } else if constexpr (R == 3) {
+                if (u < 16) {  // a 1 KB block holds 16 units of 32 activations (four slots)
+                    uint32_t src[16], dst[16];
+#pragma unroll
+                    for (int sl = 0; sl < 4; ++sl) {
+                        const u32x4 t = *reinterpret_cast<const u32x4 *>(blk + (((4 * u + sl) ^ (b & 15)) << 4));
+                        src[4 * sl] = t.x, src[4 * sl + 1] = t.y, src[4 * sl + 2] = t.z, src[4 * sl + 3] = t.w;
+                    }
+#pragma unroll
+                    for (int o = 0; o < 16; ++o) {  // register o of the unit: operand o / 4, register o % 4
+                        const int ea = kOrder3[2 * o], eb = kOrder3[2 * o + 1];  // low half, high half
+                        const uint32_t lo = (ea & 1) ? src[ea >> 1] >> 16 : src[ea >> 1] & 0xFFFFu;
+                        const uint32_t hi = (eb & 1) ? src[eb >> 1] & 0xFFFF0000u : src[eb >> 1] << 16;
+                        dst[o] = lo | hi;
+                        if (with_sums) {
+                            const float e = __uint_as_float(dst[o] << 16) + __uint_as_float(dst[o] & 0xFFFF0000u);
+                            s1 += e;
+                            s2 += e * offset3(o >> 2, o & 3);
+                        }
+                    }
+#pragma unroll
+                    for (int sl = 0; sl < 4; ++sl)
+                        *reinterpret_cast<u32x4 *>(blk + (((4 * u + sl) ^ (b & 15)) << 4)) =
+                            u32x4{dst[4 * sl], dst[4 * sl + 1], dst[4 * sl + 2], dst[4 * sl + 3]};
+                }
             } else {
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
@@ -342,7 +414,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
         __syncthreads();
         pair_pass(with_sums);
         if (with_sums) {  // running totals; complete after the last chunk's pass
-            const float t1 = half_wave_sum(s1), t2 = R == 2 ? half_wave_sum(s2) : 0.f;
+            const float t1 = half_wave_sum(s1), t2 = (R == 2 || R == 3) ? half_wave_sum(s2) : 0.f;
             if ((lane & 31) == 0) {
                 sums[wave * 2 + (lane >> 5)] = t1;
                 sums[32 + wave * 2 + (lane >> 5)] = t2;
@@ -498,6 +570,11 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                         slot = j >> 3;
                         dw = e8 & 3;
                         half = e8 >> 2;
+                    } else if constexpr (R == 3) {
+                        const int place = kPlace3[j & 31];  // 8 v + 2 p + h inside the unit of 32
+                        slot = ((j >> 5) << 2) + (place >> 3);
+                        dw = (place >> 1) & 3;
+                        half = place & 1;
                     } else {
                         slot = j >> 3;
                         dw = (j & 7) >> 1;
@@ -622,8 +699,8 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                         const int rl = rg * 16 + 4 * g + cc, row = n0 + rl;
                         if (row < a.N) {
                             float dot = acc[rg][cc];
-                            if constexpr (R == 2) dot -= xoff;
-                            if constexpr (R == 4 || R == 6 || R == 3) dot -= 128.0f * xsum;
+                            if constexpr (R == 2 || R == 3) dot -= xoff;
+                            if constexpr (R == 4 || R == 6) dot -= 128.0f * xsum;
                             if constexpr (EP) dot += ovf[(rw * ROWS + rl) * 16 + b];
                             const float yv = pal[rg][cc] * (kScale * dot - pze[rg][cc] * xsum);
                             a.y[(size_t)b * a.N + row] = (uint16_t)float_to_bf16_bits(yv);
