@@ -12,22 +12,10 @@
 #include <cstdlib>
 #include <type_traits>
 
-#include "mq_common.h"
+#include "mq_gemv.h"
 
 namespace mq {
 
-struct GemvArgs {
-    const uint16_t *x;        // [B, K] bf16
-    const uint8_t *packed;    // [N, KB]
-    const uint16_t *alpha;    // [N] bf16
-    const uint16_t *zero;     // [N] bf16
-    const int32_t *row_ptr;   // [N + 1] or null
-    const uint16_t *col_idx;  // overflow columns
-    uint16_t *y;              // [B, N] bf16
-    int B, N, K;
-    int KB;       // bytes per packed row
-    float scale;  // 2^s: one step of the stored codes on the int8 grid
-};
 
 __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -802,6 +790,13 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     a.KB = (int)kb;
     a.scale = (float)(1 << shift);
 
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    {
+        bool handled = false;
+        const mq_status qs = launch_gemv_quad(a, r, st, &handled);
+        if (qs != MQ_OK || handled) return qs;
+    }
+
     // Rows per wave (16 RG): every activation operand read from LDS serves RG matrix-core products, so
     // larger batches and tall matrices take two row groups; short ones keep RG = 1 for more waves.
     int rg = (B > 2 || (N >= 8192 && !ovf)) ? 2 : 1;  // (a list is walked by the waves of a group: more groups)
@@ -822,7 +817,6 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     if (const char *e = getenv("MQ_GEMV_NW")) nw = atoi(e);
     if (nw < ks) nw = ks;
 #endif
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
 #define MQ_GEMV_CASE(R_, RG_, D_) \
     if (r == R_ && rg == RG_) return launch_gemv<R_, RG_, D_>(a, nw, ks, st);
     MQ_GEMV_CASE(2, 1, 3) MQ_GEMV_CASE(2, 2, 2)
