@@ -10,17 +10,17 @@
 // result of a product is y[b] of the lane's own row in accumulator register b.  Nothing is shared
 // between lanes until a row block is finished.
 //
-// A wave owns NL consecutive 128-byte lines of every row (its K slice, index ks) and walks over row
-// blocks of 16 rows ("visits"); the KS slices of a row block sit in one workgroup and meet in LDS at
-// the end.  Weight lines are fetched as whole 128-byte lines by eight neighbouring lanes through
-// buffer loads (a request past the wave's last visit is out of range: it returns zeros and costs no
-// traffic, so the number of loads in flight is the same in every iteration), two visits ahead, and
-// change lanes through a 2 KB LDS tile per wave one step before they are used.
+// A wave owns NL consecutive 128-byte lines of every row (a K slice) and walks over row blocks of 16
+// rows ("visits"); all slices of a row block sit in one workgroup and meet in LDS at the end.  Weight
+// lines are fetched as whole 128-byte lines by eight neighbouring lanes, by direct global->LDS loads
+// into a ring of 2 KB tiles per wave, a few steps ahead (a request past the wave's last step is out
+// of range: it moves no data, so the number of loads in flight is the same in every iteration); the
+// compute layout (lane = row and 16-byte piece) is read back out of the tile one step before use.
 //
 // Codes become bf16 numbers with one AND-OR per two codes: a field at mantissa bits 0-1 / 2-3 / 4-5
 // under the exponent of 128 / 32 / 8 reads as 128 + c, 32 + c, 8 + c.  The offsets leave in the
-// epilogue through sum_k x_k * offset_k, which every workgroup computes once next to sum_k x_k (the
-// zero-point term).
+// epilogue through sum_k x_k * offset_k, which comes out of the activation registers next to
+// sum_k x_k (the zero-point term).
 #include <algorithm>
 #include <cstdlib>
 
@@ -98,11 +98,14 @@ __device__ __forceinline__ void quad_dword(uint32_t d, int dwi, const u32x2 (&xr
     }
 }
 
-// R = bits per code (4 or 2), NL = 128-byte lines of a row per K slice.  Workgroup = KS * RW waves;
-// wave (ks, rw) = (wave % KS, wave / KS) takes slice ks of row blocks rb0 + rw, rb0 + rw + RW, ...
-// of the CH row blocks [rb0, rb0 + CH) that the workgroup owns.
-template <int R, int NL>
-__global__ __launch_bounds__(512) void gemv_quad_kernel(GemvArgs a, int KS, int RW, int CH) {
+// R = bits per code (4 or 2), NL = 128-byte lines of a row per K slice, S = tiles in a wave's ring.
+// Workgroup = KS * RW waves; wave (ks, rw) = (wave % KS, wave / KS) takes the slices ks, ks + KS, ...
+// (one "round" each) of the workgroup's row blocks number rw, rw + RW, ...  The workgroup owns every
+// G-th row block (G = workgroups in the grid): its c-th one is row block c * G + blockIdx, c < CH, so
+// that at any time the requests of the whole grid fall into one narrow window of the matrix that
+// moves from its first row to its last.
+template <int R, int NL, int S>
+__global__ __launch_bounds__(512) void gemv_quad_kernel(GemvArgs a, int KS, int RW, int CH, int NSL) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     constexpr int CPD = 32 / R;      // codes per dword
     constexpr int QD = CPD / 4;      // quads per dword
@@ -118,21 +121,22 @@ __global__ __launch_bounds__(512) void gemv_quad_kernel(GemvArgs a, int KS, int 
     const int t = (lane >> 2) & 3, b = lane & 3;   // activations: block t, batch entry b
 
     const int NRB = (a.N + 15) >> 4;
-    const int rb0 = blockIdx.x * CH, rb1 = min(rb0 + CH, NRB);
-    const int row0 = rb0 * 16;
-    const int rows_wg = min(rb1 * 16, a.N) - row0;  // >= 1 (the grid covers exactly the row blocks)
-    const int line0 = ks * NL;
+    const int G = gridDim.x, wg = blockIdx.x;
+    const int nblk = (NRB - wg + G - 1) / G;             // row blocks of this workgroup (>= 1)
+    const int nv = max(0, (nblk - rw + RW - 1) / RW);    // visits per round of this wave (wave-uniform)
+    const int nr = (NSL - ks + KS - 1) / KS;             // rounds of this wave: slices ks + KS r < NSL
+    const int nsteps = nr * nv * NL;
 
     float *sums = reinterpret_cast<float *>(lds);
-    uint8_t *tile = lds + kSumsBytes + wave * kTileBytes;
-    f32x4 *ypart = reinterpret_cast<f32x4 *>(lds + kSumsBytes + NW * kTileBytes);  // [KS][CH * 16]
+    uint8_t *ring = lds + kSumsBytes + wave * (S * kTileBytes);                          // S tiles of 16 rows x 128 bytes
+    f32x4 *ypart = reinterpret_cast<f32x4 *>(lds + kSumsBytes + NW * S * kTileBytes);    // [NSL][CH * 16]
     // activations of the whole workgroup: row b at b * xpitch, natural order, zero-filled up to a whole 512-k block
     const int kblocks = (a.K + 511) >> 9;
     const int xpitch = kblocks * 1024 + kXPad;
-    uint8_t *xbuf = lds + kSumsBytes + NW * kTileBytes + KS * CH * 16 * (int)sizeof(f32x4);
+    const uint8_t *xbuf = lds + kSumsBytes + NW * S * kTileBytes + NSL * CH * 16 * (int)sizeof(f32x4);
 
     const __amdgpu_buffer_rsrc_t rwt = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(a.packed + (size_t)row0 * a.KB), 0, (int)((uint32_t)rows_wg * (uint32_t)a.KB), 0x00020000);
+        const_cast<uint8_t *>(a.packed), 0, (int)(uint32_t)((size_t)a.N * a.KB), 0x00020000);
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(a.x), 0, (int)((uint32_t)a.B * (uint32_t)a.K * 2u), 0x00020000);
 
@@ -141,193 +145,212 @@ __global__ __launch_bounds__(512) void gemv_quad_kernel(GemvArgs a, int KS, int 
         const int bj = j / kblocks, kb = j - bj * kblocks;
         const int k = kb * 512 + lane * 8;
         const uint32_t vo = k < a.K ? ((uint32_t)bj * (uint32_t)a.K + (uint32_t)k) * 2u : kOutOfRange;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(xbuf + bj * xpitch + kb * 1024), 16, vo, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(const_cast<uint8_t *>(xbuf) + bj * xpitch + kb * 1024), 16,
+                                                 vo, 0, 0, 0);
     }
 
-    // ---- weight ring: raw[slot][line][first / second eight rows], two visits deep ---------------------
-    u32x4 raw[2][NL][2];
-    uint32_t piece_off[NL];  // byte offset of the lane's piece inside a row (clamped into the row)
-#pragma unroll
-    for (int ln = 0; ln < NL; ++ln) piece_off[ln] = (uint32_t)min((line0 + ln) * 128 + lc * 16, a.KB - 16);
-    const int nv = max(0, (rb1 - rb0 - rw + RW - 1) / RW);  // visits of this wave (wave-uniform)
-    auto issue = [&](int visit, u32x4 (&dst)[2], int ln) {
-        const int rb = rb0 + rw + visit * RW;
-        // bit 31 of the offset set when the visit does not exist (arithmetic on purpose: a branch
-        // around a load would make the number of loads in flight depend on the path)
-        const uint32_t gone = (uint32_t)((rb1 - 1 - rb) >> 31) << 31;
-        const uint32_t r_a = (uint32_t)(min(rb * 16 + li, a.N - 1) - row0) * (uint32_t)a.KB;
-        const uint32_t r_b = (uint32_t)(min(rb * 16 + li + 8, a.N - 1) - row0) * (uint32_t)a.KB;
-        dst[0] = __builtin_amdgcn_raw_buffer_load_b128(rwt, (r_a + piece_off[ln]) | gone, 0, 0);
-        dst[1] = __builtin_amdgcn_raw_buffer_load_b128(rwt, (r_b + piece_off[ln]) | gone, 0, 0);
-    };
-#pragma unroll
-    for (int ln = 0; ln < NL; ++ln) issue(0, raw[0][ln], ln);
-
-#pragma unroll
-    for (int ln = 0; ln < NL; ++ln) issue(1, raw[1][ln], ln);
-    // the staged activations are older than the 4 NL weight loads requested since, and loads return in order
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * NL) : "memory");
-    __syncthreads();
-
-    // ---- activations of the slice -> registers ------------------------------------------------------
-    // pair p of line ln, lane (g, t, b): quad 4 p + t of the lane's stream of the line, i.e. the dwords
-    // of x that hold codes (2u, 2u + 1) and (2u + CPD/2, 2u + 1 + CPD/2) of the quad's weight dword
-    u32x2 xr[NL][XP];
-    {
-        const uint8_t *xrow = xbuf + min(b, a.B - 1) * xpitch;
-#pragma unroll
-        for (int ln = 0; ln < NL; ++ln)
-#pragma unroll
-            for (int p = 0; p < XP; ++p) {
-                const int qi = 4 * p + t, dwi = qi / QD, u = qi % QD, h = dwi >> 2, w = dwi & 3;
-                const int byte_in_row = (line0 + ln) * 128 + (g + 4 * h) * 16 + 4 * w;
-                const bool valid = byte_in_row < a.KB && b < a.B;
-                const uint32_t *q = reinterpret_cast<const uint32_t *>(xrow + (valid ? (byte_in_row * CPB + 2 * u) * 2 : 0));
-                const uint32_t first = q[0], second = q[CPD / 4];
-                xr[ln][p].x = valid ? first : 0u;
-                xr[ln][p].y = valid ? second : 0u;
-            }
-    }
-
-    // alpha and z of the first outputs this thread will write, requested ahead
-    const int total_out = rows_wg * a.B;
+    // alpha and z of the first outputs this thread will write, requested ahead.
+    // output idx = (b * nblk + c) * 16 + i: row (c * G + wg) * 16 + i of batch entry b
+    const int total_out = a.B * nblk * 16;
+    auto out_row = [&](int idx) { return (((idx >> 4) % nblk) * G + wg) * 16 + (idx & 15); };
     constexpr int PF = 2;
     float pal[PF], pze[PF];
 #pragma unroll
     for (int m = 0; m < PF; ++m) {
         const int idx = tid + m * nthreads;
-        const int row = row0 + (idx < total_out ? idx % rows_wg : 0);
+        const int row = min(out_row(idx < total_out ? idx : 0), a.N - 1);
         pal[m] = bf16_bits_to_float(a.alpha[row]);
         pze[m] = bf16_bits_to_float(a.zero[row]);
     }
 
-    // The operand order of a quad is (2u, 2u + CPD/2, 2u + 1, 2u + 1 + CPD/2).  sum_k x and
-    // sum_k x * offset_k of the slice come out of the same registers (every activation of the slice
-    // sits in exactly one lane); line ln is summed by the wave with rw == ln % RW.
-    {
-        // offset of code position k % 8 at int2: 128 32 8 128 32 8 128 32; lane t holds positions 2t, 2t + 1
-        const float off_a = R != 2 ? 128.f : (t == 1 ? 8.f : (t == 2 ? 32.f : 128.f));
-        const float off_b = R != 2 ? 128.f : (t == 1 ? 128.f : (t == 2 ? 8.f : 32.f));
-        float s1 = 0.f, s2 = 0.f;
+    // ---- weight ring: S tiles per wave in LDS, filled by direct loads ----------------------------------
+    // Step s of the wave = line s % NL of visit (s / NL) % nv of round s / (NL nv).  Lane l of a load
+    // lands at byte 16 l of its half of the tile; it fetches piece (l % 8) ^ swz(row) of row l / 8
+    // (+ 8), so that the tile reads [row][piece ^ swz(row)], swz(row) = row / 2 % 8: whole 128-byte
+    // lines on the memory side, and the row-shaped reads of the compute layout hit every bank once.
+    const int lp0 = lc ^ ((li >> 1) & 7), lp1 = lc ^ (((li + 8) >> 1) & 7);  // pieces this lane fetches
+    int iround = 0, ivisit = 0, iln = 0, islot = 0;  // the next step to request and the slot it goes to
+    auto issue_next = [&]() {
+        const int c = rw + ivisit * RW, rb = c * G + wg;
+        // bit 31 of the offset set when the step does not exist: such a request is out of range, moves
+        // no data and still counts as a load in flight (arithmetic on purpose, no branch)
+        const uint32_t gone = (uint32_t)(((nblk - 1 - c) | (nr - 1 - iround)) >> 31) << 31;
+        // the row block's first byte goes into the scalar offset; rows past the last one re-read it
+        const uint32_t sbase = gone ? 0u : (uint32_t)rb * 16u * (uint32_t)a.KB;
+        const int last = a.N - 1 - rb * 16;
+        const uint32_t r_a = (uint32_t)max(min(li, last), 0) * (uint32_t)a.KB;
+        const uint32_t r_b = (uint32_t)max(min(li + 8, last), 0) * (uint32_t)a.KB;
+        const int lb = ((ks + KS * iround) * NL + iln) * 128;
+        const uint32_t p_a = (uint32_t)max(min(lb + lp0 * 16, a.KB - 16), 0);
+        const uint32_t p_b = (uint32_t)max(min(lb + lp1 * 16, a.KB - 16), 0);
+        uint8_t *dst = ring + islot * kTileBytes;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt, (lds_ptr)dst, 16, (r_a + p_a) | gone, sbase, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt, (lds_ptr)(dst + 1024), 16, (r_b + p_b) | gone, sbase, 0, 0);
+        if (++iln == NL) {
+            iln = 0;
+            if (++ivisit >= nv) ivisit = 0, ++iround;
+        }
+        islot = islot + 1 == S ? 0 : islot + 1;
+    };
+#pragma unroll
+    for (int st = 0; st < S; ++st) issue_next();  // the first S steps are requested now
+    // the staged activations are older than the 2 S weight loads requested since, and loads return in order
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * S) : "memory");
+    // (the bare barrier: a fence here would wait for the tiles still on their way, which no other wave reads)
+    __builtin_amdgcn_s_barrier();
+
+    // ---- activations of a slice -> registers --------------------------------------------------------
+    // pair p of line ln, lane (g, t, b): quad 4 p + t of the lane's stream of the line, i.e. the dwords
+    // of x that hold codes (2u, 2u + 1) and (2u + CPD/2, 2u + 1 + CPD/2) of the quad's weight dword,
+    // rearranged to the operand order (2u, 2u + CPD/2, 2u + 1, 2u + 1 + CPD/2).  sum_k x and
+    // sum_k x * offset_k come out of the same registers (every activation of the slice sits in
+    // exactly one lane); line ln is summed by the wave with rw == ln % RW.
+    u32x2 xr[NL][XP];
+    float s1 = 0.f, s2 = 0.f;
+    // offset of code position k % 8 at int2: 128 32 8 128 32 8 128 32; lane t holds positions 2t, 2t + 1 in
+    // its first register (both halves) and its second
+    const float off_a = R != 2 ? 128.f : (t == 1 ? 8.f : (t == 2 ? 32.f : 128.f));
+    const float off_b = R != 2 ? 128.f : (t == 1 ? 128.f : (t == 2 ? 8.f : 32.f));
+    const uint32_t offs_a = pack_bf16x2(off_a, off_a), offs_b = pack_bf16x2(off_b, off_b);
+    typedef __bf16 bfp __attribute__((ext_vector_type(2)));
+    auto dot2 = [](uint32_t v, uint32_t c, float acc) {
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bfp, v), __builtin_bit_cast(bfp, c), acc, false);
+    };
+    const uint8_t *xrow = xbuf + min(b, a.B - 1) * xpitch;
+    auto load_x = [&](int slice) {
 #pragma unroll
         for (int ln = 0; ln < NL; ++ln) {
 #pragma unroll
             for (int p = 0; p < XP; ++p) {
-                const uint32_t first = xr[ln][p].x, second = xr[ln][p].y;
+                const int qi = 4 * p + t, dwi = qi / QD, u = qi % QD, h = dwi >> 2, w = dwi & 3;
+                const int byte_in_row = (slice * NL + ln) * 128 + (g + 4 * h) * 16 + 4 * w;
+                const bool valid = byte_in_row < a.KB && b < a.B;
+                const uint32_t *q = reinterpret_cast<const uint32_t *>(xrow + (valid ? (byte_in_row * CPB + 2 * u) * 2 : 0));
+                const uint32_t first = valid ? q[0] : 0u, second = valid ? q[CPD / 4] : 0u;
                 xr[ln][p] = u32x2{__builtin_amdgcn_perm(second, first, 0x05040100u),   // (first.lo, second.lo)
                                   __builtin_amdgcn_perm(second, first, 0x07060302u)};  // (first.hi, second.hi)
             }
             if (ln % RW == rw) {
 #pragma unroll
                 for (int p = 0; p < XP; ++p) {
-                    const float ea = __uint_as_float(xr[ln][p].x << 16) + __uint_as_float(xr[ln][p].x & 0xFFFF0000u);
-                    const float eb = __uint_as_float(xr[ln][p].y << 16) + __uint_as_float(xr[ln][p].y & 0xFFFF0000u);
-                    s1 += ea + eb;
-                    s2 += ea * off_a + eb * off_b;
+                    s1 = dot2(xr[ln][p].x, 0x3F803F80u, s1);
+                    s1 = dot2(xr[ln][p].y, 0x3F803F80u, s1);
+                    if constexpr (R == 2) {
+                        s2 = dot2(xr[ln][p].x, offs_a, s2);
+                        s2 = dot2(xr[ln][p].y, offs_b, s2);
+                    }
                 }
             }
         }
-#pragma unroll
-        for (int m = 4; m < 64; m <<= 1) {  // over the lanes of one batch entry
-            s1 += __shfl_xor(s1, m);
-            s2 += __shfl_xor(s2, m);
-        }
-        if (lane < 4) {
-            sums[(wave * 4 + lane) * 2] = s1;
-            sums[(wave * 4 + lane) * 2 + 1] = s2;
-        }
-    }
+    };
+    if (nr > 0) load_x(ks);
 
     // ---- main loop ------------------------------------------------------------------------------------
-    // tile [row][piece ^ (row / 2 % 8)]: conflict-free for the line-shaped writes and the row-shaped reads
-    const uint32_t wslot0 = (uint32_t)(8 * li + (lc ^ ((li >> 1) & 7))) << 4;
-    const uint32_t wslot1 = (uint32_t)(8 * (li + 8) + (lc ^ (((li + 8) >> 1) & 7))) << 4;
+    // In the iteration of step s: the tile of step s + 1 has landed (all but the 2 (S - 2) newest loads
+    // are back; loads return in order) and is read into the other register set; the reads of step s,
+    // issued an iteration ago, are complete by then, so its slot is requested again for step s + S;
+    // then step s is computed.  LDS operations of one wave execute in order.
+    static_assert(S >= 2 && S <= 16, "ring depth");
+    constexpr int U = (NL % 2 == 0) ? NL : 2 * NL;  // steps per unrolled iteration: line and register set known
     const uint32_t rslot0 = (uint32_t)(8 * i + (g ^ ((i >> 1) & 7))) << 4;
     const uint32_t rslot1 = (uint32_t)(8 * i + ((4 + g) ^ ((i >> 1) & 7))) << 4;
-    // LDS operations of one wave execute in order, so the tile needs no barrier
-    auto transpose = [&](const u32x4 (&src)[2], u32x4 (&dst)[2]) {
-        *reinterpret_cast<u32x4 *>(tile + wslot0) = src[0];
-        *reinterpret_cast<u32x4 *>(tile + wslot1) = src[1];
+    auto read_tile = [&](int slot, u32x4 (&dst)[2]) {
+        const uint8_t *tile = ring + slot * kTileBytes;
         dst[0] = *reinterpret_cast<const u32x4 *>(tile + rslot0);
         dst[1] = *reinterpret_cast<const u32x4 *>(tile + rslot1);
     };
     const QuadConsts qc = quad_consts<R>();
     f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
     u32x4 wt[2][2];
-    transpose(raw[0][0], wt[0]);
-    issue(2, raw[0][0], 0);
-    for (int v = 0; v < nv; v += 2) {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (S - 1)) : "memory");  // step 0 has landed
+    read_tile(0, wt[0]);
+    int nslot = 1;            // slot of step s + 1 (islot = slot of step s + S = slot of step s)
+    int vcur = 0, rcur = 0;   // visit and round of step s
+    for (int s0 = 0; s0 < nsteps; s0 += U) {
 #pragma unroll
-        for (int vv = 0; vv < 2; ++vv) {
-            const bool active = v + vv < nv;
-#pragma unroll
-            for (int ln = 0; ln < NL; ++ln) {
-                const int par = (vv * NL + ln) & 1;
-                // the step after this one changes lanes now and is used in the next step; its ring
-                // registers are requested again at once, for the visit two further on
-                const int nln = ln + 1 == NL ? 0 : ln + 1, nvv = ln + 1 == NL ? vv + 1 : vv;
-                transpose(raw[nvv & 1][nln], wt[par ^ 1]);
-                issue(v + nvv + 2, raw[nvv & 1][nln], nln);
-                __builtin_amdgcn_sched_barrier(0);
-                if (active) {
-#pragma unroll
-                    for (int dwi = 0; dwi < 8; ++dwi)
-                        quad_dword<R, XP>(wt[par][dwi >> 2][dwi & 3], dwi, xr[ln], qc, acc0, acc1);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        for (int u = 0; u < U; ++u) {
+            const int ln = u % NL, par = u & 1;
+            const bool active = s0 + u < nsteps;
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (S - 2)) : "memory");
+            read_tile(nslot, wt[par ^ 1]);
+            asm volatile("s_waitcnt lgkmcnt(2)" ::: "memory");
+            issue_next();
+            nslot = nslot + 1 == S ? 0 : nslot + 1;
+            __builtin_amdgcn_sched_barrier(0);
             if (active) {
+#pragma unroll
+                for (int dwi = 0; dwi < 8; ++dwi)
+                    quad_dword<R, XP>(wt[par][dwi >> 2][dwi & 3], dwi, xr[ln], qc, acc0, acc1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (ln == NL - 1 && active) {
                 // accumulator register b = y[b] of row i, k-group g: add the four k-groups
-                f32x4 s = acc0 + acc1;
+                f32x4 sum = acc0 + acc1;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    s[c] += __shfl_xor(s[c], 16);
-                    s[c] += __shfl_xor(s[c], 32);
+                    sum[c] += __shfl_xor(sum[c], 16);
+                    sum[c] += __shfl_xor(sum[c], 32);
                 }
-                const int rbl = rw + (v + vv) * RW;  // row block inside the workgroup's range
-                if (g == 0) ypart[(ks * CH + rbl) * 16 + i] = s;
+                const int cblk = rw + vcur * RW;  // row block inside the workgroup's list
+                if (g == 0) ypart[((ks + KS * rcur) * CH + cblk) * 16 + i] = sum;
                 acc0 = acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (++vcur == nv) {  // next round: the activations of the next slice
+                    vcur = 0;
+                    if (++rcur < nr) load_x(ks + KS * rcur);
+                }
             }
         }
+    }
+    // every request of this wave (the last ones are out of range) is back before its tiles are given up
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int m = 4; m < 64; m <<= 1) {  // over the lanes of one batch entry
+        s1 += __shfl_xor(s1, m);
+        s2 += __shfl_xor(s2, m);
+    }
+    if (lane < 4) {
+        sums[(wave * 4 + lane) * 2] = s1;
+        sums[(wave * 4 + lane) * 2 + 1] = R == 2 ? s2 : 128.f * s1;
     }
 
     // ---- epilogue: y[b, n] = alpha_n * (2^s * (sum_k (offset_k + code) x - sum_k offset_k x) - z_n * sum_k x) --
     __syncthreads();
     const float kScale = a.scale;
     for (int idx = tid, m = 0; idx < total_out; idx += nthreads, ++m) {
-        const int bb = idx / rows_wg, r = idx - bb * rows_wg;
+        const int bb = idx / (nblk * 16), r = idx - bb * (nblk * 16), row = out_row(idx);
+        if (row >= a.N) continue;
         float xsum = 0.f, xoff = 0.f;
         for (int w = 0; w < NW; ++w) {
             xsum += sums[(w * 4 + bb) * 2];
             xoff += sums[(w * 4 + bb) * 2 + 1];
         }
         float dot = 0.f;
-        for (int k = 0; k < KS; ++k) dot += ypart[k * CH * 16 + r][bb];
+        for (int k = 0; k < NSL; ++k) dot += ypart[k * CH * 16 + r][bb];
         float al, ze;
         if (m < PF) {
             al = m == 0 ? pal[0] : pal[1];
             ze = m == 0 ? pze[0] : pze[1];
         } else {
-            al = bf16_bits_to_float(a.alpha[row0 + r]);
-            ze = bf16_bits_to_float(a.zero[row0 + r]);
+            al = bf16_bits_to_float(a.alpha[row]);
+            ze = bf16_bits_to_float(a.zero[row]);
         }
         const float yv = al * (kScale * (dot - xoff) - ze * xsum);
-        a.y[(size_t)bb * a.N + row0 + r] = (uint16_t)float_to_bf16_bits(yv);
+        a.y[(size_t)bb * a.N + row] = (uint16_t)float_to_bf16_bits(yv);
     }
 }
 
 struct QuadPlan {
-    int nl, ks, rw, ch, grid;
+    int nl, nsl, ks, rw, ch, grid, depth;
     size_t lds;
 };
 
-template <int R, int NL>
+template <int R, int NL, int S>
 mq_status launch_quad(const GemvArgs &a, const QuadPlan &p, hipStream_t st) {
-    auto kern = gemv_quad_kernel<R, NL>;
+    auto kern = gemv_quad_kernel<R, NL, S>;
     if (p.lds > 65536 && hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds) != hipSuccess)
         return MQ_ERR_DEVICE;
-    kern<<<dim3(p.grid), dim3(64 * p.ks * p.rw), p.lds, st>>>(a, p.ks, p.rw, p.ch);
+    kern<<<dim3(p.grid), dim3(64 * p.ks * p.rw), p.lds, st>>>(a, p.ks, p.rw, p.ch, p.nsl);
     return launch_status();
 }
 
@@ -338,58 +361,74 @@ mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handl
     if (a.B > 4 || (r != 2 && r != 4) || a.row_ptr) return MQ_OK;
     const int lines = (a.KB + 127) / 128;
     const int nrb = (a.N + 15) / 16;
-    // Lines per slice: the widest slice (fewest activation reloads per byte of weights) that wastes
-    // no more than one line in ten on padding and leaves at least about a thousand waves.
-    QuadPlan p{};
-    p.nl = 0;
-    for (int nl = 4; nl >= 1; --nl) {
-        const int ks = (lines + nl - 1) / nl;
-        if (ks > 8) break;
-        const bool enough = (int64_t)nrb * ks >= 1024 || nl == 1;
-        if (10 * (ks * nl - lines) <= lines && enough) {
-            p.nl = nl;
-            p.ks = ks;
-            break;
-        }
-        if (p.nl == 0 || nl == 1) {  // fallback if nothing passes both tests
-            p.nl = nl;
-            p.ks = ks;
-        }
-    }
-    if (p.nl == 0) return MQ_OK;  // K too long for one workgroup of slices: the general kernel takes it
-    int wpc = 8;                   // waves per compute unit the grid is sized for
+    // Measured against the general kernel on 4096..36864 rows: faster from about 8192 rows on (0.8x the
+    // time at 36864 x 4608), level or slower below, where a launch is bound by latencies and not by bytes.
+    auto env = [](const char *name, int fallback) {
 #ifdef MQ_GEMV_TUNE
-    if (const char *e = getenv("MQ_GEMVQ_NL")) {
-        p.nl = atoi(e);
-        p.ks = (lines + p.nl - 1) / p.nl;
-        if (p.nl < 1 || p.nl > 4 || p.ks > 8) return MQ_ERR_SHAPE;
-    }
-    if (const char *e = getenv("MQ_GEMVQ_WPC")) wpc = atoi(e);
+        if (const char *e = getenv(name)) return atoi(e);
 #endif
+        return fallback;
+    };
+    if (nrb < env("MQ_GEMVQ_MINRB", 512)) return MQ_OK;
+    // Lines per slice: no padded lines if possible, then the widest slice (the activation registers are
+    // filled once per slice and wave).
+    QuadPlan p{};
+    {
+        int best = -1, best_cost = 0;
+        for (int nl = 1; nl <= 4; ++nl) {
+            const int nsl = (lines + nl - 1) / nl, pad = nsl * nl - lines;
+            const int cost = pad * 16 + (4 - nl);
+            if (best < 0 || cost < best_cost) best = nl, best_cost = cost;
+        }
+        p.nl = env("MQ_GEMVQ_NL", best);
+        if (p.nl < 1 || p.nl > 4) return MQ_ERR_SHAPE;
+    }
+    p.nsl = (lines + p.nl - 1) / p.nl;
+    // Slices per round: all of them up to eight waves, otherwise the largest divisor (every wave the
+    // same number of rounds), otherwise eight.
+    p.ks = std::min(p.nsl, 8);
+    if (p.nsl > 8)
+        for (int d = 8; d >= 5; --d)
+            if (p.nsl % d == 0) {
+                p.ks = d;
+                break;
+            }
+    p.ks = env("MQ_GEMVQ_KS", p.ks);
+    if (p.ks < 1 || p.ks > 8) return MQ_ERR_SHAPE;
+    const int wpc = env("MQ_GEMVQ_WPC", 12);  // waves per compute unit the grid is sized for
     // Row-block waves per workgroup and row blocks per workgroup: the whole grid resident at once
     // (wpc waves per compute unit), every wave the same number of visits where the shape allows.
-    p.rw = std::max(1, std::min(8 / p.ks, wpc / p.ks));
-#ifdef MQ_GEMV_TUNE
-    if (const char *e = getenv("MQ_GEMVQ_RW")) p.rw = atoi(e);
+    p.rw = env("MQ_GEMVQ_RW", 1);
     if (p.rw < 1 || p.rw * p.ks > 8) return MQ_ERR_SHAPE;
-#endif
     const int nw = p.ks * p.rw;
     const int per_cu = std::max(1, wpc / nw);
     const int capacity = 256 * per_cu;
-    int visits = (int)cdiv(nrb, (int64_t)capacity * p.rw);  // per wave
-    p.ch = visits * p.rw;
-#ifdef MQ_GEMV_TUNE
-    if (const char *e = getenv("MQ_GEMVQ_CH")) p.ch = atoi(e);
+    const int visits = (int)cdiv(nrb, (int64_t)capacity * p.rw);  // per wave and round
+    p.ch = env("MQ_GEMVQ_CH", visits * p.rw);
     if (p.ch < 1) return MQ_ERR_SHAPE;
-#endif
     p.grid = (int)cdiv(nrb, p.ch);
-    p.lds = kSumsBytes + (size_t)nw * kTileBytes + (size_t)p.ks * p.ch * 16 * sizeof(f32x4) +
-            (size_t)a.B * (((size_t)a.K + 511) / 512 * 1024 + kXPad);
-    if (p.lds > 160 * 1024 || (int64_t)p.ch * 16 * a.KB > 0x7FFFFFFFll || (int64_t)a.B * a.K * 2 > 0x7FFFFFFFll)
+    p.ch = (int)cdiv(nrb, p.grid);  // (the most row blocks any workgroup gets)
+    // Ring depth, as far as the LDS of a compute unit (160 KB, shared by per_cu workgroups) allows.
+    const size_t fixed = kSumsBytes + (size_t)p.nsl * p.ch * 16 * sizeof(f32x4) +
+                         (size_t)a.B * (((size_t)a.K + 511) / 512 * 1024 + kXPad);
+    const size_t budget = (size_t)160 * 1024 / per_cu;
+    p.depth = 0;
+    for (int d : {3, 2}) {  // (deeper rings measured slower: three steps in flight per wave are enough)
+        if (fixed + (size_t)nw * d * kTileBytes > budget) continue;
+        p.depth = d;
+        break;
+    }
+    p.depth = env("MQ_GEMVQ_S", p.depth);
+    if (p.depth == 0) return MQ_OK;
+    p.lds = fixed + (size_t)nw * p.depth * kTileBytes;
+    if (p.lds > 160 * 1024 || (int64_t)a.N * a.KB > 0x7FFFFFFFll || (int64_t)a.B * a.K * 2 > 0x7FFFFFFFll)
         return MQ_OK;
     *handled = true;
-#define MQ_QUAD_CASE(R_, NL_) \
-    if (r == R_ && p.nl == NL_) return launch_quad<R_, NL_>(a, p, st);
+#define MQ_QUAD_CASE(R_, NL_)                                             \
+    if (r == R_ && p.nl == NL_) {                                         \
+        if (p.depth == 3) return launch_quad<R_, NL_, 3>(a, p, st);       \
+        if (p.depth == 2) return launch_quad<R_, NL_, 2>(a, p, st);       \
+    }
     MQ_QUAD_CASE(2, 1) MQ_QUAD_CASE(2, 2) MQ_QUAD_CASE(2, 3) MQ_QUAD_CASE(2, 4)
     MQ_QUAD_CASE(4, 1) MQ_QUAD_CASE(4, 2) MQ_QUAD_CASE(4, 3) MQ_QUAD_CASE(4, 4)
 #undef MQ_QUAD_CASE

@@ -333,6 +333,43 @@ def test_gemv_many_rows(mq, oracle, r, B):
     assert np.all(err <= 2.0 ** -7 * np.abs(want) + 1e-4 * np.abs(want).max())
 
 
+@pytest.mark.parametrize("r,N,K,B", [(2, 8200, 4608, 1), (2, 8192, 1344, 3), (4, 9000, 4608, 4), (4, 8192, 14336, 1),
+                                     (2, 8195, 14336, 2), (4, 8192, 544, 4)])
+def test_gemv_small_batch_tall_matrix(mq, oracle, r, N, K, B):
+    """At least 8192 rows and B <= 4 on int4 / int2 planes: the kernel that keeps the activations of a K slice
+    in registers.  Shapes with one, several and padded 128-byte lines per slice, more slices than waves
+    (several rounds per wave), a ragged last line, ragged row counts; checked row by row."""
+    from paper_2502_06786_amd import synth
+    q = synth.uniform_codes(50 + r + B, N, K)
+    a = (torch.rand(N, generator=torch.Generator().manual_seed(16)) * 1e-3 + 1e-4).to(torch.bfloat16)
+    z = (torch.rand(N, generator=torch.Generator().manual_seed(17)) * 255).to(torch.bfloat16)
+    packed = mq.mq_slice(dev(q), r, packed=True)
+    x = _randn(B + r + 3, B, K).to(torch.bfloat16)
+    y = mq.mq_gemv_sliced(dev(x), packed, dev(a), dev(z), r, K)
+    want = oracle.gemv_sliced(bf16_bits(x), packed.cpu().numpy(), bf16_bits(a), bf16_bits(z), r, K)
+    got = y.float().cpu().numpy().astype(np.float64)
+    assert rel_l2(got, want) <= TOL
+    err = np.abs(got - want)
+    assert np.all(err <= 2.0 ** -7 * np.abs(want) + 1e-3 * np.abs(want).max())
+
+
+def test_gemv_small_batch_tall_matrix_one_hot_exact(mq, oracle):
+    # alpha = 1, z = 0, one-hot activations: y[b, n] is exactly the sliced value of code [n, k_b] (tall matrix, B <= 4)
+    N, K = 8208, 1024
+    q = torch.arange(N * K, dtype=torch.int64).mul(7).add(torch.arange(N * K, dtype=torch.int64) // K).remainder(256)
+    q = q.to(torch.uint8).reshape(N, K)
+    a = torch.ones(N).to(torch.bfloat16)
+    z = torch.zeros(N).to(torch.bfloat16)
+    for r in (2, 4):
+        packed = mq.mq_slice(dev(q), r, packed=True)
+        for k0 in (0, 17, 511, 1020):
+            x = torch.zeros(4, K)
+            x[torch.arange(4), k0 + torch.arange(4)] = 1.0
+            y = mq.mq_gemv_sliced(dev(x.to(torch.bfloat16)), packed, dev(a), dev(z), r, K)
+            want = oracle.slice_values(q.numpy(), r)[:, k0:k0 + 4].T.astype(np.float64)
+            assert np.array_equal(y.float().cpu().numpy().astype(np.float64), want), (r, k0)
+
+
 def test_gemv_one_hot_exact(mq, oracle):
     # alpha = 1, z = 0, one-hot activations: y[b, n] is exactly the sliced value of code [n, b].
     N, K = 64, 256
