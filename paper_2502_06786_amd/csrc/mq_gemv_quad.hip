@@ -361,23 +361,24 @@ mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handl
     if (a.B > 4 || (r != 2 && r != 4) || a.row_ptr) return MQ_OK;
     const int lines = (a.KB + 127) / 128;
     const int nrb = (a.N + 15) / 16;
-    // Measured against the general kernel on 4096..36864 rows: faster from about 8192 rows on (0.8x the
-    // time at 36864 x 4608), level or slower below, where a launch is bound by latencies and not by bytes.
+    // Measured against the general kernel on 4096..36864 rows: 0.85-0.9x the time at 36864 x 4608, level or
+    // slower at 14336 rows and below, where a launch is bound by latencies and not by bytes.
     auto env = [](const char *name, int fallback) {
 #ifdef MQ_GEMV_TUNE
         if (const char *e = getenv(name)) return atoi(e);
 #endif
         return fallback;
     };
-    if (nrb < env("MQ_GEMVQ_MINRB", 512)) return MQ_OK;
-    // Lines per slice: no padded lines if possible, then the widest slice (the activation registers are
-    // filled once per slice and wave).
+    if (nrb < env("MQ_GEMVQ_MINRB", 1024)) return MQ_OK;
+    // Lines per slice: no padded lines if possible, then about four slices per row (measured over the
+    // decode shapes: fewer leave a workgroup with too few waves, more spend their time filling activation
+    // registers), one round.
     QuadPlan p{};
     {
         int best = -1, best_cost = 0;
         for (int nl = 1; nl <= 4; ++nl) {
             const int nsl = (lines + nl - 1) / nl, pad = nsl * nl - lines;
-            const int cost = pad * 16 + (4 - nl);
+            const int cost = pad * 8 + (nsl > 8 ? 4 : 0) + std::abs(nsl - 4);
             if (best < 0 || cost < best_cost) best = nl, best_cost = cost;
         }
         p.nl = env("MQ_GEMVQ_NL", best);

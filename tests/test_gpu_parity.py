@@ -333,10 +333,10 @@ def test_gemv_many_rows(mq, oracle, r, B):
     assert np.all(err <= 2.0 ** -7 * np.abs(want) + 1e-4 * np.abs(want).max())
 
 
-@pytest.mark.parametrize("r,N,K,B", [(2, 8200, 4608, 1), (2, 8192, 1344, 3), (4, 9000, 4608, 4), (4, 8192, 14336, 1),
-                                     (2, 8195, 14336, 2), (4, 8192, 544, 4)])
+@pytest.mark.parametrize("r,N,K,B", [(2, 16400, 4608, 1), (2, 16384, 1344, 3), (4, 17000, 4608, 4), (4, 16384, 14336, 1),
+                                     (2, 16387, 14336, 2), (4, 16384, 544, 4)])
 def test_gemv_small_batch_tall_matrix(mq, oracle, r, N, K, B):
-    """At least 8192 rows and B <= 4 on int4 / int2 planes: the kernel that keeps the activations of a K slice
+    """At least 16384 rows and B <= 4 on int4 / int2 planes: the kernel that keeps the activations of a K slice
     in registers.  Shapes with one, several and padded 128-byte lines per slice, more slices than waves
     (several rounds per wave), a ragged last line, ragged row counts; checked row by row."""
     from paper_2502_06786_amd import synth
@@ -355,7 +355,7 @@ def test_gemv_small_batch_tall_matrix(mq, oracle, r, N, K, B):
 
 def test_gemv_small_batch_tall_matrix_one_hot_exact(mq, oracle):
     # alpha = 1, z = 0, one-hot activations: y[b, n] is exactly the sliced value of code [n, k_b] (tall matrix, B <= 4)
-    N, K = 8208, 1024
+    N, K = 16400, 1024
     q = torch.arange(N * K, dtype=torch.int64).mul(7).add(torch.arange(N * K, dtype=torch.int64) // K).remainder(256)
     q = q.to(torch.uint8).reshape(N, K)
     a = torch.ones(N).to(torch.bfloat16)
