@@ -56,7 +56,7 @@ enum {
                                     per code that keeps code 2^r, instead of plane + list     */
 };
 
-enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1 };
+enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1, MQ_OP_FFN_DECODE = 2 };
 
 /*
  * Extra-precision overflow set (errata section: weights whose rounded r-bit
@@ -199,6 +199,38 @@ mq_status mq_gemv_sliced_dense_ep(const uint16_t *x, const uint8_t *packed, cons
                                   uint16_t *y, void *hip_stream);
 
 /*
+ * Layer-wise Mix'n'Match on the decode path (section 4.3 "Mix'n'Match", section 5.1.3 and appendix B:
+ * every feed-forward layer of the stack is served at its own bit-width, e.g. int2 in the first and
+ * last layers and int8 in the middle, "Pyramid"): a stack of gated feed-forward layers, each reading
+ * the r_l-bit planes sliced from its own 8-bit codes,
+ *     h_0 = x;   g, u = W_gate h_l, W_up h_l;   a = act(g) * u;   o = W_down a;
+ *     h_(l+1) = o   (or h_l + o with MQ_FLAG_FFN_RESIDUAL);          y = h_L
+ * with every matrix-vector product computed as mq_gemv_sliced does and every intermediate (g, u, a, o,
+ * h) rounded to bf16.  The paper does not write the block out; Gemma-2 uses act = GELU (tanh form),
+ * the default here, Mistral SiLU (MQ_FLAG_FFN_SILU).
+ *   x        [B, d] bf16, 1 <= B <= 16
+ *   layers   HOST array of n_layers descriptors; all pointers in them are device pointers:
+ *              gate_up   packed plane of the gate rows followed by the up rows, [2F, d*r/8]
+ *              down      packed plane [d, F*r/8]
+ *              alpha_gu, zero_gu  bf16 [2F];  alpha_dn, zero_dn  bf16 [d]
+ *              r         bits of this layer's planes: 8, 6, 4, 3 or 2
+ *   y        [B, d] bf16 out (may not alias x)
+ *   ws       workspace of at least mq_workspace_bytes(MQ_OP_FFN_DECODE, B, F, d, 1)
+ * Alignment of the planes as for mq_gemv_sliced; F a multiple of 8.
+ */
+typedef struct {
+    const uint8_t *gate_up;
+    const uint8_t *down;
+    const uint16_t *alpha_gu, *zero_gu;
+    const uint16_t *alpha_dn, *zero_dn;
+    int r;
+} mq_ffn_layer;
+enum { MQ_FLAG_FFN_SILU = 16, MQ_FLAG_FFN_RESIDUAL = 32 };
+mq_status mq_ffn_mixnmatch(const uint16_t *x, const mq_ffn_layer *layers, int n_layers,
+                           int64_t B, int64_t d, int64_t F, uint32_t flags, uint16_t *y,
+                           void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Measurement helpers (they compute nothing of the method): ceilings of this GPU as measured by
  * kernels that only multiply or only read, to put next to the published peaks.
  *
@@ -213,7 +245,7 @@ mq_status mq_gemv_sliced_dense_ep(const uint16_t *x, const uint8_t *packed, cons
 mq_status mq_probe_mfma(const uint16_t *operands_bf16, int64_t iters, float *sink, void *hip_stream);
 mq_status mq_probe_read(const void *src, int64_t bytes, uint32_t *sink, void *hip_stream);
 
-/* Bytes of workspace `op` needs at these sizes (0 on invalid arguments). */
+/* Bytes of workspace `op` needs at these sizes (0 on invalid arguments).  MQ_OP_FFN_DECODE: M = B, N = F, K = d. */
 size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int nr);
 
 /* Static, human-readable name of a status code. */

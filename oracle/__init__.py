@@ -259,3 +259,42 @@ def gemv_sliced(x_bf16, packed, alpha_bf16, zero_bf16, r: int, K: int, ovf=None,
     _load().mqo_gemv_sliced(_p(x), _p(packed), _p(a), _p(z), _p(rp), _p(ci), _i64(B), _i64(N), _i64(K),
                             ctypes.c_int(r), ctypes.c_int(shift), _p(y))
     return y
+
+
+def bf16_round(v):
+    """fp64 array -> bf16 bit patterns (uint16): to fp32, then round-to-nearest-even on the upper 16 bits."""
+    u = np.ascontiguousarray(v, dtype=np.float64).astype(np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_to_f64(bits):
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def ffn_mixnmatch(x_bf16, layers, d: int, F: int, silu: bool = False, residual: bool = False):
+    """Layer-wise Mix'n'Match on the decode path (section 4.3, appendix B): a stack of gated feed-forward
+    layers, layer l read at its own bit-width r_l,
+        g, u = W_gate h, W_up h;  a = act(g) * u;  o = W_down a;  h <- o  (or h + o)
+    with the matrix-vector products of gemv_sliced (fp64) and every intermediate rounded to bf16.
+    act = GELU in its tanh form (default) or SiLU.  layers: dicts with gate_up [2F, d*r/8], down
+    [d, F*r/8] (packed uint8), alpha_gu, zero_gu [2F], alpha_dn, zero_dn [d] (bf16 bit patterns), r.
+    Returns (y as bf16 bit patterns [B, d], the last layer's output before its final rounding, fp64)."""
+    h = _c(x_bf16, np.uint16)
+    last = bf16_to_f64(h)
+    for L in layers:
+        r = int(L["r"])
+        gu = bf16_to_f64(bf16_round(gemv_sliced(h, L["gate_up"], L["alpha_gu"], L["zero_gu"], r, d)))
+        g, u = gu[:, :F], gu[:, F:]
+        if silu:
+            with np.errstate(over="ignore"):  # exp(-g) = inf for very negative g gives the limit -0
+                act = g / (1.0 + np.exp(-g))
+        else:
+            act = 0.5 * g * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (g + 0.044715 * g ** 3)))
+        a = bf16_round(act * u)
+        o = gemv_sliced(a, L["down"], L["alpha_dn"], L["zero_dn"], r, F)
+        if residual:
+            o = bf16_to_f64(h) + bf16_to_f64(bf16_round(o))
+        last = o
+        h = bf16_round(o)
+    return h, last

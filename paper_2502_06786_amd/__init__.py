@@ -8,6 +8,7 @@ _BINDING_NAMES = {
     "mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced", "mq_params_to_bf16",
     "mq_workspace_bytes", "mq_probe_mfma", "mq_probe_read", "mq_gemv_sliced_dense_ep", "MQ_FLAG_EP_DENSE", "status_string", "Overflow", "MqError", "lib", "LIB_PATH", "EXPORTS",
     "MQ_FLAG_EXTRA_PRECISION", "MQ_FLAG_PACKED", "MQ_FLAG_ACCUM_DW", "MQ_OP_LINEAR_FWD", "MQ_OP_LINEAR_BWD",
+    "mq_ffn_mixnmatch", "MQ_OP_FFN_DECODE", "MQ_FLAG_FFN_SILU", "MQ_FLAG_FFN_RESIDUAL",
 }
 
 

@@ -20,16 +20,25 @@ MQ_FLAG_PACKED = 2
 MQ_FLAG_ACCUM_DW = 4
 MQ_OP_LINEAR_FWD = 0
 MQ_OP_LINEAR_BWD = 1
+MQ_OP_FFN_DECODE = 2
+MQ_FLAG_FFN_SILU = 16
+MQ_FLAG_FFN_RESIDUAL = 32
 
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
            "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string", "mq_probe_mfma", "mq_probe_read",
-           "mq_gemv_sliced_dense_ep"]
+           "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch"]
 
 
 class MqError(RuntimeError):
     def __init__(self, status: int, what: str):
         super().__init__(f"{what}: mq_status {status} ({status_string(status)})")
         self.status = status
+
+
+class _FfnLayer(ctypes.Structure):
+    _fields_ = [("gate_up", ctypes.c_void_p), ("down", ctypes.c_void_p), ("alpha_gu", ctypes.c_void_p),
+                ("zero_gu", ctypes.c_void_p), ("alpha_dn", ctypes.c_void_p), ("zero_dn", ctypes.c_void_p),
+                ("r", ctypes.c_int)]
 
 
 class _Overflow(ctypes.Structure):
@@ -57,6 +66,7 @@ def _load() -> ctypes.CDLL:
     lib.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
+    lib.mq_ffn_mixnmatch.argtypes = [vp, ctypes.POINTER(_FfnLayer), ci, i64, i64, i64, u32, vp, vp, sz, vp]
     lib.mq_probe_read.argtypes = [vp, i64, vp, vp]
     for name in EXPORTS:
         if name not in ("mq_workspace_bytes", "mq_status_string"):
@@ -267,4 +277,32 @@ def mq_gemv_sliced(x, packed, alpha_bf16, zero_bf16, r: int, K: int, ovf: Overfl
     st = _lib.mq_gemv_sliced(_ptr(x, torch.bfloat16), _ptr(packed, torch.uint8), _ptr(alpha_bf16, torch.bfloat16),
                              _ptr(zero_bf16, torch.bfloat16), c_ovf, B, N, K, r, _ptr(y, torch.bfloat16), _stream())
     _check(st, "mq_gemv_sliced")
+    return y
+
+
+def mq_ffn_mixnmatch(x, layers, F: int, silu: bool = False, residual: bool = False, y=None, ws=None):
+    """Stack of gated feed-forward layers on the decode path, one bit-width per layer.
+    x bf16 [B, d]; layers: sequence of dicts with the device tensors gate_up uint8 [2F, d*r/8],
+    down uint8 [d, F*r/8], alpha_gu, zero_gu bf16 [2F], alpha_dn, zero_dn bf16 [d] and the int r."""
+    B, d = x.shape
+    arr = (_FfnLayer * max(len(layers), 1))()
+    for i, L in enumerate(layers):
+        r = int(L["r"])
+        if tuple(L["gate_up"].shape) != (2 * F, d * r // 8) or tuple(L["down"].shape) != (d, F * r // 8):
+            raise ValueError("plane shapes do not match B, d, F, r")
+        if L["alpha_gu"].numel() != 2 * F or L["zero_gu"].numel() != 2 * F or L["alpha_dn"].numel() != d \
+                or L["zero_dn"].numel() != d:
+            raise ValueError("parameter sizes do not match d, F")
+        arr[i] = _FfnLayer(_ptr(L["gate_up"], torch.uint8), _ptr(L["down"], torch.uint8),
+                           _ptr(L["alpha_gu"], torch.bfloat16), _ptr(L["zero_gu"], torch.bfloat16),
+                           _ptr(L["alpha_dn"], torch.bfloat16), _ptr(L["zero_dn"], torch.bfloat16), r)
+    if y is None:
+        y = torch.empty(B, d, dtype=torch.bfloat16, device=x.device)
+    nbytes = mq_workspace_bytes(MQ_OP_FFN_DECODE, B, F, d, 1)
+    if ws is None:
+        ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=x.device)
+    flags = (MQ_FLAG_FFN_SILU if silu else 0) | (MQ_FLAG_FFN_RESIDUAL if residual else 0)
+    st = _lib.mq_ffn_mixnmatch(_ptr(x, torch.bfloat16), arr, len(layers), B, d, F, flags, _ptr(y, torch.bfloat16),
+                               _ptr(ws, torch.uint8), ws.numel(), _stream())
+    _check(st, "mq_ffn_mixnmatch")
     return y

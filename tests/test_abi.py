@@ -37,6 +37,7 @@ def lib():
     lib_.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
     lib_.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
+    lib_.mq_ffn_mixnmatch.argtypes = [vp, vp, ci, i64, i64, i64, u32, vp, vp, sz, vp]
     lib_.mq_probe_read.argtypes = [vp, i64, vp, vp]
     lib_.mq_workspace_bytes.argtypes = [ci, i64, i64, i64, ci]
     lib_.mq_workspace_bytes.restype = sz
@@ -79,6 +80,9 @@ def test_workspace_bytes(lib):
     assert bwd >= 3 * M * N * 2 + M * N * 2 + M * K * 2 + N * K
     assert f(1, M, N, K, 1) < bwd
     assert f(0, -1, N, K, 3) == 0 and f(1, M, N, K, 4) == 0 and f(1, M, N, K, 0) == 0
+    # decode feed-forward stack (M = B, N = F, K = d): g and u, the gated product, three copies of the state
+    assert f(2, 4, 14336, 4096, 1) >= 4 * (3 * 14336 + 3 * 4096) * 2
+    assert f(2, 17, 14336, 4096, 1) == 0 and f(2, 0, 14336, 4096, 1) == 0
 
 
 def test_slice_argument_checks(lib):
@@ -146,3 +150,24 @@ def test_dense_extra_precision_argument_checks(lib):
 def test_probe_argument_checks(lib):
     assert lib.mq_probe_mfma(None, 10, None, None) == NULL
     assert lib.mq_probe_read(None, 1024, None, None) == NULL
+
+
+def test_ffn_mixnmatch_argument_checks(lib):
+    f = lib.mq_ffn_mixnmatch
+
+    class Layer(ctypes.Structure):
+        _fields_ = [(n, ctypes.c_void_p) for n in ("gate_up", "down", "alpha_gu", "zero_gu", "alpha_dn", "zero_dn")] + \
+                   [("r", ctypes.c_int)]
+
+    bad_bits = (Layer * 1)(Layer(None, None, None, None, None, None, 5))
+    nulls = (Layer * 1)(Layer(None, None, None, None, None, None, 4))
+    x = ctypes.c_void_p(4096)    # never dereferenced: every call below returns before the first launch
+    y = ctypes.c_void_p(8192)
+    assert f(None, None, 1, 1, 256, 512, 0, None, None, 0, None) == NULL
+    assert f(x, None, 1, 17, 256, 512, 0, y, None, 0, None) == SHAPE
+    assert f(x, None, -1, 1, 256, 512, 0, y, None, 0, None) == SHAPE
+    assert f(x, None, 1, 1, 256, 500, 0, y, None, 0, None) == ALIGN
+    assert f(x, None, 1, 1, 256, 512, 0, y, None, 0, None) == NULL          # layers missing
+    assert f(x, bad_bits, 1, 1, 256, 512, 0, y, None, 0, None) == BITS
+    assert f(x, nulls, 1, 1, 256, 512, 0, y, None, 0, None) == NULL
+    assert f(x, nulls, 1, 1, 256, 512, 0, x, None, 0, None) == SHAPE        # y aliases x

@@ -386,6 +386,55 @@ def test_gemv_one_hot_exact(mq, oracle):
             assert np.array_equal(y.float().cpu().numpy().astype(np.float64), want), (r, k0)
 
 
+# --------------------------------------------------------------------------
+# layer-wise Mix'n'Match feed-forward stack (decode path)
+# --------------------------------------------------------------------------
+def _ffn_stack(mq, oracle, seed, d, F, rs, scale):
+    """Layers quantized by the library from seeded fp32 weights; planes and bf16 parameters on the GPU."""
+    layers, host = [], []
+    for i, r in enumerate(rs):
+        w_gu = _randn(seed + 10 * i, 2 * F, d, scale=scale / d ** 0.5)
+        w_dn = _randn(seed + 10 * i + 1, d, F, scale=scale / F ** 0.5)
+        L = {"r": r}
+        for name, w in (("gu", w_gu), ("dn", w_dn)):
+            Q, a, z = mq.mq_quantize_int8(dev(w))
+            a16, z16 = mq.mq_params_to_bf16(a, z)
+            L["gate_up" if name == "gu" else "down"] = mq.mq_slice(Q, r, packed=True)
+            L["alpha_" + name], L["zero_" + name] = a16, z16
+        layers.append(L)
+        host.append({k: (v if k == "r" else (bf16_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy()))
+                     for k, v in L.items()})
+    return layers, host
+
+
+@pytest.mark.parametrize("d,F,rs,B,silu,residual", [
+    (256, 512, (2, 8, 4), 1, False, False), (256, 512, (2, 8, 4), 4, True, False), (256, 512, (3, 6, 2, 4), 16, False, True),
+    (512, 1536, (4,), 3, False, False), (128, 256, (), 2, False, False)])
+def test_ffn_mixnmatch_small(mq, oracle, d, F, rs, B, silu, residual):
+    layers, host = _ffn_stack(mq, oracle, 70, d, F, rs, scale=1.5)
+    x = _randn(77 + B, B, d).to(torch.bfloat16)
+    y = mq.mq_ffn_mixnmatch(dev(x), layers, F, silu=silu, residual=residual)
+    want_bits, _ = oracle.ffn_mixnmatch(bf16_bits(x), host, d, F, silu=silu, residual=residual)
+    want = oracle.bf16_to_f64(want_bits)
+    assert np.isfinite(want).all() and np.abs(want).max() > 1e-3
+    # Every layer is two GEMVs at the single-call tolerance plus the bf16 rounding of g, u, a and o on both sides,
+    # and a difference that enters a layer leaves it about as large: the bar grows linearly with the depth.
+    assert rel_l2(y.float().cpu().numpy(), want) <= TOL * max(len(rs), 1)
+
+
+def test_ffn_mixnmatch_7b_shaped_pyramid(mq, oracle):
+    """Mistral-7B-shaped layers (d 4096, F 14336), int2 - int4 - int2: the stacked gate/up plane has 28672 rows
+    (the tall-matrix kernel at int2 / int4), B = 1."""
+    d, F, rs = 4096, 14336, (2, 4, 2)
+    layers, host = _ffn_stack(mq, oracle, 90, d, F, rs, scale=1.5)
+    x = _randn(91, 1, d).to(torch.bfloat16)
+    y = mq.mq_ffn_mixnmatch(dev(x), layers, F, silu=True)
+    want_bits, _ = oracle.ffn_mixnmatch(bf16_bits(x), host, d, F, silu=True)
+    want = oracle.bf16_to_f64(want_bits)
+    assert np.abs(want).max() > 1e-3
+    assert rel_l2(y.float().cpu().numpy(), want) <= TOL * len(rs)
+
+
 def test_measurement_probes_run(mq):
     ops = torch.randn(32768, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
     sink = torch.zeros(65536, dtype=torch.float32, device="cuda")

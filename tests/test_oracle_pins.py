@@ -459,3 +459,75 @@ def test_gemv_dense_extra_precision_plane(oracle):
     dense = oracle.pack(oracle.slice_codes(q, 2, ep=True), 3)
     y = oracle.gemv_sliced(onehot, dense, ones, zeros, 3, K, shift=6)
     assert y[np.arange(5), 0].tolist() == [0.0, 64.0, 128.0, 192.0, 256.0]
+
+
+# --------------------------------------------------------------------------
+# layer-wise Mix'n'Match feed-forward stack (decode path)
+# --------------------------------------------------------------------------
+def _ffn_layers(oracle, seed, d, F, rs):
+    """Random layers: 8-bit codes -> the r_l-bit planes, bf16 alpha / z (as bit patterns)."""
+    g = torch.Generator().manual_seed(seed)
+    layers, dense = [], []
+    for r in rs:
+        q_gu = torch.randint(0, 256, (2 * F, d), generator=g, dtype=torch.int32).to(torch.uint8).numpy()
+        q_dn = torch.randint(0, 256, (d, F), generator=g, dtype=torch.int32).to(torch.uint8).numpy()
+        a_gu = (torch.rand(2 * F, generator=g) * 4e-4 + 2e-4).to(torch.bfloat16)
+        z_gu = (torch.rand(2 * F, generator=g) * 40 + 108).to(torch.bfloat16)
+        a_dn = (torch.rand(d, generator=g) * 4e-4 + 2e-4).to(torch.bfloat16)
+        z_dn = (torch.rand(d, generator=g) * 40 + 108).to(torch.bfloat16)
+        layers.append(dict(gate_up=oracle.pack(oracle.slice_codes(q_gu, r), r), down=oracle.pack(oracle.slice_codes(q_dn, r), r),
+                           alpha_gu=bf16_bits(a_gu), zero_gu=bf16_bits(z_gu), alpha_dn=bf16_bits(a_dn),
+                           zero_dn=bf16_bits(z_dn), r=r))
+        # the same weights dequantized without the oracle's GEMV: alpha (2^s code - z), literally
+        s = 8 - r
+        code_gu = np.minimum((q_gu.astype(np.int64) + ((1 << s) >> 1)) >> s, (1 << r) - 1)
+        code_dn = np.minimum((q_dn.astype(np.int64) + ((1 << s) >> 1)) >> s, (1 << r) - 1)
+        w_gu = a_gu.double().numpy()[:, None] * (code_gu * float(1 << s) - z_gu.double().numpy()[:, None])
+        w_dn = a_dn.double().numpy()[:, None] * (code_dn * float(1 << s) - z_dn.double().numpy()[:, None])
+        dense.append((torch.from_numpy(w_gu), torch.from_numpy(w_dn)))
+    return layers, dense
+
+
+@pytest.mark.parametrize("silu,residual", [(False, False), (True, False), (False, True)])
+def test_ffn_mixnmatch_vs_library_composition(oracle, silu, residual):
+    # Library special case: torch float64 matmul + torch's own GELU(tanh) / SiLU on independently
+    # dequantized weights, bf16 rounding by torch at the same points.
+    d, F, rs = 128, 256, (2, 8, 4, 3)
+    layers, dense = _ffn_layers(oracle, 3, d, F, rs)
+    x = (torch.randn(3, d, generator=torch.Generator().manual_seed(9))).to(torch.bfloat16)
+    got_bits, _ = oracle.ffn_mixnmatch(bf16_bits(x), layers, d, F, silu=silu, residual=residual)
+    h = x.double()
+    rnd = lambda t: t.to(torch.float32).to(torch.bfloat16).double()
+    for w_gu, w_dn in dense:
+        gu = rnd(h @ w_gu.T)
+        g, u = gu[:, :F], gu[:, F:]
+        act = torch.nn.functional.silu(g) if silu else torch.nn.functional.gelu(g, approximate="tanh")
+        a = rnd(act * u)
+        o = a @ w_dn.T
+        h = rnd(h + rnd(o)) if residual else rnd(o)
+    want = h.numpy()
+    got = bits_to_f64(got_bits)
+    # identical up to values that sit within 1e-12 of a bf16 rounding boundary in one of the two evaluations
+    assert np.mean(got != want) < 0.02
+    assert np.linalg.norm(got - want) <= 2e-3 * np.linalg.norm(want)
+
+
+def test_ffn_mixnmatch_depends_on_the_order_of_the_bit_widths(oracle):
+    # Pyramid vs. reverse pyramid over the same layers' codes are different models (appendix B).
+    d, F = 128, 256
+    x = torch.randn(2, d, generator=torch.Generator().manual_seed(1)).to(torch.bfloat16)
+    la, _ = _ffn_layers(oracle, 5, d, F, (2, 8, 2))
+    lb, _ = _ffn_layers(oracle, 5, d, F, (8, 2, 8))
+    ya, _ = oracle.ffn_mixnmatch(bf16_bits(x), la, d, F)
+    yb, _ = oracle.ffn_mixnmatch(bf16_bits(x), lb, d, F)
+    assert not np.array_equal(ya, yb)
+    # no layers: the identity
+    y0, _ = oracle.ffn_mixnmatch(bf16_bits(x), [], d, F)
+    assert np.array_equal(y0, bf16_bits(x))
+
+
+def test_bf16_round_is_round_to_nearest_even(oracle):
+    v = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -2.5, 0.0])
+    want = torch.from_numpy(v).to(torch.float32).to(torch.bfloat16)
+    assert np.array_equal(oracle.bf16_round(v), bf16_bits(want))
+    assert np.array_equal(oracle.bf16_to_f64(oracle.bf16_round(v)), want.double().numpy())
