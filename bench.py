@@ -5,8 +5,9 @@ One step = one pass of the whole hot path over the Gemma-2-2B-shaped MLP (d_mode
 4096 tokens; seeded synthetic weights and activations already resident in HBM): for each of the
 three linears (gate, up, down) quantize the fp32 master weight to int8 codes, slice and pack the
 r = 4 and r = 2 planes (r = 2 also with the extra-precision overflow list), run the fused
-r = 8/4/2 forward and the straight-through backward (dX, dW), round alpha/z to bf16 and run the
-decode GEMV at B = 1, 4, 16 on the int4 and int2 planes.
+r = 8/4/2 forward, the L2 reconstruction objective of the three outputs against the output of the
+full-precision layer (losses and the gradients dY_r) and the straight-through backward (dX, dW),
+round alpha/z to bf16 and run the decode GEMV at B = 1, 4, 16 on the int4 and int2 planes.
 
 `value` is the forward + backward matrix-core work of the step (6 MNK + 8 MNK flops per linear)
 divided by the wall time of the WHOLE step, so the bandwidth-bound operations count against it.
@@ -57,7 +58,12 @@ class Linear:
         N, K = self.N, self.K
         self.W = case.W.to(dev)
         self.X = case.X.to(dev)
-        self.dY = [d.to(dev) for d in case.dY]
+        # y' of the layer-wise reconstruction objective: the output of the full-precision layer (computed once,
+        # outside the timed region, with the framework's bf16 matmul: an input of the step, not part of it)
+        self.T = (self.X @ self.W.to(torch.bfloat16).t()).contiguous()
+        self.dY = [torch.empty(M, N, dtype=torch.bfloat16, device=dev) for _ in rs]
+        self.losses = torch.empty(len(rs), dtype=torch.float32, device=dev)
+        self.ws_l = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_L2_LOSS, M, N, 0, len(rs)), dtype=torch.uint8, device=dev)
         self.Q = torch.empty(N, K, dtype=torch.uint8, device=dev)
         self.alpha = torch.empty(N, dtype=torch.float32, device=dev)
         self.zero = torch.empty(N, dtype=torch.float32, device=dev)
@@ -91,7 +97,7 @@ def main():
     _, M = synth.mlp_shapes(2)
     layers = [Linear(mq, torch, synth, name, M, rs, lambdas) for name in ("gate", "up", "down")]
 
-    ops = ["quantize", "slice", "fwd", "bwd", "gemv"]
+    ops = ["quantize", "slice", "fwd", "loss", "bwd", "gemv"]
     records = {op: [] for op in ops}   # (start event, end event) pairs inside the timed region
 
     def timed(op, fn, rec):
@@ -114,6 +120,8 @@ def main():
                 mq.mq_params_to_bf16(L.alpha, L.zero, L.alpha16, L.zero16)
             timed("slice", do_slice, rec)
             timed("fwd", lambda: mq.mq_linear_fwd_multi(L.X, L.Q, L.alpha, L.zero, rs, Y=L.Y, ws=L.ws_f), rec)
+            # L2 reconstruction losses of the three outputs against y' and the gradients the backward consumes
+            timed("loss", lambda: mq.mq_matquant_l2_loss(L.Y, L.T, None, lambdas, dY=L.dY, losses=L.losses, ws=L.ws_l), rec)
             timed("bwd", lambda: mq.mq_linear_bwd(L.X, L.Q, L.alpha, L.zero, L.dY, lambdas, rs, dX=L.dX, dW=L.dW,
                                                   ws=L.ws_b), rec)
 
@@ -155,6 +163,7 @@ def main():
         "quantize_GBs": 5.0 * nk / (op_ms["quantize"] * 1e-3) / 1e9,
         "slice_GBs": (2.0 + 0.5 + 0.25) * nk / (op_ms["slice"] * 1e-3) / 1e9,
         "gemv_GBs": gemv_bytes / (op_ms["gemv"] * 1e-3) / 1e9,
+        "loss_GBs": 14.0 * sum(L.M * L.N for L in layers) / (op_ms["loss"] * 1e-3) / 1e9,   # 3 Y + y' read, 3 dY written
         "ms": {k: round(v, 4) for k, v in op_ms.items()},
     }
 
@@ -175,7 +184,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[1]: Gemma-2-2B-shaped MLP, d_model 2304, ffn 9216, 4096 tokens, "
-                               "gate/up/down; quantize + slice/pack + fused r=8/4/2 fwd + STE bwd + decode GEMV "
+                               "gate/up/down; quantize + slice/pack + fused r=8/4/2 fwd + L2 objective + STE bwd + decode GEMV "
                                "B=1/4/16 (int4, int2)", "tokens": M, "rs": list(rs), "seed": synth.config_seed(2)},
         "per_op": per_op,
         "roofline": roofline,
@@ -191,6 +200,8 @@ def main():
             best["frac_of_measured_read"] = round(best["achieved"] / peaks["hbm_read_85MB_GBs"], 4)
     if not args.no_gemv_sweep:
         out["extra_precision_gemv"] = ep_gemv(torch, mq, synth)
+    if not args.no_gemv_sweep:
+        out["mixnmatch_decode"] = mixnmatch_decode(torch, mq, synth)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, synth, rs, lambdas)
     print(json.dumps(out))
@@ -355,6 +366,59 @@ def ep_gemv(torch, mq, synth):
             nbytes = wbytes + 4 * N + 2 * B * K + 2 * B * N
             res[f"{name}_B{B}"] = {"us": round(ms * 1e3, 2), "GBs": round(nbytes / (ms * 1e-3) / 1e9, 1),
                                    "frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    return res
+
+
+def mixnmatch_decode(torch, mq, synth):
+    """Layer-wise Mix'n'Match on the decode path: a stack of eight Mistral-7B-shaped gated feed-forward layers
+    (d 4096, F 14336; stacked gate/up plane 28672 x 4096, down plane 4096 x 14336) served as a pyramid
+    (int2 at both ends, int8 in the middle; 4 bits per feed-forward weight on average) and homogeneously at
+    int2 and int4.  Planes hold uniform random codes (the time does not depend on the values); the stack is
+    captured into a HIP graph and replayed; bytes = the packed planes + parameters + activations."""
+    d, F = 4096, 14336
+    stacks = {"pyramid_2-2-4-8-8-4-2-2": (2, 2, 4, 8, 8, 4, 2, 2), "int2_x8": (2,) * 8, "int4_x8": (4,) * 8}
+    g = torch.Generator().manual_seed(11)
+    a_gu = (torch.rand(2 * F, generator=g) * 1e-4 + 5e-5).to(torch.bfloat16).cuda()
+    z_gu = (torch.rand(2 * F, generator=g) * 40 + 108).to(torch.bfloat16).cuda()
+    a_dn = (torch.rand(d, generator=g) * 1e-4 + 5e-5).to(torch.bfloat16).cuda()
+    z_dn = (torch.rand(d, generator=g) * 40 + 108).to(torch.bfloat16).cuda()
+    res = {"d": d, "F": F, "layers": 8}
+    for name, rs in stacks.items():
+        layers, wbytes = [], 0
+        for r in rs:
+            gu = torch.randint(0, 256, (2 * F, d * r // 8), generator=g, dtype=torch.int32).to(torch.uint8).cuda()
+            dn = torch.randint(0, 256, (d, F * r // 8), generator=g, dtype=torch.int32).to(torch.uint8).cuda()
+            layers.append(dict(gate_up=gu, down=dn, alpha_gu=a_gu, zero_gu=z_gu, alpha_dn=a_dn, zero_dn=z_dn, r=r))
+            wbytes += gu.numel() + dn.numel() + 4 * (2 * F + d)
+        entry = {"bits_per_weight": round(sum(rs) / len(rs), 3), "weight_MB": round(wbytes / 1e6, 1)}
+        for B in (1, 4):
+            x = synth.activations(4, f"mnm{B}", B, d).cuda()
+            y = torch.empty(B, d, dtype=torch.bfloat16, device="cuda")
+            ws = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_FFN_DECODE, B, F, d, 1), dtype=torch.uint8, device="cuda")
+            mq.mq_ffn_mixnmatch(x, layers, F, residual=True, y=y, ws=ws)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                mq.mq_ffn_mixnmatch(x, layers, F, residual=True, y=y, ws=ws)
+            graph.replay()
+            torch.cuda.synchronize()
+            times = []
+            for _ in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                graph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1))
+            del graph
+            ms = sorted(times)[2]
+            nbytes = wbytes + len(rs) * B * 2 * (2 * d + 3 * F + 2 * F + 2 * d)   # states, g/u, gated product: written and read
+            entry[f"B{B}"] = {"us_per_layer": round(ms * 1e3 / len(rs), 2), "GBs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                              "frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        res[name] = entry
+        del layers
+    res["note"] = ("one mq_ffn_mixnmatch call (two GEMVs, the gate kernel and the residual add per layer) from a HIP-graph "
+                   "replay; every stack exceeds the 256 MB last-level cache except int2_x8 (352 MB of planes: it does too)")
     return res
 
 

@@ -56,7 +56,7 @@ enum {
                                     per code that keeps code 2^r, instead of plane + list     */
 };
 
-enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1, MQ_OP_FFN_DECODE = 2 };
+enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1, MQ_OP_FFN_DECODE = 2, MQ_OP_L2_LOSS = 3 };
 
 /*
  * Extra-precision overflow set (errata section: weights whose rounded r-bit
@@ -197,6 +197,31 @@ mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_
 mq_status mq_gemv_sliced_dense_ep(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                                   const uint16_t *zero_bf16, int64_t B, int64_t N, int64_t K, int r,
                                   uint16_t *y, void *hip_stream);
+
+/*
+ * The MatQuant objective with the layer-wise L2 reconstruction loss (section 3.2, joint objective over
+ * the bit-widths, with the loss of section 3.1.2: the output of the quantized layer against the output
+ * y' of the full-precision layer), and its co-distillation variants (section 5.2: the output of a
+ * higher-precision slice as the target of a lower one, alone or next to y' with equal weights):
+ *     loss_i   = 1/(M N) * sum_{m,n} (Y_i - T_i)^2        T_i = target (teacher[i] < 0) or Y_teacher[i]
+ *     loss_i   = 1/2 of each of the two when teacher[i] >= 0 and MQ_FLAG_LOSS_MIX
+ *     total    = sum_i lambda_i loss_i
+ *     dY_i     = d total / d Y_i with the teachers held constant (stop-gradient)
+ *              = lambda_i * 2 (Y_i - T_i) / (M N)         (the mean of the two differences when mixed)
+ *   Y        host array of nr device pointers, each [M, N] bf16 (the outputs of mq_linear_fwd_multi)
+ *   target   [M, N] bf16, y'; may be NULL when every i has a teacher and MQ_FLAG_LOSS_MIX is not set
+ *   teacher  host int[nr] or NULL (= all -1); teacher[i] in -1 .. nr-1, teacher[i] != i
+ *   lambda   host float[nr] or NULL (= 1)
+ *   dY       host array of nr device pointers, each [M, N] bf16 out: what mq_linear_bwd takes
+ *   losses   device float[nr] out: loss_i (unweighted)
+ *   ws       workspace of at least mq_workspace_bytes(MQ_OP_L2_LOSS, M, N, 0, nr)
+ * M * N must be a multiple of 8; 1 <= nr <= 3.  M * N == 0 is a no-op.
+ */
+enum { MQ_FLAG_LOSS_MIX = 64 };
+mq_status mq_matquant_l2_loss(const uint16_t *const *Y, const uint16_t *target, const int *teacher,
+                              const float *lambda, int64_t M, int64_t N, int nr, uint32_t flags,
+                              uint16_t *const *dY, float *losses, void *ws, size_t ws_bytes,
+                              void *hip_stream);
 
 /*
  * Layer-wise Mix'n'Match on the decode path (section 4.3 "Mix'n'Match", section 5.1.3 and appendix B:

@@ -298,3 +298,32 @@ def ffn_mixnmatch(x_bf16, layers, d: int, F: int, silu: bool = False, residual: 
         last = o
         h = bf16_round(o)
     return h, last
+
+
+def matquant_l2_loss(Ys_bf16, target_bf16=None, teacher=None, lambdas=None, mix: bool = False):
+    """Joint objective of section 3.2 with the layer-wise L2 loss of section 3.1.2 and the co-distillation
+    targets of section 5.2, in fp64: loss_i = mean((Y_i - T_i)^2) with T_i the target (teacher[i] < 0) or the
+    output Y_teacher[i] held constant; with mix, the equal-weight mean of both losses.  Returns
+    (losses [nr], dYs = d(sum_i lambda_i loss_i)/dY_i as fp64 arrays)."""
+    Ys = [bf16_to_f64(y) for y in Ys_bf16]
+    nr = len(Ys)
+    T = None if target_bf16 is None else bf16_to_f64(target_bf16)
+    teacher = [-1] * nr if teacher is None else list(teacher)
+    lam = [1.0] * nr if lambdas is None else [float(v) for v in lambdas]
+    mn = Ys[0].size
+    losses, dYs = [], []
+    for i in range(nr):
+        t = teacher[i]
+        if t < 0:
+            diff = Ys[i] - T
+            losses.append(float((diff ** 2).sum() / mn))
+            dYs.append(lam[i] * 2.0 * diff / mn)
+        elif not mix:
+            diff = Ys[i] - Ys[t]
+            losses.append(float((diff ** 2).sum() / mn))
+            dYs.append(lam[i] * 2.0 * diff / mn)
+        else:
+            d1, d2 = Ys[i] - Ys[t], Ys[i] - T
+            losses.append(float(0.5 * ((d1 ** 2).sum() + (d2 ** 2).sum()) / mn))
+            dYs.append(lam[i] * (d1 + d2) / mn)
+    return np.array(losses), dYs

@@ -21,12 +21,14 @@ MQ_FLAG_ACCUM_DW = 4
 MQ_OP_LINEAR_FWD = 0
 MQ_OP_LINEAR_BWD = 1
 MQ_OP_FFN_DECODE = 2
+MQ_OP_L2_LOSS = 3
+MQ_FLAG_LOSS_MIX = 64
 MQ_FLAG_FFN_SILU = 16
 MQ_FLAG_FFN_RESIDUAL = 32
 
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
            "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string", "mq_probe_mfma", "mq_probe_read",
-           "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch"]
+           "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss"]
 
 
 class MqError(RuntimeError):
@@ -66,6 +68,8 @@ def _load() -> ctypes.CDLL:
     lib.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
+    lib.mq_matquant_l2_loss.argtypes = [ctypes.POINTER(vp), vp, ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_float), i64,
+                                        i64, ci, u32, ctypes.POINTER(vp), vp, vp, sz, vp]
     lib.mq_ffn_mixnmatch.argtypes = [vp, ctypes.POINTER(_FfnLayer), ci, i64, i64, i64, u32, vp, vp, sz, vp]
     lib.mq_probe_read.argtypes = [vp, i64, vp, vp]
     for name in EXPORTS:
@@ -306,3 +310,25 @@ def mq_ffn_mixnmatch(x, layers, F: int, silu: bool = False, residual: bool = Fal
                                _ptr(ws, torch.uint8), ws.numel(), _stream())
     _check(st, "mq_ffn_mixnmatch")
     return y
+
+
+def mq_matquant_l2_loss(Y, target=None, teacher=None, lambdas=None, mix: bool = False, dY=None, losses=None, ws=None):
+    """L2 reconstruction losses of the bit-widths' outputs Y (list of bf16 [M, N]) against the target (bf16 [M, N])
+    or against another output (teacher[i] = its index, -1 = the target), and the gradients dY the backward takes.
+    Returns (losses fp32 [nr] on the GPU, list of dY bf16 [M, N])."""
+    nr = len(Y)
+    M, N = Y[0].shape
+    if dY is None:
+        dY = [torch.empty(M, N, dtype=torch.bfloat16, device=Y[0].device) for _ in range(nr)]
+    if losses is None:
+        losses = torch.empty(nr, dtype=torch.float32, device=Y[0].device)
+    nbytes = mq_workspace_bytes(MQ_OP_L2_LOSS, M, N, 0, max(1, min(nr, 3)))
+    if ws is None:
+        ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=Y[0].device)
+    c_teacher = (ctypes.c_int * nr)(*teacher) if teacher is not None else None
+    c_lambda = (ctypes.c_float * nr)(*lambdas) if lambdas is not None else None
+    st = _lib.mq_matquant_l2_loss(_ptr_array(Y, torch.bfloat16), _ptr(target, torch.bfloat16), c_teacher, c_lambda, M, N, nr,
+                                  MQ_FLAG_LOSS_MIX if mix else 0, _ptr_array(dY, torch.bfloat16),
+                                  _ptr(losses, torch.float32), _ptr(ws, torch.uint8), ws.numel(), _stream())
+    _check(st, "mq_matquant_l2_loss")
+    return losses, dY

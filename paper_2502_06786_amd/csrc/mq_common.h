@@ -41,6 +41,8 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // workspace of mq_ffn_mixnmatch (mq_ffn.hip)
 size_t ffn_workspace_bytes(int64_t B, int64_t F, int64_t d);
+// workspace of mq_matquant_l2_loss (mq_loss.hip)
+size_t loss_workspace_bytes(int64_t M, int64_t N);
 
 // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  This maps the hardware
 // id to a logical id such that each XCD owns one contiguous range of logical ids, so that tiles

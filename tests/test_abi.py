@@ -37,6 +37,7 @@ def lib():
     lib_.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
     lib_.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
+    lib_.mq_matquant_l2_loss.argtypes = [vp, vp, ctypes.POINTER(ci), vp, i64, i64, ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_ffn_mixnmatch.argtypes = [vp, vp, ci, i64, i64, i64, u32, vp, vp, sz, vp]
     lib_.mq_probe_read.argtypes = [vp, i64, vp, vp]
     lib_.mq_workspace_bytes.argtypes = [ci, i64, i64, i64, ci]
@@ -171,3 +172,16 @@ def test_ffn_mixnmatch_argument_checks(lib):
     assert f(x, bad_bits, 1, 1, 256, 512, 0, y, None, 0, None) == BITS
     assert f(x, nulls, 1, 1, 256, 512, 0, y, None, 0, None) == NULL
     assert f(x, nulls, 1, 1, 256, 512, 0, x, None, 0, None) == SHAPE        # y aliases x
+
+
+def test_l2_loss_argument_checks(lib):
+    f = lib.mq_matquant_l2_loss
+    ci = ctypes.c_int
+    assert f(None, None, None, None, 16, 64, 4, 0, None, None, None, 0, None) == BITS      # at most three outputs
+    assert f(None, None, None, None, 16, 64, 0, 0, None, None, None, 0, None) == BITS
+    assert f(None, None, None, None, 3, 5, 3, 0, None, None, None, 0, None) == ALIGN       # 15 elements
+    assert f(None, None, (ci * 3)(-1, 1, 0), None, 16, 64, 3, 0, None, None, None, 0, None) == SHAPE   # its own teacher
+    assert f(None, None, (ci * 3)(-1, 3, 0), None, 16, 64, 3, 0, None, None, None, 0, None) == SHAPE
+    assert f(None, None, None, None, 0, 64, 3, 0, None, None, None, 0, None) == OK
+    assert f(None, None, None, None, 16, 64, 3, 0, None, None, None, 0, None) == NULL
+    assert lib.mq_workspace_bytes(3, 4096, 9216, 0, 3) >= 4096 * 9216 // 8 // 512 * 16

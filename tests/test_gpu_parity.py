@@ -435,6 +435,26 @@ def test_ffn_mixnmatch_7b_shaped_pyramid(mq, oracle):
     assert rel_l2(y.float().cpu().numpy(), want) <= TOL * len(rs)
 
 
+# --------------------------------------------------------------------------
+# L2 reconstruction objective over the bit-widths (the step between forward and backward)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("M,N,nr,teacher,mix", [(16, 256, 3, None, False), (520, 1000, 3, (-1, 0, 0), False),
+                                                (4096, 2304, 3, (-1, -1, 0), True), (33, 24, 2, (1, -1), False),
+                                                (8, 8, 1, None, False), (0, 64, 3, None, False)])
+def test_l2_loss(mq, oracle, M, N, nr, teacher, mix):
+    lam = (0.1, 0.4, 1.0)[:nr]
+    Ys = [(_randn(200 + i, M, N) * (1.0 + 0.1 * i)).to(torch.bfloat16) for i in range(nr)]
+    T = _randn(210, M, N).to(torch.bfloat16)
+    losses, dYs = mq.mq_matquant_l2_loss([dev(y) for y in Ys], dev(T), teacher, lam, mix)
+    torch.cuda.synchronize()
+    if M * N == 0:
+        return
+    want_l, want_d = oracle.matquant_l2_loss([bf16_bits(y) for y in Ys], bf16_bits(T), teacher, lam, mix)
+    assert np.allclose(losses.cpu().numpy(), want_l, rtol=1e-4)         # fp32 sums of M N squares
+    for i in range(nr):
+        assert rel_l2(dYs[i].float().cpu().numpy(), want_d[i]) <= TOL    # one bf16 rounding: 2^-9 / sqrt(3)
+
+
 def test_measurement_probes_run(mq):
     ops = torch.randn(32768, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
     sink = torch.zeros(65536, dtype=torch.float32, device="cuda")

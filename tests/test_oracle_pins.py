@@ -531,3 +531,46 @@ def test_bf16_round_is_round_to_nearest_even(oracle):
     want = torch.from_numpy(v).to(torch.float32).to(torch.bfloat16)
     assert np.array_equal(oracle.bf16_round(v), bf16_bits(want))
     assert np.array_equal(oracle.bf16_to_f64(oracle.bf16_round(v)), want.double().numpy())
+
+
+# --------------------------------------------------------------------------
+# L2 reconstruction objective over the bit-widths, co-distillation targets
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("teacher,mix", [(None, False), ((-1, 0, 0), False), ((-1, -1, 0), True), ((1, -1, 1), False)])
+def test_l2_objective_vs_autograd(oracle, teacher, mix):
+    # Library special case: torch float64 autograd of sum_i lambda_i * mse(Y_i, T_i) with detached teachers.
+    g = torch.Generator().manual_seed(12)
+    M, N, lam = 24, 40, (0.1, 0.4, 1.0)
+    Ys = [torch.randn(M, N, generator=g).to(torch.bfloat16) for _ in range(3)]
+    T = torch.randn(M, N, generator=g).to(torch.bfloat16)
+    losses, dYs = oracle.matquant_l2_loss([bf16_bits(y) for y in Ys], bf16_bits(T), teacher, lam, mix)
+    Yv = [y.double().requires_grad_(True) for y in Ys]
+    mse = torch.nn.functional.mse_loss
+    total, want_losses = 0.0, []
+    for i in range(3):
+        t = -1 if teacher is None else teacher[i]
+        if t < 0:
+            li = mse(Yv[i], T.double())
+        elif not mix:
+            li = mse(Yv[i], Yv[t].detach())
+        else:
+            li = 0.5 * (mse(Yv[i], Yv[t].detach()) + mse(Yv[i], T.double()))
+        want_losses.append(li.item())
+        total = total + lam[i] * li
+    total.backward()
+    assert np.allclose(losses, want_losses, rtol=1e-12)
+    for i in range(3):
+        assert np.allclose(dYs[i], Yv[i].grad.numpy(), rtol=1e-12, atol=1e-18)
+
+
+def test_l2_objective_closed_forms(oracle):
+    M, N = 8, 16
+    Y = torch.full((M, N), 1.5).to(torch.bfloat16)
+    T = torch.full((M, N), 1.0).to(torch.bfloat16)
+    losses, dYs = oracle.matquant_l2_loss([bf16_bits(Y), bf16_bits(T)], bf16_bits(T), None, (2.0, 3.0))
+    assert losses[0] == 0.25 and losses[1] == 0.0                       # mean of 0.5^2; output equal to the target
+    assert np.all(dYs[0] == 2.0 * 2 * 0.5 / (M * N)) and np.all(dYs[1] == 0.0)
+    # a teacher is held constant: being one does not change its own gradient
+    _, d_plain = oracle.matquant_l2_loss([bf16_bits(Y), bf16_bits(T)], bf16_bits(T), (-1, -1))
+    _, d_teach = oracle.matquant_l2_loss([bf16_bits(Y), bf16_bits(T)], bf16_bits(T), (-1, 0))
+    assert np.array_equal(d_plain[0], d_teach[0]) and np.all(d_teach[1] == 2 * (1.0 - 1.5) / (M * N))
