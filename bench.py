@@ -5,9 +5,10 @@ One step = one pass of the whole hot path over the Gemma-2-2B-shaped MLP (d_mode
 4096 tokens; seeded synthetic weights and activations already resident in HBM): for each of the
 three linears (gate, up, down) quantize the fp32 master weight to int8 codes, slice and pack the
 r = 4 and r = 2 planes (r = 2 also with the extra-precision overflow list), run the fused
-r = 8/4/2 forward, the L2 reconstruction objective of the three outputs against the output of the
-full-precision layer (losses and the gradients dY_r) and the straight-through backward (dX, dW),
-round alpha/z to bf16 and run the decode GEMV at B = 1, 4, 16 on the int4 and int2 planes.
+r = 8/4/2 forward with the L2 reconstruction objective of the three outputs against the output of
+the full-precision layer evaluated in its epilogue (losses and the gradients dY_r; the outputs
+themselves are not stored, the training step has no other use for them) and the straight-through
+backward (dX, dW), round alpha/z to bf16 and run the decode GEMV at B = 1, 4, 16 on the int4 and int2 planes.
 
 `value` is the forward + backward matrix-core work of the step (6 MNK + 8 MNK flops per linear)
 divided by the wall time of the WHOLE step, so the bandwidth-bound operations count against it.
@@ -63,7 +64,6 @@ class Linear:
         self.T = (self.X @ self.W.to(torch.bfloat16).t()).contiguous()
         self.dY = [torch.empty(M, N, dtype=torch.bfloat16, device=dev) for _ in rs]
         self.losses = torch.empty(len(rs), dtype=torch.float32, device=dev)
-        self.ws_l = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_L2_LOSS, M, N, 0, len(rs)), dtype=torch.uint8, device=dev)
         self.Q = torch.empty(N, K, dtype=torch.uint8, device=dev)
         self.alpha = torch.empty(N, dtype=torch.float32, device=dev)
         self.zero = torch.empty(N, dtype=torch.float32, device=dev)
@@ -72,10 +72,9 @@ class Linear:
         self.p4 = torch.empty(N, K // 2, dtype=torch.uint8, device=dev)
         self.p2 = torch.empty(N, K // 4, dtype=torch.uint8, device=dev)
         self.ovf2 = mq.Overflow(N, N * K // 8, dev)   # room for 12.5 % overflow
-        self.Y = [torch.empty(M, N, dtype=torch.bfloat16, device=dev) for _ in rs]
         self.dX = torch.empty(M, K, dtype=torch.bfloat16, device=dev)
         self.dW = torch.empty(N, K, dtype=torch.float32, device=dev)
-        self.ws_f = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD, M, N, K, len(rs)), dtype=torch.uint8, device=dev)
+        self.ws_f = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD_L2, M, N, K, len(rs)), dtype=torch.uint8, device=dev)
         self.ws_b = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, M, N, K, len(rs)), dtype=torch.uint8, device=dev)
         self.xdec = {B: synth.activations(2, f"dec{B}:" + name, B, K).to(dev) for B in (1, 4, 16)}
         self.ydec = {B: torch.empty(B, N, dtype=torch.bfloat16, device=dev) for B in (1, 4, 16)}
@@ -97,7 +96,7 @@ def main():
     _, M = synth.mlp_shapes(2)
     layers = [Linear(mq, torch, synth, name, M, rs, lambdas) for name in ("gate", "up", "down")]
 
-    ops = ["quantize", "slice", "fwd", "loss", "bwd", "gemv"]
+    ops = ["quantize", "slice", "fwd", "bwd", "gemv"]
     records = {op: [] for op in ops}   # (start event, end event) pairs inside the timed region
 
     def timed(op, fn, rec):
@@ -119,9 +118,10 @@ def main():
                 mq.mq_slice(L.Q, 2, packed=True, extra_precision=True, out=L.p2, ovf=L.ovf2)
                 mq.mq_params_to_bf16(L.alpha, L.zero, L.alpha16, L.zero16)
             timed("slice", do_slice, rec)
-            timed("fwd", lambda: mq.mq_linear_fwd_multi(L.X, L.Q, L.alpha, L.zero, rs, Y=L.Y, ws=L.ws_f), rec)
-            # L2 reconstruction losses of the three outputs against y' and the gradients the backward consumes
-            timed("loss", lambda: mq.mq_matquant_l2_loss(L.Y, L.T, None, lambdas, dY=L.dY, losses=L.losses, ws=L.ws_l), rec)
+            # forward for r = 8, 4, 2 with the L2 reconstruction losses against y' and the gradients the
+            # backward consumes formed in its epilogue
+            timed("fwd", lambda: mq.mq_linear_fwd_multi_l2(L.X, L.Q, L.alpha, L.zero, rs, L.T, None, lambdas,
+                                                           dY=L.dY, losses=L.losses, ws=L.ws_f), rec)
             timed("bwd", lambda: mq.mq_linear_bwd(L.X, L.Q, L.alpha, L.zero, L.dY, lambdas, rs, dX=L.dX, dW=L.dW,
                                                   ws=L.ws_b), rec)
 
@@ -163,18 +163,18 @@ def main():
         "quantize_GBs": 5.0 * nk / (op_ms["quantize"] * 1e-3) / 1e9,
         "slice_GBs": (2.0 + 0.5 + 0.25) * nk / (op_ms["slice"] * 1e-3) / 1e9,
         "gemv_GBs": gemv_bytes / (op_ms["gemv"] * 1e-3) / 1e9,
-        "loss_GBs": 14.0 * sum(L.M * L.N for L in layers) / (op_ms["loss"] * 1e-3) / 1e9,   # 3 Y + y' read, 3 dY written
         "ms": {k: round(v, 4) for k, v in op_ms.items()},
     }
 
     # Roofline of the dominant kernel, the fused r = 8/4/2 forward (one launch per linear): events
-    # bracket the mq_linear_fwd_multi call, i.e. the kernel plus its few-microsecond row-sum pre-pass.
+    # bracket the mq_linear_fwd_multi_l2 call, i.e. the kernel plus its few-microsecond row-sum pre-pass
+    # and the one-workgroup finish of the loss sums.
     fwd_launches = len(records["fwd"])
     fwd_avg_ms = sum(a.elapsed_time(b) for a, b in records["fwd"]) / fwd_launches
     achieved = (flops_fwd / len(layers)) / (fwd_avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "mq::fwd_kernel<3, true, false, MB> (MB = 4 for gate and up, 5 for down)", "achieved": round(achieved, 2),
+    roofline = {"bound": "mfma", "kernel": "mq::fwd_kernel<3, true, false, MB, true> (MB = 4 for gate and up, 5 for down)", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": FWD_TRAFFIC_BYTES, "algorithmic_bytes": int(sum(L.N * L.K + 2 * L.M * L.K + 6 * L.M * L.N
+                "traffic": FWD_TRAFFIC_BYTES, "algorithmic_bytes": int(sum(L.N * L.K + 2 * L.M * L.K + 8 * L.M * L.N
                                                                          for L in layers) / len(layers)),
                 "avg_launch_ms": round(fwd_avg_ms, 4)}
 
@@ -184,7 +184,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[1]: Gemma-2-2B-shaped MLP, d_model 2304, ffn 9216, 4096 tokens, "
-                               "gate/up/down; quantize + slice/pack + fused r=8/4/2 fwd + L2 objective + STE bwd + decode GEMV "
+                               "gate/up/down; quantize + slice/pack + fused r=8/4/2 fwd with L2 objective + STE bwd + decode GEMV "
                                "B=1/4/16 (int4, int2)", "tokens": M, "rs": list(rs), "seed": synth.config_seed(2)},
         "per_op": per_op,
         "roofline": roofline,

@@ -56,7 +56,7 @@ enum {
                                     per code that keeps code 2^r, instead of plane + list     */
 };
 
-enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1, MQ_OP_FFN_DECODE = 2, MQ_OP_L2_LOSS = 3 };
+enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1, MQ_OP_FFN_DECODE = 2, MQ_OP_L2_LOSS = 3, MQ_OP_LINEAR_FWD_L2 = 4 };
 
 /*
  * Extra-precision overflow set (errata section: weights whose rounded r-bit
@@ -222,6 +222,27 @@ mq_status mq_matquant_l2_loss(const uint16_t *const *Y, const uint16_t *target, 
                               const float *lambda, int64_t M, int64_t N, int nr, uint32_t flags,
                               uint16_t *const *dY, float *losses, void *ws, size_t ws_bytes,
                               void *hip_stream);
+
+/*
+ * mq_linear_fwd_multi and mq_matquant_l2_loss in one pass: the training step of section 3.2 needs
+ * the outputs Y_i only to form the loss and its gradients, so the objective is evaluated on the
+ * rounded bf16 outputs while a tile is still on chip, and the Y_i need not travel to memory and
+ * back.  Per element the arithmetic is that of the two calls in sequence: the dY_i are bit-identical
+ * to theirs, the losses agree up to the order of the fp32 partial sums.
+ *   X, Q, alpha, zero, M, N, K, rs, nr   as for mq_linear_fwd_multi
+ *   target, teacher, lambda, dY, losses  as for mq_matquant_l2_loss (indices in the order of rs)
+ *   flags    MQ_FLAG_EXTRA_PRECISION and / or MQ_FLAG_LOSS_MIX
+ *   Y        NULL, or a host array of nr device pointers of which any may be NULL: an output
+ *            whose pointer is NULL is not stored
+ *   ws       workspace of at least mq_workspace_bytes(MQ_OP_LINEAR_FWD_L2, M, N, K, nr)
+ * Alignment and size limits as for mq_linear_fwd_multi.  M == 0 or N == 0 is a no-op.
+ */
+mq_status mq_linear_fwd_multi_l2(const uint16_t *X, const uint8_t *Q, const float *alpha,
+                                 const float *zero, int64_t M, int64_t N, int64_t K,
+                                 const int *rs, int nr, uint32_t flags,
+                                 const uint16_t *target, const int *teacher, const float *lambda,
+                                 uint16_t *const *Y, uint16_t *const *dY, float *losses,
+                                 void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Layer-wise Mix'n'Match on the decode path (section 4.3 "Mix'n'Match", section 5.1.3 and appendix B:

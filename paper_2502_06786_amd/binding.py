@@ -22,13 +22,14 @@ MQ_OP_LINEAR_FWD = 0
 MQ_OP_LINEAR_BWD = 1
 MQ_OP_FFN_DECODE = 2
 MQ_OP_L2_LOSS = 3
+MQ_OP_LINEAR_FWD_L2 = 4
 MQ_FLAG_LOSS_MIX = 64
 MQ_FLAG_FFN_SILU = 16
 MQ_FLAG_FFN_RESIDUAL = 32
 
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
            "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string", "mq_probe_mfma", "mq_probe_read",
-           "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss"]
+           "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2"]
 
 
 class MqError(RuntimeError):
@@ -70,6 +71,9 @@ def _load() -> ctypes.CDLL:
     lib.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
     lib.mq_matquant_l2_loss.argtypes = [ctypes.POINTER(vp), vp, ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_float), i64,
                                         i64, ci, u32, ctypes.POINTER(vp), vp, vp, sz, vp]
+    lib.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp,
+                                           ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_float), ctypes.POINTER(vp),
+                                           ctypes.POINTER(vp), vp, vp, sz, vp]
     lib.mq_ffn_mixnmatch.argtypes = [vp, ctypes.POINTER(_FfnLayer), ci, i64, i64, i64, u32, vp, vp, sz, vp]
     lib.mq_probe_read.argtypes = [vp, i64, vp, vp]
     for name in EXPORTS:
@@ -331,4 +335,36 @@ def mq_matquant_l2_loss(Y, target=None, teacher=None, lambdas=None, mix: bool = 
                                   MQ_FLAG_LOSS_MIX if mix else 0, _ptr_array(dY, torch.bfloat16),
                                   _ptr(losses, torch.float32), _ptr(ws, torch.uint8), ws.numel(), _stream())
     _check(st, "mq_matquant_l2_loss")
+    return losses, dY
+
+
+def mq_linear_fwd_multi_l2(X, Q, alpha, zero, rs, target=None, teacher=None, lambdas=None, mix: bool = False,
+                           extra_precision: bool = False, Y=None, dY=None, losses=None, ws=None):
+    """Forward for every r in rs with the L2 objective evaluated in the same pass: returns (losses fp32 [nr] on the
+    GPU, list of dY bf16 [M, N]).  Y, if given, is a list of nr bf16 [M, N] tensors or None entries; only the tensors
+    present are written."""
+    M, K = X.shape
+    N = Q.shape[0]
+    if Q.shape[1] != K:
+        raise ValueError("X and Q disagree on K")
+    nr = len(rs)
+    if dY is None:
+        dY = [torch.empty(M, N, dtype=torch.bfloat16, device=X.device) for _ in range(nr)]
+    if losses is None:
+        losses = torch.empty(nr, dtype=torch.float32, device=X.device)
+    need = mq_workspace_bytes(MQ_OP_LINEAR_FWD_L2, M, N, K, max(1, min(nr, 3)))
+    if ws is None:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=X.device)
+    flags = (MQ_FLAG_EXTRA_PRECISION if extra_precision else 0) | (MQ_FLAG_LOSS_MIX if mix else 0)
+    c_teacher = (ctypes.c_int * nr)(*teacher) if teacher is not None else None
+    c_lambda = (ctypes.c_float * nr)(*lambdas) if lambdas is not None else None
+    c_Y = None
+    if Y is not None:
+        c_Y = (ctypes.c_void_p * nr)(*[_ptr(t, torch.bfloat16) if t is not None else None for t in Y])
+    st = _lib.mq_linear_fwd_multi_l2(_ptr(X, torch.bfloat16), _ptr(Q, torch.uint8), _ptr(alpha, torch.float32),
+                                     _ptr(zero, torch.float32), M, N, K, _int_array(rs), nr, flags,
+                                     _ptr(target, torch.bfloat16), c_teacher, c_lambda, c_Y,
+                                     _ptr_array(dY, torch.bfloat16), _ptr(losses, torch.float32), _ptr(ws),
+                                     ws.numel(), _stream())
+    _check(st, "mq_linear_fwd_multi_l2")
     return losses, dY

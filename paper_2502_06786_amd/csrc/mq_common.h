@@ -32,6 +32,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 
 __device__ __forceinline__ uint32_t float_to_bf16_bits(float f) { return pack_bf16x2(f, 0.0f) & 0xFFFFu; }
+// the two bf16 values of a 32-bit word
+__device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xFFFF0000u); }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -43,6 +46,10 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 size_t ffn_workspace_bytes(int64_t B, int64_t F, int64_t d);
 // workspace of mq_matquant_l2_loss (mq_loss.hip)
 size_t loss_workspace_bytes(int64_t M, int64_t N);
+// losses[i] = inv_mn * sum over the workgroups of partial[workgroup][i] (rows of 4 floats), in a
+// fixed order; one small launch on `st` (mq_loss.hip)
+mq_status launch_loss_finish(const float *partial, int64_t blocks, int nr, float inv_mn, float *losses,
+                             hipStream_t st);
 
 // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  This maps the hardware
 // id to a logical id such that each XCD owns one contiguous range of logical ids, so that tiles

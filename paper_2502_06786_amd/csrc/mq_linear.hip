@@ -144,6 +144,14 @@ struct FwdArgs {
     int M, N, K;
     int r[3];  // bit-width per slot; slot 0 is the r = 8 slot when HAS8
     int tiles_m, tiles_n;
+    // LOSS kernels only (slot order as Y): the L2 objective is evaluated on the rounded outputs
+    // while they sit in the staging tiles.  Y[i] may then be NULL (that output is not stored).
+    const uint16_t *T;
+    uint16_t *dY[3];
+    int teacher[3];  // slot of the teacher, or -1 for the target T
+    float coef[3];   // lambda_i * 2 / (M N)
+    int mix;
+    float *partial;  // [workgroup][4] sums of squared differences
 };
 
 constexpr int FWD_BN = 128;
@@ -164,7 +172,7 @@ constexpr int fwd_lds(int mb, int nr) {
 // of the next 16-wide k step are fetched into registers behind the MFMAs of the current one, also
 // across the stage boundary) and stages kt + 2, kt + 3 are in flight, so a load has two full
 // iterations to arrive.
-template <int NR, bool HAS8, bool EP, int MB>
+template <int NR, bool HAS8, bool EP, int MB, bool LOSS>
 __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     constexpr int BM = 32 * MB;
@@ -369,14 +377,39 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
         const int m = m0 + j * 32 + l32;
         rs[j] = m < a.M ? a.rowsum[m] : 0.f;
     }
+    f32x4 alv[4], zev[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const int nloc = wave * 32 + 8 * g + 4 * h;
-        f32x4 al = {0.f, 0.f, 0.f, 0.f}, ze = {0.f, 0.f, 0.f, 0.f};
+        alv[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+        zev[g] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (n0 + nloc < a.N) {
-            al = *reinterpret_cast<const f32x4 *>(a.alpha + n0 + nloc);
-            ze = *reinterpret_cast<const f32x4 *>(a.zero + n0 + nloc);
+            alv[g] = *reinterpret_cast<const f32x4 *>(a.alpha + n0 + nloc);
+            zev[g] = *reinterpret_cast<const f32x4 *>(a.zero + n0 + nloc);
         }
+    }
+    // LOSS: the lane's chunks of the target are requested now, behind the parameter loads, and
+    // arrive while the accumulators are converted and staged.  With the largest accumulator set
+    // there are registers for half of them only; the other half is requested after the staging and
+    // arrives while the first half is consumed.
+    constexpr int CHUNKS = BM * 16 / 256;
+    constexpr int EARLY = NR * MB > 12 ? 3 : CHUNKS;
+    u32x4 tpre[LOSS ? CHUNKS : 1];
+    auto request_target = [&](int it) {
+        const int c = it * 256 + threadIdx.x;
+        const int m = m0 + (c >> 4), n = n0 + (c & 15) * 8;
+        tpre[it] = u32x4{0u, 0u, 0u, 0u};
+        if (a.T && m < a.M && n < a.N)
+            tpre[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.T + (size_t)m * a.N + n));
+    };
+    if constexpr (LOSS) {
+#pragma unroll
+        for (int it = 0; it < EARLY; ++it) request_target(it);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int nloc = wave * 32 + 8 * g + 4 * h;
+        const f32x4 al = alv[g], ze = zev[g];
 #pragma unroll
         for (int i = 0; i < NR; ++i) {
             const bool is8 = HAS8 && i == 0;
@@ -392,23 +425,104 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
             }
         }
     }
-    __syncthreads();
+    if constexpr (LOSS) {
 #pragma unroll
-    for (int i = 0; i < NR; ++i) {
+        for (int it = EARLY; it < CHUNKS; ++it) request_target(it);
+    }
+    __syncthreads();
+    if constexpr (!LOSS) {
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+#pragma unroll
+            for (int it = 0; it < BM * 16 / 256; ++it) {
+                const int c = it * 256 + threadIdx.x;
+                const int row = c >> 4, ch = c & 15;
+                const int m = m0 + row, n = n0 + ch * 8;
+                if (m < a.M && n < a.N) {
+                    const uint8_t *src = smem + i * OT + row * OS + ch * 16;
+                    const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
+                    const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
+                    __builtin_nontemporal_store(u32x4{lo.x, lo.y, hi.x, hi.y},
+                                                reinterpret_cast<u32x4 *>(a.Y[i] + (size_t)m * a.N + n));
+                }
+            }
+        }
+    } else {
+        // L2 objective on the staged tile (section 3.2 with the loss of section 3.1.2, co-distillation
+        // targets of section 5.2): a lane takes the same 8 channels of a token from every bit-width
+        // and from the target, adds (Y_i - T_i)^2 to its sums and stores dY_i = coef_i (Y_i - T_i);
+        // the arithmetic per element is that of the stand-alone loss kernel, on the same rounded Y.
+        float sum[NR];
+#pragma unroll
+        for (int i = 0; i < NR; ++i) sum[i] = 0.f;
 #pragma unroll
         for (int it = 0; it < BM * 16 / 256; ++it) {
             const int c = it * 256 + threadIdx.x;
             const int row = c >> 4, ch = c & 15;
             const int m = m0 + row, n = n0 + ch * 8;
             if (m < a.M && n < a.N) {
-                const uint8_t *src = smem + i * OT + row * OS + ch * 16;
-                const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
-                const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
-                __builtin_nontemporal_store(u32x4{lo.x, lo.y, hi.x, hi.y},
-                                            reinterpret_cast<u32x4 *>(a.Y[i] + (size_t)m * a.N + n));
+                const size_t at = (size_t)m * a.N + n;
+                u32x4 y[NR];
+                const u32x4 t = tpre[it];
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    const uint8_t *src = smem + i * OT + row * OS + ch * 16;
+                    const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
+                    const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
+                    y[i] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                }
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    const int th = a.teacher[i];
+                    u32x4 tt = t;
+#pragma unroll
+                    for (int u = 0; u < NR; ++u)
+                        if (th == u) tt = y[u];
+                    u32x4 o;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float y0 = bf16_lo(y[i][j]), y1 = bf16_hi(y[i][j]);
+                        float d0 = y0 - bf16_lo(tt[j]), d1 = y1 - bf16_hi(tt[j]);
+                        float s = d0 * d0 + d1 * d1;
+                        if (a.mix && th >= 0) {  // teacher and ground truth, weighted equally
+                            const float e0 = y0 - bf16_lo(t[j]), e1 = y1 - bf16_hi(t[j]);
+                            s = 0.5f * (s + e0 * e0 + e1 * e1);
+                            d0 = 0.5f * (d0 + e0);
+                            d1 = 0.5f * (d1 + e1);
+                        }
+                        sum[i] += s;
+                        o[j] = pack_bf16x2(a.coef[i] * d0, a.coef[i] * d1);
+                    }
+                    __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(a.dY[i] + at));
+                    if (a.Y[i]) __builtin_nontemporal_store(y[i], reinterpret_cast<u32x4 *>(a.Y[i] + at));
+                }
             }
         }
+        // workgroup sums in a fixed order; the staging tiles are dead after the barrier
+        __syncthreads();
+        float *red = reinterpret_cast<float *>(smem);
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            float v = sum[i];
+#pragma unroll
+            for (int msk = 1; msk < 64; msk <<= 1) v += __shfl_xor(v, msk);
+            if (lane == 0) red[wave * 4 + i] = v;
+        }
+        __syncthreads();
+        if (threadIdx.x < 4) {
+            float v = 0.f;
+            if ((int)threadIdx.x < NR)
+                for (int w = 0; w < 4; ++w) v += red[w * 4 + threadIdx.x];
+            a.partial[(size_t)blockIdx.x * 4 + threadIdx.x] = v;
+        }
     }
+}
+
+// out[i] = in[slot_i]: the losses of the fused forward, from slot order back to the caller's order
+__global__ void permute3_kernel(const float *in, float *out, int nr, int s0, int s1, int s2) {
+    if (threadIdx.x == 0 && nr > 0) out[0] = in[s0];
+    if (threadIdx.x == 1 && nr > 1) out[1] = in[s1];
+    if (threadIdx.x == 2 && nr > 2) out[2] = in[s2];
 }
 
 // sum_k X[m, k] in fp32, one wave per row
@@ -1052,12 +1166,13 @@ static bool allow_lds(Kern kern, int bytes) {
                                bytes) == hipSuccess;
 }
 
-template <int NR, bool HAS8, bool EP, int MB>
-static mq_status launch_fwd_mb(FwdArgs a, hipStream_t st) {
+template <int NR, bool HAS8, bool EP, int MB, bool LOSS>
+static mq_status launch_fwd_mb(FwdArgs a, hipStream_t st, int64_t *blocks) {
     a.tiles_m = (int)cdiv(a.M, 32 * MB);
     a.tiles_n = (int)cdiv(a.N, FWD_BN);
-    if (!allow_lds(fwd_kernel<NR, HAS8, EP, MB>, fwd_lds(MB, NR))) return MQ_ERR_DEVICE;
-    fwd_kernel<NR, HAS8, EP, MB><<<dim3(a.tiles_m * a.tiles_n), dim3(256), fwd_lds(MB, NR), st>>>(a);
+    *blocks = (int64_t)a.tiles_m * a.tiles_n;
+    if (!allow_lds(fwd_kernel<NR, HAS8, EP, MB, LOSS>, fwd_lds(MB, NR))) return MQ_ERR_DEVICE;
+    fwd_kernel<NR, HAS8, EP, MB, LOSS><<<dim3(a.tiles_m * a.tiles_n), dim3(256), fwd_lds(MB, NR), st>>>(a);
     return launch_status();
 }
 
@@ -1065,8 +1180,8 @@ static mq_status launch_fwd_mb(FwdArgs a, hipStream_t st) {
 // number of tiles rarely divides evenly over the 256 compute units; one block less can save a whole
 // round of workgroups.  Cost of a choice = rounds x (main loop + epilogue) in matrix-core cycles
 // (32 per MFMA; prologue and epilogue constants measured on the Gemma-2-2B shapes).
-template <int NR, bool HAS8, bool EP>
-static mq_status launch_fwd(const FwdArgs &a, hipStream_t st) {
+template <int NR, bool HAS8, bool EP, bool LOSS>
+static mq_status launch_fwd(const FwdArgs &a, hipStream_t st, int64_t *blocks) {
     constexpr int HI = fwd_mb(NR), LO = HI - 1;
     auto cost = [&](int mb) {
         const int64_t tiles = cdiv(a.M, 32 * mb) * cdiv(a.N, FWD_BN);
@@ -1074,13 +1189,26 @@ static mq_status launch_fwd(const FwdArgs &a, hipStream_t st) {
         const int64_t per_tile = cdiv(a.K, BKT) * NR * mb * 128 + 3000 + 890 * NR * mb;
         return rounds * per_tile;
     };
-    return cost(LO) < cost(HI) ? launch_fwd_mb<NR, HAS8, EP, LO>(a, st) : launch_fwd_mb<NR, HAS8, EP, HI>(a, st);
+    return cost(LO) < cost(HI) ? launch_fwd_mb<NR, HAS8, EP, LO, LOSS>(a, st, blocks)
+                               : launch_fwd_mb<NR, HAS8, EP, HI, LOSS>(a, st, blocks);
 }
 
-template <int NR, bool HAS8>
-static mq_status launch_fwd_ep(const FwdArgs &a, bool ep, hipStream_t st) {
-    return ep ? launch_fwd<NR, HAS8, true>(a, st) : launch_fwd<NR, HAS8, false>(a, st);
+template <int NR, bool HAS8, bool LOSS>
+static mq_status launch_fwd_ep(const FwdArgs &a, bool ep, hipStream_t st, int64_t *blocks) {
+    return ep ? launch_fwd<NR, HAS8, true, LOSS>(a, st, blocks) : launch_fwd<NR, HAS8, false, LOSS>(a, st, blocks);
 }
+
+template <bool LOSS>
+static mq_status launch_fwd_any(const FwdArgs &a, int nr, bool has8, bool ep, hipStream_t st, int64_t *blocks) {
+    if (nr == 1)
+        return has8 ? launch_fwd_ep<1, true, LOSS>(a, ep, st, blocks) : launch_fwd_ep<1, false, LOSS>(a, ep, st, blocks);
+    if (nr == 2)
+        return has8 ? launch_fwd_ep<2, true, LOSS>(a, ep, st, blocks) : launch_fwd_ep<2, false, LOSS>(a, ep, st, blocks);
+    return has8 ? launch_fwd_ep<3, true, LOSS>(a, ep, st, blocks) : launch_fwd_ep<3, false, LOSS>(a, ep, st, blocks);
+}
+
+// workgroups of the forward kernel at its smallest token tile (128 tokens): bound for the partial sums
+static int64_t fwd_max_blocks(int64_t M, int64_t N) { return cdiv(M, 128) * cdiv(N, FWD_BN); }
 
 template <int NRS, bool HAS8, bool EP>
 static mq_status launch_dx_one(const DxArgs &d, hipStream_t st) {
@@ -1107,34 +1235,64 @@ extern "C" size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, in
     using namespace mq;
     if (M < 0 || N < 0 || K < 0 || nr < 1 || nr > 3) return 0;
     if (op == MQ_OP_LINEAR_FWD) return align256((size_t)M * 4) + 256;
+    if (op == MQ_OP_LINEAR_FWD_L2) return align256((size_t)M * 4) + (size_t)fwd_max_blocks(M, N) * 16 + 256;
     if (op == MQ_OP_LINEAR_BWD) return bwd_layout(M, N, K, nr).total + 256;
     if (op == MQ_OP_FFN_DECODE) return ffn_workspace_bytes(M, N, K);
     if (op == MQ_OP_L2_LOSS) return loss_workspace_bytes(M, N);
     return 0;
 }
 
-extern "C" mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, const float *alpha,
-                                         const float *zero, int64_t M, int64_t N, int64_t K, const int *rs,
-                                         int nr, uint32_t flags, uint16_t *const *Y, void *ws, size_t ws_bytes,
-                                         void *hip_stream) {
-    using namespace mq;
+namespace mq {
+
+// the L2 objective evaluated in the forward epilogue (user order; mapped to slots below)
+struct FwdLoss {
+    const uint16_t *target;
+    const int *teacher;
+    const float *lambda;
+    uint16_t *const *dY;
+    float *losses;
+    uint32_t mix;
+};
+
+static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero, int64_t M,
+                         int64_t N, int64_t K, const int *rs, int nr, uint32_t flags, uint16_t *const *Y,
+                         const FwdLoss *loss, void *ws, size_t ws_bytes, void *hip_stream) {
     if (M < 0 || N < 0 || K < 1) return MQ_ERR_SHAPE;
     if (M > 0x7FFFFF00 || N > 0x7FFFFF00 || K > (1 << 22)) return MQ_ERR_SHAPE;
     mq_status s = check_rs(rs, nr);
     if (s != MQ_OK) return s;
     if (K % 16 != 0 || N % 8 != 0) return MQ_ERR_ALIGN;
+    bool need_target = false;
+    if (loss) {
+        need_target = loss->mix || !loss->teacher;
+        if (loss->teacher)
+            for (int i = 0; i < nr; ++i) {
+                if (loss->teacher[i] < -1 || loss->teacher[i] >= nr || loss->teacher[i] == i) return MQ_ERR_SHAPE;
+                if (loss->teacher[i] < 0) need_target = true;
+            }
+    }
     if (M == 0 || N == 0) return MQ_OK;
-    if (!X || !Q || !alpha || !zero || !Y) return MQ_ERR_NULL;
+    if (!X || !Q || !alpha || !zero) return MQ_ERR_NULL;
+    if (!loss && !Y) return MQ_ERR_NULL;
     for (int i = 0; i < nr; ++i) {
-        if (!Y[i]) return MQ_ERR_NULL;
-        if (!aligned16(Y[i])) return MQ_ERR_ALIGN;
+        uint16_t *yi = Y ? Y[i] : nullptr;
+        if (!loss && !yi) return MQ_ERR_NULL;
+        if (yi && !aligned16(yi)) return MQ_ERR_ALIGN;
+    }
+    if (loss) {
+        if (!loss->dY || !loss->losses || (need_target && !loss->target)) return MQ_ERR_NULL;
+        for (int i = 0; i < nr; ++i) {
+            if (!loss->dY[i]) return MQ_ERR_NULL;
+            if (!aligned16(loss->dY[i])) return MQ_ERR_ALIGN;
+        }
+        if (loss->target && !aligned16(loss->target)) return MQ_ERR_ALIGN;
     }
     if (!aligned16(X) || !aligned16(Q) || !aligned16(alpha) || !aligned16(zero)) return MQ_ERR_ALIGN;
-    if (!ws || ws_bytes < mq_workspace_bytes(MQ_OP_LINEAR_FWD, M, N, K, nr) || !aligned16(ws))
-        return MQ_ERR_WORKSPACE;
+    const int op = loss ? MQ_OP_LINEAR_FWD_L2 : MQ_OP_LINEAR_FWD;
+    if (!ws || ws_bytes < mq_workspace_bytes(op, M, N, K, nr) || !aligned16(ws)) return MQ_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
-    FwdArgs a;
+    FwdArgs a{};
     a.X = X;
     a.Q = Q;
     a.alpha = alpha;
@@ -1145,6 +1303,7 @@ extern "C" mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, co
     a.K = (int)K;
     // slot order: the r = 8 slot (if any) first
     int has8 = 0, pos = 0;
+    int slot_of[3] = {0, 0, 0};
     for (int i = 0; i < 3; ++i) {
         a.Y[i] = nullptr;
         a.r[i] = 8;
@@ -1152,22 +1311,62 @@ extern "C" mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, co
     for (int i = 0; i < nr; ++i)
         if (rs[i] == 8) {
             has8 = 1;
-            a.Y[0] = Y[i];
-            a.r[0] = 8;
+            slot_of[i] = 0;
         }
     pos = has8;
     for (int i = 0; i < nr; ++i)
-        if (rs[i] != 8) {
-            a.Y[pos] = Y[i];
-            a.r[pos] = rs[i];
-            ++pos;
+        if (rs[i] != 8) slot_of[i] = pos++;
+    for (int i = 0; i < nr; ++i) {
+        a.Y[slot_of[i]] = Y ? Y[i] : nullptr;
+        a.r[slot_of[i]] = rs[i];
+    }
+    const double mn = (double)M * (double)N;
+    if (loss) {
+        a.T = loss->target;
+        a.mix = loss->mix ? 1 : 0;
+        a.partial = reinterpret_cast<float *>(static_cast<uint8_t *>(ws) + align256((size_t)M * 4));
+        for (int i = 0; i < nr; ++i) {
+            const int sl = slot_of[i];
+            a.dY[sl] = loss->dY[i];
+            const int th = loss->teacher ? loss->teacher[i] : -1;
+            a.teacher[sl] = th < 0 ? -1 : slot_of[th];
+            a.coef[sl] = (float)((loss->lambda ? (double)loss->lambda[i] : 1.0) * 2.0 / mn);
         }
+    }
 
     rowsum_kernel<<<dim3((unsigned)cdiv(M, 4)), dim3(256), 0, st>>>(X, (int)M, (int)K, static_cast<float *>(ws));
     const bool ep = flags & MQ_FLAG_EXTRA_PRECISION;
-    if (nr == 1) return has8 ? launch_fwd_ep<1, true>(a, ep, st) : launch_fwd_ep<1, false>(a, ep, st);
-    if (nr == 2) return has8 ? launch_fwd_ep<2, true>(a, ep, st) : launch_fwd_ep<2, false>(a, ep, st);
-    return has8 ? launch_fwd_ep<3, true>(a, ep, st) : launch_fwd_ep<3, false>(a, ep, st);
+    int64_t blocks = 0;
+    if (!loss) return launch_fwd_any<false>(a, nr, has8, ep, st, &blocks);
+    s = launch_fwd_any<true>(a, nr, has8, ep, st, &blocks);
+    if (s != MQ_OK) return s;
+    // the kernel's sums are in slot order: where that is not the caller's order (an r = 8 that is
+    // not first) they are finished into the tail of the workspace and permuted
+    float *slot_losses = a.partial + (size_t)fwd_max_blocks(M, N) * 4;
+    bool same = true;
+    for (int i = 0; i < nr; ++i) same = same && slot_of[i] == i;
+    s = launch_loss_finish(a.partial, blocks, nr, (float)(1.0 / mn), same ? loss->losses : slot_losses, st);
+    if (s != MQ_OK || same) return s;
+    permute3_kernel<<<dim3(1), dim3(64), 0, st>>>(slot_losses, loss->losses, nr, slot_of[0], slot_of[1], slot_of[2]);
+    return launch_status();
+}
+
+}  // namespace mq
+
+extern "C" mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, const float *alpha,
+                                         const float *zero, int64_t M, int64_t N, int64_t K, const int *rs,
+                                         int nr, uint32_t flags, uint16_t *const *Y, void *ws, size_t ws_bytes,
+                                         void *hip_stream) {
+    return mq::fwd_run(X, Q, alpha, zero, M, N, K, rs, nr, flags, Y, nullptr, ws, ws_bytes, hip_stream);
+}
+
+extern "C" mq_status mq_linear_fwd_multi_l2(const uint16_t *X, const uint8_t *Q, const float *alpha,
+                                            const float *zero, int64_t M, int64_t N, int64_t K, const int *rs,
+                                            int nr, uint32_t flags, const uint16_t *target, const int *teacher,
+                                            const float *lambda, uint16_t *const *Y, uint16_t *const *dY,
+                                            float *losses, void *ws, size_t ws_bytes, void *hip_stream) {
+    const mq::FwdLoss loss{target, teacher, lambda, dY, losses, flags & MQ_FLAG_LOSS_MIX};
+    return mq::fwd_run(X, Q, alpha, zero, M, N, K, rs, nr, flags, Y, &loss, ws, ws_bytes, hip_stream);
 }
 
 extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero,

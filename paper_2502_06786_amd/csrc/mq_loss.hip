@@ -26,9 +26,6 @@ struct LossArgs {
     float *partial;  // [blocks][4]
 };
 
-__device__ __forceinline__ float lo_f(uint32_t v) { return __uint_as_float(v << 16); }
-__device__ __forceinline__ float hi_f(uint32_t v) { return __uint_as_float(v & 0xFFFF0000u); }
-
 __global__ __launch_bounds__(kLossBlock) void l2_loss_kernel(LossArgs a) {
     __shared__ float red[kLossBlock / 64][4];
     float sum[3] = {0.f, 0.f, 0.f};
@@ -50,11 +47,11 @@ __global__ __launch_bounds__(kLossBlock) void l2_loss_kernel(LossArgs a) {
             u32x4 o;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const float y0 = lo_f(y[i][j]), y1 = hi_f(y[i][j]);
-                float d0 = y0 - lo_f(tt[j]), d1 = y1 - hi_f(tt[j]);
+                const float y0 = bf16_lo(y[i][j]), y1 = bf16_hi(y[i][j]);
+                float d0 = y0 - bf16_lo(tt[j]), d1 = y1 - bf16_hi(tt[j]);
                 float s = d0 * d0 + d1 * d1;
                 if (a.mix && th >= 0) {  // teacher and ground truth, weighted equally
-                    const float e0 = y0 - lo_f(t[j]), e1 = y1 - hi_f(t[j]);
+                    const float e0 = y0 - bf16_lo(t[j]), e1 = y1 - bf16_hi(t[j]);
                     s = 0.5f * (s + e0 * e0 + e1 * e1);
                     d0 = 0.5f * (d0 + e0);
                     d1 = 0.5f * (d1 + e1);
@@ -105,6 +102,12 @@ inline int64_t loss_blocks(int64_t M, int64_t N) {
 }
 
 }  // namespace
+
+mq_status launch_loss_finish(const float *partial, int64_t blocks, int nr, float inv_mn, float *losses,
+                             hipStream_t st) {
+    l2_loss_finish_kernel<<<dim3(1), dim3(256), 0, st>>>(partial, blocks, nr, inv_mn, losses);
+    return launch_status();
+}
 
 size_t loss_workspace_bytes(int64_t M, int64_t N) {
     if (M < 0 || N < 0) return 0;
@@ -158,6 +161,5 @@ extern "C" mq_status mq_matquant_l2_loss(const uint16_t *const *Y, const uint16_
     l2_loss_kernel<<<dim3((unsigned)blocks), dim3(kLossBlock), 0, st>>>(a);
     mq_status s = launch_status();
     if (s != MQ_OK) return s;
-    l2_loss_finish_kernel<<<dim3(1), dim3(256), 0, st>>>(a.partial, blocks, nr, (float)(1.0 / mn), losses);
-    return launch_status();
+    return launch_loss_finish(a.partial, blocks, nr, (float)(1.0 / mn), losses, st);
 }

@@ -38,6 +38,8 @@ def lib():
     lib_.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
     lib_.mq_matquant_l2_loss.argtypes = [vp, vp, ctypes.POINTER(ci), vp, i64, i64, ci, u32, vp, vp, vp, sz, vp]
+    lib_.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp,
+                                            ctypes.POINTER(ci), vp, vp, vp, vp, vp, sz, vp]
     lib_.mq_ffn_mixnmatch.argtypes = [vp, vp, ci, i64, i64, i64, u32, vp, vp, sz, vp]
     lib_.mq_probe_read.argtypes = [vp, i64, vp, vp]
     lib_.mq_workspace_bytes.argtypes = [ci, i64, i64, i64, ci]
@@ -185,3 +187,18 @@ def test_l2_loss_argument_checks(lib):
     assert f(None, None, None, None, 0, 64, 3, 0, None, None, None, 0, None) == OK
     assert f(None, None, None, None, 16, 64, 3, 0, None, None, None, 0, None) == NULL
     assert lib.mq_workspace_bytes(3, 4096, 9216, 0, 3) >= 4096 * 9216 // 8 // 512 * 16
+
+
+def test_fwd_l2_argument_checks(lib):
+    f = lib.mq_linear_fwd_multi_l2
+    ci = ctypes.c_int
+    rs = (ci * 3)(8, 4, 2)
+    p = ctypes.c_void_p(4096)    # never dereferenced: every call below returns before the first launch
+    assert f(p, p, p, p, 16, 64, 64, (ci * 2)(4, 4), 2, 0, p, None, None, None, None, None, None, 0, None) == BITS
+    assert f(p, p, p, p, 16, 64, 40, rs, 3, 0, p, None, None, None, None, None, None, 0, None) == ALIGN
+    assert f(p, p, p, p, 16, 64, 64, rs, 3, 0, p, (ci * 3)(-1, 1, 0), None, None, None, None, None, 0, None) == SHAPE
+    assert f(p, p, p, p, 16, 64, 64, rs, 3, 0, p, (ci * 3)(-1, 0, 3), None, None, None, None, None, 0, None) == SHAPE
+    assert f(p, p, p, p, 0, 64, 64, rs, 3, 0, None, None, None, None, None, None, None, 0, None) == OK
+    assert f(p, p, p, p, 16, 64, 64, rs, 3, 0, p, None, None, None, None, None, None, 0, None) == NULL   # no dY
+    # the partial sums of the objective sit behind the row sums of X
+    assert lib.mq_workspace_bytes(4, 4096, 9216, 2304, 3) >= lib.mq_workspace_bytes(0, 4096, 9216, 2304, 3) + 32 * 72 * 16

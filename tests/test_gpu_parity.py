@@ -455,6 +455,56 @@ def test_l2_loss(mq, oracle, M, N, nr, teacher, mix):
         assert rel_l2(dYs[i].float().cpu().numpy(), want_d[i]) <= TOL    # one bf16 rounding: 2^-9 / sqrt(3)
 
 
+FUSED_L2_CASES = [
+    # M, N, K, rs, teacher, mix, ep
+    (300, 264, 208, (8, 4, 2), None, False, False),
+    (300, 264, 208, (8, 4, 2), (-1, 0, 0), False, True),
+    (257, 136, 1040, (8, 4, 2), (-1, 0, 1), True, False),
+    (16, 256, 256, (2, 8), (1, -1), False, False),      # r = 8 not first: the kernel's slot order differs
+    (200, 136, 336, (4, 8, 2), (1, -1, 0), True, True),
+    (200, 136, 336, (4, 2), None, False, False),
+    (1, 8, 16, (2,), None, False, False),
+    (520, 392, 64, (6, 3), (-1, 0), False, False),
+]
+
+
+@pytest.mark.parametrize("M,N,K,rs,teacher,mix,ep", FUSED_L2_CASES)
+def test_fwd_with_fused_l2_objective(mq, oracle, M, N, K, rs, teacher, mix, ep):
+    # The target is the output of the unquantized layer plus noise of the size of the output, so that
+    # Y_i - T is far above one bf16 step of Y_i: where the fp32 and the fp64 accumulation round a Y_i to
+    # different neighbours (about one element in a thousand), dY_i moves by 2^-8 of it only.
+    nr = len(rs)
+    lam = (0.1, 0.4, 1.0)[:nr]
+    W = _randn(M + N + K + 7, N, K, scale=0.02)
+    X = _randn(M * 3 + 2, M, K).to(torch.bfloat16)
+    Q, a, z, qo, ao, zo = _quantized(mq, oracle, W)
+    clean = X.float() @ W.t()
+    T = (clean + _randn(99, M, N) * clean.std()).to(torch.bfloat16)
+    Yg = [torch.empty(M, N, dtype=torch.bfloat16, device="cuda") if i != 1 else None for i in range(nr)]
+    losses, dYs = mq.mq_linear_fwd_multi_l2(dev(X), Q, a, z, rs, dev(T), teacher, lam, mix, extra_precision=ep, Y=Yg)
+    torch.cuda.synchronize()
+    want_Y = [oracle.linear_fwd(bf16_bits(X), qo, ao, zo, r, ep=ep) for r in rs]
+    want_l, want_d = oracle.matquant_l2_loss([oracle.bf16_round(y) for y in want_Y], bf16_bits(T), teacher, lam, mix)
+    assert np.allclose(losses.cpu().numpy(), want_l, rtol=1e-3)
+    for i in range(nr):
+        assert rel_l2(dYs[i].float().cpu().numpy(), want_d[i]) <= TOL, (rs[i], "dY")
+        if Yg[i] is not None:
+            assert rel_l2(Yg[i].float().cpu().numpy(), want_Y[i]) <= TOL, (rs[i], "Y")
+    # the same arithmetic as the two calls in sequence: identical gradients, sums in another order
+    Ys2 = mq.mq_linear_fwd_multi(dev(X), Q, a, z, rs, extra_precision=ep)
+    l2, d2 = mq.mq_matquant_l2_loss(Ys2, dev(T), teacher, lam, mix)
+    torch.cuda.synchronize()
+    for i in range(nr):
+        assert torch.equal(dYs[i], d2[i]), rs[i]
+        if Yg[i] is not None:
+            assert torch.equal(Yg[i], Ys2[i]), rs[i]
+    assert np.allclose(losses.cpu().numpy(), l2.cpu().numpy(), rtol=1e-5)
+    # without any Y output
+    l3, d3 = mq.mq_linear_fwd_multi_l2(dev(X), Q, a, z, rs, dev(T), teacher, lam, mix, extra_precision=ep)
+    torch.cuda.synchronize()
+    assert torch.equal(l3, losses) and all(torch.equal(u, v) for u, v in zip(d3, dYs))
+
+
 def test_measurement_probes_run(mq):
     ops = torch.randn(32768, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
     sink = torch.zeros(65536, dtype=torch.float32, device="cuda")
