@@ -455,49 +455,58 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
         float sum[NR];
 #pragma unroll
         for (int i = 0; i < NR; ++i) sum[i] = 0.f;
+        // the equal-weight mix of teacher and target is a variant of the whole loop, chosen once
+        auto chunks = [&](auto mixed) {
+            constexpr bool MIX = decltype(mixed)::value;
 #pragma unroll
-        for (int it = 0; it < BM * 16 / 256; ++it) {
-            const int c = it * 256 + threadIdx.x;
-            const int row = c >> 4, ch = c & 15;
-            const int m = m0 + row, n = n0 + ch * 8;
-            if (m < a.M && n < a.N) {
-                const size_t at = (size_t)m * a.N + n;
-                u32x4 y[NR];
-                const u32x4 t = tpre[it];
+            for (int it = 0; it < CHUNKS; ++it) {
+                const int c = it * 256 + threadIdx.x;
+                const int row = c >> 4, ch = c & 15;
+                const int m = m0 + row, n = n0 + ch * 8;
+                if (m < a.M && n < a.N) {
+                    const size_t at = (size_t)m * a.N + n;
+                    u32x4 y[NR];
+                    const u32x4 t = tpre[it];
 #pragma unroll
-                for (int i = 0; i < NR; ++i) {
-                    const uint8_t *src = smem + i * OT + row * OS + ch * 16;
-                    const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
-                    const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
-                    y[i] = u32x4{lo.x, lo.y, hi.x, hi.y};
-                }
-#pragma unroll
-                for (int i = 0; i < NR; ++i) {
-                    const int th = a.teacher[i];
-                    u32x4 tt = t;
-#pragma unroll
-                    for (int u = 0; u < NR; ++u)
-                        if (th == u) tt = y[u];
-                    u32x4 o;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float y0 = bf16_lo(y[i][j]), y1 = bf16_hi(y[i][j]);
-                        float d0 = y0 - bf16_lo(tt[j]), d1 = y1 - bf16_hi(tt[j]);
-                        float s = d0 * d0 + d1 * d1;
-                        if (a.mix && th >= 0) {  // teacher and ground truth, weighted equally
-                            const float e0 = y0 - bf16_lo(t[j]), e1 = y1 - bf16_hi(t[j]);
-                            s = 0.5f * (s + e0 * e0 + e1 * e1);
-                            d0 = 0.5f * (d0 + e0);
-                            d1 = 0.5f * (d1 + e1);
-                        }
-                        sum[i] += s;
-                        o[j] = pack_bf16x2(a.coef[i] * d0, a.coef[i] * d1);
+                    for (int i = 0; i < NR; ++i) {
+                        const uint8_t *src = smem + i * OT + row * OS + ch * 16;
+                        const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
+                        const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
+                        y[i] = u32x4{lo.x, lo.y, hi.x, hi.y};
                     }
-                    __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(a.dY[i] + at));
-                    if (a.Y[i]) __builtin_nontemporal_store(y[i], reinterpret_cast<u32x4 *>(a.Y[i] + at));
+#pragma unroll
+                    for (int i = 0; i < NR; ++i) {
+                        const int th = a.teacher[i];
+                        u32x4 tt = t;
+#pragma unroll
+                        for (int u = 0; u < NR; ++u)
+                            if (u != i && th == u) tt = y[u];
+                        const float cf = a.coef[i];
+                        u32x4 o;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float y0 = bf16_lo(y[i][j]), y1 = bf16_hi(y[i][j]);
+                            float d0 = y0 - bf16_lo(tt[j]), d1 = y1 - bf16_hi(tt[j]);
+                            if (MIX && th >= 0) {  // teacher and ground truth, weighted equally
+                                const float e0 = y0 - bf16_lo(t[j]), e1 = y1 - bf16_hi(t[j]);
+                                sum[i] += 0.5f * (d0 * d0 + d1 * d1 + e0 * e0 + e1 * e1);
+                                d0 = 0.5f * (d0 + e0);
+                                d1 = 0.5f * (d1 + e1);
+                            } else {
+                                sum[i] = __builtin_fmaf(d1, d1, __builtin_fmaf(d0, d0, sum[i]));
+                            }
+                            o[j] = pack_bf16x2(cf * d0, cf * d1);
+                        }
+                        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(a.dY[i] + at));
+                        if (a.Y[i]) __builtin_nontemporal_store(y[i], reinterpret_cast<u32x4 *>(a.Y[i] + at));
+                    }
                 }
             }
-        }
+        };
+        if (a.mix)
+            chunks(std::true_type{});
+        else
+            chunks(std::false_type{});
         // workgroup sums in a fixed order; the staging tiles are dead after the barrier
         __syncthreads();
         float *red = reinterpret_cast<float *>(smem);
