@@ -417,7 +417,7 @@ def mixnmatch_decode(torch, mq, synth):
                               "frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
         res[name] = entry
         del layers
-    res["note"] = ("one mq_ffn_mixnmatch call (two GEMVs, the gate kernel and the residual add per layer) from a HIP-graph "
+    res["note"] = ("one mq_ffn_mixnmatch call (two GEMV launches per layer: gate activation and residual add run in their epilogues) from a HIP-graph "
                    "replay; every stack exceeds the 256 MB last-level cache except int2_x8 (352 MB of planes: it does too)")
     return res
 

@@ -256,9 +256,11 @@ mq_status mq_linear_fwd_multi_l2(const uint16_t *X, const uint8_t *Q, const floa
  * the default here, Mistral SiLU (MQ_FLAG_FFN_SILU).
  *   x        [B, d] bf16, 1 <= B <= 16
  *   layers   HOST array of n_layers descriptors; all pointers in them are device pointers:
- *              gate_up   packed plane of the gate rows followed by the up rows, [2F, d*r/8]
+ *              gate_up   packed plane [2F, d*r/8] of the gate and the up rows, interleaved: row 2 f is
+ *                        gate row f, row 2 f + 1 is up row f (the two products of a pair then meet in
+ *                        one thread's epilogue; this order is this library's definition)
  *              down      packed plane [d, F*r/8]
- *              alpha_gu, zero_gu  bf16 [2F];  alpha_dn, zero_dn  bf16 [d]
+ *              alpha_gu, zero_gu  bf16 [2F], in the row order of gate_up;  alpha_dn, zero_dn  bf16 [d]
  *              r         bits of this layer's planes: 8, 6, 4, 3 or 2
  *   y        [B, d] bf16 out (may not alias x)
  *   ws       workspace of at least mq_workspace_bytes(MQ_OP_FFN_DECODE, B, F, d, 1)

@@ -277,7 +277,7 @@ def ffn_mixnmatch(x_bf16, layers, d: int, F: int, silu: bool = False, residual: 
     layers, layer l read at its own bit-width r_l,
         g, u = W_gate h, W_up h;  a = act(g) * u;  o = W_down a;  h <- o  (or h + o)
     with the matrix-vector products of gemv_sliced (fp64) and every intermediate rounded to bf16.
-    act = GELU in its tanh form (default) or SiLU.  layers: dicts with gate_up [2F, d*r/8], down
+    act = GELU in its tanh form (default) or SiLU.  layers: dicts with gate_up [2F, d*r/8] (gate and up rows interleaved, gate first), down
     [d, F*r/8] (packed uint8), alpha_gu, zero_gu [2F], alpha_dn, zero_dn [d] (bf16 bit patterns), r.
     Returns (y as bf16 bit patterns [B, d], the last layer's output before its final rounding, fp64)."""
     h = _c(x_bf16, np.uint16)
@@ -285,7 +285,7 @@ def ffn_mixnmatch(x_bf16, layers, d: int, F: int, silu: bool = False, residual: 
     for L in layers:
         r = int(L["r"])
         gu = bf16_to_f64(bf16_round(gemv_sliced(h, L["gate_up"], L["alpha_gu"], L["zero_gu"], r, d)))
-        g, u = gu[:, :F], gu[:, F:]
+        g, u = gu[:, 0::2], gu[:, 1::2]      # row 2 f of the plane is gate row f, row 2 f + 1 up row f
         if silu:
             with np.errstate(over="ignore"):  # exp(-g) = inf for very negative g gives the limit -0
                 act = g / (1.0 + np.exp(-g))

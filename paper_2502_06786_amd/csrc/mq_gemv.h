@@ -16,7 +16,37 @@ struct GemvArgs {
     int B, N, K;
     int KB;       // bytes per packed row
     float scale;  // 2^s: one step of the stored codes on the int8 grid
+    // What the epilogue does with the product o[b, n] (rounded to bf16 first in every case):
+    //   kPostNone      y[b, n] = o
+    //   kPostResidual  y[b, n] = bf16(res[b, n] + o)
+    //   kPostGelu/Silu rows come in (gate, up) pairs, gate at the even row:
+    //                  y[b, n / 2] = bf16(act(o[b, n]) * o[b, n + 1]), y is [B, N / 2]
+    int post;
+    const uint16_t *res;  // [B, N] bf16, kPostResidual only
 };
+
+enum { kPostNone = 0, kPostResidual = 1, kPostGelu = 2, kPostSilu = 3 };
+
+__device__ __forceinline__ float gelu_tanh(float v) {
+    // 0.5 v (1 + tanh(sqrt(2 / pi) (v + 0.044715 v^3)))
+    const float t = 0.7978845608028654f * (v + 0.044715f * v * v * v);
+    return 0.5f * v * (1.0f + tanhf(t));
+}
+__device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
+__device__ __forceinline__ float bf16_rounded(float v) { return __uint_as_float(float_to_bf16_bits(v) << 16); }
+// one gated output from the (gate, up) pair of products
+__device__ __forceinline__ uint16_t gated_bf16(float gate, float up, int post) {
+    const float g = bf16_rounded(gate), u = bf16_rounded(up);
+    return (uint16_t)float_to_bf16_bits((post == kPostSilu ? silu(g) : gelu_tanh(g)) * u);
+}
+__device__ __forceinline__ uint16_t residual_bf16(uint16_t res, float o) {
+    return (uint16_t)float_to_bf16_bits(__uint_as_float((uint32_t)res << 16) + bf16_rounded(o));
+}
+
+// The decode GEMV with an epilogue of the list above (the public mq_gemv_sliced is kPostNone).
+mq_status gemv_sliced_post(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
+                           const uint16_t *zero_bf16, int64_t B, int64_t N, int64_t K, int r, uint16_t *y, int post,
+                           const uint16_t *res, void *hip_stream);
 
 // Small-batch kernel (B <= 4, r = 4 or 2, no overflow list): activations live in registers.
 // Returns MQ_OK with *handled = false when the shape is outside what it covers.

@@ -681,19 +681,33 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                     xoff += sums[32 + hw];
                 }
 #pragma unroll
-                for (int rg = 0; rg < RG; ++rg)
+                for (int rg = 0; rg < RG; ++rg) {
+                    float yv[4];
 #pragma unroll
                     for (int cc = 0; cc < 4; ++cc) {
-                        const int rl = rg * 16 + 4 * g + cc, row = n0 + rl;
-                        if (row < a.N) {
-                            float dot = acc[rg][cc];
-                            if constexpr (R == 2 || R == 3) dot -= xoff;
-                            if constexpr (R == 4 || R == 6) dot -= 128.0f * xsum;
-                            if constexpr (EP) dot += ovf[(rw * ROWS + rl) * 16 + b];
-                            const float yv = pal[rg][cc] * (kScale * dot - pze[rg][cc] * xsum);
-                            a.y[(size_t)b * a.N + row] = (uint16_t)float_to_bf16_bits(yv);
+                        const int rl = rg * 16 + 4 * g + cc;
+                        float dot = acc[rg][cc];
+                        if constexpr (R == 2 || R == 3) dot -= xoff;
+                        if constexpr (R == 4 || R == 6) dot -= 128.0f * xsum;
+                        if constexpr (EP) dot += ovf[(rw * ROWS + rl) * 16 + b];
+                        yv[cc] = pal[rg][cc] * (kScale * dot - pze[rg][cc] * xsum);
+                    }
+                    const int row0 = n0 + rg * 16 + 4 * g;  // the lane's four consecutive rows
+                    if (a.post >= kPostGelu) {              // two (gate, up) pairs (N is even)
+#pragma unroll
+                        for (int cc = 0; cc < 4; cc += 2)
+                            if (row0 + cc < a.N)
+                                a.y[(size_t)b * (a.N >> 1) + ((row0 + cc) >> 1)] = gated_bf16(yv[cc], yv[cc + 1], a.post);
+                    } else {
+#pragma unroll
+                        for (int cc = 0; cc < 4; ++cc) {
+                            const size_t at = (size_t)b * a.N + row0 + cc;
+                            if (row0 + cc < a.N)
+                                a.y[at] = a.post == kPostResidual ? residual_bf16(a.res[at], yv[cc])
+                                                                  : (uint16_t)float_to_bf16_bits(yv[cc]);
                         }
                     }
+                }
             }
         }
         // the next group's tiles, overflow sums or (restaged) x area start behind a barrier
@@ -762,8 +776,11 @@ static mq_status launch_gemv(const GemvArgs &a, int nw, int ks, hipStream_t st) 
 // r = bits per stored code, shift = s of the grid the codes live on (8 - r for a plain plane)
 static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                                const uint16_t *zero_bf16, const mq_overflow *ovf, int64_t B, int64_t N, int64_t K,
-                               int r, int shift, uint16_t *y, void *hip_stream) {
+                               int r, int shift, uint16_t *y, void *hip_stream, int post = mq::kPostNone,
+                               const uint16_t *res = nullptr) {
     using namespace mq;
+    if (post >= kPostGelu && (N % 2 != 0 || ovf)) return MQ_ERR_SHAPE;
+    if (post == kPostResidual && !res && N > 0) return MQ_ERR_NULL;
     if (r != 8 && r != 6 && r != 4 && r != 3 && r != 2) return MQ_ERR_BITS;
     if (B < 1 || B > 16 || N < 0 || K < 1 || N > 0x7FFFFFF0 || K > 0x7FFFFFF0) return MQ_ERR_SHAPE;
     if (ovf && K > 65536) return MQ_ERR_SHAPE;
@@ -789,6 +806,8 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     a.K = (int)K;
     a.KB = (int)kb;
     a.scale = (float)(1 << shift);
+    a.post = post;
+    a.res = res;
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     {
@@ -826,6 +845,13 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     MQ_GEMV_CASE(3, 1, 4) MQ_GEMV_CASE(3, 2, 2)
 #undef MQ_GEMV_CASE
     return MQ_ERR_BITS;
+}
+
+mq_status mq::gemv_sliced_post(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
+                               const uint16_t *zero_bf16, int64_t B, int64_t N, int64_t K, int r, uint16_t *y, int post,
+                               const uint16_t *res, void *hip_stream) {
+    if (r < 1 || r > 8) return MQ_ERR_BITS;
+    return gemv_dispatch(x, packed, alpha_bf16, zero_bf16, nullptr, B, N, K, r, 8 - r, y, hip_stream, post, res);
 }
 
 extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,

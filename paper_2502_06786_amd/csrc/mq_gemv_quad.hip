@@ -318,7 +318,8 @@ __global__ __launch_bounds__(512) void gemv_quad_kernel(GemvArgs a, int KS, int 
     const float kScale = a.scale;
     for (int idx = tid, m = 0; idx < total_out; idx += nthreads, ++m) {
         const int bb = idx / (nblk * 16), r = idx - bb * (nblk * 16), row = out_row(idx);
-        if (row >= a.N) continue;
+        const bool live = row < a.N;
+        if (!live && a.post < kPostGelu) continue;
         float xsum = 0.f, xoff = 0.f;
         for (int w = 0; w < NW; ++w) {
             xsum += sums[(w * 4 + bb) * 2];
@@ -331,11 +332,19 @@ __global__ __launch_bounds__(512) void gemv_quad_kernel(GemvArgs a, int KS, int 
             al = m == 0 ? pal[0] : pal[1];
             ze = m == 0 ? pze[0] : pze[1];
         } else {
-            al = bf16_bits_to_float(a.alpha[row]);
-            ze = bf16_bits_to_float(a.zero[row]);
+            al = live ? bf16_bits_to_float(a.alpha[row]) : 0.f;
+            ze = live ? bf16_bits_to_float(a.zero[row]) : 0.f;
         }
         const float yv = al * (kScale * (dot - xoff) - ze * xsum);
-        a.y[(size_t)bb * a.N + row] = (uint16_t)float_to_bf16_bits(yv);
+        if (a.post >= kPostGelu) {
+            // neighbouring threads hold neighbouring rows of one 16-row block: the even one of a
+            // (gate, up) pair takes the up value from its neighbour (the trip count of this loop is
+            // the same for both, total_out and the thread count being even)
+            const float up = __shfl_xor(yv, 1);
+            if (live && !(row & 1)) a.y[(size_t)bb * (a.N >> 1) + (row >> 1)] = gated_bf16(yv, up, a.post);
+        } else {
+            a.y[(size_t)bb * a.N + row] = (uint16_t)float_to_bf16_bits(yv);
+        }
     }
 }
 
@@ -358,7 +367,7 @@ mq_status launch_quad(const GemvArgs &a, const QuadPlan &p, hipStream_t st) {
 
 mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handled) {
     *handled = false;
-    if (a.B > 4 || (r != 2 && r != 4) || a.row_ptr) return MQ_OK;
+    if (a.B > 4 || (r != 2 && r != 4) || a.row_ptr || a.post == kPostResidual) return MQ_OK;
     const int lines = (a.KB + 127) / 128;
     const int nrb = (a.N + 15) / 16;
     // Measured against the general kernel on 4096..36864 rows: 0.85-0.9x the time at 36864 x 4608, level or

@@ -76,6 +76,28 @@ def test_training_path_full_size(mq, oracle, config, name):
             want = oracle.linear_fwd_sampled(xb, qo, ao, zo, 2, ms, ns, ep=ep)
             assert rel_l2(_pick(Y2, ms, ns), want) <= TOL, ("r=2", ep)
     del Ys
+    if config == 2:
+        # the call the bench times: the same forward with the L2 objective in its epilogue (no Y stored).
+        # Sampled gradients against the oracle; the losses, sums over all M N outputs, through what ties
+        # them to the gradients at any size (loss_i = M N / (4 lambda_i^2) * mean(dY_i^2)) and against the
+        # oracle's estimate from the sample.
+        wants = [oracle.linear_fwd_sampled(xb, qo, ao, zo, r, ms, ns) for r in rs]
+        scale = float(np.std(wants[0]))
+        T = (torch.randn(M, N, generator=torch.Generator().manual_seed(config * 10 + 4)) * scale).to(torch.bfloat16)
+        teacher = (-1, 0, 0)
+        losses, dYs = mq.mq_linear_fwd_multi_l2(X, Q, alpha, zero, rs, T.cuda(), teacher, lam)
+        torch.cuda.synchronize()
+        tb = bf16_bits(T)[ms, ns].reshape(1, -1)
+        est, want_d = oracle.matquant_l2_loss([oracle.bf16_round(w).reshape(1, -1) for w in wants], tb, teacher, lam)
+        got_l = losses.cpu().numpy().astype(np.float64)
+        for i, r in enumerate(rs):
+            err = rel_l2(_pick(dYs[i], ms, ns), want_d[i].ravel() * (NSAMPLES / (M * N)))
+            print(f"  fused dY_{r}: rel-L2 {err:.2e}  loss {got_l[i]:.4e} (sample estimate {est[i]:.4e})", flush=True)
+            assert err <= TOL, (r, err)
+            tied = float((dYs[i].double() ** 2).mean().item()) * (M * N) ** 2 / (4.0 * lam[i] ** 2)
+            assert abs(got_l[i] - tied) <= TOL * tied, (r, got_l[i], tied)       # dY is rounded to bf16
+            assert abs(got_l[i] - est[i]) <= 0.1 * est[i], (r, got_l[i], est[i])  # 4096 samples: a few per cent
+        del dYs, T
 
     dY = [d.cuda() for d in case.dY]
     dyb = [bf16_bits(d) for d in case.dY]

@@ -422,17 +422,38 @@ def test_ffn_mixnmatch_small(mq, oracle, d, F, rs, B, silu, residual):
     assert rel_l2(y.float().cpu().numpy(), want) <= TOL * max(len(rs), 1)
 
 
-def test_ffn_mixnmatch_7b_shaped_pyramid(mq, oracle):
-    """Mistral-7B-shaped layers (d 4096, F 14336), int2 - int4 - int2: the stacked gate/up plane has 28672 rows
-    (the tall-matrix kernel at int2 / int4), B = 1."""
+@pytest.mark.parametrize("B,silu,residual", [(1, True, False), (3, False, True)])
+def test_ffn_mixnmatch_7b_shaped_pyramid(mq, oracle, B, silu, residual):
+    """Mistral-7B-shaped layers (d 4096, F 14336), int2 - int4 - int2: the gate/up plane has 28672 rows (the
+    tall-matrix kernel at int2 / int4 with the gate activation in its epilogue), B = 1 and 3."""
     d, F, rs = 4096, 14336, (2, 4, 2)
     layers, host = _ffn_stack(mq, oracle, 90, d, F, rs, scale=1.5)
-    x = _randn(91, 1, d).to(torch.bfloat16)
-    y = mq.mq_ffn_mixnmatch(dev(x), layers, F, silu=True)
-    want_bits, _ = oracle.ffn_mixnmatch(bf16_bits(x), host, d, F, silu=True)
+    x = _randn(91, B, d).to(torch.bfloat16)
+    y = mq.mq_ffn_mixnmatch(dev(x), layers, F, silu=silu, residual=residual)
+    want_bits, _ = oracle.ffn_mixnmatch(bf16_bits(x), host, d, F, silu=silu, residual=residual)
     want = oracle.bf16_to_f64(want_bits)
     assert np.abs(want).max() > 1e-3
     assert rel_l2(y.float().cpu().numpy(), want) <= TOL * len(rs)
+
+
+def test_ffn_layer_pairs_gate_and_up_rows(mq, oracle):
+    """One layer whose gate rows are the only non-constant ones: with gate row f next to up row f the
+    output must follow the oracle, which reads the plane as (gate, up) pairs; the order inside a pair
+    and the pairing itself would both show (GELU is not symmetric in its two factors)."""
+    d, F, r = 256, 512, 8
+    w_gu = _randn(5, 2 * F, d, scale=0.1)
+    w_gu[1::2] = w_gu[1::2].abs() + 0.05          # up rows: positive weights
+    w_dn = torch.eye(d, F) + _randn(6, d, F, scale=0.01)
+    L = {"r": r}
+    for name, w in (("gu", w_gu), ("dn", w_dn)):
+        Q, a, z = mq.mq_quantize_int8(dev(w))
+        L["alpha_" + name], L["zero_" + name] = mq.mq_params_to_bf16(a, z)
+        L["gate_up" if name == "gu" else "down"] = mq.mq_slice(Q, r, packed=True)
+    host = {k: (v if k == "r" else (bf16_bits(v) if v.dtype == torch.bfloat16 else v.cpu().numpy())) for k, v in L.items()}
+    x = _randn(7, 2, d).abs().to(torch.bfloat16)
+    y = mq.mq_ffn_mixnmatch(dev(x), [L], F)
+    want = oracle.bf16_to_f64(oracle.ffn_mixnmatch(bf16_bits(x), [host], d, F)[0])
+    assert rel_l2(y.float().cpu().numpy(), want) <= TOL
 
 
 # --------------------------------------------------------------------------
