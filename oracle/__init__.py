@@ -327,3 +327,49 @@ def matquant_l2_loss(Ys_bf16, target_bf16=None, teacher=None, lambdas=None, mix:
             losses.append(float(0.5 * ((d1 ** 2).sum() + (d2 ** 2).sum()) / mn))
             dYs.append(lam[i] * (d1 + d2) / mn)
     return np.array(losses), dYs
+
+
+def clip_factor_grads(W, X_bf16, dYs_bf16, lambdas, rs, gamma=None, beta=None, ep: bool = False):
+    """Gradients of  sum_r lambda_r <dY_r, X What_r^T>  with respect to the clip factors gamma, beta of the
+    quantizer of section 3.1.2 (alpha = (gamma max - beta min) / 255, z = -beta min / alpha), under the
+    straight-through estimator the section names: both roundings (to the 8-bit code and, in the slicing of
+    section 3.2, to the r-bit code) pass the gradient unchanged, both clamps (to 0..255, and to the top code
+    2^r - 1 of a slice) pass it only where they do not act.  With u = w / alpha + z and What_r = alpha (S_r - z):
+        d What_r / d alpha = (S_r - z) - m_r w / alpha        d What_r / d z = -alpha (1 - m_r)
+    where m_r = 1 where neither clamp acts.  The clamp decisions are the quantizer's own (fp32); everything
+    else is fp64.  Rows with gamma max == beta min (alpha set to 1 by the quantizer) get zero gradients.
+    Returns (dgamma, dbeta, dalpha, dzero), each [N] fp64."""
+    W32 = _c(W, np.float32)
+    N, K = W32.shape
+    g32 = None if gamma is None else _c(gamma, np.float32)
+    b32 = None if beta is None else _c(beta, np.float32)
+    q, alpha32, zero32 = quantize_int8(W32, g32, b32)
+    # the quantizer's rounding, before its clamp, in its own precision and operation order
+    t32 = (W32 / alpha32[:, None]).astype(np.float32)
+    u32 = (t32 + zero32[:, None]).astype(np.float32)
+    rounded = np.rint(u32)
+    inside = (rounded >= 0.0) & (rounded <= 255.0)
+    Wd, a, z = W32.astype(np.float64), alpha32.astype(np.float64), zero32.astype(np.float64)
+    X = bf16_to_f64(X_bf16)
+    dalpha, dzero = np.zeros(N), np.zeros(N)
+    for r, dY, lam in zip(rs, dYs_bf16, lambdas):
+        dWhat = float(lam) * (bf16_to_f64(dY).T @ X)                     # [N, K]: d objective / d What_r
+        s = 8 - int(r)
+        raw = (q.astype(np.int64) + ((1 << s) >> 1)) >> s
+        top = np.zeros_like(inside) if ep else raw > (1 << r) - 1
+        code = raw if ep else np.minimum(raw, (1 << r) - 1)
+        S = (code << s).astype(np.float64)
+        m = (inside & ~top).astype(np.float64)
+        dalpha += (dWhat * ((S - z[:, None]) - m * Wd / a[:, None])).sum(axis=1)
+        dzero += (dWhat * (-a[:, None] * (1.0 - m))).sum(axis=1)
+    mn, mx = Wd.min(axis=1), Wd.max(axis=1)
+    gam = np.ones(N) if g32 is None else g32.astype(np.float64)
+    bet = np.ones(N) if b32 is None else b32.astype(np.float64)
+    live = (gam * mx != bet * mn).astype(np.float64)
+    da_dg, da_db = mx / 255.0, -mn / 255.0
+    dz_dg = (bet * mn / a ** 2) * da_dg
+    dz_db = -mn / a + (bet * mn / a ** 2) * da_db
+    dgamma = live * (dalpha * da_dg + dzero * dz_dg)
+    dbeta = live * (dalpha * da_db + dzero * dz_db)
+    return dgamma, dbeta, dalpha, dzero
+

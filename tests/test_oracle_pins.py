@@ -574,3 +574,80 @@ def test_l2_objective_closed_forms(oracle):
     _, d_plain = oracle.matquant_l2_loss([bf16_bits(Y), bf16_bits(T)], bf16_bits(T), (-1, -1))
     _, d_teach = oracle.matquant_l2_loss([bf16_bits(Y), bf16_bits(T)], bf16_bits(T), (-1, 0))
     assert np.array_equal(d_plain[0], d_teach[0]) and np.all(d_teach[1] == 2 * (1.0 - 1.5) / (M * N))
+
+
+# --------------------------------------------------------------------------
+# gradients with respect to the clip factors of the quantizer (section 3.1.2)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("ep,clip", [(False, True), (True, True), (False, False)])
+def test_clip_factor_grads_vs_autograd(oracle, ep, clip):
+    # Library special case: the quantize -> slice -> dequantize -> matmul chain written in torch float64 with the
+    # straight-through estimator spelled as x + (round(x) - x).detach() and torch.clamp for the clamps; autograd
+    # then differentiates with respect to gamma and beta.  The rounding decisions (which are taken in fp32 by the
+    # quantizer) enter as constants computed here with numpy fp32.
+    N, K, M, rs, lam = 24, 96, 40, (8, 4, 2), (0.3, 0.5, 1.0)
+    g = torch.Generator().manual_seed(31)
+    W = torch.randn(N, K, generator=g) * 0.02
+    W[3, 7] = 0.2                                                  # an outlier row: most codes far from the ends
+    X = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    dYs = [(torch.randn(M, N, generator=g) * 1e-2).to(torch.bfloat16) for _ in rs]
+    gamma = (torch.rand(N, generator=g) * 0.4 + 0.5) if clip else torch.ones(N)     # < 1: the clamp to 0..255 acts
+    beta = (torch.rand(N, generator=g) * 0.4 + 0.5) if clip else torch.ones(N)
+    got = oracle.clip_factor_grads(W.numpy(), bf16_bits(X), [bf16_bits(d) for d in dYs], lam, rs,
+                                   gamma.numpy() if clip else None, beta.numpy() if clip else None, ep=ep)
+
+    mx, mn = W.max(dim=1).values.double(), W.min(dim=1).values.double()
+    # fp32 decisions, as the quantizer of section 3.1.2 is specified (one rounded operation per symbol)
+    hi32 = (gamma.numpy() * W.max(dim=1).values.numpy()).astype(np.float32)
+    lo32 = (beta.numpy() * W.min(dim=1).values.numpy()).astype(np.float32)
+    a32 = ((hi32 - lo32).astype(np.float32) / np.float32(255.0)).astype(np.float32)
+    z32 = (-lo32 / a32).astype(np.float32)
+    u32 = ((W.numpy() / a32[:, None]).astype(np.float32) + z32[:, None]).astype(np.float32)
+    rounded = torch.from_numpy(np.rint(u32).astype(np.float64))
+
+    gm = gamma.double().requires_grad_(True)
+    bt = beta.double().requires_grad_(True)
+    # alpha and z as functions of gamma, beta, evaluated AT the fp32 values the quantizer produced: the value is
+    # replaced, the derivative kept
+    a_fn = (gm * mx - bt * mn) / 255.0
+    a = a_fn + (torch.from_numpy(a32.astype(np.float64)) - a_fn).detach()
+    z_fn = -bt * mn / a
+    z = z_fn + (torch.from_numpy(z32.astype(np.float64)) - z_fn).detach()
+    u = W.double() / a[:, None] + z[:, None]
+    q = torch.clamp(u + (rounded - u).detach(), 0.0, 255.0)
+    obj = 0.0
+    for r, dY, l in zip(rs, dYs, lam):
+        s = 8 - r
+        v = (q + float((1 << s) >> 1)) / float(1 << s)
+        code = v + (torch.floor(v) - v).detach()
+        if not ep:
+            code = torch.clamp(code, max=float((1 << r) - 1))
+        What = a[:, None] * (code * float(1 << s) - z[:, None])
+        obj = obj + l * (dY.double() * (X.double() @ What.T)).sum()
+    obj.backward()
+    for name, mine, ref in (("gamma", got[0], gm.grad.numpy()), ("beta", got[1], bt.grad.numpy())):
+        assert np.abs(ref).max() > 0
+        assert np.allclose(mine, ref, rtol=1e-9, atol=1e-12 * np.abs(ref).max()), name
+
+
+def test_clip_factor_grads_special_cases(oracle):
+    N, K, M = 6, 64, 8
+    g = torch.Generator().manual_seed(5)
+    W = torch.randn(N, K, generator=g) * 0.02
+    W[2] = 0.25                                                    # a constant row: alpha is set to 1, no gradient
+    X = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    dY = (torch.randn(M, N, generator=g) * 1e-2).to(torch.bfloat16)
+    dg, db, da, dz = oracle.clip_factor_grads(W.numpy(), bf16_bits(X), [bf16_bits(dY)], (1.0,), (8,))
+    assert dg[2] == 0.0 and db[2] == 0.0
+    # without clipping (gamma = beta = 1) and at r = 8 nothing is clamped: d What / d z = 0 everywhere and
+    # d What / d alpha is the rounding residual q - u, at most 1/2 in magnitude
+    assert np.all(dz[[0, 1, 3, 4, 5]] == 0.0)
+    q, a, z = oracle.quantize_int8(W.numpy())
+    resid = q.astype(np.float64) - (W.double().numpy() / a.astype(np.float64)[:, None] + z.astype(np.float64)[:, None])
+    assert np.abs(resid[[0, 1, 3, 4, 5]]).max() <= 0.5 + 1e-4
+    dWhat = bits_to_f64(bf16_bits(dY)).T @ bits_to_f64(bf16_bits(X))
+    assert np.allclose(da[[0, 1, 3, 4, 5]], (dWhat * resid).sum(axis=1)[[0, 1, 3, 4, 5]], rtol=1e-9, atol=1e-15)
+    # lambda scales the gradients linearly
+    dg2, db2, _, _ = oracle.clip_factor_grads(W.numpy(), bf16_bits(X), [bf16_bits(dY)], (2.5,), (8,))
+    assert np.allclose(dg2, 2.5 * dg) and np.allclose(db2, 2.5 * db)
+
