@@ -202,6 +202,7 @@ def main():
         out["extra_precision_gemv"] = ep_gemv(torch, mq, synth)
     if not args.no_gemv_sweep:
         out["mixnmatch_decode"] = mixnmatch_decode(torch, mq, synth)
+        out["clip_factor_grads"] = clip_factor_grads(torch, mq, layers, rs, lambdas)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, synth, rs, lambdas)
     print(json.dumps(out))
@@ -366,6 +367,26 @@ def ep_gemv(torch, mq, synth):
             nbytes = wbytes + 4 * N + 2 * B * K + 2 * B * N
             res[f"{name}_B{B}"] = {"us": round(ms * 1e3, 2), "GBs": round(nbytes / (ms * 1e-3) / 1e9, 1),
                                    "frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    return res
+
+
+def clip_factor_grads(torch, mq, layers, rs, lambdas, reps=5):
+    """mq_linear_bwd_clip on the three linears of the step (the gradients dY_r the step left behind): one
+    dY_r^T X contraction per bit-width plus a row reduction each."""
+    res = {}
+    for L in layers:
+        ws = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD_CLIP, L.M, L.N, L.K, len(rs)), dtype=torch.uint8, device="cuda")
+        mq.mq_linear_bwd_clip(L.W, L.X, L.Q, L.alpha, L.zero, L.dY, lambdas, rs, ws=ws)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            mq.mq_linear_bwd_clip(L.W, L.X, L.Q, L.alpha, L.zero, L.dY, lambdas, rs, ws=ws)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        res[L.name] = {"ms": round(ms, 4), "TFLOPs": round(2.0 * len(rs) * L.M * L.N * L.K / (ms * 1e-3) / 1e12, 1)}
+        del ws
+    res["note"] = "flops = 2 MNK per bit-width (the three dY_r^T X contractions); the row reductions are HBM-bound"
     return res
 
 

@@ -56,7 +56,8 @@ enum {
                                     per code that keeps code 2^r, instead of plane + list     */
 };
 
-enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1, MQ_OP_FFN_DECODE = 2, MQ_OP_L2_LOSS = 3, MQ_OP_LINEAR_FWD_L2 = 4 };
+enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1, MQ_OP_FFN_DECODE = 2, MQ_OP_L2_LOSS = 3, MQ_OP_LINEAR_FWD_L2 = 4,
+       MQ_OP_LINEAR_BWD_CLIP = 5 };
 
 /*
  * Extra-precision overflow set (errata section: weights whose rounded r-bit
@@ -243,6 +244,35 @@ mq_status mq_linear_fwd_multi_l2(const uint16_t *X, const uint8_t *Q, const floa
                                  const uint16_t *target, const int *teacher, const float *lambda,
                                  uint16_t *const *Y, uint16_t *const *dY, float *losses,
                                  void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Gradients of the MatQuant objective with respect to the clip factors gamma, beta that the
+ * quantizer takes (section 3.1.2: alpha = (gamma max - beta min) / 255, z = -beta min / alpha; these
+ * are the parameters that the OmniQuant base algorithm trains through the layer-wise L2 loss), for
+ * the gradients dY_r of mq_matquant_l2_loss / mq_linear_fwd_multi_l2:
+ *     dgamma_n = sum_r lambda_r sum_{m,k} dY_r[m,n] X[m,k] * d What_r[n,k] / d gamma_n   (dbeta alike)
+ * under the straight-through estimator the section names, read as: the rounding to the 8-bit code
+ * and the rounding inside the slicing operator pass the gradient unchanged; the clamp to 0..255 and
+ * the clamp of a slice to its top code 2^r - 1 (absent with MQ_FLAG_EXTRA_PRECISION) pass it only
+ * where they do not act.  With u = w / alpha + z and What_r = alpha (S(q, r) - z):
+ *     d What_r / d alpha = (S(q, r) - z) - m_r w / alpha         d What_r / d z = -alpha (1 - m_r)
+ * (m_r = 1 where neither clamp acts), chained through alpha(gamma, beta), z(beta, alpha).  A row with
+ * gamma max == beta min (alpha set to 1 by the quantizer) gets zero gradients.
+ *   W        [N, ldw] fp32 master weights, ldw a multiple of 4
+ *   X        [M, K] bf16           Q [N, K] uint8, alpha, zero [N] fp32 as mq_quantize_int8 wrote them
+ *   gamma, beta  [N] fp32 or NULL (= 1): what the quantizer was called with
+ *   dY, lambda, rs, nr  as for mq_linear_bwd
+ *   dgamma, dbeta  [N] fp32 out;  dalpha, dzero  [N] fp32 out or NULL (the gradients with respect to
+ *            alpha and z, before the chain rule)
+ *   ws       workspace of at least mq_workspace_bytes(MQ_OP_LINEAR_BWD_CLIP, M, N, K, nr)
+ * Alignment and size limits as for mq_linear_bwd.  N == 0 is a no-op; M == 0 writes zeros.
+ */
+mq_status mq_linear_bwd_clip(const float *W, int64_t ldw, const uint16_t *X, const uint8_t *Q,
+                             const float *alpha, const float *zero, const float *gamma, const float *beta,
+                             const uint16_t *const *dY, const float *lambda,
+                             int64_t M, int64_t N, int64_t K, const int *rs, int nr, uint32_t flags,
+                             float *dgamma, float *dbeta, float *dalpha, float *dzero,
+                             void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Layer-wise Mix'n'Match on the decode path (section 4.3 "Mix'n'Match", section 5.1.3 and appendix B:

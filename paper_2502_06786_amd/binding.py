@@ -23,13 +23,14 @@ MQ_OP_LINEAR_BWD = 1
 MQ_OP_FFN_DECODE = 2
 MQ_OP_L2_LOSS = 3
 MQ_OP_LINEAR_FWD_L2 = 4
+MQ_OP_LINEAR_BWD_CLIP = 5
 MQ_FLAG_LOSS_MIX = 64
 MQ_FLAG_FFN_SILU = 16
 MQ_FLAG_FFN_RESIDUAL = 32
 
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
            "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string", "mq_probe_mfma", "mq_probe_read",
-           "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2"]
+           "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2", "mq_linear_bwd_clip"]
 
 
 class MqError(RuntimeError):
@@ -74,6 +75,8 @@ def _load() -> ctypes.CDLL:
     lib.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp,
                                            ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_float), ctypes.POINTER(vp),
                                            ctypes.POINTER(vp), vp, vp, sz, vp]
+    lib.mq_linear_bwd_clip.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float),
+                                       i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, vp, vp, sz, vp]
     lib.mq_ffn_mixnmatch.argtypes = [vp, ctypes.POINTER(_FfnLayer), ci, i64, i64, i64, u32, vp, vp, sz, vp]
     lib.mq_probe_read.argtypes = [vp, i64, vp, vp]
     for name in EXPORTS:
@@ -368,3 +371,32 @@ def mq_linear_fwd_multi_l2(X, Q, alpha, zero, rs, target=None, teacher=None, lam
                                      ws.numel(), _stream())
     _check(st, "mq_linear_fwd_multi_l2")
     return losses, dY
+
+
+def mq_linear_bwd_clip(W, X, Q, alpha, zero, dY, lambdas, rs, gamma=None, beta=None, extra_precision: bool = False,
+                       want_dalpha_dzero: bool = False, ws=None):
+    """Gradients with respect to the clip factors of the quantizer: returns (dgamma, dbeta) fp32 [N], or
+    (dgamma, dbeta, dalpha, dzero) with want_dalpha_dzero."""
+    M, K = X.shape
+    N = Q.shape[0]
+    nr = len(rs)
+    if len(dY) != nr:
+        raise ValueError("one dY per r")
+    if W.stride(1) != 1 or W.shape != (N, K):
+        raise ValueError("W must be [N, K] with unit column stride")
+    out = [torch.empty(N, dtype=torch.float32, device=X.device) for _ in range(4 if want_dalpha_dzero else 2)]
+    need = mq_workspace_bytes(MQ_OP_LINEAR_BWD_CLIP, M, N, K, max(1, min(nr, 3)))
+    if ws is None:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=X.device)
+    lam = (ctypes.c_float * nr)(*lambdas) if lambdas is not None else None
+    flags = MQ_FLAG_EXTRA_PRECISION if extra_precision else 0
+    if W.dtype != torch.float32 or not W.is_cuda:
+        raise ValueError("W must be a float32 tensor on the GPU")
+    st = _lib.mq_linear_bwd_clip(ctypes.c_void_p(W.data_ptr()), W.stride(0), _ptr(X, torch.bfloat16), _ptr(Q, torch.uint8),
+                                 _ptr(alpha, torch.float32), _ptr(zero, torch.float32), _ptr(gamma, torch.float32),
+                                 _ptr(beta, torch.float32), _ptr_array(dY, torch.bfloat16), lam, M, N, K, _int_array(rs), nr,
+                                 flags, _ptr(out[0]), _ptr(out[1]), _ptr(out[2]) if want_dalpha_dzero else None,
+                                 _ptr(out[3]) if want_dalpha_dzero else None, _ptr(ws), ws.numel(), _stream())
+    _check(st, "mq_linear_bwd_clip")
+    return tuple(out)
+

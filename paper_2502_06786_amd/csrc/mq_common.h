@@ -46,6 +46,8 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 size_t ffn_workspace_bytes(int64_t B, int64_t F, int64_t d);
 // workspace of mq_matquant_l2_loss (mq_loss.hip)
 size_t loss_workspace_bytes(int64_t M, int64_t N);
+// workspace of mq_linear_bwd_clip (mq_clip.hip)
+size_t clip_workspace_bytes(int64_t M, int64_t N, int64_t K);
 // losses[i] = inv_mn * sum over the workgroups of partial[workgroup][i] (rows of 4 floats), in a
 // fixed order; one small launch on `st` (mq_loss.hip)
 mq_status launch_loss_finish(const float *partial, int64_t blocks, int nr, float inv_mn, float *losses,

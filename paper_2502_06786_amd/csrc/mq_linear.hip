@@ -1248,6 +1248,7 @@ extern "C" size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, in
     if (op == MQ_OP_LINEAR_BWD) return bwd_layout(M, N, K, nr).total + 256;
     if (op == MQ_OP_FFN_DECODE) return ffn_workspace_bytes(M, N, K);
     if (op == MQ_OP_L2_LOSS) return loss_workspace_bytes(M, N);
+    if (op == MQ_OP_LINEAR_BWD_CLIP) return clip_workspace_bytes(M, N, K);
     return 0;
 }
 

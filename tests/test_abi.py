@@ -40,6 +40,8 @@ def lib():
     lib_.mq_matquant_l2_loss.argtypes = [vp, vp, ctypes.POINTER(ci), vp, i64, i64, ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp,
                                             ctypes.POINTER(ci), vp, vp, vp, vp, vp, sz, vp]
+    lib_.mq_linear_bwd_clip.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32,
+                                        vp, vp, vp, vp, vp, sz, vp]
     lib_.mq_ffn_mixnmatch.argtypes = [vp, vp, ci, i64, i64, i64, u32, vp, vp, sz, vp]
     lib_.mq_probe_read.argtypes = [vp, i64, vp, vp]
     lib_.mq_workspace_bytes.argtypes = [ci, i64, i64, i64, ci]
@@ -202,3 +204,24 @@ def test_fwd_l2_argument_checks(lib):
     assert f(p, p, p, p, 16, 64, 64, rs, 3, 0, p, None, None, None, None, None, None, 0, None) == NULL   # no dY
     # the partial sums of the objective sit behind the row sums of X
     assert lib.mq_workspace_bytes(4, 4096, 9216, 2304, 3) >= lib.mq_workspace_bytes(0, 4096, 9216, 2304, 3) + 32 * 72 * 16
+
+
+def test_bwd_clip_argument_checks(lib):
+    f = lib.mq_linear_bwd_clip
+    ci = ctypes.c_int
+    rs = (ci * 3)(8, 4, 2)
+    p = ctypes.c_void_p(4096)    # never dereferenced: every call below returns before the first launch
+    def call(M=16, N=64, K=64, ldw=64, rs_=rs, nr=3, W=p, dg=p):
+        return f(W, ldw, p, p, p, p, None, None, None, None, M, N, K, rs_, nr, 0, dg, p, None, None, None, 0, None)
+    assert call(nr=4) == BITS
+    assert call(rs_=(ci * 2)(4, 4), nr=2) == BITS
+    assert call(ldw=32) == SHAPE
+    assert call(K=40, ldw=40) == ALIGN
+    assert call(ldw=66) == ALIGN
+    assert call(N=0) == OK
+    assert call(W=None) == NULL
+    assert call(dg=None) == NULL
+    assert call() == NULL                                         # dY missing
+    # the per-bit-width contraction goes into a scratch matrix next to the backward's own workspace
+    assert lib.mq_workspace_bytes(5, 4096, 9216, 2304, 3) >= 9216 * 2304 * 4 + lib.mq_workspace_bytes(1, 4096, 9216, 2304, 1)
+

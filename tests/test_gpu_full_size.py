@@ -101,6 +101,18 @@ def test_training_path_full_size(mq, oracle, config, name):
 
     dY = [d.cuda() for d in case.dY]
     dyb = [bf16_bits(d) for d in case.dY]
+    if config == 2 and name == "gate":
+        # gradients with respect to the clip factors: every row is an independent reduction, so the oracle
+        # evaluates a sample of rows (its inputs restricted to them) in full
+        Wd = case.W.cuda()
+        dg, db = mq.mq_linear_bwd_clip(Wd, X, Q, alpha, zero, dY, lam, rs)
+        rows_c = np.random.default_rng(config * 10 + 5).choice(N, 96, replace=False)
+        want_g, want_b, _, _ = oracle.clip_factor_grads(case.W.numpy()[rows_c], xb, [d[:, rows_c] for d in dyb], lam, rs)
+        for nm, mine, ref in (("dgamma", dg, want_g), ("dbeta", db, want_b)):
+            err = rel_l2(mine.cpu().numpy().astype(np.float64)[rows_c], ref)
+            print(f"  {nm}: rel-L2 {err:.2e}", flush=True)
+            assert err <= TOL, (nm, err)
+        del Wd
     dX, dW = mq.mq_linear_bwd(X, Q, alpha, zero, dY, lam, rs)
     ms, ks = _samples(config * 10 + 2, M, K)
     want = oracle.linear_bwd_dx_sampled(qo, ao, zo, dyb, lam, rs, ms, ks)

@@ -526,6 +526,44 @@ def test_fwd_with_fused_l2_objective(mq, oracle, M, N, K, rs, teacher, mix, ep):
     assert torch.equal(l3, losses) and all(torch.equal(u, v) for u, v in zip(d3, dYs))
 
 
+# --------------------------------------------------------------------------
+# gradients with respect to the clip factors of the quantizer
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("M,N,K,rs,clip,ep", [(64, 48, 96, (8, 4, 2), True, False), (264, 272, 208, (8, 4, 2), True, True),
+                                              (520, 400, 1040, (4, 2), False, False), (8, 16, 4112, (2,), True, False),
+                                              (0, 32, 64, (8, 4, 2), False, False)])
+def test_bwd_clip_factor_grads(mq, oracle, M, N, K, rs, clip, ep):
+    nr = len(rs)
+    lam = (0.3, 0.5, 1.0)[:nr]
+    W = _randn(M + N + K + 3, N, K, scale=0.02)
+    W[1] = 0.125                                  # constant row: no gradient unless gamma != beta
+    W[2, 5] = 0.3                                 # outlier: the other weights of the row sit in few codes
+    X = _randn(M * 7 + 1, M, K).to(torch.bfloat16)
+    dYs = [(_randn(300 + i, M, N) * 1e-2).to(torch.bfloat16) for i in range(nr)]
+    g = torch.rand(N, generator=torch.Generator().manual_seed(1)) * 0.4 + 0.5 if clip else None
+    b = torch.rand(N, generator=torch.Generator().manual_seed(2)) * 0.4 + 0.5 if clip else None
+    Wd = dev(W)
+    Q, a, z = mq.mq_quantize_int8(Wd, dev(g) if clip else None, dev(b) if clip else None)
+    qo, ao, zo = oracle.quantize_int8(W.numpy(), g.numpy() if clip else None, b.numpy() if clip else None)
+    assert np.array_equal(Q.cpu().numpy(), qo)
+    got = mq.mq_linear_bwd_clip(Wd, dev(X), Q, a, z, [dev(d) for d in dYs], lam, rs, dev(g) if clip else None,
+                                dev(b) if clip else None, extra_precision=ep, want_dalpha_dzero=True)
+    torch.cuda.synchronize()
+    if M == 0:
+        assert all(float(t.abs().max()) == 0.0 for t in got)
+        return
+    want = oracle.clip_factor_grads(W.numpy(), bf16_bits(X), [bf16_bits(d) for d in dYs], lam, rs,
+                                    g.numpy() if clip else None, b.numpy() if clip else None, ep=ep)
+    for name, mine, ref in zip(("dgamma", "dbeta", "dalpha", "dzero"), got, want):
+        mine = mine.cpu().numpy().astype(np.float64)
+        if np.abs(ref).max() == 0.0:              # e.g. d z without any clamp acting
+            assert np.abs(mine).max() == 0.0, name
+        else:
+            assert rel_l2(mine, ref) <= TOL, (name, rel_l2(mine, ref))
+    if not clip:                                  # (with gamma != beta the constant row has a range of its own)
+        assert got[0][1].item() == 0.0 and got[1][1].item() == 0.0 and want[0][1] == 0.0
+
+
 def test_measurement_probes_run(mq):
     ops = torch.randn(32768, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
     sink = torch.zeros(65536, dtype=torch.float32, device="cuda")
