@@ -373,3 +373,49 @@ def clip_factor_grads(W, X_bf16, dYs_bf16, lambdas, rs, gamma=None, beta=None, e
     dbeta = live * (dalpha * da_db + dzero * dz_db)
     return dgamma, dbeta, dalpha, dzero
 
+
+def affine_weight(W, s=None, delta=None, b=None):
+    """Weight side of the learnable affine re-parameterisation of a projection (section 3.1.2, the equation
+    X W + b -> ((X - delta) / s) Q(W * s) + b + delta W):  Ws = W * s is what the quantizer is given, so it is formed
+    exactly as the quantizer will see it, one fp32 product per weight;  c = b + W delta (fp64) is the bias of
+    the transformed layer.  W is [N, K] (out x in), s and delta are per input feature [K].  Returns (Ws fp32, c fp64)."""
+    W32 = _c(W, np.float32)
+    N, K = W32.shape
+    Ws = W32 if s is None else (W32 * _c(s, np.float32)[None, :]).astype(np.float32)
+    c = np.zeros(N) if b is None else np.asarray(b, dtype=np.float64).copy()
+    if delta is not None:
+        c = c + W32.astype(np.float64) @ np.asarray(delta, dtype=np.float64)
+    return Ws, c
+
+
+def affine_input(X_bf16, s=None, delta=None):
+    """Input side of the same equation: (X - delta) / s per input feature, fp64, rounded once to bf16 (bit patterns)."""
+    X = bf16_to_f64(X_bf16)
+    if delta is not None:
+        X = X - np.asarray(delta, dtype=np.float64)[None, :]
+    if s is not None:
+        X = X / np.asarray(s, dtype=np.float64)[None, :]
+    return bf16_round(X)
+
+
+def affine_bwd(X_bf16, dXt_bf16, W, dWs, dYs_bf16, lambdas, s, delta):
+    """Gradients of the objective with respect to delta and s of the same equation, given the gradients the
+    straight-through backward of the transformed layer returns: dXt = d/d((X - delta)/s) [M, K] and
+    dWs = d/d(W * s) [N, K] (identity through the quantizer).  With dc_n = sum_r lambda_r sum_m dY_r[m, n],
+        ddelta_k = -(1/s_k) sum_m dXt[m,k] + sum_n dc_n W[n,k]
+        ds_k     = -(1/s_k^2) sum_m dXt[m,k] (X[m,k] - delta_k) + sum_n dWs[n,k] W[n,k]
+    The dependence of the quantizer's range on s (through max and min of W * s) carries no gradient, like the
+    weights themselves under the clip-factor reading.  Returns (ddelta, ds, dc), fp64."""
+    X = bf16_to_f64(X_bf16)
+    dXt = bf16_to_f64(dXt_bf16)
+    Wd = np.asarray(W, dtype=np.float64)
+    dWs = np.asarray(dWs, dtype=np.float64)
+    s = np.asarray(s, dtype=np.float64)
+    delta = np.asarray(delta, dtype=np.float64)
+    dc = np.zeros(Wd.shape[0])
+    for dY, lam in zip(dYs_bf16, lambdas):
+        dc += float(lam) * bf16_to_f64(dY).sum(axis=0)
+    ddelta = -dXt.sum(axis=0) / s + dc @ Wd
+    ds = -(dXt * (X - delta[None, :])).sum(axis=0) / s ** 2 + (dWs * Wd).sum(axis=0)
+    return ddelta, ds, dc
+

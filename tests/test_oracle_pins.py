@@ -651,3 +651,69 @@ def test_clip_factor_grads_special_cases(oracle):
     dg2, db2, _, _ = oracle.clip_factor_grads(W.numpy(), bf16_bits(X), [bf16_bits(dY)], (2.5,), (8,))
     assert np.allclose(dg2, 2.5 * dg) and np.allclose(db2, 2.5 * db)
 
+
+# --------------------------------------------------------------------------
+# learnable affine re-parameterisation of a projection (section 3.1.2)
+# --------------------------------------------------------------------------
+def test_affine_reparameterisation_is_the_identity_without_quantization(oracle):
+    # ((X - delta) / s) (W * s)^T + b + W delta == X W^T + b when nothing is rounded: the two halves of the oracle
+    # composed in float64 (the bf16 rounding of the transformed input undone by feeding values it keeps exactly)
+    N, K, M = 12, 32, 6
+    g = torch.Generator().manual_seed(4)
+    W = torch.randn(N, K, generator=g) * 0.05
+    X = torch.randint(-8, 9, (M, K), generator=g).to(torch.bfloat16)          # small integers
+    s = torch.tensor([0.5, 1.0, 2.0, 4.0]).repeat(K // 4)                      # powers of two: exact divisions
+    delta = torch.randint(-4, 5, (K,), generator=g).float()                    # integers: exact differences
+    b = torch.randn(N, generator=g)
+    Ws, c = oracle.affine_weight(W.numpy(), s.numpy(), delta.numpy(), b.numpy())
+    Xt = bits_to_f64(oracle.affine_input(bf16_bits(X), s.numpy(), delta.numpy()))
+    assert np.array_equal(Ws, (W * s[None, :]).numpy())                        # the single fp32 product
+    want = X.double().numpy() @ W.double().numpy().T + b.double().numpy()[None, :]
+    got = Xt @ Ws.astype(np.float64).T + c[None, :]
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_affine_input_rounds_once(oracle):
+    X = torch.tensor([[1.0, 3.0, -2.5, 100.0]]).to(torch.bfloat16)
+    s = np.array([3.0, 7.0, 0.3, 1.0], np.float32)
+    d = np.array([0.1, -0.2, 0.0, 0.5], np.float32)
+    want = torch.from_numpy((X.double().numpy() - d.astype(np.float64)) / s.astype(np.float64)).to(torch.bfloat16)
+    assert np.array_equal(oracle.affine_input(bf16_bits(X), s, d), bf16_bits(want))
+    assert np.array_equal(oracle.affine_input(bf16_bits(X)), bf16_bits(X))
+
+
+def test_affine_bwd_vs_autograd(oracle):
+    # Library special case: torch float64 autograd of sum_r lambda_r <dY_r, ((X - delta)/s) What_r^T + b + W delta>
+    # with What_r = W*s + stopgrad(V_r - W*s) for arbitrary constants V_r (the straight-through estimator: the
+    # value of the quantized weight, the derivative of the unquantized one).
+    N, K, M, lam = 10, 16, 14, (0.2, 0.7, 1.0)
+    g = torch.Generator().manual_seed(8)
+    W = (torch.randn(N, K, generator=g) * 0.05).double()
+    X = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    dYs = [(torch.randn(M, N, generator=g) * 1e-2).to(torch.bfloat16) for _ in lam]
+    V = [W * 1.0 + torch.randn(N, K, generator=g).double() * 1e-3 for _ in lam]       # stand-ins for the quantized values
+    s = (torch.rand(K, generator=g) + 0.5).double().requires_grad_(True)
+    delta = (torch.randn(K, generator=g) * 0.1).double().requires_grad_(True)
+    b = torch.randn(N, generator=g).double()
+    Xt = (X.double() - delta[None, :]) / s[None, :]
+    Ws = W * s[None, :]
+    obj = 0.0
+    for l, dY, v in zip(lam, dYs, V):
+        What = Ws + (v * s.detach()[None, :] - Ws).detach()
+        obj = obj + l * (dY.double() * (Xt @ What.T + b[None, :] + (W @ delta)[None, :])).sum()
+    obj.backward()
+    # what the layer's own backward hands over: gradients with respect to Xt and to W*s, in float64 here
+    dXt = sum(l * dY.double() @ (v * s.detach()[None, :]) for l, dY, v in zip(lam, dYs, V))
+    dWs = sum(l * dY.double().T @ Xt.detach() for l, dY in zip(lam, dYs))
+    # (the oracle takes dXt as bf16: give it values bf16 keeps, and compare against autograd run on the same values)
+    dXt_b = dXt.to(torch.float32).to(torch.bfloat16)
+    corr = ((dXt_b.double() - dXt))                                                    # what the rounding changed
+    dd, ds, dc = oracle.affine_bwd(bf16_bits(X), bf16_bits(dXt_b), W.numpy(), dWs.numpy(), [bf16_bits(d) for d in dYs], lam,
+                                   s.detach().numpy(), delta.detach().numpy())
+    sd, dl = s.detach(), delta.detach()
+    want_dd = delta.grad.numpy() + (-(corr.sum(dim=0)) / sd).numpy()
+    want_ds = s.grad.numpy() + (-(corr * (X.double() - dl[None, :])).sum(dim=0) / sd ** 2).numpy()
+    assert np.allclose(dd, want_dd, rtol=1e-10, atol=1e-14)
+    assert np.allclose(ds, want_ds, rtol=1e-10, atol=1e-14)
+    assert np.allclose(dc, sum(l * d.double().sum(dim=0) for l, d in zip(lam, dYs)).numpy(), rtol=1e-12)
+
