@@ -178,6 +178,26 @@ def main():
                                                                          for L in layers) / len(layers)),
                 "avg_launch_ms": round(fwd_avg_ms, 4)}
 
+    # the same forward without the objective (outputs stored), outside the timed region, for comparison
+    plain_ms = []
+    for L in layers:
+        Y = [torch.empty(L.M, L.N, dtype=torch.bfloat16, device="cuda") for _ in rs]
+        ws = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD, L.M, L.N, L.K, len(rs)), dtype=torch.uint8, device="cuda")
+        mq.mq_linear_fwd_multi(L.X, L.Q, L.alpha, L.zero, rs, Y=Y, ws=ws)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            mq.mq_linear_fwd_multi(L.X, L.Q, L.alpha, L.zero, rs, Y=Y, ws=ws)
+        b.record()
+        torch.cuda.synchronize()
+        plain_ms.append(a.elapsed_time(b) / 5)
+        del Y, ws
+    plain_avg = sum(plain_ms) / len(plain_ms)
+    plain_tf = (flops_fwd / len(layers)) / (plain_avg * 1e-3) / 1e12
+    roofline["plain_forward"] = {"kernel": "mq::fwd_kernel<3, true, false, MB, false> (mq_linear_fwd_multi: Y_r stored, no objective)",
+                                 "avg_launch_ms": round(plain_avg, 4), "achieved": round(plain_tf, 2),
+                                 "frac": round(plain_tf / PEAK_BF16_TFLOPS, 4)}
+
     out = {
         "metric": "fused r=8/4/2 quant-linear TFLOP/s (fwd 6MNK + STE bwd 8MNK over the whole hot-path step)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -486,6 +486,7 @@ FUSED_L2_CASES = [
     (200, 136, 336, (4, 2), None, False, False),
     (1, 8, 16, (2,), None, False, False),
     (520, 392, 64, (6, 3), (-1, 0), False, False),
+    (72, 200, 96, (8, 4), (1, 0), False, False),        # every bit-width has a teacher: no target is read
 ]
 
 
@@ -501,11 +502,13 @@ def test_fwd_with_fused_l2_objective(mq, oracle, M, N, K, rs, teacher, mix, ep):
     Q, a, z, qo, ao, zo = _quantized(mq, oracle, W)
     clean = X.float() @ W.t()
     T = (clean + _randn(99, M, N) * clean.std()).to(torch.bfloat16)
+    if not mix and teacher is not None and min(teacher) >= 0:
+        T = None
     Yg = [torch.empty(M, N, dtype=torch.bfloat16, device="cuda") if i != 1 else None for i in range(nr)]
-    losses, dYs = mq.mq_linear_fwd_multi_l2(dev(X), Q, a, z, rs, dev(T), teacher, lam, mix, extra_precision=ep, Y=Yg)
+    losses, dYs = mq.mq_linear_fwd_multi_l2(dev(X), Q, a, z, rs, (dev(T) if T is not None else None), teacher, lam, mix, extra_precision=ep, Y=Yg)
     torch.cuda.synchronize()
     want_Y = [oracle.linear_fwd(bf16_bits(X), qo, ao, zo, r, ep=ep) for r in rs]
-    want_l, want_d = oracle.matquant_l2_loss([oracle.bf16_round(y) for y in want_Y], bf16_bits(T), teacher, lam, mix)
+    want_l, want_d = oracle.matquant_l2_loss([oracle.bf16_round(y) for y in want_Y], (bf16_bits(T) if T is not None else None), teacher, lam, mix)
     assert np.allclose(losses.cpu().numpy(), want_l, rtol=1e-3)
     for i in range(nr):
         assert rel_l2(dYs[i].float().cpu().numpy(), want_d[i]) <= TOL, (rs[i], "dY")
@@ -513,7 +516,7 @@ def test_fwd_with_fused_l2_objective(mq, oracle, M, N, K, rs, teacher, mix, ep):
             assert rel_l2(Yg[i].float().cpu().numpy(), want_Y[i]) <= TOL, (rs[i], "Y")
     # the same arithmetic as the two calls in sequence: identical gradients, sums in another order
     Ys2 = mq.mq_linear_fwd_multi(dev(X), Q, a, z, rs, extra_precision=ep)
-    l2, d2 = mq.mq_matquant_l2_loss(Ys2, dev(T), teacher, lam, mix)
+    l2, d2 = mq.mq_matquant_l2_loss(Ys2, (dev(T) if T is not None else None), teacher, lam, mix)
     torch.cuda.synchronize()
     for i in range(nr):
         assert torch.equal(dYs[i], d2[i]), rs[i]
@@ -521,7 +524,7 @@ def test_fwd_with_fused_l2_objective(mq, oracle, M, N, K, rs, teacher, mix, ep):
             assert torch.equal(Yg[i], Ys2[i]), rs[i]
     assert np.allclose(losses.cpu().numpy(), l2.cpu().numpy(), rtol=1e-5)
     # without any Y output
-    l3, d3 = mq.mq_linear_fwd_multi_l2(dev(X), Q, a, z, rs, dev(T), teacher, lam, mix, extra_precision=ep)
+    l3, d3 = mq.mq_linear_fwd_multi_l2(dev(X), Q, a, z, rs, (dev(T) if T is not None else None), teacher, lam, mix, extra_precision=ep)
     torch.cuda.synchronize()
     assert torch.equal(l3, losses) and all(torch.equal(u, v) for u, v in zip(d3, dYs))
 
