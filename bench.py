@@ -223,6 +223,7 @@ def main():
     if not args.no_gemv_sweep:
         out["mixnmatch_decode"] = mixnmatch_decode(torch, mq, synth)
         out["clip_factor_grads"] = clip_factor_grads(torch, mq, layers, rs, lambdas)
+        out["omniquant_step"] = omniquant_step(torch, mq, layers, rs, lambdas)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, synth, rs, lambdas)
     print(json.dumps(out))
@@ -407,6 +408,48 @@ def clip_factor_grads(torch, mq, layers, rs, lambdas, reps=5):
         res[L.name] = {"ms": round(ms, 4), "TFLOPs": round(2.0 * len(rs) * L.M * L.N * L.K / (ms * 1e-3) / 1e12, 1)}
         del ws
     res["note"] = "flops = 2 MNK per bit-width (the three dY_r^T X contractions); the row reductions are HBM-bound"
+    return res
+
+
+def omniquant_step(torch, mq, layers, rs, lambdas, reps=5):
+    """One calibration step of the OmniQuant base algorithm under the MatQuant objective on each linear of the
+    workload: affine re-parameterisation of weight and input, quantizer with clip factors, forward for r = 8/4/2
+    with bias and the L2 objective, straight-through backward, gradients of gamma, beta, delta, s."""
+    res = {}
+    for L in layers:
+        g = torch.Generator().manual_seed(17)
+        gamma = (torch.rand(L.N, generator=g) * 0.2 + 0.8).cuda()
+        beta = (torch.rand(L.N, generator=g) * 0.2 + 0.8).cuda()
+        s = (torch.rand(L.K, generator=g) + 0.5).cuda()
+        delta = (torch.randn(L.K, generator=g) * 0.05).cuda()
+        ws_f = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD_L2, L.M, L.N, L.K, len(rs)), dtype=torch.uint8, device="cuda")
+        ws_b = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, L.M, L.N, L.K, len(rs)), dtype=torch.uint8, device="cuda")
+        ws_c = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD_CLIP, L.M, L.N, L.K, len(rs)), dtype=torch.uint8, device="cuda")
+        ws_a = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_AFFINE_BWD, L.M, L.N, L.K, len(rs)), dtype=torch.uint8, device="cuda")
+        Xt = torch.empty_like(L.X)
+
+        def one():
+            Ws, c = mq.mq_affine_weight(L.W, s, delta, None)
+            mq.mq_affine_input(L.X, s, delta, Xt=Xt)
+            Q, a, z = mq.mq_quantize_int8(Ws, gamma, beta, Q=L.Q, alpha=L.alpha, zero=L.zero)
+            mq.mq_linear_fwd_multi_l2(Xt, Q, a, z, rs, L.T, None, lambdas, dY=L.dY, losses=L.losses, ws=ws_f, bias=c)
+            dXt, dWs = mq.mq_linear_bwd(Xt, Q, a, z, L.dY, None, rs, dX=L.dX, dW=L.dW, ws=ws_b)
+            mq.mq_linear_bwd_clip(Ws, Xt, Q, a, z, L.dY, None, rs, gamma, beta, ws=ws_c)
+            mq.mq_affine_bwd(L.X, dXt, L.W, dWs, L.dY, None, s, delta, ws=ws_a)
+
+        one()
+        a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a_.record()
+        for _ in range(reps):
+            one()
+        b_.record()
+        torch.cuda.synchronize()
+        ms = a_.elapsed_time(b_) / reps
+        flops = (6.0 + 8.0 + 6.0) * L.M * L.N * L.K      # forward, backward, one more contraction per bit-width for the clip factors
+        res[L.name] = {"ms": round(ms, 4), "TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1)}
+        del ws_f, ws_b, ws_c, ws_a, Xt
+    res["note"] = ("mq_affine_weight + mq_affine_input + mq_quantize_int8(gamma, beta) + mq_linear_fwd_multi_l2(bias) + mq_linear_bwd "
+                   "+ mq_linear_bwd_clip + mq_affine_bwd; flops = 20 MNK (forward 6, backward 8, clip-factor contractions 6)")
     return res
 
 

@@ -57,7 +57,7 @@ enum {
 };
 
 enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1, MQ_OP_FFN_DECODE = 2, MQ_OP_L2_LOSS = 3, MQ_OP_LINEAR_FWD_L2 = 4,
-       MQ_OP_LINEAR_BWD_CLIP = 5 };
+       MQ_OP_LINEAR_BWD_CLIP = 5, MQ_OP_AFFINE_BWD = 6 };
 
 /*
  * Extra-precision overflow set (errata section: weights whose rounded r-bit
@@ -233,6 +233,8 @@ mq_status mq_matquant_l2_loss(const uint16_t *const *Y, const uint16_t *target, 
  *   X, Q, alpha, zero, M, N, K, rs, nr   as for mq_linear_fwd_multi
  *   target, teacher, lambda, dY, losses  as for mq_matquant_l2_loss (indices in the order of rs)
  *   flags    MQ_FLAG_EXTRA_PRECISION and / or MQ_FLAG_LOSS_MIX
+ *   bias     [N] fp32 or NULL: added to every output before it is rounded to bf16 (the bias of the
+ *            layer; with the affine re-parameterisation of section 3.1.2 the vector c of mq_affine_weight)
  *   Y        NULL, or a host array of nr device pointers of which any may be NULL: an output
  *            whose pointer is NULL is not stored
  *   ws       workspace of at least mq_workspace_bytes(MQ_OP_LINEAR_FWD_L2, M, N, K, nr)
@@ -240,7 +242,7 @@ mq_status mq_matquant_l2_loss(const uint16_t *const *Y, const uint16_t *target, 
  */
 mq_status mq_linear_fwd_multi_l2(const uint16_t *X, const uint8_t *Q, const float *alpha,
                                  const float *zero, int64_t M, int64_t N, int64_t K,
-                                 const int *rs, int nr, uint32_t flags,
+                                 const int *rs, int nr, uint32_t flags, const float *bias,
                                  const uint16_t *target, const int *teacher, const float *lambda,
                                  uint16_t *const *Y, uint16_t *const *dY, float *losses,
                                  void *ws, size_t ws_bytes, void *hip_stream);
@@ -273,6 +275,40 @@ mq_status mq_linear_bwd_clip(const float *W, int64_t ldw, const uint16_t *X, con
                              int64_t M, int64_t N, int64_t K, const int *rs, int nr, uint32_t flags,
                              float *dgamma, float *dbeta, float *dalpha, float *dzero,
                              void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Learnable affine re-parameterisation of a projection (section 3.1.2, the second OmniQuant equation):
+ *     X W + b  ->  ((X - delta) / s) Q(W * s) + b + delta W
+ * with W stored [N, K] (output channels x input features), s and delta per input feature.  Three
+ * bandwidth-bound operations around the quantized layer; the layer itself is mq_quantize_int8 on Ws,
+ * mq_linear_fwd_multi_l2 on Xt with bias c, mq_linear_bwd (and mq_linear_bwd_clip) on Xt.
+ *
+ * mq_affine_weight:  Ws[n,k] = W[n,k] * s[k] (one fp32 product: the quantizer's input, bit for bit)
+ *                    c[n]    = b[n] + sum_k W[n,k] delta[k]
+ *   W [N, ldw] fp32;  s, delta [K] fp32 or NULL (= 1, = 0);  b [N] fp32 or NULL (= 0)
+ *   Ws [N, K] fp32 out or NULL;  c [N] fp32 out or NULL (at least one of the two)
+ *   K and ldw multiples of 4.
+ * mq_affine_input:   Xt[m,k] = bf16((X[m,k] - delta[k]) / s[k]);  X, Xt [M, K] bf16, K a multiple of 8
+ * mq_affine_bwd:     with dXt = d objective / d Xt (the dX of mq_linear_bwd), dWs = d objective / d Ws
+ *                    (its dW: the straight-through estimator is the identity through the quantizer) and
+ *                    dc[n] = sum_r lambda_r sum_m dY_r[m,n]:
+ *                      ddelta[k] = -(1/s[k]) sum_m dXt[m,k] + sum_n dc[n] W[n,k]
+ *                      ds[k]     = -(1/s[k]^2) sum_m dXt[m,k] (X[m,k] - delta[k]) + sum_n dWs[n,k] W[n,k]
+ *                    (the range of the quantizer follows s through max and min of Ws without a gradient,
+ *                    as in mq_linear_bwd_clip)
+ *   X, dXt [M, K] bf16;  W [N, ldw] fp32;  dWs [N, K] fp32;  dY, lambda, nr as for mq_linear_bwd
+ *   ddelta, ds [K] fp32 out, dc [N] fp32 out; any may be NULL (not all)
+ *   ws       workspace of at least mq_workspace_bytes(MQ_OP_AFFINE_BWD, M, N, K, nr)
+ *   M, N, K >= 1; N, K, ldw multiples of 4.
+ */
+mq_status mq_affine_weight(const float *W, int64_t N, int64_t K, int64_t ldw, const float *s,
+                           const float *delta, const float *b, float *Ws, float *c, void *hip_stream);
+mq_status mq_affine_input(const uint16_t *X, int64_t M, int64_t K, const float *s, const float *delta,
+                          uint16_t *Xt, void *hip_stream);
+mq_status mq_affine_bwd(const uint16_t *X, const uint16_t *dXt, const float *W, int64_t ldw,
+                        const float *dWs, const uint16_t *const *dY, const float *lambda, int nr,
+                        int64_t M, int64_t N, int64_t K, const float *s, const float *delta,
+                        float *ddelta, float *ds, float *dc, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Layer-wise Mix'n'Match on the decode path (section 4.3 "Mix'n'Match", section 5.1.3 and appendix B:

@@ -24,13 +24,15 @@ MQ_OP_FFN_DECODE = 2
 MQ_OP_L2_LOSS = 3
 MQ_OP_LINEAR_FWD_L2 = 4
 MQ_OP_LINEAR_BWD_CLIP = 5
+MQ_OP_AFFINE_BWD = 6
 MQ_FLAG_LOSS_MIX = 64
 MQ_FLAG_FFN_SILU = 16
 MQ_FLAG_FFN_RESIDUAL = 32
 
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
            "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string", "mq_probe_mfma", "mq_probe_read",
-           "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2", "mq_linear_bwd_clip"]
+           "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2", "mq_linear_bwd_clip",
+           "mq_affine_weight", "mq_affine_input", "mq_affine_bwd"]
 
 
 class MqError(RuntimeError):
@@ -72,7 +74,11 @@ def _load() -> ctypes.CDLL:
     lib.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
     lib.mq_matquant_l2_loss.argtypes = [ctypes.POINTER(vp), vp, ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_float), i64,
                                         i64, ci, u32, ctypes.POINTER(vp), vp, vp, sz, vp]
-    lib.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp,
+    lib.mq_affine_weight.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
+    lib.mq_affine_input.argtypes = [vp, i64, i64, vp, vp, vp, vp]
+    lib.mq_affine_bwd.argtypes = [vp, vp, vp, i64, vp, ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float), ci, i64, i64, i64,
+                                  vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp,
                                            ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_float), ctypes.POINTER(vp),
                                            ctypes.POINTER(vp), vp, vp, sz, vp]
     lib.mq_linear_bwd_clip.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float),
@@ -342,7 +348,7 @@ def mq_matquant_l2_loss(Y, target=None, teacher=None, lambdas=None, mix: bool = 
 
 
 def mq_linear_fwd_multi_l2(X, Q, alpha, zero, rs, target=None, teacher=None, lambdas=None, mix: bool = False,
-                           extra_precision: bool = False, Y=None, dY=None, losses=None, ws=None):
+                           extra_precision: bool = False, Y=None, dY=None, losses=None, ws=None, bias=None):
     """Forward for every r in rs with the L2 objective evaluated in the same pass: returns (losses fp32 [nr] on the
     GPU, list of dY bf16 [M, N]).  Y, if given, is a list of nr bf16 [M, N] tensors or None entries; only the tensors
     present are written."""
@@ -366,7 +372,7 @@ def mq_linear_fwd_multi_l2(X, Q, alpha, zero, rs, target=None, teacher=None, lam
         c_Y = (ctypes.c_void_p * nr)(*[_ptr(t, torch.bfloat16) if t is not None else None for t in Y])
     st = _lib.mq_linear_fwd_multi_l2(_ptr(X, torch.bfloat16), _ptr(Q, torch.uint8), _ptr(alpha, torch.float32),
                                      _ptr(zero, torch.float32), M, N, K, _int_array(rs), nr, flags,
-                                     _ptr(target, torch.bfloat16), c_teacher, c_lambda, c_Y,
+                                     _ptr(bias, torch.float32), _ptr(target, torch.bfloat16), c_teacher, c_lambda, c_Y,
                                      _ptr_array(dY, torch.bfloat16), _ptr(losses, torch.float32), _ptr(ws),
                                      ws.numel(), _stream())
     _check(st, "mq_linear_fwd_multi_l2")
@@ -399,4 +405,49 @@ def mq_linear_bwd_clip(W, X, Q, alpha, zero, dY, lambdas, rs, gamma=None, beta=N
                                  _ptr(out[3]) if want_dalpha_dzero else None, _ptr(ws), ws.numel(), _stream())
     _check(st, "mq_linear_bwd_clip")
     return tuple(out)
+
+
+def mq_affine_weight(W, s=None, delta=None, b=None, want_Ws: bool = True, want_c: bool = True):
+    """Weight side of the affine re-parameterisation: returns (Ws fp32 [N, K] or None, c fp32 [N] or None)."""
+    N, K = W.shape
+    if W.dtype != torch.float32 or not W.is_cuda or W.stride(1) != 1:
+        raise ValueError("W must be a float32 GPU tensor with unit column stride")
+    Ws = torch.empty(N, K, dtype=torch.float32, device=W.device) if want_Ws else None
+    c = torch.empty(N, dtype=torch.float32, device=W.device) if want_c else None
+    st = _lib.mq_affine_weight(ctypes.c_void_p(W.data_ptr()), N, K, W.stride(0), _ptr(s, torch.float32),
+                               _ptr(delta, torch.float32), _ptr(b, torch.float32), _ptr(Ws), _ptr(c), _stream())
+    _check(st, "mq_affine_weight")
+    return Ws, c
+
+
+def mq_affine_input(X, s=None, delta=None, Xt=None):
+    """Xt = bf16((X - delta) / s) per input feature."""
+    M, K = X.shape
+    if Xt is None:
+        Xt = torch.empty_like(X)
+    st = _lib.mq_affine_input(_ptr(X, torch.bfloat16), M, K, _ptr(s, torch.float32), _ptr(delta, torch.float32),
+                              _ptr(Xt, torch.bfloat16), _stream())
+    _check(st, "mq_affine_input")
+    return Xt
+
+
+def mq_affine_bwd(X, dXt, W, dWs, dY, lambdas, s=None, delta=None, ws=None):
+    """Gradients with respect to delta and s (and the bias gradient dc): returns (ddelta [K], ds [K], dc [N]) fp32."""
+    M, K = X.shape
+    N = W.shape[0]
+    nr = len(dY)
+    out = (torch.empty(K, dtype=torch.float32, device=X.device), torch.empty(K, dtype=torch.float32, device=X.device),
+           torch.empty(N, dtype=torch.float32, device=X.device))
+    need = mq_workspace_bytes(MQ_OP_AFFINE_BWD, M, N, K, max(1, min(nr, 3)))
+    if ws is None:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=X.device)
+    lam = (ctypes.c_float * nr)(*lambdas) if lambdas is not None else None
+    if W.dtype != torch.float32 or W.stride(1) != 1:
+        raise ValueError("W must be float32 with unit column stride")
+    st = _lib.mq_affine_bwd(_ptr(X, torch.bfloat16), _ptr(dXt, torch.bfloat16), ctypes.c_void_p(W.data_ptr()), W.stride(0),
+                            _ptr(dWs, torch.float32), _ptr_array(dY, torch.bfloat16), lam, nr, M, N, K,
+                            _ptr(s, torch.float32), _ptr(delta, torch.float32), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]),
+                            _ptr(ws), ws.numel(), _stream())
+    _check(st, "mq_affine_bwd")
+    return out
 

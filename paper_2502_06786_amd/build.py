@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmq.so")
-SOURCES = ["mq_quantize.hip", "mq_slice.hip", "mq_gemv.hip", "mq_gemv_quad.hip", "mq_linear.hip", "mq_ffn.hip", "mq_loss.hip", "mq_clip.hip", "mq_probe.hip"]
+SOURCES = ["mq_quantize.hip", "mq_slice.hip", "mq_gemv.hip", "mq_gemv_quad.hip", "mq_linear.hip", "mq_ffn.hip", "mq_loss.hip", "mq_clip.hip", "mq_affine.hip", "mq_probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -48,6 +48,8 @@ size_t ffn_workspace_bytes(int64_t B, int64_t F, int64_t d);
 size_t loss_workspace_bytes(int64_t M, int64_t N);
 // workspace of mq_linear_bwd_clip (mq_clip.hip)
 size_t clip_workspace_bytes(int64_t M, int64_t N, int64_t K);
+// workspace of mq_affine_bwd (mq_affine.hip)
+size_t affine_workspace_bytes(int64_t M, int64_t N, int64_t K);
 // losses[i] = inv_mn * sum over the workgroups of partial[workgroup][i] (rows of 4 floats), in a
 // fixed order; one small launch on `st` (mq_loss.hip)
 mq_status launch_loss_finish(const float *partial, int64_t blocks, int nr, float inv_mn, float *losses,

@@ -152,6 +152,7 @@ struct FwdArgs {
     float coef[3];   // lambda_i * 2 / (M N)
     int mix;
     float *partial;  // [workgroup][4] sums of squared differences
+    const float *bias;  // [N] added to every output before it is rounded, or null
 };
 
 constexpr int FWD_BN = 128;
@@ -377,23 +378,27 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
         const int m = m0 + j * 32 + l32;
         rs[j] = m < a.M ? a.rowsum[m] : 0.f;
     }
-    f32x4 alv[4], zev[4];
+    f32x4 alv[4], zev[4], bv[LOSS ? 4 : 1];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const int nloc = wave * 32 + 8 * g + 4 * h;
         alv[g] = f32x4{0.f, 0.f, 0.f, 0.f};
         zev[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (LOSS) bv[g] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (n0 + nloc < a.N) {
             alv[g] = *reinterpret_cast<const f32x4 *>(a.alpha + n0 + nloc);
             zev[g] = *reinterpret_cast<const f32x4 *>(a.zero + n0 + nloc);
+            if constexpr (LOSS)
+                if (a.bias) bv[g] = *reinterpret_cast<const f32x4 *>(a.bias + n0 + nloc);
         }
     }
     // LOSS: the lane's chunks of the target are requested now, behind the parameter loads, and
-    // arrive while the accumulators are converted and staged.  With the largest accumulator set
-    // there are registers for half of them only; the other half is requested after the staging and
-    // arrives while the first half is consumed.
+    // arrive while the accumulators are converted and staged.  With the largest accumulator sets
+    // there are registers for some of them only (the counts below are the largest that compile
+    // without spills); the others are requested after the staging and arrive while the first ones
+    // are consumed.
     constexpr int CHUNKS = BM * 16 / 256;
-    constexpr int EARLY = NR * MB > 12 ? 3 : CHUNKS;
+    constexpr int EARLY = NR * MB > 12 ? 2 : (NR * MB == 12 ? CHUNKS / 2 : CHUNKS);
     u32x4 tpre[LOSS ? CHUNKS : 1];
     auto request_target = [&](int it) {
         const int c = it * 256 + threadIdx.x;
@@ -420,6 +425,10 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
                 float y[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) y[e] = al[e] * (mult * acc[i][j][4 * g + e] - (bias + ze[e]) * rs[j]);
+                if constexpr (LOSS) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) y[e] += bv[g][e];
+                }
                 const u32x2 o = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
                 *reinterpret_cast<u32x2 *>(smem + i * OT + (j * 32 + l32) * OS + nloc * 2) = o;
             }
@@ -1249,6 +1258,7 @@ extern "C" size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, in
     if (op == MQ_OP_FFN_DECODE) return ffn_workspace_bytes(M, N, K);
     if (op == MQ_OP_L2_LOSS) return loss_workspace_bytes(M, N);
     if (op == MQ_OP_LINEAR_BWD_CLIP) return clip_workspace_bytes(M, N, K);
+    if (op == MQ_OP_AFFINE_BWD) return affine_workspace_bytes(M, N, K);
     return 0;
 }
 
@@ -1262,6 +1272,7 @@ struct FwdLoss {
     uint16_t *const *dY;
     float *losses;
     uint32_t mix;
+    const float *bias;
 };
 
 static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero, int64_t M,
@@ -1296,6 +1307,7 @@ static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha
             if (!aligned16(loss->dY[i])) return MQ_ERR_ALIGN;
         }
         if (loss->target && !aligned16(loss->target)) return MQ_ERR_ALIGN;
+        if (loss->bias && !aligned16(loss->bias)) return MQ_ERR_ALIGN;
     }
     if (!aligned16(X) || !aligned16(Q) || !aligned16(alpha) || !aligned16(zero)) return MQ_ERR_ALIGN;
     const int op = loss ? MQ_OP_LINEAR_FWD_L2 : MQ_OP_LINEAR_FWD;
@@ -1333,6 +1345,7 @@ static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha
     const double mn = (double)M * (double)N;
     if (loss) {
         a.T = loss->target;
+        a.bias = loss->bias;
         a.mix = loss->mix ? 1 : 0;
         a.partial = reinterpret_cast<float *>(static_cast<uint8_t *>(ws) + align256((size_t)M * 4));
         for (int i = 0; i < nr; ++i) {
@@ -1372,10 +1385,11 @@ extern "C" mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, co
 
 extern "C" mq_status mq_linear_fwd_multi_l2(const uint16_t *X, const uint8_t *Q, const float *alpha,
                                             const float *zero, int64_t M, int64_t N, int64_t K, const int *rs,
-                                            int nr, uint32_t flags, const uint16_t *target, const int *teacher,
-                                            const float *lambda, uint16_t *const *Y, uint16_t *const *dY,
-                                            float *losses, void *ws, size_t ws_bytes, void *hip_stream) {
-    const mq::FwdLoss loss{target, teacher, lambda, dY, losses, flags & MQ_FLAG_LOSS_MIX};
+                                            int nr, uint32_t flags, const float *bias, const uint16_t *target,
+                                            const int *teacher, const float *lambda, uint16_t *const *Y,
+                                            uint16_t *const *dY, float *losses, void *ws, size_t ws_bytes,
+                                            void *hip_stream) {
+    const mq::FwdLoss loss{target, teacher, lambda, dY, losses, flags & MQ_FLAG_LOSS_MIX, bias};
     return mq::fwd_run(X, Q, alpha, zero, M, N, K, rs, nr, flags, Y, &loss, ws, ws_bytes, hip_stream);
 }
 

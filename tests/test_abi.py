@@ -38,8 +38,11 @@ def lib():
     lib_.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
     lib_.mq_matquant_l2_loss.argtypes = [vp, vp, ctypes.POINTER(ci), vp, i64, i64, ci, u32, vp, vp, vp, sz, vp]
-    lib_.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp,
+    lib_.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp,
                                             ctypes.POINTER(ci), vp, vp, vp, vp, vp, sz, vp]
+    lib_.mq_affine_weight.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
+    lib_.mq_affine_input.argtypes = [vp, i64, i64, vp, vp, vp, vp]
+    lib_.mq_affine_bwd.argtypes = [vp, vp, vp, i64, vp, vp, vp, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib_.mq_linear_bwd_clip.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32,
                                         vp, vp, vp, vp, vp, sz, vp]
     lib_.mq_ffn_mixnmatch.argtypes = [vp, vp, ci, i64, i64, i64, u32, vp, vp, sz, vp]
@@ -196,12 +199,12 @@ def test_fwd_l2_argument_checks(lib):
     ci = ctypes.c_int
     rs = (ci * 3)(8, 4, 2)
     p = ctypes.c_void_p(4096)    # never dereferenced: every call below returns before the first launch
-    assert f(p, p, p, p, 16, 64, 64, (ci * 2)(4, 4), 2, 0, p, None, None, None, None, None, None, 0, None) == BITS
-    assert f(p, p, p, p, 16, 64, 40, rs, 3, 0, p, None, None, None, None, None, None, 0, None) == ALIGN
-    assert f(p, p, p, p, 16, 64, 64, rs, 3, 0, p, (ci * 3)(-1, 1, 0), None, None, None, None, None, 0, None) == SHAPE
-    assert f(p, p, p, p, 16, 64, 64, rs, 3, 0, p, (ci * 3)(-1, 0, 3), None, None, None, None, None, 0, None) == SHAPE
-    assert f(p, p, p, p, 0, 64, 64, rs, 3, 0, None, None, None, None, None, None, None, 0, None) == OK
-    assert f(p, p, p, p, 16, 64, 64, rs, 3, 0, p, None, None, None, None, None, None, 0, None) == NULL   # no dY
+    assert f(p, p, p, p, 16, 64, 64, (ci * 2)(4, 4), 2, 0, None, p, None, None, None, None, None, None, 0, None) == BITS
+    assert f(p, p, p, p, 16, 64, 40, rs, 3, 0, None, p, None, None, None, None, None, None, 0, None) == ALIGN
+    assert f(p, p, p, p, 16, 64, 64, rs, 3, 0, None, p, (ci * 3)(-1, 1, 0), None, None, None, None, None, 0, None) == SHAPE
+    assert f(p, p, p, p, 16, 64, 64, rs, 3, 0, None, p, (ci * 3)(-1, 0, 3), None, None, None, None, None, 0, None) == SHAPE
+    assert f(p, p, p, p, 0, 64, 64, rs, 3, 0, None, None, None, None, None, None, None, None, 0, None) == OK
+    assert f(p, p, p, p, 16, 64, 64, rs, 3, 0, None, p, None, None, None, None, None, None, 0, None) == NULL   # no dY
     # the partial sums of the objective sit behind the row sums of X
     assert lib.mq_workspace_bytes(4, 4096, 9216, 2304, 3) >= lib.mq_workspace_bytes(0, 4096, 9216, 2304, 3) + 32 * 72 * 16
 
@@ -224,4 +227,20 @@ def test_bwd_clip_argument_checks(lib):
     assert call() == NULL                                         # dY missing
     # the per-bit-width contraction goes into a scratch matrix next to the backward's own workspace
     assert lib.mq_workspace_bytes(5, 4096, 9216, 2304, 3) >= 9216 * 2304 * 4 + lib.mq_workspace_bytes(1, 4096, 9216, 2304, 1)
+
+
+def test_affine_argument_checks(lib):
+    p = ctypes.c_void_p(4096)    # never dereferenced: every call below returns before the first launch
+    assert lib.mq_affine_weight(p, 8, 64, 32, None, None, None, p, p, None) == SHAPE        # ldw < K
+    assert lib.mq_affine_weight(p, 8, 66, 66, None, None, None, p, p, None) == ALIGN
+    assert lib.mq_affine_weight(p, 0, 64, 64, None, None, None, None, None, None) == OK
+    assert lib.mq_affine_weight(p, 8, 64, 64, None, None, None, None, None, None) == NULL   # nothing to write
+    assert lib.mq_affine_input(p, 4, 60, None, None, p, None) == ALIGN
+    assert lib.mq_affine_input(p, 0, 64, None, None, p, None) == OK
+    assert lib.mq_affine_input(None, 4, 64, None, None, p, None) == NULL
+    f = lib.mq_affine_bwd
+    assert f(p, p, p, 64, p, None, None, 4, 8, 16, 64, None, None, p, p, p, None, 0, None) == BITS
+    assert f(p, p, p, 64, p, None, None, 3, 8, 18, 64, None, None, p, p, p, None, 0, None) == ALIGN
+    assert f(p, p, p, 64, p, None, None, 3, 8, 16, 64, None, None, p, p, p, None, 0, None) == NULL   # dY missing
+    assert lib.mq_workspace_bytes(6, 4096, 9216, 2304, 3) > 0
 

@@ -567,6 +567,77 @@ def test_bwd_clip_factor_grads(mq, oracle, M, N, K, rs, clip, ep):
         assert got[0][1].item() == 0.0 and got[1][1].item() == 0.0 and want[0][1] == 0.0
 
 
+# --------------------------------------------------------------------------
+# learnable affine re-parameterisation of a projection
+# --------------------------------------------------------------------------
+def _affine_case(seed, M, N, K):
+    g = torch.Generator().manual_seed(seed)
+    W = torch.randn(N, K, generator=g) * 0.02
+    X = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    s = torch.rand(K, generator=g) * 1.5 + 0.5
+    delta = torch.randn(K, generator=g) * 0.1
+    b = torch.randn(N, generator=g) * 0.05
+    return W, X, s, delta, b
+
+
+@pytest.mark.parametrize("M,N,K", [(50, 48, 96), (520, 400, 1040), (1, 4, 8), (3, 7, 4100)])
+def test_affine_weight_and_input(mq, oracle, M, N, K):
+    W, X, s, delta, b = _affine_case(M + N + K, M, N, K)
+    if K % 8 == 0:
+        Xt = mq.mq_affine_input(dev(X), dev(s), dev(delta))
+        want = oracle.affine_input(bf16_bits(X), s.numpy(), delta.numpy())
+        got = bf16_bits(Xt.cpu())
+        assert np.mean(got != want) <= 2e-3          # fp32 then bf16 against fp64 then bf16: rare double roundings
+        assert rel_l2(Xt.float().cpu().numpy(), oracle.bf16_to_f64(want)) <= 1e-3
+        assert torch.equal(mq.mq_affine_input(dev(X)), dev(X))
+    Ws, c = mq.mq_affine_weight(dev(W), dev(s), dev(delta), dev(b))
+    want_Ws, want_c = oracle.affine_weight(W.numpy(), s.numpy(), delta.numpy(), b.numpy())
+    assert np.array_equal(Ws.cpu().numpy(), want_Ws)                     # the quantizer's input: bit for bit
+    assert rel_l2(c.cpu().numpy().astype(np.float64), want_c) <= 1e-5    # fp32 products, fp64 across the workgroup
+    wide = dev(torch.cat([W, W], dim=1))[:, :K]                          # a row stride
+    Ws2, c2 = mq.mq_affine_weight(wide, dev(s), None, None)
+    assert torch.equal(Ws2, Ws) and float(c2.abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("M,N,K", [(72, 48, 96), (264, 272, 208)])
+def test_affine_layer_forward(mq, oracle, M, N, K):
+    # the whole transformed layer: quantize W * s, forward on (X - delta) / s with the bias b + W delta
+    rs = (8, 4, 2)
+    W, X, s, delta, b = _affine_case(M * 3 + N, M, N, K)
+    Ws, c = mq.mq_affine_weight(dev(W), dev(s), dev(delta), dev(b))
+    Xt = mq.mq_affine_input(dev(X), dev(s), dev(delta))
+    Q, a, z = mq.mq_quantize_int8(Ws)
+    Ws_o, c_o = oracle.affine_weight(W.numpy(), s.numpy(), delta.numpy(), b.numpy())
+    Xt_o = oracle.affine_input(bf16_bits(X), s.numpy(), delta.numpy())
+    qo, ao, zo = oracle.quantize_int8(Ws_o)
+    assert np.array_equal(Q.cpu().numpy(), qo)
+    Y = [torch.empty(M, N, dtype=torch.bfloat16, device="cuda") for _ in rs]
+    T = torch.zeros(M, N, dtype=torch.bfloat16, device="cuda")
+    mq.mq_linear_fwd_multi_l2(Xt, Q, a, z, rs, T, Y=Y, bias=c)
+    torch.cuda.synchronize()
+    for r, y in zip(rs, Y):
+        want = oracle.linear_fwd(Xt_o, qo, ao, zo, r) + c_o[None, :]
+        assert rel_l2(y.float().cpu().numpy(), want) <= TOL, r
+    # at 8 bits the transformed layer reproduces X W^T + b up to the quantization error
+    plain = X.double().numpy() @ W.double().numpy().T + b.double().numpy()[None, :]
+    assert rel_l2(Y[0].float().cpu().numpy(), plain) <= 3e-2
+
+
+@pytest.mark.parametrize("M,N,K,nr", [(72, 48, 96, 3), (520, 400, 1040, 2), (5, 4, 8, 1), (4096, 256, 512, 3)])
+def test_affine_bwd(mq, oracle, M, N, K, nr):
+    W, X, s, delta, _ = _affine_case(M + 2 * N + K, M, N, K)
+    lam = (0.2, 0.7, 1.0)[:nr]
+    dXt = (_randn(41, M, K) * 1e-2).to(torch.bfloat16)
+    dWs = _randn(42, N, K) * 1e-2
+    dYs = [(_randn(43 + i, M, N) * 1e-2).to(torch.bfloat16) for i in range(nr)]
+    dd, ds, dc = mq.mq_affine_bwd(dev(X), dev(dXt), dev(W), dev(dWs), [dev(d) for d in dYs], lam, dev(s), dev(delta))
+    torch.cuda.synchronize()
+    want = oracle.affine_bwd(bf16_bits(X), bf16_bits(dXt), W.numpy(), dWs.numpy(), [bf16_bits(d) for d in dYs], lam,
+                             s.numpy(), delta.numpy())
+    for name, mine, ref in zip(("ddelta", "ds", "dc"), (dd, ds, dc), want):
+        assert rel_l2(mine.cpu().numpy().astype(np.float64), ref) <= 1e-4, name   # fp32 partial sums, fp64 across them
+
+
 def test_measurement_probes_run(mq):
     ops = torch.randn(32768, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
     sink = torch.zeros(65536, dtype=torch.float32, device="cuda")
