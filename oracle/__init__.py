@@ -419,3 +419,39 @@ def affine_bwd(X_bf16, dXt_bf16, W, dWs, dYs_bf16, lambdas, s, delta):
     ds = -(dXt * (X - delta[None, :])).sum(axis=0) / s ** 2 + (dWs * Wd).sum(axis=0)
     return ddelta, ds, dc
 
+
+def _gate_act(g, silu: bool):
+    if silu:
+        with np.errstate(over="ignore"):
+            return g / (1.0 + np.exp(-g))
+    return 0.5 * g * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (g + 0.044715 * g ** 3)))
+
+
+def gated_unit(GU_bf16, silu: bool = False):
+    """The gate of the feed-forward block on the training path: GU [M, 2F] bf16 holds the outputs of the stacked
+    gate / up projection with the columns of a pair next to each other (gate first, as the rows of the plane in
+    ffn_mixnmatch); a[m, f] = act(g) * u in fp64, rounded once to bf16 (bit patterns)."""
+    GU = bf16_to_f64(GU_bf16)
+    return bf16_round(_gate_act(GU[:, 0::2], silu) * GU[:, 1::2])
+
+
+def gated_unit_bwd(GU_bf16, dA_bf16, silu: bool = False):
+    """Its backward: dg = dA u act'(g), du = dA act(g), interleaved like GU; fp64.
+    GELU (tanh form): act'(g) = (1 + th)/2 + g (1 - th^2) c (1 + 3 * 0.044715 g^2) / 2 with th = tanh(c (g + 0.044715 g^3)),
+    c = sqrt(2 / pi);  SiLU: act'(g) = sig (1 + g (1 - sig))."""
+    GU = bf16_to_f64(GU_bf16)
+    dA = bf16_to_f64(dA_bf16)
+    g, u = GU[:, 0::2], GU[:, 1::2]
+    if silu:
+        with np.errstate(over="ignore"):
+            sig = 1.0 / (1.0 + np.exp(-g))
+        dact = sig * (1.0 + g * (1.0 - sig))
+    else:
+        c = np.sqrt(2.0 / np.pi)
+        th = np.tanh(c * (g + 0.044715 * g ** 3))
+        dact = 0.5 * (1.0 + th) + 0.5 * g * (1.0 - th ** 2) * c * (1.0 + 3 * 0.044715 * g ** 2)
+    out = np.empty_like(GU)
+    out[:, 0::2] = dA * u * dact
+    out[:, 1::2] = dA * _gate_act(g, silu)
+    return out
+
