@@ -224,6 +224,7 @@ def main():
         out["mixnmatch_decode"] = mixnmatch_decode(torch, mq, synth)
         out["clip_factor_grads"] = clip_factor_grads(torch, mq, layers, rs, lambdas)
         out["omniquant_step"] = omniquant_step(torch, mq, layers, rs, lambdas)
+        out["ffn_block_train"] = ffn_block_train(torch, mq, layers, rs)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, synth, rs, lambdas)
     print(json.dumps(out))
@@ -451,6 +452,60 @@ def omniquant_step(torch, mq, layers, rs, lambdas, reps=5):
     res["note"] = ("mq_affine_weight + mq_affine_input + mq_quantize_int8(gamma, beta) + mq_linear_fwd_multi_l2(bias) + mq_linear_bwd "
                    "+ mq_linear_bwd_clip + mq_affine_bwd; flops = 20 MNK (forward 6, backward 8, clip-factor contractions 6)")
     return res
+
+
+def ffn_block_train(torch, mq, layers, rs, reps=3):
+    """Forward and straight-through backward of the whole gated feed-forward block of the workload for r = 8/4/2,
+    composed from the library's calls: one fused forward over the stacked gate/up weight (rows interleaved), the gate,
+    one down forward per bit-width; back through the three down layers (dW accumulated), the gate, the stacked layer."""
+    gate, up, down = layers
+    M, d, F = gate.M, gate.K, gate.N
+    Wgu = torch.empty(2 * F, d, dtype=torch.float32, device="cuda")
+    Wgu[0::2], Wgu[1::2] = gate.W, up.W
+    Qg, ag, zg = mq.mq_quantize_int8(Wgu)
+    Qd, ad, zd = down.Q, down.alpha, down.zero
+    mq.mq_quantize_int8(down.W, Q=Qd, alpha=ad, zero=zd)
+    X = gate.X
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    GU = [torch.empty(M, 2 * F, **bf) for _ in rs]
+    A = [torch.empty(M, F, **bf) for _ in rs]
+    Y = [torch.empty(M, d, **bf) for _ in rs]
+    dY = [(torch.randn(M, d, generator=torch.Generator().manual_seed(5 + i)) * 1e-3).to(torch.bfloat16).cuda() for i in range(len(rs))]
+    dA = [torch.empty(M, F, **bf) for _ in rs]
+    dGU = [torch.empty(M, 2 * F, **bf) for _ in rs]
+    dX = torch.empty(M, d, **bf)
+    dWgu = torch.empty(2 * F, d, dtype=torch.float32, device="cuda")
+    dWd = torch.empty(d, F, dtype=torch.float32, device="cuda")
+    u8 = dict(dtype=torch.uint8, device="cuda")
+    ws_fg = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD, M, 2 * F, d, len(rs)), **u8)
+    ws_fd = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD, M, d, F, 1), **u8)
+    ws_bg = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, M, 2 * F, d, len(rs)), **u8)
+    ws_bd = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, M, d, F, 1), **u8)
+
+    def one():
+        mq.mq_linear_fwd_multi(X, Qg, ag, zg, rs, Y=GU, ws=ws_fg)
+        mq.mq_gated_unit_fwd(GU, A=A)
+        for i, r in enumerate(rs):
+            mq.mq_linear_fwd_multi(A[i], Qd, ad, zd, (r,), Y=[Y[i]], ws=ws_fd)
+        for i, r in enumerate(rs):
+            mq.mq_linear_bwd(A[i], Qd, ad, zd, [dY[i]], None, (r,), dX=dA[i], dW=dWd, accumulate_dW=i > 0, ws=ws_bd)
+        mq.mq_gated_unit_bwd(GU, dA, dGU=dGU)
+        mq.mq_linear_bwd(X, Qg, ag, zg, dGU, None, rs, dX=dX, dW=dWgu, ws=ws_bg)
+
+    one()
+    a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a_.record()
+    for _ in range(reps):
+        one()
+    b_.record()
+    torch.cuda.synchronize()
+    ms = a_.elapsed_time(b_) / reps
+    n = len(rs)
+    # stacked layer: forward 2 n, dX 2 n, dW 2 (pre-summed); down layers: forward 2, dX 2, dW 2 per bit-width
+    flops = (4.0 * n + 2.0) * M * 2 * F * d + 6.0 * n * M * d * F
+    return {"M": M, "d": d, "F": F, "ms": round(ms, 4), "TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),
+            "note": "mq_linear_fwd_multi (stacked gate/up, r = 8/4/2) + mq_gated_unit_fwd + 3 x mq_linear_fwd_multi (down) + "
+                    "3 x mq_linear_bwd (down) + mq_gated_unit_bwd + mq_linear_bwd (stacked)"}
 
 
 def mixnmatch_decode(torch, mq, synth):

@@ -345,6 +345,26 @@ mq_status mq_ffn_mixnmatch(const uint16_t *x, const mq_ffn_layer *layers, int n_
                            void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The gate of the feed-forward block on the training path (the block of section 5 whose weights the
+ * paper quantizes; section 3.1.2 optimizes the error of whole layers).  The gate and up projections are
+ * one quantized linear layer over the stacked weight [2F, d] with the rows of a pair next to each other
+ * (row 2 f = gate row f, row 2 f + 1 = up row f, as in mq_ffn_mixnmatch), so that one
+ * mq_linear_fwd_multi call over the shared input yields GU_r [M, 2F] for every bit-width; then
+ *     A_r[m, f]  = bf16(act(GU_r[m, 2f]) * GU_r[m, 2f+1])                     (mq_gated_unit_fwd)
+ * feeds the down projection (one mq_linear_fwd_multi / _l2 call per bit-width, their inputs differ), and
+ *     dGU_r[m, 2f]   = bf16(dA_r[m, f] * GU_r[m, 2f+1] * act'(GU_r[m, 2f]))
+ *     dGU_r[m, 2f+1] = bf16(dA_r[m, f] * act(GU_r[m, 2f]))                   (mq_gated_unit_bwd)
+ * takes the down projection's dX_r back to the stacked layer's mq_linear_bwd.  act = GELU in its tanh
+ * form, or SiLU with MQ_FLAG_FFN_SILU.  All nr (1..3) tensors are processed in one launch.
+ *   GU, dGU  host arrays of nr device pointers, each [M, 2F] bf16;  A, dA  each [M, F] bf16
+ * F must be a multiple of 8.  M == 0 is a no-op.
+ */
+mq_status mq_gated_unit_fwd(const uint16_t *const *GU, int nr, int64_t M, int64_t F, uint32_t flags,
+                            uint16_t *const *A, void *hip_stream);
+mq_status mq_gated_unit_bwd(const uint16_t *const *GU, const uint16_t *const *dA, int nr, int64_t M,
+                            int64_t F, uint32_t flags, uint16_t *const *dGU, void *hip_stream);
+
+/*
  * Measurement helpers (they compute nothing of the method): ceilings of this GPU as measured by
  * kernels that only multiply or only read, to put next to the published peaks.
  *

@@ -32,7 +32,7 @@ MQ_FLAG_FFN_RESIDUAL = 32
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
            "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string", "mq_probe_mfma", "mq_probe_read",
            "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2", "mq_linear_bwd_clip",
-           "mq_affine_weight", "mq_affine_input", "mq_affine_bwd"]
+           "mq_affine_weight", "mq_affine_input", "mq_affine_bwd", "mq_gated_unit_fwd", "mq_gated_unit_bwd"]
 
 
 class MqError(RuntimeError):
@@ -74,6 +74,8 @@ def _load() -> ctypes.CDLL:
     lib.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
     lib.mq_matquant_l2_loss.argtypes = [ctypes.POINTER(vp), vp, ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_float), i64,
                                         i64, ci, u32, ctypes.POINTER(vp), vp, vp, sz, vp]
+    lib.mq_gated_unit_fwd.argtypes = [ctypes.POINTER(vp), ci, i64, i64, u32, ctypes.POINTER(vp), vp]
+    lib.mq_gated_unit_bwd.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), ci, i64, i64, u32, ctypes.POINTER(vp), vp]
     lib.mq_affine_weight.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
     lib.mq_affine_input.argtypes = [vp, i64, i64, vp, vp, vp, vp]
     lib.mq_affine_bwd.argtypes = [vp, vp, vp, i64, vp, ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float), ci, i64, i64, i64,
@@ -450,4 +452,28 @@ def mq_affine_bwd(X, dXt, W, dWs, dY, lambdas, s=None, delta=None, ws=None):
                             _ptr(ws), ws.numel(), _stream())
     _check(st, "mq_affine_bwd")
     return out
+
+
+def mq_gated_unit_fwd(GU, silu: bool = False, A=None):
+    """GU: list of bf16 [M, 2F] (gate / up columns interleaved) -> list of A bf16 [M, F] = act(gate) * up."""
+    M, F2 = GU[0].shape
+    F = F2 // 2
+    if A is None:
+        A = [torch.empty(M, F, dtype=torch.bfloat16, device=GU[0].device) for _ in GU]
+    st = _lib.mq_gated_unit_fwd(_ptr_array(GU, torch.bfloat16), len(GU), M, F, MQ_FLAG_FFN_SILU if silu else 0,
+                                _ptr_array(A, torch.bfloat16), _stream())
+    _check(st, "mq_gated_unit_fwd")
+    return A
+
+
+def mq_gated_unit_bwd(GU, dA, silu: bool = False, dGU=None):
+    """Backward of mq_gated_unit_fwd: list of dGU bf16 [M, 2F]."""
+    M, F2 = GU[0].shape
+    F = F2 // 2
+    if dGU is None:
+        dGU = [torch.empty(M, F2, dtype=torch.bfloat16, device=GU[0].device) for _ in GU]
+    st = _lib.mq_gated_unit_bwd(_ptr_array(GU, torch.bfloat16), _ptr_array(dA, torch.bfloat16), len(GU), M, F,
+                                MQ_FLAG_FFN_SILU if silu else 0, _ptr_array(dGU, torch.bfloat16), _stream())
+    _check(st, "mq_gated_unit_bwd")
+    return dGU
 

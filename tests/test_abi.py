@@ -40,6 +40,8 @@ def lib():
     lib_.mq_matquant_l2_loss.argtypes = [vp, vp, ctypes.POINTER(ci), vp, i64, i64, ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp,
                                             ctypes.POINTER(ci), vp, vp, vp, vp, vp, sz, vp]
+    lib_.mq_gated_unit_fwd.argtypes = [vp, ci, i64, i64, u32, vp, vp]
+    lib_.mq_gated_unit_bwd.argtypes = [vp, vp, ci, i64, i64, u32, vp, vp]
     lib_.mq_affine_weight.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
     lib_.mq_affine_input.argtypes = [vp, i64, i64, vp, vp, vp, vp]
     lib_.mq_affine_bwd.argtypes = [vp, vp, vp, i64, vp, vp, vp, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -243,4 +245,13 @@ def test_affine_argument_checks(lib):
     assert f(p, p, p, 64, p, None, None, 3, 8, 18, 64, None, None, p, p, p, None, 0, None) == ALIGN
     assert f(p, p, p, 64, p, None, None, 3, 8, 16, 64, None, None, p, p, p, None, 0, None) == NULL   # dY missing
     assert lib.mq_workspace_bytes(6, 4096, 9216, 2304, 3) > 0
+
+
+def test_gated_unit_argument_checks(lib):
+    assert lib.mq_gated_unit_fwd(None, 4, 8, 64, 0, None, None) == BITS
+    assert lib.mq_gated_unit_fwd(None, 3, 8, 60, 0, None, None) == ALIGN
+    assert lib.mq_gated_unit_fwd(None, 3, 0, 64, 0, None, None) == OK
+    assert lib.mq_gated_unit_fwd(None, 3, 8, 64, 0, None, None) == NULL
+    assert lib.mq_gated_unit_bwd(None, None, 0, 8, 64, 0, None, None) == BITS
+    assert lib.mq_gated_unit_bwd(None, None, 2, 8, 64, 0, None, None) == NULL
 

@@ -638,6 +638,64 @@ def test_affine_bwd(mq, oracle, M, N, K, nr):
         assert rel_l2(mine.cpu().numpy().astype(np.float64), ref) <= 1e-4, name   # fp32 partial sums, fp64 across them
 
 
+# --------------------------------------------------------------------------
+# feed-forward block on the training path
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("M,F,nr,silu", [(40, 64, 3, False), (257, 1000, 2, True), (1, 8, 1, False), (0, 64, 3, False)])
+def test_gated_unit_fwd_bwd(mq, oracle, M, F, nr, silu):
+    GU = [(_randn(60 + i, M, 2 * F) * 2.0).to(torch.bfloat16) for i in range(nr)]
+    dA = [_randn(70 + i, M, F).to(torch.bfloat16) for i in range(nr)]
+    A = mq.mq_gated_unit_fwd([dev(t) for t in GU], silu)
+    dGU = mq.mq_gated_unit_bwd([dev(t) for t in GU], [dev(t) for t in dA], silu)
+    torch.cuda.synchronize()
+    if M == 0:
+        return
+    for i in range(nr):
+        want = oracle.bf16_to_f64(oracle.gated_unit(bf16_bits(GU[i]), silu))
+        assert rel_l2(A[i].float().cpu().numpy(), want) <= 3e-3, i         # one bf16 rounding
+        want = oracle.gated_unit_bwd(bf16_bits(GU[i]), bf16_bits(dA[i]), silu)
+        assert rel_l2(dGU[i].float().cpu().numpy(), want) <= 3e-3, i
+
+
+def test_ffn_block_training_step_composes(mq, oracle):
+    """Forward and straight-through backward of a whole gated feed-forward block for r = 8, 4, 2 out of the
+    library's calls (stacked gate/up layer -> gate -> one down layer per bit-width, and back), against the same
+    composition of the oracle's functions."""
+    M, d, F, rs, lam = 72, 96, 64, (8, 4, 2), (0.3, 0.6, 1.0)
+    Wgu, Wd = _randn(1, 2 * F, d, scale=1.0 / d ** 0.5), _randn(2, d, F, scale=1.0 / F ** 0.5)
+    X = _randn(3, M, d).to(torch.bfloat16)
+    dYs = [(_randn(4 + i, M, d) * 1e-2).to(torch.bfloat16) for i in range(3)]
+    Qg, ag, zg, qg, aog, zog = _quantized(mq, oracle, Wgu)
+    Qd, ad, zd, qd, aod, zod = _quantized(mq, oracle, Wd)
+    xb = bf16_bits(X)
+    # ---- library
+    GU = mq.mq_linear_fwd_multi(dev(X), Qg, ag, zg, rs)
+    A = mq.mq_gated_unit_fwd(GU)
+    Y = [mq.mq_linear_fwd_multi(A[i], Qd, ad, zd, (r,))[0] for i, r in enumerate(rs)]
+    dA, dWd = [], torch.zeros(d, F, device="cuda")
+    for i, r in enumerate(rs):
+        dx, _ = mq.mq_linear_bwd(A[i], Qd, ad, zd, [dev(dYs[i])], (lam[i],), (r,), dW=dWd, accumulate_dW=True)
+        dA.append(dx)
+    dGU = mq.mq_gated_unit_bwd(GU, dA)
+    dX, dWgu = mq.mq_linear_bwd(dev(X), Qg, ag, zg, dGU, None, rs)
+    torch.cuda.synchronize()
+    # ---- oracle
+    ones = (1.0,) * 3
+    GU_o = [oracle.bf16_round(oracle.linear_fwd(xb, qg, aog, zog, r)) for r in rs]
+    A_o = [oracle.gated_unit(g) for g in GU_o]
+    dA_o, dWd_o, dGU_o = [], np.zeros((d, F)), []
+    for i, r in enumerate(rs):
+        want = oracle.linear_fwd(A_o[i], qd, aod, zod, r)
+        assert rel_l2(Y[i].float().cpu().numpy(), want) <= 2 * TOL, ("Y", r)
+        dyb = bf16_bits(dYs[i])
+        dA_o.append(oracle.bf16_round(oracle.linear_bwd_dx(qd, aod, zod, [dyb], (lam[i],), (r,))))
+        dWd_o += oracle.linear_bwd_dw(A_o[i], [dyb], (lam[i],))
+        dGU_o.append(oracle.bf16_round(oracle.gated_unit_bwd(GU_o[i], dA_o[i])))
+    assert rel_l2(dWd.cpu().numpy().astype(np.float64), dWd_o) <= 2 * TOL
+    assert rel_l2(dX.float().cpu().numpy(), oracle.linear_bwd_dx(qg, aog, zog, dGU_o, ones, rs)) <= 2 * TOL
+    assert rel_l2(dWgu.cpu().numpy().astype(np.float64), oracle.linear_bwd_dw(xb, dGU_o, ones)) <= 2 * TOL
+
+
 def test_measurement_probes_run(mq):
     ops = torch.randn(32768, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
     sink = torch.zeros(65536, dtype=torch.float32, device="cuda")
