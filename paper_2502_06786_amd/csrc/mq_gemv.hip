@@ -817,8 +817,10 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     }
 
     // Rows per wave (16 RG): every activation operand read from LDS serves RG matrix-core products, so
-    // larger batches and tall matrices take two row groups; short ones keep RG = 1 for more waves.
-    int rg = (B > 2 || (N >= 8192 && !ovf)) ? 2 : 1;  // (a list is walked by the waves of a group: more groups)
+    // tall matrices take two row groups; short ones keep RG = 1 for more waves (measured on the decode
+    // shapes at B = 4 and 16: 4096 rows run 10-25 % faster with RG = 1, 14336 rows level or faster with 2).
+    // With an overflow list the waves of a group walk the list together: two row groups from B = 3 on.
+    int rg = ovf ? (B > 2 ? 2 : 1) : (N >= 8192 ? 2 : 1);
 #ifdef MQ_GEMV_TUNE
     if (const char *e = getenv("MQ_GEMV_RG")) rg = atoi(e);
 #endif
@@ -829,7 +831,9 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     const int64_t segs = cdiv(kb, line_bytes(r));  // weight lines per row
     const int64_t row_blocks = cdiv(N, 16 * rg);
     int ks = 1;
-    while (ks < 16 && row_blocks * ks * 2 <= 2048 && 2 * ks <= segs) ks <<= 1;
+    // (short matrices with batched activations: shorter slices pay off; at 14336 rows they cost 15-25 %)
+    const int64_t wave_budget = (B >= 4 && rg == 1) ? 4096 : 2048;
+    while (ks < 16 && row_blocks * ks * 2 <= wave_budget && 2 * ks <= segs) ks <<= 1;
     int nw = ks > 8 ? ks : 8;
 #ifdef MQ_GEMV_TUNE
     if (const char *e = getenv("MQ_GEMV_KS")) ks = atoi(e);
