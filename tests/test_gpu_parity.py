@@ -696,6 +696,66 @@ def test_ffn_block_training_step_composes(mq, oracle):
     assert rel_l2(dWgu.cpu().numpy().astype(np.float64), oracle.linear_bwd_dw(xb, dGU_o, ones)) <= 2 * TOL
 
 
+# --------------------------------------------------------------------------
+# the whole step under HIP graph capture
+# --------------------------------------------------------------------------
+def test_step_replays_from_a_hip_graph(mq):
+    """The library allocates nothing, never synchronises and records no memset: a whole step (quantize, slice with
+    overflow list, forward with the objective, backward, clip-factor gradients, decode GEMV) is captured once and
+    replayed on new inputs; every replay must reproduce the eager results bit for bit."""
+    M, N, K, rs, lam = 136, 144, 256, (8, 4, 2), (0.2, 0.5, 1.0)
+    W = dev(_randn(1, N, K, scale=0.02))
+    X = dev(_randn(2, M, K).to(torch.bfloat16))
+    T = dev(_randn(3, M, N).to(torch.bfloat16))
+    xd = dev(_randn(4, 4, K).to(torch.bfloat16))
+    u8 = dict(dtype=torch.uint8, device="cuda")
+    Q, a, z = torch.empty(N, K, **u8), torch.empty(N, device="cuda"), torch.empty(N, device="cuda")
+    a16, z16 = torch.empty(N, dtype=torch.bfloat16, device="cuda"), torch.empty(N, dtype=torch.bfloat16, device="cuda")
+    p2 = torch.empty(N, K // 4, **u8)
+    ovf = mq.Overflow(N, N * K // 4)
+    dY = [torch.empty(M, N, dtype=torch.bfloat16, device="cuda") for _ in rs]
+    losses = torch.empty(3, device="cuda")
+    dX, dW = torch.empty(M, K, dtype=torch.bfloat16, device="cuda"), torch.empty(N, K, device="cuda")
+    y = torch.empty(4, N, dtype=torch.bfloat16, device="cuda")
+    ws_f = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD_L2, M, N, K, 3), **u8)
+    ws_b = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, M, N, K, 3), **u8)
+    ws_c = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD_CLIP, M, N, K, 3), **u8)
+    def step():
+        mq.mq_quantize_int8(W, Q=Q, alpha=a, zero=z)
+        mq.mq_slice(Q, 2, packed=True, extra_precision=True, out=p2, ovf=ovf)
+        mq.mq_params_to_bf16(a, z, a16, z16)
+        mq.mq_linear_fwd_multi_l2(X, Q, a, z, rs, T, (-1, 0, 0), lam, dY=dY, losses=losses, ws=ws_f)
+        mq.mq_linear_bwd(X, Q, a, z, dY, None, rs, dX=dX, dW=dW, ws=ws_b)
+        grads = mq.mq_linear_bwd_clip(W, X, Q, a, z, dY, None, rs, ws=ws_c)     # (allocates its two outputs)
+        mq.mq_gemv_sliced(xd, p2, a16, z16, 2, K, y=y, ovf=ovf)
+        return list(grads)
+
+    fixed = (Q, a, z, p2, ovf.row_ptr, losses, dX, dW, y, *dY)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream (kernel attributes are set here)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            captured = step()                    # the tensors the replays write their clip-factor gradients to
+    for trial in range(3):
+        W.copy_(dev(_randn(10 + trial, N, K, scale=0.02)))
+        X.copy_(dev(_randn(20 + trial, M, K).to(torch.bfloat16)))
+        torch.cuda.synchronize()
+        eager = step()                           # eager, default stream
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (*fixed, *eager)]
+        for t in (Q, p2, losses, dX, dW, y, *dY, *captured):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (*fixed, *captured)]
+        for i, (g_, w_) in enumerate(zip(got, want)):
+            assert torch.equal(g_, w_), (trial, i)
+
+
 def test_measurement_probes_run(mq):
     ops = torch.randn(32768, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
     sink = torch.zeros(65536, dtype=torch.float32, device="cuda")
