@@ -122,7 +122,8 @@ def main():
             # backward consumes formed in its epilogue
             timed("fwd", lambda: mq.mq_linear_fwd_multi_l2(L.X, L.Q, L.alpha, L.zero, rs, L.T, None, lambdas,
                                                            dY=L.dY, losses=L.losses, ws=L.ws_f), rec)
-            timed("bwd", lambda: mq.mq_linear_bwd(L.X, L.Q, L.alpha, L.zero, L.dY, lambdas, rs, dX=L.dX, dW=L.dW,
+            # (the dY_r of the objective already carry lambda_r: the backward takes them unweighted)
+            timed("bwd", lambda: mq.mq_linear_bwd(L.X, L.Q, L.alpha, L.zero, L.dY, None, rs, dX=L.dX, dW=L.dW,
                                                   ws=L.ws_b), rec)
 
             def do_gemv():
