@@ -216,11 +216,16 @@ def main():
         roofline["frac_of_measured"] = round(achieved / peaks["mfma_bf16_normal_operands_TFLOPs"], 4)
     if not args.no_gemv_sweep:
         out["gemv_roofline"] = gemv_sweep(torch, mq, synth)
-        if not args.no_probes:
-            best = out["gemv_roofline"]["best_int2"]
-            best["frac_of_measured_read"] = round(best["achieved"] / peaks["hbm_read_85MB_GBs"], 4)
-    if not args.no_gemv_sweep:
         out["extra_precision_gemv"] = ep_gemv(torch, mq, synth)
+        # the int2 GEMV of the metric: best over the 7B shapes of configuration 4 and the plain int2 plane of the
+        # 27B-shaped matrix of configuration 5
+        best = out["gemv_roofline"]["best_int2"]
+        for B in (1, 4, 16):
+            e = out["extra_precision_gemv"][f"plain_int2_B{B}"]
+            if e["GBs"] > best["achieved"]:
+                best.update({"case": f"int2_36864x4608_B{B}", "achieved": e["GBs"], "frac": round(e["GBs"] / PEAK_HBM_GBS, 4)})
+        if not args.no_probes:
+            best["frac_of_measured_read"] = round(best["achieved"] / peaks["hbm_read_85MB_GBs"], 4)
     if not args.no_gemv_sweep:
         out["mixnmatch_decode"] = mixnmatch_decode(torch, mq, synth)
         out["clip_factor_grads"] = clip_factor_grads(torch, mq, layers, rs, lambdas)
