@@ -464,39 +464,60 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
         float sum[NR];
 #pragma unroll
         for (int i = 0; i < NR; ++i) sum[i] = 0.f;
+        // The parameters of the objective are read once into vector registers (left to itself the compiler
+        // reloads them from the kernel arguments for every chunk, a scalar-memory round trip each time):
+        // the factor, the lane's addresses in dY_i / Y_i, and the choice of the teacher as bit masks.
+        const int crow = threadIdx.x >> 4, cch = threadIdx.x & 15;  // chunk `it` is row crow + 16 it, channels 8 cch ..
+        const size_t at0 = (size_t)(m0 + crow) * a.N + n0 + cch * 8;
+        const bool cols_ok = n0 + cch * 8 < a.N;
+        float cf[NR];
+        uint32_t pick[NR][NR], mixed_slot[NR];
+        uint16_t *pd[NR], *py[NR];
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            cf[i] = a.coef[i];
+            pd[i] = a.dY[i] + at0;
+            py[i] = a.Y[i] ? a.Y[i] + at0 : nullptr;
+            mixed_slot[i] = a.teacher[i] >= 0 ? 0xFFFFFFFFu : 0u;
+            asm volatile("" : "+v"(cf[i]), "+v"(pd[i]), "+v"(py[i]), "+v"(mixed_slot[i]));
+#pragma unroll
+            for (int u = 0; u < NR; ++u) {
+                pick[i][u] = a.teacher[i] == u ? 0xFFFFFFFFu : 0u;
+                asm volatile("" : "+v"(pick[i][u]));
+            }
+        }
+        const size_t chunk_step = (size_t)16 * a.N;  // elements between a lane's consecutive chunks
         // the equal-weight mix of teacher and target is a variant of the whole loop, chosen once
         auto chunks = [&](auto mixed) {
             constexpr bool MIX = decltype(mixed)::value;
 #pragma unroll
             for (int it = 0; it < CHUNKS; ++it) {
-                const int c = it * 256 + threadIdx.x;
-                const int row = c >> 4, ch = c & 15;
-                const int m = m0 + row, n = n0 + ch * 8;
-                if (m < a.M && n < a.N) {
-                    const size_t at = (size_t)m * a.N + n;
+                const int row = crow + 16 * it;
+                if (cols_ok && m0 + row < a.M) {
                     u32x4 y[NR];
                     const u32x4 t = tpre[it];
 #pragma unroll
                     for (int i = 0; i < NR; ++i) {
-                        const uint8_t *src = smem + i * OT + row * OS + ch * 16;
+                        const uint8_t *src = smem + i * OT + row * OS + cch * 16;
                         const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
                         const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
                         y[i] = u32x4{lo.x, lo.y, hi.x, hi.y};
                     }
 #pragma unroll
                     for (int i = 0; i < NR; ++i) {
-                        const int th = a.teacher[i];
                         u32x4 tt = t;
 #pragma unroll
                         for (int u = 0; u < NR; ++u)
-                            if (u != i && th == u) tt = y[u];
-                        const float cf = a.coef[i];
+                            if (u != i) {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) tt[j] = (y[u][j] & pick[i][u]) | (tt[j] & ~pick[i][u]);
+                            }
                         u32x4 o;
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const float y0 = bf16_lo(y[i][j]), y1 = bf16_hi(y[i][j]);
                             float d0 = y0 - bf16_lo(tt[j]), d1 = y1 - bf16_hi(tt[j]);
-                            if (MIX && th >= 0) {  // teacher and ground truth, weighted equally
+                            if (MIX && mixed_slot[i]) {  // teacher and ground truth, weighted equally
                                 const float e0 = y0 - bf16_lo(t[j]), e1 = y1 - bf16_hi(t[j]);
                                 sum[i] += 0.5f * (d0 * d0 + d1 * d1 + e0 * e0 + e1 * e1);
                                 d0 = 0.5f * (d0 + e0);
@@ -504,10 +525,10 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
                             } else {
                                 sum[i] = __builtin_fmaf(d1, d1, __builtin_fmaf(d0, d0, sum[i]));
                             }
-                            o[j] = pack_bf16x2(cf * d0, cf * d1);
+                            o[j] = pack_bf16x2(cf[i] * d0, cf[i] * d1);
                         }
-                        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(a.dY[i] + at));
-                        if (a.Y[i]) __builtin_nontemporal_store(y[i], reinterpret_cast<u32x4 *>(a.Y[i] + at));
+                        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(pd[i] + it * chunk_step));
+                        if (py[i]) __builtin_nontemporal_store(y[i], reinterpret_cast<u32x4 *>(py[i] + it * chunk_step));
                     }
                 }
             }
