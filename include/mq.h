@@ -159,7 +159,7 @@ mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, const float *
  *   dX      [M, K] bf16 out, or NULL to skip
  *   dW      [N, K] fp32 out (accumulated into with MQ_FLAG_ACCUM_DW), or NULL to skip
  *   ws      workspace of at least mq_workspace_bytes(MQ_OP_LINEAR_BWD, M, N, K, nr)
- * K must be a multiple of 16, N a multiple of 16 and M a multiple of 8.
+ * K must be a multiple of 16 and N a multiple of 16.  M is free.
  * The bf16 rounding of lambda_i * alpha_n * dY_i (dX) and of
  * sum_i lambda_i dY_i (dW) before the matrix-core contraction is part of the
  * stated tolerance.

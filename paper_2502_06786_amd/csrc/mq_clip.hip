@@ -139,7 +139,7 @@ extern "C" mq_status mq_linear_bwd_clip(const float *W, int64_t ldw, const uint1
     }
     if (M < 0 || N < 0 || K < 1 || ldw < K) return MQ_ERR_SHAPE;
     if (M > (1 << 22) || N > (1 << 22) || K > (1 << 22)) return MQ_ERR_SHAPE;
-    if (K % 16 != 0 || N % 16 != 0 || M % 8 != 0 || ldw % 4 != 0) return MQ_ERR_ALIGN;
+    if (K % 16 != 0 || N % 16 != 0 || ldw % 4 != 0) return MQ_ERR_ALIGN;
     if (N == 0) return MQ_OK;
     if (!W || !Q || !alpha || !zero || !dgamma || !dbeta || (M > 0 && (!X || !dY))) return MQ_ERR_NULL;
     for (int i = 0; i < nr && M > 0; ++i)

@@ -596,8 +596,9 @@ struct PrepArgs {
     float mult[3];       // 2^s_i
     float bias[3];       // 128 for sliced slots, 0 for the r = 8 slot
     float *cpart;        // [nsplit][M] partial sums of c over column ranges, or null
-    uint16_t *GT;        // [N, M] or null
+    uint16_t *GT;        // [N, ldm] or null (columns M .. ldm - 1 are written as zeros)
     int nr, M, N;
+    int ldm;             // M rounded up to a multiple of 8: rows of GT start on 16-byte boundaries
     int cols_per_split;  // multiple of 64
 };
 
@@ -657,9 +658,9 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(PrepArgs a) {
             for (int j = 0; j < 8; ++j) tile[ch * 8 + j][r] = (uint16_t)float_to_bf16_bits(g[j]);
             __syncthreads();
             const int nn = t >> 2, part = t & 3;  // 64 rows of GT, four 16-byte pieces each
-            if (n0 + nn < a.N && m0 + part * 8 < a.M) {
+            if (n0 + nn < a.N && m0 + part * 8 < a.M) {  // (a piece that straddles M ends with zeros)
                 const uint32_t *src = reinterpret_cast<const uint32_t *>(&tile[nn][part * 8]);
-                *reinterpret_cast<u32x4 *>(a.GT + (size_t)(n0 + nn) * a.M + m0 + part * 8) =
+                *reinterpret_cast<u32x4 *>(a.GT + (size_t)(n0 + nn) * a.ldm + m0 + part * 8) =
                     u32x4{src[0], src[1], src[2], src[3]};
             }
         }
@@ -672,12 +673,13 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(PrepArgs a) {
     }
 }
 
-// out[c, r] = in[r, c] for a [rows, cols] matrix of 1- or 2-byte elements; rows and cols are
-// multiples of 16 bytes' worth of elements.  64 x (64 bytes) tiles, 16-byte global accesses on both
-// sides, the turn happens in LDS.
+// out[c, r] = in[r, c] for a [rows, cols] matrix of 1- or 2-byte elements; cols is a multiple of 16
+// bytes' worth of elements, the rows of out are ld_out elements apart (rows rounded up to such a
+// multiple) and end with zeros.  64 x (64 bytes) tiles, 16-byte global accesses on both sides, the
+// turn happens in LDS.
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in, T *__restrict__ out, int rows,
-                                                        int cols) {
+                                                        int cols, int ld_out) {
     constexpr int E = 16 / sizeof(T);  // elements per 16 bytes
     constexpr int TC = 4 * E;          // tile columns (64 bytes)
     constexpr int S = 64 + 4 / sizeof(T);  // padded row of the turned tile (a multiple of 4 bytes)
@@ -686,8 +688,9 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * TC;
     {
         const int r = t >> 2, chunk = t & 3;
-        if (r0 + r < rows && c0 + chunk * E < cols) {
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(in + (size_t)(r0 + r) * cols + c0 + chunk * E);
+        if (c0 + chunk * E < cols) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (r0 + r < rows) v = *reinterpret_cast<const u32x4 *>(in + (size_t)(r0 + r) * cols + c0 + chunk * E);
             T e[E];
             __builtin_memcpy(e, &v, 16);
 #pragma unroll
@@ -700,7 +703,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in
         const int c = t / PIECES, piece = t % PIECES;
         if (c < TC && c0 + c < cols && r0 + piece * E < rows) {
             const uint32_t *src = reinterpret_cast<const uint32_t *>(&tile[c][piece * E]);
-            *reinterpret_cast<u32x4 *>(out + (size_t)(c0 + c) * rows + r0 + piece * E) =
+            *reinterpret_cast<u32x4 *>(out + (size_t)(c0 + c) * ld_out + r0 + piece * E) =
                 u32x4{src[0], src[1], src[2], src[3]};
         }
     }
@@ -996,10 +999,11 @@ __global__ __launch_bounds__(256) void dx_kernel(DxArgs a) {
 // backward dW: dW[n, k] (+)= sum_m GT[n, m] * XT[k, m]   (plain bf16 GEMM, fp32 out)
 // ============================================================================================
 struct DwArgs {
-    const uint16_t *GT;  // [N, M]
-    const uint16_t *XT;  // [K, M]
+    const uint16_t *GT;  // [N, ldm]
+    const uint16_t *XT;  // [K, ldm]
     float *dW;           // [N, K]
     int M, N, K;
+    int ldm;             // M rounded up to a multiple of 8; columns M .. ldm - 1 hold zeros
     int accumulate;
     int tiles_n, tiles_k;
 };
@@ -1039,13 +1043,13 @@ __global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
     const int tk = (int)(lid % width) / gsz;
     const int n0 = tn * DW_BN, k0 = tk * DW_BK;
 
-    const __amdgpu_buffer_rsrc_t rG = make_rsrc(a.GT + (size_t)n0 * a.M, (uint64_t)(a.N - n0) * a.M * 2);
-    const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.XT + (size_t)k0 * a.M, (uint64_t)(a.K - k0) * a.M * 2);
+    const __amdgpu_buffer_rsrc_t rG = make_rsrc(a.GT + (size_t)n0 * a.ldm, (uint64_t)(a.N - n0) * a.ldm * 2);
+    const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.XT + (size_t)k0 * a.ldm, (uint64_t)(a.K - k0) * a.ldm * 2);
 
     uint32_t off0;
     int colb;  // byte column of this lane's 16-byte piece inside a 64-byte row
-    u8_tile_lane<4>(wave, lane, 0, (uint32_t)a.M * 2u, off0, colb);
-    const uint32_t rstep = 64u * (uint32_t)a.M * 2u;  // 64 rows further down
+    u8_tile_lane<4>(wave, lane, 0, (uint32_t)a.ldm * 2u, off0, colb);
+    const uint32_t rstep = 64u * (uint32_t)a.ldm * 2u;  // 64 rows further down
 
     // load i of the stage of token tile mt into LDS buffer `buf`; a tile past M is requested at an
     // out-of-range offset and answered with zeros, so the loads in flight are the same every stage
@@ -1178,10 +1182,11 @@ static BwdWorkspace bwd_layout(int64_t M, int64_t N, int64_t K, int nr) {
         w.as[i] = o;
         if (i < nr) o += align256((size_t)M * N * 2);
     }
+    const size_t ldm = ((size_t)M + 7) & ~(size_t)7;
     w.gt = o;
-    o += align256((size_t)M * N * 2);
+    o += align256(ldm * N * 2);
     w.xt = o;
-    o += align256((size_t)M * K * 2);
+    o += align256(ldm * K * 2);
     w.qt = o;
     o += align256((size_t)N * K);
     w.total = o;
@@ -1423,7 +1428,7 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
     if (M > (1 << 22) || N > (1 << 22) || K > (1 << 22)) return MQ_ERR_SHAPE;
     mq_status s = check_rs(rs, nr);
     if (s != MQ_OK) return s;
-    if (K % 16 != 0 || N % 16 != 0 || M % 8 != 0) return MQ_ERR_ALIGN;
+    if (K % 16 != 0 || N % 16 != 0) return MQ_ERR_ALIGN;
     if (M == 0 || N == 0) return MQ_OK;  // note: with M == 0 and no ACCUM flag dW is left untouched
     if (!dY) return MQ_ERR_NULL;
     for (int i = 0; i < nr; ++i) {
@@ -1459,6 +1464,7 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
     p.nr = nr;
     p.M = (int)M;
     p.N = (int)N;
+    p.ldm = (int)((M + 7) & ~(int64_t)7);
     // column ranges so that about a thousand workgroups exist; c[m] is summed over them in the dX epilogue
     const int64_t strips = cdiv(M, PREP_ROWS);
     int nsplit = (int)std::min<int64_t>(std::min<int64_t>(PREP_MAX_SPLIT, cdiv(N, 64)), std::max<int64_t>(1, cdiv(1024, strips)));
@@ -1469,7 +1475,7 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
     if (dX) {
         uint8_t *QT = base + lay.qt;
         transpose_kernel<uint8_t><<<dim3((unsigned)cdiv(K, 64), (unsigned)cdiv(N, 64)), dim3(256), 0, st>>>(
-            Q, QT, (int)N, (int)K);
+            Q, QT, (int)N, (int)K, (int)N);
 
         // slot order of the kernel: the r = 8 bit-width (if any) first
         DxArgs d;
@@ -1501,7 +1507,7 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
     if (dW) {
         uint16_t *XT = reinterpret_cast<uint16_t *>(base + lay.xt);
         transpose_kernel<uint16_t><<<dim3((unsigned)cdiv(K, 32), (unsigned)cdiv(M, 64)), dim3(256), 0, st>>>(
-            X, XT, (int)M, (int)K);
+            X, XT, (int)M, (int)K, p.ldm);
         DwArgs w;
         w.GT = p.GT;
         w.XT = XT;
@@ -1509,6 +1515,7 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
         w.M = (int)M;
         w.N = (int)N;
         w.K = (int)K;
+        w.ldm = p.ldm;
         w.accumulate = (flags & MQ_FLAG_ACCUM_DW) ? 1 : 0;
         w.tiles_n = (int)cdiv(N, DW_BN);
         w.tiles_k = (int)cdiv(K, DW_BK);

@@ -128,7 +128,8 @@ def test_linear_argument_checks(lib):
     assert fwd(None, None, None, None, 16, 256, 250, rs, 3, 0, None, None, 0, None) == ALIGN
     assert bwd(None, None, None, None, None, None, 16, 256, 256, rs, 0, 0, None, None, None, 0, None) == BITS
     assert bwd(None, None, None, None, None, None, 16, 256, 250, rs, 3, 0, None, None, None, 0, None) == ALIGN
-    assert bwd(None, None, None, None, None, None, 12, 256, 256, rs, 3, 0, None, None, None, 0, None) == ALIGN
+    assert bwd(None, None, None, None, None, None, 12, 250, 256, rs, 3, 0, None, None, None, 0, None) == ALIGN
+    assert bwd(None, None, None, None, None, None, 13, 256, 256, rs, 3, 0, None, None, None, 0, None) == NULL     # any M: no dY
     assert bwd(None, None, None, None, None, None, 16, 256, 256, rs, 3, 0, None, None, None, 0, None) == NULL
     assert bwd(None, None, None, None, None, None, 0, 256, 256, rs, 3, 0, None, None, None, 0, None) == OK
 

@@ -208,7 +208,7 @@ def test_fwd_exact_small_integers(mq, oracle):
 # --------------------------------------------------------------------------
 # STE backward
 # --------------------------------------------------------------------------
-BWD_SHAPES = [(16, 256, 256), (264, 272, 208), (8, 16, 16), (520, 400, 320)]
+BWD_SHAPES = [(16, 256, 256), (264, 272, 208), (8, 16, 16), (520, 400, 320), (301, 272, 208), (1, 16, 16), (77, 48, 96)]
 
 
 @pytest.mark.parametrize("M,N,K", BWD_SHAPES)
@@ -532,7 +532,7 @@ def test_fwd_with_fused_l2_objective(mq, oracle, M, N, K, rs, teacher, mix, ep):
 # --------------------------------------------------------------------------
 # gradients with respect to the clip factors of the quantizer
 # --------------------------------------------------------------------------
-@pytest.mark.parametrize("M,N,K,rs,clip,ep", [(64, 48, 96, (8, 4, 2), True, False), (264, 272, 208, (8, 4, 2), True, True),
+@pytest.mark.parametrize("M,N,K,rs,clip,ep", [(64, 48, 96, (8, 4, 2), True, False), (67, 48, 96, (8, 4, 2), True, False), (264, 272, 208, (8, 4, 2), True, True),
                                               (520, 400, 1040, (4, 2), False, False), (8, 16, 4112, (2,), True, False),
                                               (0, 32, 64, (8, 4, 2), False, False)])
 def test_bwd_clip_factor_grads(mq, oracle, M, N, K, rs, clip, ep):
