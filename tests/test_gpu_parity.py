@@ -756,6 +756,34 @@ def test_step_replays_from_a_hip_graph(mq):
             assert torch.equal(g_, w_), (trial, i)
 
 
+# --------------------------------------------------------------------------
+# the calls as a training loop
+# --------------------------------------------------------------------------
+def test_cotraining_loop_reduces_every_loss(mq):
+    """Quantization-aware training of one linear layer towards a teacher layer with the MatQuant objective
+    (section 3.2): quantize -> forward for r = 8, 4, 2 with the L2 objective -> straight-through backward ->
+    SGD on the fp32 master weights.  Signs and scales of the gradients are right if all three losses fall;
+    the int2 loss cannot reach zero (four levels per row) but must fall well below its starting value."""
+    M, N, K, rs, lam = 512, 64, 128, (8, 4, 2), (1.0, 1.0, 1.0)
+    g = torch.Generator().manual_seed(0)
+    W_teacher = torch.randn(N, K, generator=g) * 0.05
+    W = (W_teacher + torch.randn(N, K, generator=g) * 0.05).cuda()       # start away from the teacher
+    X = torch.randn(M, K, generator=g).to(torch.bfloat16).cuda()
+    T = (X.float() @ W_teacher.cuda().t()).to(torch.bfloat16)
+    first = last = None
+    lr = 0.1 * N                                     # curvature of the summed mean losses: about 6 / N per weight
+    for step in range(60):
+        Q, a, z = mq.mq_quantize_int8(W)
+        losses, dY = mq.mq_linear_fwd_multi_l2(X, Q, a, z, rs, T, None, lam)
+        _, dW = mq.mq_linear_bwd(X, Q, a, z, dY, None, rs, need_dX=False)
+        W -= lr * dW
+        if step == 0:
+            first = losses.cpu().numpy().copy()
+        last = losses.cpu().numpy().copy()
+    assert np.all(np.isfinite(last))
+    assert last[0] < 0.05 * first[0] and last[1] < 0.1 * first[1] and last[2] < 0.7 * first[2], (first, last)
+
+
 def test_measurement_probes_run(mq):
     ops = torch.randn(32768, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
     sink = torch.zeros(65536, dtype=torch.float32, device="cuda")
