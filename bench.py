@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per launch of the fused forward kernel on this workload (average of the three
 # linears), from the FETCH_SIZE / WRITE_SIZE counter passes summarised in
 # profiles/hot_path_step_gemma2b_mlp_hbm_traffic.txt (FETCH_SIZE scaled by 2.00, WRITE_SIZE by 1.00).
-FWD_TRAFFIC_BYTES = (386742 + 165940) * 1024
+FWD_TRAFFIC_BYTES = (393924 + 165941) * 1024
 
 
 def parse():
