@@ -788,7 +788,10 @@ __global__ __launch_bounds__(256) void dx_kernel(DxArgs a) {
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rA[SLOT], (lds_ptr)(as + (wave + i * 4) * 1024), 16,
                                                      ab + (uint32_t)i * astep, 0, 0, 0);
         } else {
-            const uint32_t qb = (n0 + qcol < a.N) ? qoff0 + (uint32_t)n0 : kOOB;
+            // The code bytes of an n tile are fetched with its first bit-width only: the other bit-widths
+            // of the tile slice the same bytes, which the lanes then still hold in registers.  Their
+            // requests go out of range (no traffic) so that every stage has the same number of loads.
+            const uint32_t qb = (SLOT == 0 && n0 + qcol < a.N) ? qoff0 + (uint32_t)n0 : kOOB;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rQ, (lds_ptr)(as + DX_A_TILE + (wave + (i - MB) * 4) * 1024), 16,
                                                      qb + (uint32_t)(i - MB) * qstep, 0, 0, 0);
         }
@@ -906,7 +909,10 @@ __global__ __launch_bounds__(256) void dx_kernel(DxArgs a) {
                 }
                 if (MORE && t == 2 && q >= NM - 2 * RB) {
                     const int e = q - (NM - 2 * RB);
-                    rawn[e / 2][e % 2] = *reinterpret_cast<const u32x4 *>(nxt + qa[e / 2][e % 2]);
+                    if constexpr (NEXT == 0)  // a new n tile: its code bytes
+                        rawn[e / 2][e % 2] = *reinterpret_cast<const u32x4 *>(nxt + qa[e / 2][e % 2]);
+                    else                      // the next bit-width of this n tile: the bytes at hand
+                        rawn[e / 2][e % 2] = raw[e / 2][e % 2];
                 }
                 if (MORE && t == 0 && NM - 1 - q < LPS)
                     issue_one(nt + (SLOT + 3) / NRS, std::integral_constant<int, (SLOT + 3) % NRS>{}, (st + 3) & 3, NM - 1 - q);
