@@ -56,12 +56,17 @@ __global__ __launch_bounds__(256) void affine_input_kernel(const uint16_t *__res
     const int64_t ch = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (ch >= chunks) return;
     const int k = (int)((ch * 8) % K);
-    const u32x4 x = reinterpret_cast<const u32x4 *>(X)[ch];
+    const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(X) + ch);
     float sv[8], dv[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        sv[j] = s ? s[k + j] : 1.0f;
-        dv[j] = delta ? delta[k + j] : 0.0f;
+    for (int j = 0; j < 8; ++j) sv[j] = 1.0f, dv[j] = 0.0f;
+    if (s) {  // (K is a multiple of 8 and the vectors are 16-byte aligned: two 16-byte loads each)
+        *reinterpret_cast<f32x4 *>(sv) = *reinterpret_cast<const f32x4 *>(s + k);
+        *reinterpret_cast<f32x4 *>(sv + 4) = *reinterpret_cast<const f32x4 *>(s + k + 4);
+    }
+    if (delta) {
+        *reinterpret_cast<f32x4 *>(dv) = *reinterpret_cast<const f32x4 *>(delta + k);
+        *reinterpret_cast<f32x4 *>(dv + 4) = *reinterpret_cast<const f32x4 *>(delta + k + 4);
     }
     u32x4 o;
 #pragma unroll
@@ -70,7 +75,7 @@ __global__ __launch_bounds__(256) void affine_input_kernel(const uint16_t *__res
         const float hi = __fdiv_rn(__fsub_rn(bf16_hi(x[j]), dv[2 * j + 1]), sv[2 * j + 1]);
         o[j] = pack_bf16x2(lo, hi);
     }
-    reinterpret_cast<u32x4 *>(Xt)[ch] = o;
+    __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(Xt) + ch);
 }
 
 // Column reductions.  A workgroup covers 256 columns (64 column threads x 4 columns) and one range of
@@ -145,30 +150,40 @@ __global__ __launch_bounds__(256) void colreduce_kernel(ColArgs a) {
     }
 }
 
-// out[c] = sum over the splits of partial[split][0][c] (fp64, fixed order)
-__global__ __launch_bounds__(256) void colfinish_dc_kernel(const float *partial, int splits, int cols, float *dc) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= cols) return;
+// Sum over the splits of partial[split][which][c] for 16 columns per workgroup: thread (c, q) adds the
+// splits q, q + 16, ... in fp64, the sixteen lanes of a column meet in LDS (a fixed order).
+constexpr int kFinishCols = 16;
+__device__ __forceinline__ double split_sum(const float *partial, int splits, int cols, int which, int c, int q,
+                                            double (*red)[kFinishCols]) {
     double v = 0.0;
-    for (int sp = 0; sp < splits; ++sp) v += (double)partial[(size_t)sp * 2 * cols + c];
-    dc[c] = (float)v;
+    if (c < cols)
+        for (int sp = q; sp < splits; sp += 16) v += (double)partial[((size_t)sp * 2 + which) * cols + c];
+    __syncthreads();  // (the previous use of red is over)
+    const int t = threadIdx.x & (kFinishCols - 1);
+    red[q][t] = v;
+    __syncthreads();
+    double r = 0.0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r += red[i][t];
+    return r;
+}
+
+__global__ __launch_bounds__(256) void colfinish_dc_kernel(const float *partial, int splits, int cols, float *dc) {
+    __shared__ double red[16][kFinishCols];
+    const int c = blockIdx.x * kFinishCols + (threadIdx.x & (kFinishCols - 1)), q = threadIdx.x >> 4;
+    const double v = split_sum(partial, splits, cols, 0, c, q, red);
+    if (q == 0 && c < cols) dc[c] = (float)v;
 }
 
 // ddelta_k = -(1/s_k) P0 + R0,  ds_k = -(1/s_k^2) (P1 - delta_k P0) + R1
 __global__ __launch_bounds__(256) void affine_bwd_finish_kernel(const float *px, int sx, const float *pw, int sw, int K,
                                                                 const float *s, const float *delta, float *ddelta,
                                                                 float *ds) {
-    const int k = blockIdx.x * 256 + threadIdx.x;
-    if (k >= K) return;
-    double p0 = 0.0, p1 = 0.0, r0 = 0.0, r1 = 0.0;
-    for (int sp = 0; sp < sx; ++sp) {
-        p0 += (double)px[(size_t)sp * 2 * K + k];
-        p1 += (double)px[(size_t)sp * 2 * K + K + k];
-    }
-    for (int sp = 0; sp < sw; ++sp) {
-        r0 += (double)pw[(size_t)sp * 2 * K + k];
-        r1 += (double)pw[(size_t)sp * 2 * K + K + k];
-    }
+    __shared__ double red[16][kFinishCols];
+    const int k = blockIdx.x * kFinishCols + (threadIdx.x & (kFinishCols - 1)), q = threadIdx.x >> 4;
+    const double p0 = split_sum(px, sx, K, 0, k, q, red), p1 = split_sum(px, sx, K, 1, k, q, red);
+    const double r0 = split_sum(pw, sw, K, 0, k, q, red), r1 = split_sum(pw, sw, K, 1, k, q, red);
+    if (q != 0 || k >= K) return;
     const double sv = s ? (double)s[k] : 1.0, dv = delta ? (double)delta[k] : 0.0;
     if (ddelta) ddelta[k] = (float)(-p0 / sv + r0);
     if (ds) ds[k] = (float)(-(p1 - dv * p0) / (sv * sv) + r1);
@@ -180,7 +195,7 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 inline int splits_for(int64_t rows, int64_t cols) {
     const int64_t colblocks = cdiv(cols, kColsPerBlock);
     int64_t sp = std::max<int64_t>(1, std::min<int64_t>(cdiv(2048, colblocks), cdiv(rows, 16)));
-    return (int)std::min<int64_t>(sp, 1024);
+    return (int)std::min<int64_t>(sp, 128);
 }
 
 struct AffineLayout {
@@ -230,7 +245,7 @@ extern "C" mq_status mq_affine_input(const uint16_t *X, int64_t M, int64_t K, co
     if (K % 8 != 0) return MQ_ERR_ALIGN;
     if (M == 0) return MQ_OK;
     if (!X || !Xt) return MQ_ERR_NULL;
-    if (!aligned16(X) || !aligned16(Xt)) return MQ_ERR_ALIGN;
+    if (!aligned16(X) || !aligned16(Xt) || (s && !aligned16(s)) || (delta && !aligned16(delta))) return MQ_ERR_ALIGN;
     const int64_t chunks = M * K / 8;
     affine_input_kernel<<<dim3((unsigned)cdiv(chunks, 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(
         X, chunks, (int)K, s, delta, Xt);
@@ -272,7 +287,7 @@ extern "C" mq_status mq_affine_bwd(const uint16_t *X, const uint16_t *dXt, const
     a.rows_per_split = (int)cdiv(M, lay.sdy);
     a.partial = pdy;
     colreduce_kernel<0><<<dim3((unsigned)cdiv(N, kColsPerBlock), (unsigned)lay.sdy), dim3(256), 0, st>>>(a);
-    colfinish_dc_kernel<<<dim3((unsigned)cdiv(N, 256)), dim3(256), 0, st>>>(pdy, lay.sdy, (int)N, dcv);
+    colfinish_dc_kernel<<<dim3((unsigned)cdiv(N, kFinishCols)), dim3(256), 0, st>>>(pdy, lay.sdy, (int)N, dcv);
     if (!ddelta && !ds) return launch_status();
 
     // over the tokens: sum dXt, sum dXt * X
@@ -295,7 +310,7 @@ extern "C" mq_status mq_affine_bwd(const uint16_t *X, const uint16_t *dXt, const
     w.rows_per_split = (int)cdiv(N, lay.sw);
     w.partial = pw;
     colreduce_kernel<2><<<dim3((unsigned)cdiv(K, kColsPerBlock), (unsigned)lay.sw), dim3(256), 0, st>>>(w);
-    affine_bwd_finish_kernel<<<dim3((unsigned)cdiv(K, 256)), dim3(256), 0, st>>>(px, lay.sx, pw, lay.sw, (int)K, s, delta,
+    affine_bwd_finish_kernel<<<dim3((unsigned)cdiv(K, kFinishCols)), dim3(256), 0, st>>>(px, lay.sx, pw, lay.sw, (int)K, s, delta,
                                                                                  ddelta, ds);
     return launch_status();
 }
