@@ -289,7 +289,8 @@ mq_status mq_linear_bwd_clip(const float *W, int64_t ldw, const uint16_t *X, con
  *   Ws [N, K] fp32 out or NULL;  c [N] fp32 out or NULL (at least one of the two)
  *   K and ldw multiples of 4.
  * mq_affine_input:   Xt[m,k] = bf16((X[m,k] - delta[k]) / s[k]);  X, Xt [M, K] bf16, K a multiple of 8
- *                    (s and delta 16-byte aligned like every other pointer)
+ *                    (s and delta 16-byte aligned like every other pointer; M K below 2^42 elements,
+ *                    MQ_ERR_SHAPE beyond)
  * mq_affine_bwd:     with dXt = d objective / d Xt (the dX of mq_linear_bwd), dWs = d objective / d Ws
  *                    (its dW: the straight-through estimator is the identity through the quantizer) and
  *                    dc[n] = sum_r lambda_r sum_m dY_r[m,n]:

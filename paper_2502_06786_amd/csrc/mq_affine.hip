@@ -247,6 +247,7 @@ extern "C" mq_status mq_affine_input(const uint16_t *X, int64_t M, int64_t K, co
     if (!X || !Xt) return MQ_ERR_NULL;
     if (!aligned16(X) || !aligned16(Xt) || (s && !aligned16(s)) || (delta && !aligned16(delta))) return MQ_ERR_ALIGN;
     const int64_t chunks = M * K / 8;
+    if (cdiv(chunks, 256) > 0x7FFFFFFF) return MQ_ERR_SHAPE;
     affine_input_kernel<<<dim3((unsigned)cdiv(chunks, 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(
         X, chunks, (int)K, s, delta, Xt);
     return launch_status();
