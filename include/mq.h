@@ -140,7 +140,8 @@ mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uint32_t flags
  *   Y      host array of nr device pointers, each [M, N] bf16 out
  *   ws     workspace of at least mq_workspace_bytes(MQ_OP_LINEAR_FWD, M, N, K, nr)
  * K must be a multiple of 16 and N a multiple of 8 (16-byte rows).  M is free.
- * M == 0 or N == 0 is a no-op.
+ * M == 0 or N == 0 is a no-op.  Limits (MQ_ERR_SHAPE beyond): M, N below 2^31 - 256,
+ * K <= 2^22, ceil(M / 128) * ceil(N / 128) below 2^31.
  */
 mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, const float *alpha,
                               const float *zero, int64_t M, int64_t N, int64_t K,

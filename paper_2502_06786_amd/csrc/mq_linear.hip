@@ -1312,6 +1312,7 @@ static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha
                          const FwdLoss *loss, void *ws, size_t ws_bytes, void *hip_stream) {
     if (M < 0 || N < 0 || K < 1) return MQ_ERR_SHAPE;
     if (M > 0x7FFFFF00 || N > 0x7FFFFF00 || K > (1 << 22)) return MQ_ERR_SHAPE;
+    if (cdiv(M, 128) * cdiv(N, FWD_BN) > 0x7FFFFFFF) return MQ_ERR_SHAPE;  // tiles of one launch
     mq_status s = check_rs(rs, nr);
     if (s != MQ_OK) return s;
     if (K % 16 != 0 || N % 8 != 0) return MQ_ERR_ALIGN;
