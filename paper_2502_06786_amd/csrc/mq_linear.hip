@@ -184,6 +184,28 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = lane >> 5, l32 = lane & 31;
 
+    // What the epilogue needs from the kernel arguments is fetched now, into scalar registers that stay
+    // live through the main loop: read where it is used, each costs a scalar-memory round trip with
+    // nothing to hide it (one wave per SIMD).
+    const float *k_alpha = a.alpha, *k_zero = a.zero, *k_rowsum = a.rowsum, *k_bias = LOSS ? a.bias : nullptr;
+    const uint16_t *k_T = LOSS ? a.T : nullptr;
+    uint16_t *k_Y[NR], *k_dY[NR];
+    float k_coef[NR];
+    int k_teacher[NR], k_mix = LOSS ? a.mix : 0;
+    asm volatile("" : "+s"(k_alpha), "+s"(k_zero), "+s"(k_rowsum));
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+        k_Y[i] = a.Y[i];
+        asm volatile("" : "+s"(k_Y[i]));
+        if constexpr (LOSS) {
+            k_dY[i] = a.dY[i];
+            k_coef[i] = a.coef[i];
+            k_teacher[i] = a.teacher[i];
+            asm volatile("" : "+s"(k_dY[i]), "+s"(k_coef[i]), "+s"(k_teacher[i]));
+        }
+    }
+    if constexpr (LOSS) asm volatile("" : "+s"(k_bias), "+s"(k_T), "+s"(k_mix));
+
     // XCD-aware tile order: each XCD walks groups of 4 token tiles across the channel tiles
     const uint32_t lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
     constexpr int GROUP = 4;
@@ -376,7 +398,7 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
 #pragma unroll
     for (int j = 0; j < MB; ++j) {
         const int m = m0 + j * 32 + l32;
-        rs[j] = m < a.M ? a.rowsum[m] : 0.f;
+        rs[j] = m < a.M ? k_rowsum[m] : 0.f;
     }
     f32x4 alv[4], zev[4], bv[LOSS ? 4 : 1];
 #pragma unroll
@@ -386,10 +408,10 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
         zev[g] = f32x4{0.f, 0.f, 0.f, 0.f};
         if constexpr (LOSS) bv[g] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (n0 + nloc < a.N) {
-            alv[g] = *reinterpret_cast<const f32x4 *>(a.alpha + n0 + nloc);
-            zev[g] = *reinterpret_cast<const f32x4 *>(a.zero + n0 + nloc);
+            alv[g] = *reinterpret_cast<const f32x4 *>(k_alpha + n0 + nloc);
+            zev[g] = *reinterpret_cast<const f32x4 *>(k_zero + n0 + nloc);
             if constexpr (LOSS)
-                if (a.bias) bv[g] = *reinterpret_cast<const f32x4 *>(a.bias + n0 + nloc);
+                if (k_bias) bv[g] = *reinterpret_cast<const f32x4 *>(k_bias + n0 + nloc);
         }
     }
     // LOSS: the lane's chunks of the target are requested now, behind the parameter loads, and
@@ -404,8 +426,8 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
         const int c = it * 256 + threadIdx.x;
         const int m = m0 + (c >> 4), n = n0 + (c & 15) * 8;
         tpre[it] = u32x4{0u, 0u, 0u, 0u};
-        if (a.T && m < a.M && n < a.N)
-            tpre[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.T + (size_t)m * a.N + n));
+        if (k_T && m < a.M && n < a.N)
+            tpre[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(k_T + (size_t)m * a.N + n));
     };
     if constexpr (LOSS) {
 #pragma unroll
@@ -420,14 +442,18 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
             const bool is8 = HAS8 && i == 0;
             const float mult = is8 ? 1.0f : (float)(1 << (8 - a.r[i]));
             const float bias = is8 ? 0.0f : 128.0f * mult;
+            float bz[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) bz[e] = bias + ze[e];
 #pragma unroll
             for (int j = 0; j < MB; ++j) {
                 float y[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[e] = al[e] * (mult * acc[i][j][4 * g + e] - (bias + ze[e]) * rs[j]);
-                if constexpr (LOSS) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) y[e] += bv[g][e];
+                for (int e = 0; e < 4; ++e) {
+                    // (mult is a power of two, so the fused form rounds exactly like mult * acc - t)
+                    const float t = bz[e] * rs[j];
+                    const float inner = is8 ? acc[i][j][4 * g + e] - t : __builtin_fmaf(mult, acc[i][j][4 * g + e], -t);
+                    y[e] = LOSS ? __builtin_fmaf(al[e], inner, bv[g][e]) : al[e] * inner;
                 }
                 const u32x2 o = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
                 *reinterpret_cast<u32x2 *>(smem + i * OT + (j * 32 + l32) * OS + nloc * 2) = o;
@@ -452,7 +478,7 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
                     const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
                     const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
                     __builtin_nontemporal_store(u32x4{lo.x, lo.y, hi.x, hi.y},
-                                                reinterpret_cast<u32x4 *>(a.Y[i] + (size_t)m * a.N + n));
+                                                reinterpret_cast<u32x4 *>(k_Y[i] + (size_t)m * a.N + n));
                 }
             }
         }
@@ -473,45 +499,64 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
         float cf[NR];
         uint32_t pick[NR][NR], mixed_slot[NR];
         uint16_t *pd[NR], *py[NR];
+        int stored = 0, taught = 0;  // wave-uniform: bit i = Y_i is stored / slot i has a teacher
 #pragma unroll
         for (int i = 0; i < NR; ++i) {
-            cf[i] = a.coef[i];
-            pd[i] = a.dY[i] + at0;
-            py[i] = a.Y[i] ? a.Y[i] + at0 : nullptr;
-            mixed_slot[i] = a.teacher[i] >= 0 ? 0xFFFFFFFFu : 0u;
+            cf[i] = k_coef[i];
+            pd[i] = k_dY[i] + at0;
+            py[i] = k_Y[i] ? k_Y[i] + at0 : nullptr;
+            stored |= k_Y[i] ? 1 << i : 0;
+            taught |= k_teacher[i] >= 0 ? 1 << i : 0;
+            mixed_slot[i] = k_teacher[i] >= 0 ? 0xFFFFFFFFu : 0u;
             asm volatile("" : "+v"(cf[i]), "+v"(pd[i]), "+v"(py[i]), "+v"(mixed_slot[i]));
 #pragma unroll
             for (int u = 0; u < NR; ++u) {
-                pick[i][u] = a.teacher[i] == u ? 0xFFFFFFFFu : 0u;
+                pick[i][u] = k_teacher[i] == u ? 0xFFFFFFFFu : 0u;
                 asm volatile("" : "+v"(pick[i][u]));
             }
         }
+        stored = __builtin_amdgcn_readfirstlane(stored);
+        taught = __builtin_amdgcn_readfirstlane(taught);
+        asm volatile("" : "+s"(stored), "+s"(taught));
         const size_t chunk_step = (size_t)16 * a.N;  // elements between a lane's consecutive chunks
-        // the equal-weight mix of teacher and target is a variant of the whole loop, chosen once
-        auto chunks = [&](auto mixed) {
-            constexpr bool MIX = decltype(mixed)::value;
+        // The equal-weight mix of teacher and target, and the presence of any teacher at all, are variants
+        // of the whole loop, chosen once: without teachers every bit-width is compared with the target and
+        // the selection of the reference disappears.
+        auto chunks = [&](auto mixed, auto teach) {
+            constexpr bool MIX = decltype(mixed)::value, TEACH = decltype(teach)::value;
+            // the staged values of chunk it + 1 are read (every chunk lies inside the tile) before chunk it is
+            // worked on, outside the bounds test, so that the LDS latency hides behind arithmetic
+            auto staged = [&](int it, u32x4 (&dst)[NR]) {
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    const uint8_t *src = smem + i * OT + (crow + 16 * it) * OS + cch * 16;
+                    const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
+                    const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
+                    dst[i] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                }
+            };
+            u32x4 ynext[NR];
+            staged(0, ynext);
 #pragma unroll
             for (int it = 0; it < CHUNKS; ++it) {
                 const int row = crow + 16 * it;
+                u32x4 y[NR];
+#pragma unroll
+                for (int i = 0; i < NR; ++i) y[i] = ynext[i];
+                if (it + 1 < CHUNKS) staged(it + 1, ynext);
                 if (cols_ok && m0 + row < a.M) {
-                    u32x4 y[NR];
                     const u32x4 t = tpre[it];
 #pragma unroll
                     for (int i = 0; i < NR; ++i) {
-                        const uint8_t *src = smem + i * OT + row * OS + cch * 16;
-                        const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
-                        const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
-                        y[i] = u32x4{lo.x, lo.y, hi.x, hi.y};
-                    }
-#pragma unroll
-                    for (int i = 0; i < NR; ++i) {
                         u32x4 tt = t;
+                        if constexpr (TEACH) {
 #pragma unroll
-                        for (int u = 0; u < NR; ++u)
-                            if (u != i) {
+                            for (int u = 0; u < NR; ++u)
+                                if (u != i) {
 #pragma unroll
-                                for (int j = 0; j < 4; ++j) tt[j] = (y[u][j] & pick[i][u]) | (tt[j] & ~pick[i][u]);
-                            }
+                                    for (int j = 0; j < 4; ++j) tt[j] = (y[u][j] & pick[i][u]) | (tt[j] & ~pick[i][u]);
+                                }
+                        }
                         u32x4 o;
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
@@ -528,15 +573,18 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
                             o[j] = pack_bf16x2(cf[i] * d0, cf[i] * d1);
                         }
                         __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(pd[i] + it * chunk_step));
-                        if (py[i]) __builtin_nontemporal_store(y[i], reinterpret_cast<u32x4 *>(py[i] + it * chunk_step));
+                        if (stored & (1 << i))
+                            __builtin_nontemporal_store(y[i], reinterpret_cast<u32x4 *>(py[i] + it * chunk_step));
                     }
                 }
             }
         };
-        if (a.mix)
-            chunks(std::true_type{});
+        if (k_mix)
+            chunks(std::true_type{}, std::true_type{});
+        else if (taught)
+            chunks(std::false_type{}, std::true_type{});
         else
-            chunks(std::false_type{});
+            chunks(std::false_type{}, std::false_type{});
         // workgroup sums in a fixed order; the staging tiles are dead after the barrier
         __syncthreads();
         float *red = reinterpret_cast<float *>(smem);
