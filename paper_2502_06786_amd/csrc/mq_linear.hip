@@ -1013,12 +1013,29 @@ __global__ __launch_bounds__(256) void dx_kernel(DxArgs a) {
     // ---- epilogue: rows of the product are k, columns tokens; dX = acc - c[m] --------------------
     // assembled in LDS as [token][k] bf16 (rows padded by 8 bytes) and stored as whole 512-byte rows
     __syncthreads();
+    // c[m] = sum over the column ranges of the prep kernel, in their order.  The partial sums of all the
+    // lane's tokens are requested four ranges at a time (20 loads in flight: one memory round trip per
+    // group instead of one per value, which with nothing else to run cost more than the stores).
+    float cs[MB];
+#pragma unroll
+    for (int j = 0; j < MB; ++j) cs[j] = 0.f;
+    for (int sp0 = 0; sp0 < a.nsplit; sp0 += 4) {
+        float part[4][MB];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int j = 0; j < MB; ++j) {
+                const int m = m0 + j * 32 + l32;
+                part[u][j] = (sp0 + u < a.nsplit && m < a.M) ? a.cvec[(size_t)(sp0 + u) * a.M + m] : 0.f;
+            }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int j = 0; j < MB; ++j) cs[j] += part[u][j];
+    }
 #pragma unroll
     for (int j = 0; j < MB; ++j) {
-        const int m = m0 + j * 32 + l32;
-        float c = 0.f;
-        if (m < a.M)
-            for (int sp = 0; sp < a.nsplit; ++sp) c += a.cvec[(size_t)sp * a.M + m];
+        const float c = cs[j];
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
