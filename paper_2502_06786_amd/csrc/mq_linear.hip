@@ -1212,24 +1212,53 @@ __global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
     tile(std::false_type{}, nmt - 1, cb);
     wait_vm0();  // zero-fill loads of dead stages must have landed before the workgroup ends
 
-    // rows of the product are n, columns k: 32 consecutive k (one 128-byte line) per row and half-wave
+    // Rows of the product are n, columns k: a store instruction writes 32 consecutive k (one 128-byte line)
+    // of two rows.  Branch-free: every store goes through a buffer descriptor that starts at the first
+    // element of the wave's 32-row block and ends with dW, so rows past N fall out of range and are
+    // dropped by the memory unit; a column past K is sent out of range explicitly.  The row part of the
+    // address (wave-uniform) travels in the scalar offset, the lane part in one register per k block.
+    // All workgroups of a round reach this point together, so the phase lasts as long as the memory takes
+    // to absorb their 50 MB (about 10 us); when accumulating, the old values of four rows are requested
+    // together, one memory round trip per 24 values.
+    auto store_tile = [&](auto accumulate_tag) {
+        constexpr bool ACCUMULATE = decltype(accumulate_tag)::value;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+        for (int rb = 0; rb < RB; ++rb) {
+            const int nb = n0 + wave * 64 + rb * 32;
+            const int64_t left = ((int64_t)a.N - nb) * a.K - k0;  // elements from (nb, k0) to the end of dW
+            const __amdgpu_buffer_rsrc_t rW =
+                make_rsrc(a.dW + (int64_t)nb * a.K + k0, left > 0 ? (uint64_t)left * 4u : 0u);
+            uint32_t voff[MB];
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+            for (int j = 0; j < MB; ++j)
+                voff[j] = k0 + j * 32 + l32 < a.K ? ((uint32_t)(4 * h) * (uint32_t)a.K + (uint32_t)(j * 32 + l32)) * 4u : kOOB;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int n = n0 + wave * 64 + rb * 32 + 8 * g + 4 * h + e;
-                if (n >= a.N) continue;
+            for (int g = 0; g < 4; ++g) {
+                uint32_t old[ACCUMULATE ? 4 : 1][MB];
+                if constexpr (ACCUMULATE) {  // the 24 values of four rows are requested together
 #pragma unroll
-                for (int j = 0; j < MB; ++j) {
-                    const int k = k0 + j * 32 + l32;
-                    if (k >= a.K) continue;
-                    float *p = a.dW + (size_t)n * a.K + k;
-                    const float v = acc[rb][j][4 * g + e];
-                    *p = a.accumulate ? *p + v : v;
+                    for (int e = 0; e < 4; ++e)
+#pragma unroll
+                        for (int j = 0; j < MB; ++j)
+                            old[e][j] = __builtin_amdgcn_raw_buffer_load_b32(rW, voff[j], (uint32_t)(8 * g + e) * (uint32_t)a.K * 4u, 0);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t row = (uint32_t)(8 * g + e) * (uint32_t)a.K * 4u;
+#pragma unroll
+                    for (int j = 0; j < MB; ++j) {
+                        float v = acc[rb][j][4 * g + e];
+                        if constexpr (ACCUMULATE) v = __uint_as_float(old[e][j]) + v;
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rW, voff[j], row, 0);
+                    }
                 }
             }
+        }
+    };
+    if (a.accumulate)
+        store_tile(std::true_type{});
+    else
+        store_tile(std::false_type{});
 #else
     (void)a;
 #endif
