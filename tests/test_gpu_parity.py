@@ -487,6 +487,7 @@ FUSED_L2_CASES = [
     (1, 8, 16, (2,), None, False, False),
     (520, 392, 64, (6, 3), (-1, 0), False, False),
     (72, 200, 96, (8, 4), (1, 0), False, False),        # every bit-width has a teacher: no target is read
+    (96, 72, 80, (8, 4, 2), None, True, False),         # the mix flag without any teacher changes nothing
 ]
 
 
