@@ -213,7 +213,11 @@ def main():
     if not args.no_probes:
         peaks = measured_peaks(torch, mq)
         out["measured_peaks"] = peaks
+        # against the probe with the kernel's own product shape and occupancy, and against the best any bf16
+        # loop sustains on this GPU on such operands (16x16x32 products, two waves per SIMD)
         roofline["frac_of_measured"] = round(achieved / peaks["mfma_bf16_normal_operands_TFLOPs"], 4)
+        roofline["frac_of_best_measured"] = round(
+            achieved / max(peaks["mfma_bf16_normal_operands_TFLOPs"], peaks["mfma16_bf16_normal_operands_TFLOPs"]), 4)
     if not args.no_gemv_sweep:
         out["gemv_roofline"] = gemv_sweep(torch, mq, synth)
         out["extra_precision_gemv"] = ep_gemv(torch, mq, synth)
@@ -260,6 +264,10 @@ def measured_peaks(torch, mq):
         "mfma_bf16_normal_operands_TFLOPs": round(timed(lambda: mq.mq_probe_mfma(normal, 30000, sink)) / 1e12, 1),
         "mfma_bf16_constant_operands_TFLOPs": round(timed(lambda: mq.mq_probe_mfma(const, 30000, sink)) / 1e12, 1),
     }
+    sink16 = torch.empty(131072, dtype=torch.float32, device="cuda")
+    mq.mq_probe_mfma16(normal, 2000, sink16)
+    res["mfma16_bf16_normal_operands_TFLOPs"] = round(timed(lambda: mq.mq_probe_mfma16(normal, 30000, sink16)) / 1e12, 1)
+    res["mfma16_bf16_constant_operands_TFLOPs"] = round(timed(lambda: mq.mq_probe_mfma16(const, 30000, sink16)) / 1e12, 1)
     big = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
     isink = torch.zeros(1, dtype=torch.int32, device="cuda")
     mq.mq_probe_read(big, isink)
@@ -280,8 +288,9 @@ def measured_peaks(torch, mq):
         return 8 * nb
     replay()
     res["hbm_read_85MB_GBs"] = round(timed(replay, reps=5) / 1e9, 1)
-    res["note"] = ("library probes mq_probe_mfma (1024 waves, 12 accumulators each, ~10 ms) and mq_probe_read; "
-                   "published peaks: 2500 TFLOP/s, 8000 GB/s")
+    res["note"] = ("library probes mq_probe_mfma (32x32x16 products, 1024 waves, 12 accumulators each, ~10 ms: the "
+                   "shape and occupancy of the fused kernels), mq_probe_mfma16 (16x16x32 products, 2048 waves, 24 "
+                   "accumulators each) and mq_probe_read; published peaks: 2500 TFLOP/s, 8000 GB/s")
     return res
 
 

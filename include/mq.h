@@ -376,10 +376,14 @@ mq_status mq_gated_unit_bwd(const uint16_t *const *GU, const uint16_t *const *dA
  *   operands_bf16  device, 32768 bf16 values (64 KB) the products are fed with: their bit patterns
  *                  set the power the loop draws, hence the clock it sustains
  *   sink           device [65536] float, overwritten
+ * mq_probe_mfma16: the same loop with 16x16x32 bf16 products, 256 workgroups of two waves per SIMD, 24
+ *   independent accumulators per wave = 256 * 8 * iters * 24 * 16384 flops.
+ *   operands_bf16  as above;  sink  device [131072] float, overwritten
  * mq_probe_read: reads `bytes` (a multiple of 16) from src once with 16-byte loads.
  *   sink           device [1] uint32, practically never written
  */
 mq_status mq_probe_mfma(const uint16_t *operands_bf16, int64_t iters, float *sink, void *hip_stream);
+mq_status mq_probe_mfma16(const uint16_t *operands_bf16, int64_t iters, float *sink, void *hip_stream);
 mq_status mq_probe_read(const void *src, int64_t bytes, uint32_t *sink, void *hip_stream);
 
 /* Bytes of workspace `op` needs at these sizes (0 on invalid arguments).  MQ_OP_FFN_DECODE: M = B, N = F, K = d. */

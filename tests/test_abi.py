@@ -37,6 +37,7 @@ def lib():
     lib_.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
     lib_.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
+    lib_.mq_probe_mfma16.argtypes = [vp, i64, vp, vp]
     lib_.mq_matquant_l2_loss.argtypes = [vp, vp, ctypes.POINTER(ci), vp, i64, i64, ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp,
                                             ctypes.POINTER(ci), vp, vp, vp, vp, vp, sz, vp]
@@ -160,6 +161,7 @@ def test_dense_extra_precision_argument_checks(lib):
 
 def test_probe_argument_checks(lib):
     assert lib.mq_probe_mfma(None, 10, None, None) == NULL
+    assert lib.mq_probe_mfma16(None, 10, None, None) == NULL
     assert lib.mq_probe_read(None, 1024, None, None) == NULL
 
 

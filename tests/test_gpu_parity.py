@@ -818,6 +818,10 @@ def test_measurement_probes_run(mq):
     assert flops == 256 * 4 * 8 * 12 * 32768
     torch.cuda.synchronize()
     assert torch.isfinite(sink).all() and sink.abs().sum() > 0
+    sink16 = torch.zeros(131072, dtype=torch.float32, device="cuda")
+    assert mq.mq_probe_mfma16(ops, 8, sink16) == 256 * 8 * 8 * 24 * 16384
+    torch.cuda.synchronize()
+    assert torch.isfinite(sink16).all() and sink16.abs().sum() > 0
     src = torch.arange(1 << 20, dtype=torch.int32).to(torch.uint8).cuda()
     assert mq.mq_probe_read(src) == src.numel()
     torch.cuda.synchronize()
