@@ -98,9 +98,7 @@ constexpr int line_bytes(int r) { return (r == 6 || r == 3) ? 96 : 128; }
 constexpr int piece_bytes(int r) { return line_bytes(r) / 8; }
 constexpr int line_codes(int r) { return line_bytes(r) * 8 / r; }            // k values per line
 constexpr int operands_per_piece(int r) { return line_codes(r) / 8 / 8; }    // XV
-struct __attribute__((packed, aligned(4))) Piece12 {
-    uint32_t a, b, c;
-};
+typedef uint32_t u32x3_a4 __attribute__((ext_vector_type(3), aligned(4)));  // a 12-byte piece as one load
 
 // Order in which the 32 codes of a 3-bit piece (12 bytes) enter its four matrix-core operands:
 // kOrder3[8 v + 2 p + h] = code that operand v holds in half h of register p.  Codes that sit at the
@@ -452,13 +450,14 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
 #pragma unroll
             for (int rg = 0; rg < RG; ++rg) {
                 if constexpr (PIECE == 16) {
-                    dst[0][rg] = *reinterpret_cast<const u32x4 *>(wbase + (roff[rg][0] + o));
-                    dst[1][rg] = *reinterpret_cast<const u32x4 *>(wbase + (roff[rg][1] + o));
+                    // (non-temporal: every weight byte is read once)
+                    dst[0][rg] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wbase + (roff[rg][0] + o)));
+                    dst[1][rg] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wbase + (roff[rg][1] + o)));
                 } else {  // 12-byte pieces, 4-byte aligned
-                    const Piece12 p0 = *reinterpret_cast<const Piece12 *>(wbase + (roff[rg][0] + o));
-                    const Piece12 p1 = *reinterpret_cast<const Piece12 *>(wbase + (roff[rg][1] + o));
-                    dst[0][rg] = u32x4{p0.a, p0.b, p0.c, 0u};
-                    dst[1][rg] = u32x4{p1.a, p1.b, p1.c, 0u};
+                    const u32x3_a4 p0 = __builtin_nontemporal_load(reinterpret_cast<const u32x3_a4 *>(wbase + (roff[rg][0] + o)));
+                    const u32x3_a4 p1 = __builtin_nontemporal_load(reinterpret_cast<const u32x3_a4 *>(wbase + (roff[rg][1] + o)));
+                    dst[0][rg] = u32x4{p0.x, p0.y, p0.z, 0u};
+                    dst[1][rg] = u32x4{p1.x, p1.y, p1.z, 0u};
                 }
             }
             off += KS * LINEB;

@@ -34,6 +34,7 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr uint32_t kE128 = 0x43004300u, kE32 = 0x42004200u, kE8 = 0x41004100u;  // (128,128) (32,32) (8,8)
 constexpr uint32_t kOutOfRange = 0x80000000u;
+constexpr int kStreamed = 2;  // cache policy of the weight loads: non-temporal (each byte is read once; measured 7-9 % more read bandwidth)
 constexpr int kSumsBytes = 1024;  // float [16 waves][4 batch entries][2]
 constexpr int kTileBytes = 2048;  // per wave
 constexpr int kXPad = 32;         // row pitch of the staged activations = whole 1 KB blocks + this (bank shift per batch entry)
@@ -184,8 +185,8 @@ __global__ __launch_bounds__(512) void gemv_quad_kernel(GemvArgs a, int KS, int 
         const uint32_t p_a = (uint32_t)max(min(lb + lp0 * 16, a.KB - 16), 0);
         const uint32_t p_b = (uint32_t)max(min(lb + lp1 * 16, a.KB - 16), 0);
         uint8_t *dst = ring + islot * kTileBytes;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt, (lds_ptr)dst, 16, (r_a + p_a) | gone, sbase, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt, (lds_ptr)(dst + 1024), 16, (r_b + p_b) | gone, sbase, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt, (lds_ptr)dst, 16, (r_a + p_a) | gone, sbase, 0, kStreamed);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt, (lds_ptr)(dst + 1024), 16, (r_b + p_b) | gone, sbase, 0, kStreamed);
         if (++iln == NL) {
             iln = 0;
             if (++ivisit >= nv) ivisit = 0, ++iround;
