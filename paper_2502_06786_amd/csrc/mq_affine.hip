@@ -24,7 +24,7 @@ __global__ __launch_bounds__(256) void affine_weight_kernel(const float *__restr
     const float *w = W + (size_t)n * ldw;
     float dot = 0.f;
     for (int k = threadIdx.x * 4; k < K; k += 1024) {
-        const f32x4 wv = *reinterpret_cast<const f32x4 *>(w + k);
+        const f32x4 wv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(w + k));
         if (Ws) {
             f32x4 o = wv;
             if (s) {
@@ -107,15 +107,15 @@ __global__ __launch_bounds__(256) void colreduce_kernel(ColArgs a) {
         for (int r = r0 + rt; r < r1; r += 4) {
             if (MODE == 0) {
                 for (int i = 0; i < a.nr; ++i) {
-                    const u32x2 v = *reinterpret_cast<const u32x2 *>(a.A16[i] + (size_t)r * a.cols + col);
+                    const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(a.A16[i] + (size_t)r * a.cols + col));
                     s0[0] += a.lam[i] * bf16_lo(v.x);
                     s0[1] += a.lam[i] * bf16_hi(v.x);
                     s0[2] += a.lam[i] * bf16_lo(v.y);
                     s0[3] += a.lam[i] * bf16_hi(v.y);
                 }
             } else if (MODE == 1) {
-                const u32x2 g = *reinterpret_cast<const u32x2 *>(a.A16[0] + (size_t)r * a.cols + col);
-                const u32x2 x = *reinterpret_cast<const u32x2 *>(a.A16[1] + (size_t)r * a.cols + col);
+                const u32x2 g = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(a.A16[0] + (size_t)r * a.cols + col));
+                const u32x2 x = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(a.A16[1] + (size_t)r * a.cols + col));
                 const float gv[4] = {bf16_lo(g.x), bf16_hi(g.x), bf16_lo(g.y), bf16_hi(g.y)};
                 const float xv[4] = {bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y)};
 #pragma unroll
@@ -124,8 +124,8 @@ __global__ __launch_bounds__(256) void colreduce_kernel(ColArgs a) {
                     s1[j] += gv[j] * xv[j];
                 }
             } else {
-                const f32x4 w = *reinterpret_cast<const f32x4 *>(a.A32[0] + (size_t)r * a.ld32 + col);
-                const f32x4 g = *reinterpret_cast<const f32x4 *>(a.A32[1] + (size_t)r * a.cols + col);
+                const f32x4 w = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.A32[0] + (size_t)r * a.ld32 + col));
+                const f32x4 g = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.A32[1] + (size_t)r * a.cols + col));
                 const float f = a.rowvec[r];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {

@@ -40,9 +40,9 @@ __global__ __launch_bounds__(256) void clip_reduce_kernel(ClipArgs a) {
     const int s = 8 - a.r, half = (1 << s) >> 1, top = (1 << a.r) - 1;
     float sa = 0.f, sz = 0.f, mn = INFINITY, mx = -INFINITY;
     for (int k = threadIdx.x * 4; k < a.K; k += 1024) {
-        const f32x4 wv = *reinterpret_cast<const f32x4 *>(w + k);
-        const f32x4 gv = *reinterpret_cast<const f32x4 *>(g + k);
-        const uint32_t qv = *reinterpret_cast<const uint32_t *>(q + k);
+        const f32x4 wv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(w + k));
+        const f32x4 gv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(g + k));
+        const uint32_t qv = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(q + k));
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             // the quantizer's own operations, in its order, decide whether its clamp acted

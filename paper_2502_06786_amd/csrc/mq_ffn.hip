@@ -36,7 +36,8 @@ __global__ __launch_bounds__(256) void gate_train_kernel(GateArgs a) {
     const int64_t ch = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (ch >= a.chunks) return;
     for (int i = 0; i < a.nr; ++i) {
-        const u32x4 p0 = reinterpret_cast<const u32x4 *>(a.GU[i])[2 * ch], p1 = reinterpret_cast<const u32x4 *>(a.GU[i])[2 * ch + 1];
+        const u32x4 p0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.GU[i]) + 2 * ch);
+        const u32x4 p1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.GU[i]) + 2 * ch + 1);
         const uint32_t pairs[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};  // (gate, up) per dword
         if constexpr (!BWD) {
             u32x4 o;
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(256) void gate_train_kernel(GateArgs a) {
             }
             reinterpret_cast<u32x4 *>(a.out[i])[ch] = o;
         } else {
-            const u32x4 d = reinterpret_cast<const u32x4 *>(a.dA[i])[ch];
+            const u32x4 d = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.dA[i]) + ch);
             uint32_t o[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {

@@ -680,7 +680,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(PrepArgs a) {
             u32x4 dy[3];
 #pragma unroll
             for (int i = 0; i < 3; ++i)
-                if (i < a.nr) dy[i] = *reinterpret_cast<const u32x4 *>(a.dY[i] + (size_t)m * a.N + n);
+                if (i < a.nr) dy[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.dY[i] + (size_t)m * a.N + n));
 #pragma unroll
             for (int i = 0; i < 3; ++i) {
                 if (i >= a.nr) break;
@@ -738,7 +738,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in
         const int r = t >> 2, chunk = t & 3;
         if (c0 + chunk * E < cols) {
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (r0 + r < rows) v = *reinterpret_cast<const u32x4 *>(in + (size_t)(r0 + r) * cols + c0 + chunk * E);
+            if (r0 + r < rows) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(in + (size_t)(r0 + r) * cols + c0 + chunk * E));
             T e[E];
             __builtin_memcpy(e, &v, 16);
 #pragma unroll

@@ -37,8 +37,8 @@ __global__ __launch_bounds__(kLossBlock) void l2_loss_kernel(LossArgs a) {
         u32x4 y[3], t = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < 3; ++i)
-            if (i < a.nr) y[i] = reinterpret_cast<const u32x4 *>(a.Y[i])[ch];
-        if (a.target) t = reinterpret_cast<const u32x4 *>(a.target)[ch];
+            if (i < a.nr) y[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.Y[i]) + ch);
+        if (a.target) t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.target) + ch);
 #pragma unroll
         for (int i = 0; i < 3; ++i) {
             if (i >= a.nr) break;
