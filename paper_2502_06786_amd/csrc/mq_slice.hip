@@ -168,30 +168,34 @@ __global__ __launch_bounds__(256) void overflow_count_kernel(const uint8_t *__re
     }
 }
 
-// Single block, in place: row_ptr[1..N] counts -> inclusive prefix sums; *nnz = total.
+// Single block, in place: row_ptr[1..N] counts -> inclusive prefix sums; *nnz = total.  Every thread sums
+// its run of counts, the 1024 sums are scanned inside the waves with lane shuffles and across the 16 waves
+// through LDS (two barriers in all).
 __global__ __launch_bounds__(1024) void overflow_scan_kernel(int32_t *__restrict__ row_ptr, int64_t N,
                                                              int64_t *__restrict__ nnz) {
-    __shared__ int64_t part[1024];
+    __shared__ int64_t wave_total[16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t per = (N + 1023) / 1024;
     const int64_t lo = 1 + threadIdx.x * per;
     const int64_t hi = lo + per < N + 1 ? lo + per : N + 1;
     int64_t sum = 0;
     for (int64_t i = lo; i < hi; ++i) sum += row_ptr[i];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    // Hillis-Steele inclusive scan over the 1024 partial sums
-    for (int o = 1; o < 1024; o <<= 1) {
-        int64_t add = threadIdx.x >= (unsigned)o ? part[threadIdx.x - o] : 0;
-        __syncthreads();
-        part[threadIdx.x] += add;
-        __syncthreads();
+    int64_t incl = sum;  // inclusive scan over the lanes of the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int64_t up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
     }
-    int64_t run = threadIdx.x ? part[threadIdx.x - 1] : 0;
+    if (lane == 63) wave_total[wave] = incl;
+    __syncthreads();
+    int64_t before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_total[w];
+    int64_t run = before + incl - sum;  // total of the threads before this one
     for (int64_t i = lo; i < hi; ++i) {
         run += row_ptr[i];
         row_ptr[i] = (int32_t)run;
     }
-    if (threadIdx.x == 1023) *nnz = part[1023];
+    if (threadIdx.x == 1023) *nnz = before + incl;
 }
 
 // One block per row: columns with code >= thr, ascending, written at row_ptr[n] (bounded by capacity).
