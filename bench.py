@@ -211,7 +211,8 @@ def main():
         "roofline": roofline,
     }
     if not args.no_probes:
-        peaks = measured_peaks(torch, mq)
+        from paper_2502_06786_amd import bench_probes
+        peaks = measured_peaks(torch, bench_probes)
         out["measured_peaks"] = peaks
         # against the probe with the kernel's own product shape and occupancy, and against the best any bf16
         # loop sustains on this GPU on such operands (16x16x32 products, two waves per SIMD)
@@ -359,7 +360,8 @@ def ep_gemv(torch, mq, synth):
     overflow list, and the dense 3-bit extra-precision plane.  Seven copies of each plane in turn (more than
     the last-level cache holds), HIP-graph replay, time per call."""
     N, K, r = 36864, 4608, 2
-    q = synth.planted_overflow_codes(55, N, K, r, 0.05).cuda()
+    # codes from 256 - half up round to 2^r: the overflow bucket of the errata section
+    q = synth.planted_codes(55, N, K, 256 - (1 << (8 - r)) // 2, 0.05).cuda()
     plain, ovf = mq.mq_slice(q, r, packed=True, extra_precision=True, capacity=N * K // 8)
     dense = mq.mq_slice(q, r, packed=True, extra_precision=True, dense_ep=True)
     torch.cuda.synchronize()

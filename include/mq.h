@@ -44,7 +44,8 @@ typedef enum {
     MQ_ERR_BITS = 3,      /* r outside the accepted set, duplicate r, nr out of range      */
     MQ_ERR_ALIGN = 4,     /* pointer not 16-byte aligned or a row length not a legal multiple */
     MQ_ERR_WORKSPACE = 5, /* workspace NULL or smaller than mq_workspace_bytes()           */
-    MQ_ERR_CAPACITY = 6,  /* reserved: overflow-list capacity (see mq_overflow.nnz)         */
+    MQ_ERR_CAPACITY = 6,  /* mq_overflow.capacity negative.  A capacity that turns out too
+                             small is not an error of the call: see mq_overflow.nnz          */
     MQ_ERR_DEVICE = 7     /* a HIP call failed (launch error)                              */
 } mq_status;
 
@@ -73,7 +74,10 @@ typedef struct {
     int64_t *nnz;      /* device scalar, out: total size of the set.  If it exceeds
                           `capacity`, col_idx holds only the first `capacity` entries in
                           row order and row_ptr still describes the full set; the caller
-                          must check after the stream has completed.                      */
+                          checks after the stream has completed.  mq_gemv_sliced given
+                          such a list uses exactly the entries that were stored (list
+                          positions >= capacity are dropped, nothing past col_idx is
+                          read).                                                          */
 } mq_overflow;
 
 /*
@@ -161,6 +165,7 @@ mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, const float *
  *   dW      [N, K] fp32 out (accumulated into with MQ_FLAG_ACCUM_DW), or NULL to skip
  *   ws      workspace of at least mq_workspace_bytes(MQ_OP_LINEAR_BWD, M, N, K, nr)
  * K must be a multiple of 16 and N a multiple of 16.  M is free.
+ * M == 0: dW (a sum over no tokens) is set to zero unless MQ_FLAG_ACCUM_DW; N == 0: dX is set to zero.
  * The bf16 rounding of lambda_i * alpha_n * dY_i (dX) and of
  * sum_i lambda_i dY_i (dW) before the matrix-core contraction is part of the
  * stated tolerance.
@@ -179,8 +184,9 @@ mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const float *alpha,
  *   x       [B, K] bf16, 1 <= B <= 16
  *   packed  [N, K*r/8] as written by mq_slice with MQ_FLAG_PACKED, r in {8, 6, 4, 3, 2}
  *   alpha_bf16, zero_bf16  [N] bf16
- *   ovf     host struct or NULL (= plain slice); row_ptr/col_idx as written by mq_slice
- *           with nnz <= capacity
+ *   ovf     host struct or NULL (= plain slice); row_ptr/col_idx as written by mq_slice, capacity =
+ *           entries col_idx holds (list positions beyond it are ignored; negative: MQ_ERR_CAPACITY);
+ *           nnz is not read
  *   y       [B, N] bf16 out
  * A packed row must be a whole number of 16-byte units (K*r a multiple of 128 bits; for
  * r = 6 and r = 3 of 12-byte units, K*r a multiple of 96 bits; else MQ_ERR_ALIGN); B*K <= 2^29 and, with an overflow list, K <= 65536 (else MQ_ERR_SHAPE).
@@ -366,25 +372,6 @@ mq_status mq_gated_unit_fwd(const uint16_t *const *GU, int nr, int64_t M, int64_
                             uint16_t *const *A, void *hip_stream);
 mq_status mq_gated_unit_bwd(const uint16_t *const *GU, const uint16_t *const *dA, int nr, int64_t M,
                             int64_t F, uint32_t flags, uint16_t *const *dGU, void *hip_stream);
-
-/*
- * Measurement helpers (they compute nothing of the method): ceilings of this GPU as measured by
- * kernels that only multiply or only read, to put next to the published peaks.
- *
- * mq_probe_mfma: 256 workgroups of one wave per SIMD run `iters` rounds of 12 independent
- *   32x32x16 bf16 matrix-core products per wave = 256 * 4 * iters * 12 * 32768 flops.
- *   operands_bf16  device, 32768 bf16 values (64 KB) the products are fed with: their bit patterns
- *                  set the power the loop draws, hence the clock it sustains
- *   sink           device [65536] float, overwritten
- * mq_probe_mfma16: the same loop with 16x16x32 bf16 products, 256 workgroups of two waves per SIMD, 24
- *   independent accumulators per wave = 256 * 8 * iters * 24 * 16384 flops.
- *   operands_bf16  as above;  sink  device [131072] float, overwritten
- * mq_probe_read: reads `bytes` (a multiple of 16) from src once with 16-byte loads.
- *   sink           device [1] uint32, practically never written
- */
-mq_status mq_probe_mfma(const uint16_t *operands_bf16, int64_t iters, float *sink, void *hip_stream);
-mq_status mq_probe_mfma16(const uint16_t *operands_bf16, int64_t iters, float *sink, void *hip_stream);
-mq_status mq_probe_read(const void *src, int64_t bytes, uint32_t *sink, void *hip_stream);
 
 /* Bytes of workspace `op` needs at these sizes (0 on invalid arguments).  MQ_OP_FFN_DECODE: M = B, N = F, K = d. */
 size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int nr);

@@ -2,7 +2,8 @@
 // products, and on a kernel that does nothing but read.  They put the roofline fractions of the
 // method's kernels next to a measured ceiling as well as the published one; they compute nothing
 // of the method.
-#include "mq_common.h"
+#include "../csrc/mq_common.h"
+#include "probes.h"
 
 namespace mq {
 
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4 *__restrict
 
 }  // namespace mq
 
-extern "C" mq_status mq_probe_mfma(const uint16_t *operands_bf16, int64_t iters, float *sink, void *hip_stream) {
+extern "C" int mq_probe_mfma(const uint16_t *operands_bf16, int64_t iters, float *sink, void *hip_stream) {
     using namespace mq;
     if (!operands_bf16 || !sink) return MQ_ERR_NULL;
     if (iters < 1 || iters > (1ll << 24)) return MQ_ERR_SHAPE;
@@ -94,7 +95,7 @@ extern "C" mq_status mq_probe_mfma(const uint16_t *operands_bf16, int64_t iters,
     return launch_status();
 }
 
-extern "C" mq_status mq_probe_mfma16(const uint16_t *operands_bf16, int64_t iters, float *sink, void *hip_stream) {
+extern "C" int mq_probe_mfma16(const uint16_t *operands_bf16, int64_t iters, float *sink, void *hip_stream) {
     using namespace mq;
     if (!operands_bf16 || !sink) return MQ_ERR_NULL;
     if (iters < 1 || iters > (1ll << 24)) return MQ_ERR_SHAPE;
@@ -104,7 +105,7 @@ extern "C" mq_status mq_probe_mfma16(const uint16_t *operands_bf16, int64_t iter
     return launch_status();
 }
 
-extern "C" mq_status mq_probe_read(const void *src, int64_t bytes, uint32_t *sink, void *hip_stream) {
+extern "C" int mq_probe_read(const void *src, int64_t bytes, uint32_t *sink, void *hip_stream) {
     using namespace mq;
     if (!src || !sink) return MQ_ERR_NULL;
     if (bytes < 16 || (bytes & 15)) return MQ_ERR_SHAPE;

@@ -30,7 +30,7 @@ MQ_FLAG_FFN_SILU = 16
 MQ_FLAG_FFN_RESIDUAL = 32
 
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
-           "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string", "mq_probe_mfma", "mq_probe_mfma16", "mq_probe_read",
+           "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string",
            "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2", "mq_linear_bwd_clip",
            "mq_affine_weight", "mq_affine_input", "mq_affine_bwd", "mq_gated_unit_fwd", "mq_gated_unit_bwd"]
 
@@ -71,8 +71,6 @@ def _load() -> ctypes.CDLL:
     lib.mq_status_string.restype = ctypes.c_char_p
     lib.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
-    lib.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
-    lib.mq_probe_mfma16.argtypes = [vp, i64, vp, vp]
     lib.mq_matquant_l2_loss.argtypes = [ctypes.POINTER(vp), vp, ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_float), i64,
                                         i64, ci, u32, ctypes.POINTER(vp), vp, vp, sz, vp]
     lib.mq_gated_unit_fwd.argtypes = [ctypes.POINTER(vp), ci, i64, i64, u32, ctypes.POINTER(vp), vp]
@@ -87,7 +85,6 @@ def _load() -> ctypes.CDLL:
     lib.mq_linear_bwd_clip.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float),
                                        i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, vp, vp, sz, vp]
     lib.mq_ffn_mixnmatch.argtypes = [vp, ctypes.POINTER(_FfnLayer), ci, i64, i64, i64, u32, vp, vp, sz, vp]
-    lib.mq_probe_read.argtypes = [vp, i64, vp, vp]
     for name in EXPORTS:
         if name not in ("mq_workspace_bytes", "mq_status_string"):
             getattr(lib, name).restype = ci
@@ -185,35 +182,6 @@ def mq_gemv_sliced_dense_ep(x, packed, alpha_bf16, zero_bf16, r: int, K: int, y=
                                       _ptr(zero_bf16, torch.bfloat16), B, N, K, r, _ptr(y, torch.bfloat16), _stream())
     _check(st, "mq_gemv_sliced_dense_ep")
     return y
-
-
-def mq_probe_mfma(operands, iters: int, sink=None):
-    """Measurement helper: `iters` rounds of 12 bf16 32x32x16 products per wave on 1024 waves, fed with the
-    32768 bf16 values of `operands`.  Returns the flop count of the launch."""
-    assert operands.numel() >= 32768
-    sink = torch.empty(65536, dtype=torch.float32, device=operands.device) if sink is None else sink
-    st = _lib.mq_probe_mfma(_ptr(operands, torch.bfloat16), int(iters), _ptr(sink, torch.float32), _stream())
-    _check(st, "mq_probe_mfma")
-    return 256 * 4 * int(iters) * 12 * 32 * 32 * 16 * 2
-
-
-def mq_probe_mfma16(operands, iters: int, sink=None):
-    """Measurement helper: `iters` rounds of 24 bf16 16x16x32 products per wave on 2048 waves (two per SIMD),
-    fed with the 32768 bf16 values of `operands`.  Returns the flop count of the launch."""
-    assert operands.numel() >= 32768
-    sink = torch.empty(131072, dtype=torch.float32, device=operands.device) if sink is None else sink
-    assert sink.numel() >= 131072
-    st = _lib.mq_probe_mfma16(_ptr(operands, torch.bfloat16), int(iters), _ptr(sink, torch.float32), _stream())
-    _check(st, "mq_probe_mfma16")
-    return 256 * 8 * int(iters) * 24 * 16 * 16 * 32 * 2
-
-
-def mq_probe_read(src, sink=None):
-    """Measurement helper: one kernel that reads every byte of `src` (uint8, a multiple of 16 bytes) once."""
-    sink = torch.zeros(1, dtype=torch.int32, device=src.device) if sink is None else sink
-    st = _lib.mq_probe_read(_ptr(src, torch.uint8), src.numel(), _ptr(sink, torch.int32), _stream())
-    _check(st, "mq_probe_read")
-    return src.numel()
 
 
 def mq_slice(Q, r: int, packed: bool = False, extra_precision: bool = False, out=None, ovf: Overflow | None = None,

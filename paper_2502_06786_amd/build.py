@@ -8,7 +8,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmq.so")
-SOURCES = ["mq_quantize.hip", "mq_slice.hip", "mq_gemv.hip", "mq_gemv_quad.hip", "mq_linear.hip", "mq_ffn.hip", "mq_loss.hip", "mq_clip.hip", "mq_affine.hip", "mq_probe.hip"]
+# measurement-only kernels used by bench.py (matrix-core and read ceilings): a library of their own
+PROBE_DIR = os.path.join(HERE, "bench_probes")
+PROBE_LIB = os.path.join(PROBE_DIR, "libmq_probe.so")
+SOURCES = ["mq_quantize.hip", "mq_slice.hip", "mq_gemv.hip", "mq_gemv_quad.hip", "mq_linear.hip", "mq_ffn.hip", "mq_loss.hip", "mq_clip.hip", "mq_affine.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -19,7 +22,7 @@ HIPCC_FLAGS = [
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every HIP source and link the shared library; returns its path."""
+    """Compile every HIP source, link libmq.so and the bench-only libmq_probe.so; returns the path of libmq.so."""
     objs = []
     procs = []
     for src in SOURCES:
@@ -29,6 +32,10 @@ def build(verbose: bool = False) -> str:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
+    cmd = ["hipcc", *HIPCC_FLAGS, "-shared", os.path.join(PROBE_DIR, "probes.hip"), "-o", PROBE_LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    procs.append(("probes.hip", subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     failed = False
     for src, p in procs:
         out, _ = p.communicate()

@@ -100,6 +100,10 @@ extern "C" mq_status mq_ffn_mixnmatch(const uint16_t *x, const mq_ffn_layer *lay
         const mq_ffn_layer &L = layers[l];
         if (L.r != 8 && L.r != 6 && L.r != 4 && L.r != 3 && L.r != 2) return MQ_ERR_BITS;
         if (!L.gate_up || !L.down || !L.alpha_gu || !L.zero_gu || !L.alpha_dn || !L.zero_dn) return MQ_ERR_NULL;
+        // both products of the layer are checked now, so that no layer is enqueued when a later one is refused
+        mq_status s = gemv_sliced_check(L.gate_up, B, 2 * F, d, L.r, kPostGelu);
+        if (s == MQ_OK) s = gemv_sliced_check(L.down, B, d, F, L.r, kPostNone);
+        if (s != MQ_OK) return s;
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (n_layers == 0) {

@@ -12,6 +12,7 @@ struct GemvArgs {
     const uint16_t *zero;     // [N] bf16
     const int32_t *row_ptr;   // [N + 1] or null
     const uint16_t *col_idx;  // overflow columns
+    int ovf_cap;              // entries col_idx holds: list positions at or beyond it are never read
     uint16_t *y;              // [B, N] bf16
     int B, N, K;
     int KB;       // bytes per packed row
@@ -47,6 +48,10 @@ __device__ __forceinline__ uint16_t residual_bf16(uint16_t res, float o) {
 mq_status gemv_sliced_post(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                            const uint16_t *zero_bf16, int64_t B, int64_t N, int64_t K, int r, uint16_t *y, int post,
                            const uint16_t *res, void *hip_stream);
+
+// The host-side checks of such a call that do not involve x or y (callers that enqueue several
+// GEMVs run them for every one before the first launch).
+mq_status gemv_sliced_check(const uint8_t *packed, int64_t B, int64_t N, int64_t K, int r, int post);
 
 // Small-batch kernel (B <= 4, r = 4 or 2, no overflow list): activations live in registers.
 // Returns MQ_OK with *handled = false when the shape is outside what it covers.

@@ -9,7 +9,6 @@
 // AND-OR per two codes does the unpack; the constant 2^(7-p) offsets are summed by one extra
 // matrix-core product with a constant operand and subtracted in the epilogue.
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 
 #include "mq_gemv.h"
@@ -539,7 +538,9 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
             const int ra = nb + wave * rpw;
             const int nrows = min(rpw, a.N - ra);  // wave-uniform
             if (nrows > 0) {
-                const int myrp = lane <= nrows ? a.row_ptr[ra + lane] : 0x7FFFFFFF;
+                // (a list that mq_slice had to cut short keeps row pointers of the full set: positions
+                // past the capacity of col_idx are dropped here, never read)
+                const int myrp = lane <= nrows ? min(a.row_ptr[ra + lane], a.ovf_cap) : 0x7FFFFFFF;
                 const int e0 = __builtin_amdgcn_readlane(myrp, 0), e1 = __builtin_amdgcn_readlane(myrp, nrows);
                 // x[b, k] as staged: block k / 512 of entry b, 16-byte slot (k % 512) / 8 kept at
                 // slot ^ b, and inside the slot (or the pair of slots, int2) the order the pairing
@@ -752,10 +753,7 @@ static mq_status launch_gemv(const GemvArgs &a, int nw, int ks, hipStream_t st) 
     const int rw = nw / ks;
     const int ngroups = (int)cdiv(a.N, 16 * RG * rw);
     // resident workgroups: 16 waves and 160 KB of LDS per compute unit, 256 compute units
-    int wpc = 16;
-#ifdef MQ_GEMV_TUNE
-    if (const char *e = getenv("MQ_GEMV_WPC")) wpc = atoi(e);
-#endif
+    const int wpc = 16;
     const int per_cu = std::max(1, std::min(wpc / nw, (int)((160 * 1024) / lds)));
     const int capacity = 256 * per_cu;
     const int rounds = (ngroups + capacity - 1) / capacity;
@@ -772,25 +770,38 @@ static mq_status launch_gemv(const GemvArgs &a, int nw, int ks, hipStream_t st) 
 
 }  // namespace mq
 
+// Everything about one GEMV that can be refused before a launch and does not depend on x or y: bit-width,
+// sizes, row alignment of the plane, the plane pointer.  `post` as in GemvArgs.
+mq_status mq::gemv_sliced_check(const uint8_t *packed, int64_t B, int64_t N, int64_t K, int r, int post) {
+    if (post >= kPostGelu && N % 2 != 0) return MQ_ERR_SHAPE;
+    if (r != 8 && r != 6 && r != 4 && r != 3 && r != 2) return MQ_ERR_BITS;
+    if (B < 1 || B > 16 || N < 0 || K < 1 || N > 0x7FFFFFF0 || K > 0x7FFFFFF0) return MQ_ERR_SHAPE;
+    if (B * K > (1ll << 29)) return MQ_ERR_SHAPE;  // 32-bit byte offsets into x
+    // packed rows are whole 16-byte units (12-byte units for the bit streams of r = 6 and r = 3)
+    if ((K * r) % (8 * piece_bytes(r)) != 0) return MQ_ERR_ALIGN;
+    if (N == 0) return MQ_OK;
+    if (!packed) return MQ_ERR_NULL;
+    if (!aligned16(packed)) return MQ_ERR_ALIGN;
+    return MQ_OK;
+}
+
 // r = bits per stored code, shift = s of the grid the codes live on (8 - r for a plain plane)
 static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                                const uint16_t *zero_bf16, const mq_overflow *ovf, int64_t B, int64_t N, int64_t K,
                                int r, int shift, uint16_t *y, void *hip_stream, int post = mq::kPostNone,
                                const uint16_t *res = nullptr) {
     using namespace mq;
-    if (post >= kPostGelu && (N % 2 != 0 || ovf)) return MQ_ERR_SHAPE;
     if (post == kPostResidual && !res && N > 0) return MQ_ERR_NULL;
-    if (r != 8 && r != 6 && r != 4 && r != 3 && r != 2) return MQ_ERR_BITS;
-    if (B < 1 || B > 16 || N < 0 || K < 1 || N > 0x7FFFFFF0 || K > 0x7FFFFFF0) return MQ_ERR_SHAPE;
     if (ovf && K > 65536) return MQ_ERR_SHAPE;
-    if (B * K > (1ll << 29)) return MQ_ERR_SHAPE;  // 32-bit byte offsets into x
+    if (post >= kPostGelu && ovf) return MQ_ERR_SHAPE;
+    const mq_status cs = gemv_sliced_check(packed, B, N, K, r, post);
+    if (cs != MQ_OK) return cs;
     const int64_t kb = K * r / 8;
-    // packed rows are whole 16-byte units (12-byte units for the bit streams of r = 6 and r = 3)
-    if ((K * r) % (8 * piece_bytes(r)) != 0) return MQ_ERR_ALIGN;
     if (N == 0) return MQ_OK;
-    if (!x || !packed || !alpha_bf16 || !zero_bf16 || !y) return MQ_ERR_NULL;
+    if (!x || !alpha_bf16 || !zero_bf16 || !y) return MQ_ERR_NULL;
     if (ovf && (!ovf->row_ptr || !ovf->col_idx)) return MQ_ERR_NULL;
-    if (!aligned16(x) || !aligned16(packed)) return MQ_ERR_ALIGN;
+    if (ovf && ovf->capacity < 0) return MQ_ERR_CAPACITY;
+    if (!aligned16(x)) return MQ_ERR_ALIGN;
 
     GemvArgs a;
     a.x = x;
@@ -799,6 +810,7 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     a.zero = zero_bf16;
     a.row_ptr = ovf ? ovf->row_ptr : nullptr;
     a.col_idx = ovf ? ovf->col_idx : nullptr;
+    a.ovf_cap = ovf ? (int)std::min<int64_t>(ovf->capacity, 0x7FFFFFFF) : 0;
     a.y = y;
     a.B = (int)B;
     a.N = (int)N;
@@ -819,10 +831,7 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     // tall matrices take two row groups; short ones keep RG = 1 for more waves (measured on the decode
     // shapes at B = 4 and 16: 4096 rows run 10-25 % faster with RG = 1, 14336 rows level or faster with 2).
     // With an overflow list the waves of a group walk the list together: two row groups from B = 3 on.
-    int rg = ovf ? (B > 2 ? 2 : 1) : (N >= 8192 ? 2 : 1);
-#ifdef MQ_GEMV_TUNE
-    if (const char *e = getenv("MQ_GEMV_RG")) rg = atoi(e);
-#endif
+    const int rg = ovf ? (B > 2 ? 2 : 1) : (N >= 8192 ? 2 : 1);
     // K-split: about 2048 waves in total (8 per compute unit measured best across the decode shapes:
     // enough loads in flight, and the whole grid resident at once) when there are few row blocks,
     // none when the rows alone provide them.  Workgroups have 8 waves (KS of them per row block),
@@ -833,12 +842,7 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     // (short matrices with batched activations: shorter slices pay off; at 14336 rows they cost 15-25 %)
     const int64_t wave_budget = (B >= 4 && rg == 1) ? 4096 : 2048;
     while (ks < 16 && row_blocks * ks * 2 <= wave_budget && 2 * ks <= segs) ks <<= 1;
-    int nw = ks > 8 ? ks : 8;
-#ifdef MQ_GEMV_TUNE
-    if (const char *e = getenv("MQ_GEMV_KS")) ks = atoi(e);
-    if (const char *e = getenv("MQ_GEMV_NW")) nw = atoi(e);
-    if (nw < ks) nw = ks;
-#endif
+    const int nw = ks > 8 ? ks : 8;
 #define MQ_GEMV_CASE(R_, RG_, D_) \
     if (r == R_ && rg == RG_) return launch_gemv<R_, RG_, D_>(a, nw, ks, st);
     MQ_GEMV_CASE(2, 1, 3) MQ_GEMV_CASE(2, 2, 2)

@@ -373,13 +373,7 @@ mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handl
     const int nrb = (a.N + 15) / 16;
     // Measured against the general kernel on 4096..36864 rows: 0.85-0.9x the time at 36864 x 4608, level or
     // slower at 14336 rows and below, where a launch is bound by latencies and not by bytes.
-    auto env = [](const char *name, int fallback) {
-#ifdef MQ_GEMV_TUNE
-        if (const char *e = getenv(name)) return atoi(e);
-#endif
-        return fallback;
-    };
-    if (nrb < env("MQ_GEMVQ_MINRB", 1024)) return MQ_OK;
+    if (nrb < 1024) return MQ_OK;
     // Lines per slice: no padded lines if possible, then about four slices per row (measured over the
     // decode shapes: fewer leave a workgroup with too few waves, more spend their time filling activation
     // registers), one round.
@@ -391,7 +385,7 @@ mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handl
             const int cost = pad * 8 + (nsl > 8 ? 4 : 0) + std::abs(nsl - 4);
             if (best < 0 || cost < best_cost) best = nl, best_cost = cost;
         }
-        p.nl = env("MQ_GEMVQ_NL", best);
+        p.nl = best;
         if (p.nl < 1 || p.nl > 4) return MQ_ERR_SHAPE;
     }
     p.nsl = (lines + p.nl - 1) / p.nl;
@@ -404,18 +398,17 @@ mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handl
                 p.ks = d;
                 break;
             }
-    p.ks = env("MQ_GEMVQ_KS", p.ks);
     if (p.ks < 1 || p.ks > 8) return MQ_ERR_SHAPE;
-    const int wpc = env("MQ_GEMVQ_WPC", 12);  // waves per compute unit the grid is sized for
+    const int wpc = 12;  // waves per compute unit the grid is sized for
     // Row-block waves per workgroup and row blocks per workgroup: the whole grid resident at once
     // (wpc waves per compute unit), every wave the same number of visits where the shape allows.
-    p.rw = env("MQ_GEMVQ_RW", 1);
+    p.rw = 1;
     if (p.rw < 1 || p.rw * p.ks > 8) return MQ_ERR_SHAPE;
     const int nw = p.ks * p.rw;
     const int per_cu = std::max(1, wpc / nw);
     const int capacity = 256 * per_cu;
     const int visits = (int)cdiv(nrb, (int64_t)capacity * p.rw);  // per wave and round
-    p.ch = env("MQ_GEMVQ_CH", visits * p.rw);
+    p.ch = visits * p.rw;
     if (p.ch < 1) return MQ_ERR_SHAPE;
     p.grid = (int)cdiv(nrb, p.ch);
     p.ch = (int)cdiv(nrb, p.grid);  // (the most row blocks any workgroup gets)
@@ -429,7 +422,6 @@ mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handl
         p.depth = d;
         break;
     }
-    p.depth = env("MQ_GEMVQ_S", p.depth);
     if (p.depth == 0) return MQ_OK;
     p.lds = fixed + (size_t)nw * p.depth * kTileBytes;
     if (p.lds > 160 * 1024 || (int64_t)a.N * a.KB > 0x7FFFFFFFll || (int64_t)a.B * a.K * 2 > 0x7FFFFFFFll)

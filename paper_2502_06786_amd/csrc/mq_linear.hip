@@ -1,9 +1,10 @@
 // mq_linear_fwd_multi / mq_linear_bwd: the nested quantized linear on the bf16 matrix cores.
 //
 // Forward (MatQuant objective, section 3.2: the same input goes through the layer once per
-// bit-width): ONE pass over X and the int8 codes.  Each workgroup stages a [256 x 64] bf16 tile of
-// X and a [128 x 64] tile of int8 codes in LDS (direct global->LDS loads, double buffered), every
-// wave turns its codes into one bf16 operand per requested bit-width in registers and issues
+// bit-width): ONE pass over X and the int8 codes.  A workgroup (256 threads, one wave per SIMD) owns
+// 128 output channels x 32 MB tokens (MB = 4 or 5); four LDS stages of a [32 MB x 64] bf16 tile of X
+// and a [128 x 64] tile of int8 codes are filled by direct global->LDS loads, every wave turns the
+// codes of its 32 channels into one bf16 operand per requested bit-width in registers and issues
 // 32x32x16 MFMAs into one accumulator set per bit-width.
 //
 //   r = 8     : int8 -> fp32 -> bf16 (exact, codes <= 255).
@@ -1501,6 +1502,12 @@ static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha
     return launch_status();
 }
 
+// 16-byte chunks of zeros (a kernel, not a memset node: callers may capture the stream into a graph)
+__global__ __launch_bounds__(256) void zero_fill_kernel(u32x4 *__restrict__ dst, int64_t chunks) {
+    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < chunks; c += (int64_t)gridDim.x * 256)
+        dst[c] = u32x4{0u, 0u, 0u, 0u};
+}
+
 }  // namespace mq
 
 extern "C" mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, const float *alpha,
@@ -1530,7 +1537,23 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
     mq_status s = check_rs(rs, nr);
     if (s != MQ_OK) return s;
     if (K % 16 != 0 || N % 16 != 0) return MQ_ERR_ALIGN;
-    if (M == 0 || N == 0) return MQ_OK;  // note: with M == 0 and no ACCUM flag dW is left untouched
+    if (M == 0 || N == 0) {
+        // empty sums: dW (over no tokens) and dX (over no channels) are zero
+        hipStream_t st0 = static_cast<hipStream_t>(hip_stream);
+        const bool zero_dw = M == 0 && N > 0 && dW && !(flags & MQ_FLAG_ACCUM_DW), zero_dx = N == 0 && M > 0 && dX;
+        if (!zero_dw && !zero_dx) return MQ_OK;
+        if (M == 0 && N > 0 && dW && !(flags & MQ_FLAG_ACCUM_DW)) {
+            if (!aligned16(dW)) return MQ_ERR_ALIGN;
+            zero_fill_kernel<<<dim3((unsigned)std::min<int64_t>(cdiv(N * K / 4, 256), 65536)), dim3(256), 0, st0>>>(
+                reinterpret_cast<u32x4 *>(dW), N * K / 4);
+        }
+        if (N == 0 && M > 0 && dX) {
+            if (!aligned16(dX)) return MQ_ERR_ALIGN;
+            zero_fill_kernel<<<dim3((unsigned)std::min<int64_t>(cdiv(M * K / 8, 256), 65536)), dim3(256), 0, st0>>>(
+                reinterpret_cast<u32x4 *>(dX), M * K / 8);
+        }
+        return launch_status();
+    }
     if (!dY) return MQ_ERR_NULL;
     for (int i = 0; i < nr; ++i) {
         if (!dY[i]) return MQ_ERR_NULL;

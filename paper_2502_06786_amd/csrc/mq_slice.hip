@@ -283,8 +283,8 @@ extern "C" mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uin
     if (ep && !dense_ep) {
         if (!ovf) return MQ_ERR_NULL;
         if (N > 0 && (!ovf->row_ptr || !ovf->nnz || (ovf->capacity > 0 && !ovf->col_idx))) return MQ_ERR_NULL;
-        if (ovf->capacity < 0 || K > 65536 || N > 0x7FFFFFFE || (N > 0 && K > 0x7FFFFFFF / N))
-            return MQ_ERR_SHAPE;
+        if (ovf->capacity < 0) return MQ_ERR_CAPACITY;
+        if (K > 65536 || N > 0x7FFFFFFE || (N > 0 && K > 0x7FFFFFFF / N)) return MQ_ERR_SHAPE;
     }
     if (N == 0 || K == 0) {
         return MQ_OK;

@@ -97,20 +97,19 @@ def uniform_codes(seed: int, N: int, K: int) -> torch.Tensor:
     return torch.randint(0, 256, (N, K), generator=g, dtype=torch.int32).to(torch.uint8)
 
 
-def planted_overflow_codes(seed: int, N: int, K: int, r: int, frac: float) -> torch.Tensor:
-    """int8 codes in which a Bernoulli(frac) subset falls in the overflow bucket of an r-bit slice.
+def planted_codes(seed: int, N: int, K: int, first_hot: int, frac: float) -> torch.Tensor:
+    """int8 codes in which a Bernoulli(frac) subset is uniform on first_hot..255 and the rest uniform on
+    0..first_hot-1.
 
-    The paper's trained extra-precision models put about 2-5 % of the weights in
-    that bucket (Table 7, average bits minus r); min-max quantized random
-    weights put almost none there, so the sparse path is exercised with planted
-    codes instead.
+    The caller chooses `first_hot` (the tests pass the first code of the overflow bucket of the slice they
+    exercise: the paper's trained extra-precision models put about 2-5 % of the weights there, Table 7,
+    while min-max quantized random weights put almost none).  No method arithmetic happens here.
     """
     g = torch.Generator(device="cpu")
     g.manual_seed(seed)
-    first_overflow = 256 - (1 << (8 - r)) // 2
-    q = torch.randint(0, first_overflow, (N, K), generator=g, dtype=torch.int32)
+    q = torch.randint(0, first_hot, (N, K), generator=g, dtype=torch.int32)
     hot = torch.rand(N, K, generator=g) < frac
-    q[hot] = torch.randint(first_overflow, 256, (int(hot.sum()),), generator=g, dtype=torch.int32)
+    q[hot] = torch.randint(first_hot, 256, (int(hot.sum()),), generator=g, dtype=torch.int32)
     return q.to(torch.uint8)
 
 

@@ -36,8 +36,6 @@ def lib():
     lib_.mq_gemv_sliced.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
     lib_.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
-    lib_.mq_probe_mfma.argtypes = [vp, i64, vp, vp]
-    lib_.mq_probe_mfma16.argtypes = [vp, i64, vp, vp]
     lib_.mq_matquant_l2_loss.argtypes = [vp, vp, ctypes.POINTER(ci), vp, i64, i64, ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_linear_fwd_multi_l2.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp,
                                             ctypes.POINTER(ci), vp, vp, vp, vp, vp, sz, vp]
@@ -49,7 +47,6 @@ def lib():
     lib_.mq_linear_bwd_clip.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32,
                                         vp, vp, vp, vp, vp, sz, vp]
     lib_.mq_ffn_mixnmatch.argtypes = [vp, vp, ci, i64, i64, i64, u32, vp, vp, sz, vp]
-    lib_.mq_probe_read.argtypes = [vp, i64, vp, vp]
     lib_.mq_workspace_bytes.argtypes = [ci, i64, i64, i64, ci]
     lib_.mq_workspace_bytes.restype = sz
     lib_.mq_status_string.argtypes = [ci]
@@ -159,10 +156,20 @@ def test_dense_extra_precision_argument_checks(lib):
     assert s(None, 4, 64, 2, 11, None, None, None) == NULL                  # fine up to the pointers (no list needed)
 
 
-def test_probe_argument_checks(lib):
-    assert lib.mq_probe_mfma(None, 10, None, None) == NULL
-    assert lib.mq_probe_mfma16(None, 10, None, None) == NULL
-    assert lib.mq_probe_read(None, 1024, None, None) == NULL
+def test_probe_library_argument_checks():
+    """The measurement-only library of bench.py loads, exports what its header declares and checks its arguments."""
+    import re
+    from paper_2502_06786_amd import build as mq_build
+    hdr = open(os.path.join(mq_build.PROBE_DIR, "probes.h")).read()
+    declared = set(re.findall(r"\b(mq_probe_\w+)\s*\(", hdr))
+    plib = ctypes.CDLL(mq_build.PROBE_LIB)
+    assert declared == {"mq_probe_mfma", "mq_probe_mfma16", "mq_probe_read"}
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+    for name in declared:
+        getattr(plib, name).argtypes = [vp, i64, vp, vp]
+    assert plib.mq_probe_mfma(None, 10, None, None) == NULL
+    assert plib.mq_probe_mfma16(None, 10, None, None) == NULL
+    assert plib.mq_probe_read(None, 1024, None, None) == NULL
 
 
 def test_ffn_mixnmatch_argument_checks(lib):
@@ -184,6 +191,26 @@ def test_ffn_mixnmatch_argument_checks(lib):
     assert f(x, bad_bits, 1, 1, 256, 512, 0, y, None, 0, None) == BITS
     assert f(x, nulls, 1, 1, 256, 512, 0, y, None, 0, None) == NULL
     assert f(x, nulls, 1, 1, 256, 512, 0, x, None, 0, None) == SHAPE        # y aliases x
+    # every layer is checked before the first launch: a second layer with a misaligned plane (first layer fine)
+    # is refused with its own status, not with the launch error the first layer would meet without a GPU
+    p = 1 << 20
+    good = Layer(p, p, p, p, p, p, 4)
+    odd_plane = Layer(p + 4, p, p, p, p, p, 4)
+    two = (Layer * 2)(good, odd_plane)
+    assert f(x, two, 2, 1, 256, 512, 0, y, None, 0, None) == ALIGN
+    two = (Layer * 2)(good, Layer(p, p, p, p, p, p, 2))       # d = 96: 384 bits per row at int4, 192 at int2
+    assert f(x, two, 2, 1, 96, 512, 0, y, None, 0, None) == ALIGN
+
+
+def test_overflow_capacity_checks(lib):
+    class Ovf(ctypes.Structure):
+        _fields_ = [("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("capacity", ctypes.c_int64),
+                    ("nnz", ctypes.c_void_p)]
+
+    p = 1 << 20
+    neg = Ovf(p, p, -1, p)
+    assert lib.mq_slice(p, 4, 64, 2, 1 | 2, p, ctypes.byref(neg), None) == CAPACITY
+    assert lib.mq_gemv_sliced(p, p, p, p, ctypes.byref(neg), 1, 64, 256, 2, p, None) == CAPACITY
 
 
 def test_l2_loss_argument_checks(lib):

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.util import bf16_bits, rel_l2
+from tests.util import bf16_bits, first_overflow_code, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -160,7 +160,7 @@ def test_extra_precision_gemv_27b_shape(mq, oracle, name):
     del W
     a16, z16 = mq.mq_params_to_bf16(alpha, zero)
     ab, zb = bf16_bits(a16), bf16_bits(z16)
-    for label, codes in (("minmax", Q), ("planted5pct", synth.planted_overflow_codes(55, N, K, 2, 0.05).cuda())):
+    for label, codes in (("minmax", Q), ("planted5pct", synth.planted_codes(55, N, K, first_overflow_code(2), 0.05).cuda())):
         packed, ovf = mq.mq_slice(codes, 2, packed=True, extra_precision=True, capacity=N * K // 8)
         torch.cuda.synchronize()
         qn = codes.cpu().numpy()

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.util import bf16_bits, rel_l2
+from tests.util import bf16_bits, first_overflow_code, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -273,7 +273,7 @@ def test_gemv_plain(mq, oracle, N, K, r):
 def test_gemv_extra_precision(mq, oracle, r, frac):
     from paper_2502_06786_amd import synth
     N, K = 300, 1024
-    q = synth.uniform_codes(9, N, K) if frac == 0.125 else synth.planted_overflow_codes(9, N, K, r, frac)
+    q = synth.uniform_codes(9, N, K) if frac == 0.125 else synth.planted_codes(9, N, K, first_overflow_code(r), frac)
     a = (torch.rand(N, generator=torch.Generator().manual_seed(4)) * 1e-3 + 1e-4).to(torch.bfloat16)
     z = (torch.rand(N, generator=torch.Generator().manual_seed(5)) * 255).to(torch.bfloat16)
     packed, ovf = mq.mq_slice(dev(q), r, packed=True, extra_precision=True)
@@ -296,7 +296,7 @@ def test_dense_extra_precision_plane_and_gemv(mq, oracle, r):
     """One plane of r + 1 bits per code holding the unclamped extra-precision codes, and the GEMV that reads it."""
     from paper_2502_06786_amd import synth
     N, K = 200, 1536
-    q = synth.uniform_codes(40 + r, N, K) if r != 2 else synth.planted_overflow_codes(41, N, K, 2, 0.05)
+    q = synth.uniform_codes(40 + r, N, K) if r != 2 else synth.planted_codes(41, N, K, first_overflow_code(2), 0.05)
     a = (torch.rand(N, generator=torch.Generator().manual_seed(8)) * 1e-3 + 1e-4).to(torch.bfloat16)
     z = (torch.rand(N, generator=torch.Generator().manual_seed(9)) * 255).to(torch.bfloat16)
     dense = mq.mq_slice(dev(q), r, packed=True, extra_precision=True, dense_ep=True)
@@ -811,7 +811,8 @@ def test_clip_factor_calibration_reduces_the_int2_loss(mq):
     assert float(gamma.mean()) < 0.99 and float(beta.mean()) < 0.99      # the range was clipped
 
 
-def test_measurement_probes_run(mq):
+def test_measurement_probes_run():
+    from paper_2502_06786_amd import bench_probes as mq
     ops = torch.randn(32768, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).cuda()
     sink = torch.zeros(65536, dtype=torch.float32, device="cuda")
     flops = mq.mq_probe_mfma(ops, 8, sink)

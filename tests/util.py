@@ -23,3 +23,9 @@ def rel_l2(got: np.ndarray, want: np.ndarray) -> float:
     den = np.linalg.norm(want.ravel())
     num = np.linalg.norm((got - want).ravel())
     return float(num / den) if den > 0 else float(num)
+
+
+def first_overflow_code(r: int) -> int:
+    """Smallest 8-bit code whose r-bit slice rounds up to 2^r (errata section: q / 2^(8-r) + 1/2 >= 2^r),
+    i.e. 256 - 2^(8-r)/2.  Used only to plant test inputs; the expected values come from the oracle."""
+    return 256 - (1 << (8 - r)) // 2
