@@ -1,19 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the nested quantized linear hot path on one MI355X.
 
-One step = one pass of the whole hot path over the Gemma-2-2B-shaped MLP (d_model 2304, ffn 9216,
-4096 tokens; seeded synthetic weights and activations already resident in HBM): for each of the
-three linears (gate, up, down) quantize the fp32 master weight to int8 codes, slice and pack the
-r = 4 and r = 2 planes (r = 2 also with the extra-precision overflow list), run the fused
-r = 8/4/2 forward with the L2 reconstruction objective of the three outputs against the output of
-the full-precision layer evaluated in its epilogue (losses and the gradients dY_r; the outputs
-themselves are not stored, the training step has no other use for them) and the straight-through
+One step = one pass of the whole hot path over the Gemma-2-9B-shaped MLP of the workload list (d_model 3584,
+ffn 14336, 8192 tokens, weights N(0, 0.015^2) with 0.1 % outliers, loss weights (0.1, 0.1, 1.0) of appendix B;
+seeded synthetic tensors already resident in HBM): for each of the three linears (gate, up, down) quantize the
+fp32 master weight to int8 codes, slice and pack the r = 4 and r = 2 planes (r = 2 also with the extra-precision
+overflow list), run the fused r = 8/4/2 forward with the L2 reconstruction objective of the three outputs
+against the output of the full-precision layer evaluated in its epilogue (losses and the gradients dY_r; the
+outputs themselves are not stored, the training step has no other use for them) and the straight-through
 backward (dX, dW), round alpha/z to bf16 and run the decode GEMV at B = 1, 4, 16 on the int4 and int2 planes.
 
-`value` is the forward + backward matrix-core work of the step (6 MNK + 8 MNK flops per linear)
-divided by the wall time of the WHOLE step, so the bandwidth-bound operations count against it.
-Per-operation figures from HIP events recorded inside the timed region are reported next to it,
-and `roofline` prices the fused forward kernel against the bf16 MFMA peak.
+`value` is the metric's first half: the fused r = 8/4/2 forward in TFLOP/s (6 M N K flops per linear over the
+HIP-event time of the three forward calls of a step, averaged over the timed steps); `roofline` prices it
+against the bf16 matrix-core peak per linear.  The metric's second half, the sliced int2 GEMV in GB/s against
+the HBM peak, is `gemv_roofline` (7B decode shapes, cache-defeating copies).  `ms_per_step` is the wall time of
+the whole step; `step_blended_TFLOPs` divides all matrix-core work of the step (forward 6 MNK + backward 8 MNK)
+by it, so the bandwidth-bound operations count against that figure.
 """
 from __future__ import annotations
 
@@ -29,10 +31,13 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-# HBM-side bytes per launch of the fused forward kernel on this workload (average of the three
-# linears), from the FETCH_SIZE / WRITE_SIZE counter passes summarised in
-# profiles/hot_path_step_gemma2b_mlp_hbm_traffic.txt (FETCH_SIZE scaled by 2.00, WRITE_SIZE by 1.00).
-FWD_TRAFFIC_BYTES = (393924 + 165941) * 1024
+# HBM-side bytes per launch of the fused forward kernel on the headline workload, per linear, from the
+# FETCH_SIZE / WRITE_SIZE counter passes summarised in profiles/ (scale factors stated there); None until taken.
+FWD_TRAFFIC_BYTES = {3: {"gate": None, "up": None, "down": None}, 2: {"gate": None, "up": None, "down": None}}
+WORKLOADS = {
+    3: "configs[2]: Gemma-2-9B-shaped MLP, d_model 3584, ffn 14336, 8192 tokens, outlier weights, lambda = (0.1, 0.1, 1.0)",
+    2: "configs[1]: Gemma-2-2B-shaped MLP, d_model 2304, ffn 9216, 4096 tokens",
+}
 
 
 def parse():
@@ -40,8 +45,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, choices=(2, 3),
+                    help="workload of the step: 3 = the Gemma-2-9B-shaped MLP (headline), 2 = the 2B-shaped one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gemv-sweep", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the 27B-shaped forward block and the added operations")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured-ceiling probes")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 256 MiB device-to-device copies before the timed region: a kernel of "
@@ -52,9 +60,9 @@ def parse():
 class Linear:
     """Device buffers of one linear of the MLP; everything is allocated before the timed region."""
 
-    def __init__(self, mq, torch, synth, name, M, rs, lambdas):
+    def __init__(self, mq, torch, synth, config, name, M, rs, lambdas):
         dev = "cuda"
-        case = synth.linear_case(2, name)
+        case = synth.linear_case(config, name, with_grads=False)
         self.name, self.M, self.N, self.K, self.rs, self.lambdas = name, M, case.N, case.K, rs, lambdas
         N, K = self.N, self.K
         self.W = case.W.to(dev)
@@ -76,8 +84,20 @@ class Linear:
         self.dW = torch.empty(N, K, dtype=torch.float32, device=dev)
         self.ws_f = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD_L2, M, N, K, len(rs)), dtype=torch.uint8, device=dev)
         self.ws_b = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, M, N, K, len(rs)), dtype=torch.uint8, device=dev)
-        self.xdec = {B: synth.activations(2, f"dec{B}:" + name, B, K).to(dev) for B in (1, 4, 16)}
+        self.xdec = {B: synth.activations(config, f"dec{B}:" + name, B, K).to(dev) for B in (1, 4, 16)}
         self.ydec = {B: torch.empty(B, N, dtype=torch.bfloat16, device=dev) for B in (1, 4, 16)}
+
+
+def event_ms(torch, fn, reps):
+    """Average HIP-event time of `reps` calls of fn on the current stream (after one untimed call)."""
+    fn()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
 
 
 def main():
@@ -92,14 +112,15 @@ def main():
 
     mq.lib()  # fails loudly when libmq.so is missing
     torch.cuda.set_device(0)
-    rs, lambdas = (8, 4, 2), synth.LAMBDAS[2]
-    _, M = synth.mlp_shapes(2)
-    layers = [Linear(mq, torch, synth, name, M, rs, lambdas) for name in ("gate", "up", "down")]
+    cfg = args.config
+    rs, lambdas = (8, 4, 2), synth.LAMBDAS[cfg]
+    _, M = synth.mlp_shapes(cfg)
+    layers = [Linear(mq, torch, synth, cfg, name, M, rs, lambdas) for name in ("gate", "up", "down")]
 
     ops = ["quantize", "slice", "fwd", "bwd", "gemv"]
-    records = {op: [] for op in ops}   # (start event, end event) pairs inside the timed region
+    records = {op: [] for op in ops}   # (linear, start event, end event) inside the timed region
 
-    def timed(op, fn, rec):
+    def timed(op, L, fn, rec):
         if not rec:
             fn()
             return
@@ -107,30 +128,30 @@ def main():
         a.record()
         fn()
         b.record()
-        records[op].append((a, b))
+        records[op].append((L.name, a, b))
 
     def step(rec):
         for L in layers:
-            timed("quantize", lambda: mq.mq_quantize_int8(L.W, Q=L.Q, alpha=L.alpha, zero=L.zero), rec)
+            timed("quantize", L, lambda: mq.mq_quantize_int8(L.W, Q=L.Q, alpha=L.alpha, zero=L.zero), rec)
 
             def do_slice():
                 mq.mq_slice(L.Q, 4, packed=True, out=L.p4)
                 mq.mq_slice(L.Q, 2, packed=True, extra_precision=True, out=L.p2, ovf=L.ovf2)
                 mq.mq_params_to_bf16(L.alpha, L.zero, L.alpha16, L.zero16)
-            timed("slice", do_slice, rec)
+            timed("slice", L, do_slice, rec)
             # forward for r = 8, 4, 2 with the L2 reconstruction losses against y' and the gradients the
             # backward consumes formed in its epilogue
-            timed("fwd", lambda: mq.mq_linear_fwd_multi_l2(L.X, L.Q, L.alpha, L.zero, rs, L.T, None, lambdas,
-                                                           dY=L.dY, losses=L.losses, ws=L.ws_f), rec)
+            timed("fwd", L, lambda: mq.mq_linear_fwd_multi_l2(L.X, L.Q, L.alpha, L.zero, rs, L.T, None, lambdas,
+                                                              dY=L.dY, losses=L.losses, ws=L.ws_f), rec)
             # (the dY_r of the objective already carry lambda_r: the backward takes them unweighted)
-            timed("bwd", lambda: mq.mq_linear_bwd(L.X, L.Q, L.alpha, L.zero, L.dY, None, rs, dX=L.dX, dW=L.dW,
-                                                  ws=L.ws_b), rec)
+            timed("bwd", L, lambda: mq.mq_linear_bwd(L.X, L.Q, L.alpha, L.zero, L.dY, None, rs, dX=L.dX, dW=L.dW,
+                                                     ws=L.ws_b), rec)
 
             def do_gemv():
                 for B in (1, 4, 16):
                     mq.mq_gemv_sliced(L.xdec[B], L.p4, L.alpha16, L.zero16, 4, L.K, y=L.ydec[B])
                     mq.mq_gemv_sliced(L.xdec[B], L.p2, L.alpha16, L.zero16, 2, L.K, y=L.ydec[B])
-            timed("gemv", do_gemv, rec)
+            timed("gemv", L, do_gemv, rec)
 
     if args.copy_calibration:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
@@ -152,14 +173,17 @@ def main():
 
     mnk = sum(L.M * L.N * L.K for L in layers)
     flops_fwd, flops_bwd = 6.0 * mnk, 8.0 * mnk
-    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
 
-    op_ms = {op: sum(a.elapsed_time(b) for a, b in records[op]) / args.steps for op in ops}   # ms per step
+    def op_ms_of(op, name=None):   # ms per step spent in `op` (of linear `name`)
+        return sum(a.elapsed_time(b) for n, a, b in records[op] if name is None or n == name) / args.steps
+
+    op_ms = {op: op_ms_of(op) for op in ops}
     nk = sum(L.N * L.K for L in layers)
     gemv_bytes = sum(sum(L.N * L.K * r // 8 + 4 * L.N + 2 * B * L.K + 2 * B * L.N for r in (4, 2)) for B in (1, 4, 16)
                      for L in layers)
+    fwd_tf = flops_fwd / (op_ms["fwd"] * 1e-3) / 1e12
     per_op = {
-        "fwd_TFLOPs": flops_fwd / (op_ms["fwd"] * 1e-3) / 1e12,
+        "fwd_TFLOPs": fwd_tf,
         "bwd_TFLOPs": flops_bwd / (op_ms["bwd"] * 1e-3) / 1e12,
         "quantize_GBs": 5.0 * nk / (op_ms["quantize"] * 1e-3) / 1e9,
         "slice_GBs": (2.0 + 0.5 + 0.25) * nk / (op_ms["slice"] * 1e-3) / 1e9,
@@ -167,48 +191,63 @@ def main():
         "ms": {k: round(v, 4) for k, v in op_ms.items()},
     }
 
-    # Roofline of the dominant kernel, the fused r = 8/4/2 forward (one launch per linear): events
-    # bracket the mq_linear_fwd_multi_l2 call, i.e. the kernel plus its few-microsecond row-sum pre-pass
-    # and the one-workgroup finish of the loss sums.
-    fwd_launches = len(records["fwd"])
-    fwd_avg_ms = sum(a.elapsed_time(b) for a, b in records["fwd"]) / fwd_launches
-    achieved = (flops_fwd / len(layers)) / (fwd_avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "mq::fwd_kernel<3, true, false, MB, true> (MB = 4 for gate and up, 5 for down)", "achieved": round(achieved, 2),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": FWD_TRAFFIC_BYTES, "algorithmic_bytes": int(sum(L.N * L.K + 2 * L.M * L.K + 8 * L.M * L.N
-                                                                         for L in layers) / len(layers)),
-                "avg_launch_ms": round(fwd_avg_ms, 4)}
+    # Roofline of the dominant kernel, the fused r = 8/4/2 forward (one launch per linear): events bracket the
+    # mq_linear_fwd_multi_l2 call, i.e. the kernel plus its few-microsecond row-sum pre-pass and the
+    # one-workgroup finish of the loss sums.  Per linear and over the three.
+    per_linear = {}
+    for L in layers:
+        ms = op_ms_of("fwd", L.name)
+        tf = 6.0 * L.M * L.N * L.K / (ms * 1e-3) / 1e12
+        per_linear[L.name] = {"M": L.M, "N": L.N, "K": L.K, "avg_launch_ms": round(ms, 4), "achieved": round(tf, 2),
+                              "frac": round(tf / PEAK_BF16_TFLOPS, 4),
+                              "algorithmic_bytes": L.N * L.K + 2 * L.M * L.K + 8 * L.M * L.N,
+                              "traffic": FWD_TRAFFIC_BYTES[cfg][L.name]}
+    traffics = [per_linear[L.name]["traffic"] for L in layers]
+    roofline = {"bound": "mfma", "kernel": "mq::fwd_kernel<3, true, false, MB, true> (r = 8/4/2 with the objective in the epilogue)",
+                "achieved": round(fwd_tf, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(fwd_tf / PEAK_BF16_TFLOPS, 4),
+                "traffic": None if any(t is None for t in traffics) else int(sum(traffics) / len(traffics)),
+                "algorithmic_bytes": int(sum(v["algorithmic_bytes"] for v in per_linear.values()) / len(layers)),
+                "avg_launch_ms": round(op_ms["fwd"] / len(layers), 4), "per_linear": per_linear}
 
-    # the same forward without the objective (outputs stored), outside the timed region, for comparison
-    plain_ms = []
+    # the same forward without the objective (outputs stored), and the two halves of the backward on their
+    # own, outside the timed region
+    plain, bwd_split = {}, {}
     for L in layers:
         Y = [torch.empty(L.M, L.N, dtype=torch.bfloat16, device="cuda") for _ in rs]
         ws = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD, L.M, L.N, L.K, len(rs)), dtype=torch.uint8, device="cuda")
-        mq.mq_linear_fwd_multi(L.X, L.Q, L.alpha, L.zero, rs, Y=Y, ws=ws)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(5):
-            mq.mq_linear_fwd_multi(L.X, L.Q, L.alpha, L.zero, rs, Y=Y, ws=ws)
-        b.record()
-        torch.cuda.synchronize()
-        plain_ms.append(a.elapsed_time(b) / 5)
+        ms = event_ms(torch, lambda: mq.mq_linear_fwd_multi(L.X, L.Q, L.alpha, L.zero, rs, Y=Y, ws=ws), 5)
+        tf = 6.0 * L.M * L.N * L.K / (ms * 1e-3) / 1e12
+        plain[L.name] = {"avg_launch_ms": round(ms, 4), "achieved": round(tf, 2), "frac": round(tf / PEAK_BF16_TFLOPS, 4)}
         del Y, ws
-    plain_avg = sum(plain_ms) / len(plain_ms)
-    plain_tf = (flops_fwd / len(layers)) / (plain_avg * 1e-3) / 1e12
+        ms_dx = event_ms(torch, lambda: mq.mq_linear_bwd(L.X, L.Q, L.alpha, L.zero, L.dY, None, rs, dX=L.dX,
+                                                         need_dW=False, ws=L.ws_b), 3)
+        ms_dw = event_ms(torch, lambda: mq.mq_linear_bwd(L.X, L.Q, L.alpha, L.zero, L.dY, None, rs, need_dX=False,
+                                                         dW=L.dW, ws=L.ws_b), 3)
+        tdx, tdw = 6.0 * L.M * L.N * L.K / (ms_dx * 1e-3) / 1e12, 2.0 * L.M * L.N * L.K / (ms_dw * 1e-3) / 1e12
+        bwd_split[L.name] = {"dX_call_ms": round(ms_dx, 4), "dX_TFLOPs": round(tdx, 1), "dX_frac": round(tdx / PEAK_BF16_TFLOPS, 4),
+                             "dW_call_ms": round(ms_dw, 4), "dW_TFLOPs": round(tdw, 1), "dW_frac": round(tdw / PEAK_BF16_TFLOPS, 4)}
+    plain_ms = sum(v["avg_launch_ms"] for v in plain.values())
+    plain_tf = flops_fwd / (plain_ms * 1e-3) / 1e12
     roofline["plain_forward"] = {"kernel": "mq::fwd_kernel<3, true, false, MB, false> (mq_linear_fwd_multi: Y_r stored, no objective)",
-                                 "avg_launch_ms": round(plain_avg, 4), "achieved": round(plain_tf, 2),
-                                 "frac": round(plain_tf / PEAK_BF16_TFLOPS, 4)}
+                                 "achieved": round(plain_tf, 2), "frac": round(plain_tf / PEAK_BF16_TFLOPS, 4),
+                                 "per_linear": plain}
+    bwd_split["note"] = ("mq_linear_bwd with only dX (prep pass + code transpose + dx_kernel, 6 MNK flops) and with only dW "
+                         "(prep pass + activation transpose + dw_kernel, 2 MNK flops); helper passes included in each time")
 
     out = {
-        "metric": "fused r=8/4/2 quant-linear TFLOP/s (fwd 6MNK + STE bwd 8MNK over the whole hot-path step)",
-        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": "fused r=8/4/2 quant-linear TFLOP/s (%MFMA peak); sliced int2 GEMV GB/s (%HBM)",
+        "value": round(fwd_tf, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1]: Gemma-2-2B-shaped MLP, d_model 2304, ffn 9216, 4096 tokens, "
-                               "gate/up/down; quantize + slice/pack + fused r=8/4/2 fwd with L2 objective + STE bwd + decode GEMV "
-                               "B=1/4/16 (int4, int2)", "tokens": M, "rs": list(rs), "seed": synth.config_seed(2)},
+        "config": {"workload": WORKLOADS[cfg] + "; step = per linear (gate, up, down): quantize + slice/pack r=4, r=2 (+ overflow "
+                               "list) + fused r=8/4/2 fwd with L2 objective + STE bwd (dX, dW) + decode GEMV B=1/4/16 (int4, int2)",
+                   "tokens": M, "rs": list(rs), "lambdas": list(lambdas), "seed": synth.config_seed(cfg)},
+        "value_note": "6 MNK flops of the three fused forward calls of a step over their HIP-event time inside the timed region",
+        "step_blended_TFLOPs": round((flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12, 2),
         "per_op": per_op,
         "roofline": roofline,
+        "backward": bwd_split,
     }
     if not args.no_probes:
         from paper_2502_06786_amd import bench_probes
@@ -216,9 +255,9 @@ def main():
         out["measured_peaks"] = peaks
         # against the probe with the kernel's own product shape and occupancy, and against the best any bf16
         # loop sustains on this GPU on such operands (16x16x32 products, two waves per SIMD)
-        roofline["frac_of_measured"] = round(achieved / peaks["mfma_bf16_normal_operands_TFLOPs"], 4)
+        roofline["frac_of_measured"] = round(fwd_tf / peaks["mfma_bf16_normal_operands_TFLOPs"], 4)
         roofline["frac_of_best_measured"] = round(
-            achieved / max(peaks["mfma_bf16_normal_operands_TFLOPs"], peaks["mfma16_bf16_normal_operands_TFLOPs"]), 4)
+            fwd_tf / max(peaks["mfma_bf16_normal_operands_TFLOPs"], peaks["mfma16_bf16_normal_operands_TFLOPs"]), 4)
     if not args.no_gemv_sweep:
         out["gemv_roofline"] = gemv_sweep(torch, mq, synth)
         out["extra_precision_gemv"] = ep_gemv(torch, mq, synth)
@@ -231,14 +270,43 @@ def main():
                 best.update({"case": f"int2_36864x4608_B{B}", "achieved": e["GBs"], "frac": round(e["GBs"] / PEAK_HBM_GBS, 4)})
         if not args.no_probes:
             best["frac_of_measured_read"] = round(best["achieved"] / peaks["hbm_read_85MB_GBs"], 4)
-    if not args.no_gemv_sweep:
+    if not args.no_extras:
         out["mixnmatch_decode"] = mixnmatch_decode(torch, mq, synth)
         out["clip_factor_grads"] = clip_factor_grads(torch, mq, layers, rs, lambdas)
         out["omniquant_step"] = omniquant_step(torch, mq, layers, rs, lambdas)
         out["ffn_block_train"] = ffn_block_train(torch, mq, layers, rs)
+        del layers
+        torch.cuda.empty_cache()
+        out["config5_forward"] = config5_forward(torch, mq, synth)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(torch, synth, rs, lambdas)
+        out["cpu_baseline"] = cpu_baseline(torch, synth)
     print(json.dumps(out))
+
+
+def config5_forward(torch, mq, synth):
+    """configs[4]: the Gemma-2-27B-shaped linears (36864 x 4608 and 4608 x 36864, heavy-tailed weights, 4096 tokens):
+    quantize, then the forward for r = 8/4/2 in one launch, for r = 2 alone and for r = 2 with extra precision
+    (outputs stored; HIP events around 3 calls each)."""
+    res = {"workload": "configs[4]: Gemma-2-27B-shaped MLP, d_model 4608, ffn 36864, 4096 tokens, W ~ Student-t(3) * 0.01"}
+    for name in ("gate", "down"):
+        case = synth.linear_case(5, name, with_grads=False)
+        M, N, K = case.M, case.N, case.K
+        W, X = case.W.cuda(), case.X.cuda()
+        Q, alpha, zero = mq.mq_quantize_int8(W)
+        del W
+        entry = {"M": M, "N": N, "K": K}
+        Y = [torch.empty(M, N, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+        ws = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD, M, N, K, 3), dtype=torch.uint8, device="cuda")
+        for label, rs_, ep in (("r842", (8, 4, 2), False), ("r2", (2,), False), ("r2_extra_precision", (2,), True)):
+            ms = event_ms(torch, lambda: mq.mq_linear_fwd_multi(X, Q, alpha, zero, rs_, extra_precision=ep,
+                                                                Y=Y[:len(rs_)], ws=ws), 3)
+            tf = 2.0 * len(rs_) * M * N * K / (ms * 1e-3) / 1e12
+            entry[label] = {"avg_launch_ms": round(ms, 4), "achieved": round(tf, 2), "frac": round(tf / PEAK_BF16_TFLOPS, 4)}
+        res[name] = entry
+        del Q, X, Y, ws
+        torch.cuda.empty_cache()
+    res["note"] = "TFLOP/s = 2 * (number of bit-widths) * M N K over the HIP-event time of one mq_linear_fwd_multi call; peak 2500"
+    return res
 
 
 def measured_peaks(torch, mq):
@@ -409,7 +477,7 @@ def ep_gemv(torch, mq, synth):
     return res
 
 
-def clip_factor_grads(torch, mq, layers, rs, lambdas, reps=5):
+def clip_factor_grads(torch, mq, layers, rs, lambdas, reps=2):
     """mq_linear_bwd_clip on the three linears of the step (the gradients dY_r the step left behind): one
     dY_r^T X contraction per bit-width plus a row reduction each."""
     res = {}
@@ -429,7 +497,7 @@ def clip_factor_grads(torch, mq, layers, rs, lambdas, reps=5):
     return res
 
 
-def omniquant_step(torch, mq, layers, rs, lambdas, reps=5):
+def omniquant_step(torch, mq, layers, rs, lambdas, reps=2):
     """One calibration step of the OmniQuant base algorithm under the MatQuant objective on each linear of the
     workload: affine re-parameterisation of weight and input, quantizer with clip factors, forward for r = 8/4/2
     with bias and the L2 objective, straight-through backward, gradients of gamma, beta, delta, s."""
@@ -471,7 +539,7 @@ def omniquant_step(torch, mq, layers, rs, lambdas, reps=5):
     return res
 
 
-def ffn_block_train(torch, mq, layers, rs, reps=3):
+def ffn_block_train(torch, mq, layers, rs, reps=2):
     """Forward and straight-through backward of the whole gated feed-forward block of the workload for r = 8/4/2,
     composed from the library's calls: one fused forward over the stacked gate/up weight (rows interleaved), the gate,
     one down forward per bit-width; back through the three down layers (dW accumulated), the gate, the stacked layer."""
@@ -578,38 +646,86 @@ def mixnmatch_decode(torch, mq, synth):
     return res
 
 
-def cpu_baseline(torch, synth, rs, lambdas):
-    """The CPU oracle as it stands on a bounded slab of the gate linear (about 10-15 s of host work):
-    forward for 6144 of the 9216 output channels, dX for 1536 of the 4096 tokens, dW for 3072 of the
-    9216 weight rows."""
+def cpu_baseline(torch, synth):
+    """The CPU oracle as it stands, timed on the host cores of the box on a bounded sample of the same work:
+    configuration 1 in full, the decode GEMVs of configuration 4 in full, quantize + slice + pack of one whole
+    matrix (gate) of configurations 2, 3 and 5, and the fp64 contractions of the gate linear of configurations 2, 3, 5
+    on a slab (forward: all tokens x 256 channels per bit-width; dX: 128 tokens x all channels; dW: 256 weight
+    rows x all tokens), extrapolated linearly to the full layer.  `value` is the oracle's fused-forward rate
+    on the headline workload (configuration 3 slab)."""
     import numpy as np
     import oracle
 
     def bits(t):
         return t.contiguous().view(torch.int16).numpy().view(np.uint16)
 
-    case = synth.linear_case(2, "gate")
-    Wn = case.W.numpy()
-    nf, md, nw = 6144, 1536, 3072
-    t0 = time.perf_counter()
-    q, a, z = oracle.quantize_int8(Wn)
-    for r in (4, 2):
-        oracle.pack(oracle.slice_codes(q, r), r)
-    t_q = time.perf_counter() - t0
-    xb = bits(case.X)
-    t0 = time.perf_counter()
-    for r in rs:
-        oracle.linear_fwd(xb, q[:nf], a[:nf], z[:nf], r)
-    dyb = [bits(d[:md]) for d in case.dY]
-    oracle.linear_bwd_dx(q, a, z, dyb, lambdas, rs)
-    dyw = [bits(d[:, :nw]) for d in case.dY]
-    oracle.linear_bwd_dw(xb, dyw, lambdas)
-    t_mm = time.perf_counter() - t0
-    flops = 6.0 * case.M * nf * case.K + 6.0 * md * case.N * case.K + 2.0 * case.M * nw * case.K
-    return {"value": round(flops / t_mm / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"gate linear slab: fwd r=8/4/2 on {nf}/{case.N} channels, dX on {md}/{case.M} tokens, "
-                      f"dW on {nw}/{case.N} rows ({flops / 1e9:.0f} GFLOP in {t_mm:.1f} s); quantize+slice+pack of "
-                      f"the full {case.N}x{case.K} matrix took {t_q:.2f} s"}
+    def clock(fn):
+        t0 = time.perf_counter()
+        r = fn()
+        return time.perf_counter() - t0, r
+
+    rs = (8, 4, 2)
+    res = {}
+    # configuration 1, every operation of the path in full
+    c1 = synth.linear_case(1)
+    t_q, (q, a, z) = clock(lambda: oracle.quantize_int8(c1.W.numpy()))
+    t_s, _ = clock(lambda: [oracle.pack(oracle.slice_codes(q, r), r) for r in (4, 2)])
+    xb, dyb = bits(c1.X), [bits(d) for d in c1.dY]
+    t_f, _ = clock(lambda: [oracle.linear_fwd(xb, q, a, z, r) for r in rs])
+    t_b, _ = clock(lambda: (oracle.linear_bwd_dx(q, a, z, dyb, c1.lambdas, rs), oracle.linear_bwd_dw(xb, dyb, c1.lambdas)))
+    res["config1_full"] = {"quantize_ms": round(t_q * 1e3, 3), "slice_pack_ms": round(t_s * 1e3, 3),
+                           "fwd_r842_ms": round(t_f * 1e3, 3), "bwd_ms": round(t_b * 1e3, 3)}
+    # configuration 4: the decode GEMVs in full (r = 4, 2; B = 1, 4, 16)
+    gemv = {}
+    for (N, K) in synth.DECODE_SHAPES:
+        W = synth.weight(4, f"{N}x{K}", (N, K)).numpy()
+        q, a, z = oracle.quantize_int8(W)
+        a16 = bits(torch.from_numpy(a).to(torch.bfloat16))
+        z16 = bits(torch.from_numpy(z).to(torch.bfloat16))
+        for r in (4, 2):
+            plane = oracle.pack(oracle.slice_codes(q, r), r)
+            for B in (1, 4, 16):
+                x = bits(synth.activations(4, f"x{B}:{N}x{K}", B, K))
+                t, _ = clock(lambda: oracle.gemv_sliced(x, plane, a16, z16, r, K))
+                nbytes = N * K * r // 8 + 4 * N + 2 * B * K + 2 * B * N
+                gemv[f"int{r}_{N}x{K}_B{B}"] = {"ms": round(t * 1e3, 2), "GBs": round(nbytes / t / 1e9, 3)}
+    res["config4_gemv_full"] = gemv
+    # quantize + slice + pack of a whole matrix, and the contractions on a slab, per configuration
+    SLAB, SLAB_DX = 256, 128
+    value = None
+    for cfg in (2, 3, 5):
+        case = synth.linear_case(cfg, "gate", with_grads=False, M=None)
+        M, N, K = case.M, case.N, case.K
+        t_q, (q, a, z) = clock(lambda: oracle.quantize_int8(case.W.numpy()))
+        t_s, _ = clock(lambda: [oracle.pack(oracle.slice_codes(q, r), r) for r in (4, 2)])
+        entry = {"shape": f"gate {N}x{K}, {M} tokens", "quantize_full_s": round(t_q, 3), "slice_pack_r4_r2_full_s": round(t_s, 3),
+                 "quantize_GBs": round(5.0 * N * K / t_q / 1e9, 2), "slice_pack_GBs": round(2.75 * N * K / t_s / 1e9, 3)}
+        xb = bits(case.X)
+        t_f, _ = clock(lambda: [oracle.linear_fwd(xb, q[:SLAB], a[:SLAB], z[:SLAB], r) for r in rs])
+        lam = synth.LAMBDAS[cfg]
+        dY = [(torch.randn(SLAB_DX, N, generator=torch.Generator().manual_seed(i)) * 1e-3).to(torch.bfloat16) for i in range(3)]
+        t_dx, _ = clock(lambda: oracle.linear_bwd_dx(q, a, z, [bits(d) for d in dY], lam, rs))
+        dYw = [(torch.randn(M, SLAB, generator=torch.Generator().manual_seed(7 + i)) * 1e-3).to(torch.bfloat16) for i in range(3)]
+        t_dw, _ = clock(lambda: oracle.linear_bwd_dw(xb, [bits(d) for d in dYw], lam))
+        f_fwd, f_dx, f_dw = 6.0 * M * SLAB * K, 6.0 * SLAB_DX * N * K, 2.0 * M * SLAB * K
+        entry.update({
+            "fwd_slab": f"all {M} tokens x {SLAB} of {N} channels, r = 8/4/2", "fwd_slab_s": round(t_f, 3),
+            "fwd_TFLOPs": round(f_fwd / t_f / 1e12, 5), "fwd_full_layer_s_extrapolated": round(t_f * N / SLAB, 1),
+            "dX_slab": f"{SLAB_DX} of {M} tokens x all channels", "dX_slab_s": round(t_dx, 3),
+            "dX_full_layer_s_extrapolated": round(t_dx * M / SLAB_DX, 1),
+            "dW_slab": f"{SLAB} of {N} weight rows x all tokens", "dW_slab_s": round(t_dw, 3),
+            "dW_full_layer_s_extrapolated": round(t_dw * N / SLAB, 1),
+            "bwd_TFLOPs": round((f_dx + f_dw) / (t_dx + t_dw) / 1e12, 5)})
+        res[f"config{cfg}_gate"] = entry
+        if cfg == 3:
+            value = f_fwd / t_f / 1e12
+        del case, q, xb
+    return {"value": round(value, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "fused r=8/4/2 forward of the configs[2] gate linear (8192 tokens, 14336 x 3584) on a slab of 256 of its "
+                      "14336 output channels (all tokens, fp64 accumulation); full-layer times in `detail` are linear "
+                      "extrapolations of the slabs and labelled so; configuration 1 and the configuration-4 GEMVs ran in full, "
+                      "quantize/slice/pack ran on a whole matrix of configurations 2, 3 and 5",
+            "detail": res}
 
 
 if __name__ == "__main__":
