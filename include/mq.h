@@ -153,6 +153,24 @@ mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, const float *
                               uint16_t *const *Y, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * mq_linear_fwd_multi for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and limits
+ * as mq_linear_fwd_multi without `ws`; the per-token sums of X that the forward keeps between its
+ * pre-pass and its epilogue live in a fixed device array inside the library (1 MiB, one copy per GPU,
+ * held until the process ends).  No hipMalloc, hipFree or other allocating call is made.
+ *   - M <= 262144 tokens (MQ_ERR_SHAPE beyond: the built-in scratch holds one float per token).
+ *   - Every call on one GPU uses that GPU's array: calls that overlap in time on the same GPU (two
+ *     streams, two host threads) race and must be serialised by the caller.  Calls on different GPUs
+ *     are independent.  Nothing is kept between calls.
+ *   - The device address of the array is looked up once per GPU at the first call made with that GPU
+ *     current; make that first call outside a graph capture.
+ */
+mq_status mq_linear_fwd_multi_noalloc(const uint16_t *X, const uint8_t *Q, const float *alpha,
+                                      const float *zero, int64_t M, int64_t N, int64_t K,
+                                      const int *rs, int nr, uint32_t flags,
+                                      uint16_t *const *Y, void *hip_stream);
+
+/*
  * Straight-through backward of the same layer (sections 3.1.1 / 3.1.2 use an
  * STE through the quantizer; identity through both rounds and both clamps,
  * alpha and z held constant) for the weighted sum of per-bit-width losses of

@@ -32,7 +32,8 @@ MQ_FLAG_FFN_RESIDUAL = 32
 EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd", "mq_gemv_sliced",
            "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string",
            "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2", "mq_linear_bwd_clip",
-           "mq_affine_weight", "mq_affine_input", "mq_affine_bwd", "mq_gated_unit_fwd", "mq_gated_unit_bwd"]
+           "mq_affine_weight", "mq_affine_input", "mq_affine_bwd", "mq_gated_unit_fwd", "mq_gated_unit_bwd",
+           "mq_linear_fwd_multi_noalloc"]
 
 
 class MqError(RuntimeError):
@@ -62,6 +63,8 @@ def _load() -> ctypes.CDLL:
     lib.mq_slice.argtypes = [vp, i64, i64, ci, u32, vp, ctypes.POINTER(_Overflow), vp]
     lib.mq_linear_fwd_multi.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32,
                                         ctypes.POINTER(vp), vp, sz, vp]
+    lib.mq_linear_fwd_multi_noalloc.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32,
+                                                ctypes.POINTER(vp), vp]
     lib.mq_linear_bwd.argtypes = [vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float), i64, i64,
                                   i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib.mq_gemv_sliced.argtypes = [vp, vp, vp, vp, ctypes.POINTER(_Overflow), i64, i64, i64, ci, vp, vp]
@@ -233,6 +236,21 @@ def mq_linear_fwd_multi(X, Q, alpha, zero, rs, extra_precision: bool = False, Y=
                                   _ptr(zero, torch.float32), M, N, K, _int_array(rs), nr, flags,
                                   _ptr_array(Y, torch.bfloat16), _ptr(ws), ws.numel(), _stream())
     _check(st, "mq_linear_fwd_multi")
+    return Y
+
+
+def mq_linear_fwd_multi_noalloc(X, Q, alpha, zero, rs, Y, extra_precision: bool = False):
+    """mq_linear_fwd_multi without a workspace (the library's built-in scratch; at most 262144 tokens).  The
+    outputs Y are the caller's: nothing is allocated here either."""
+    M, K = X.shape
+    N = Q.shape[0]
+    if Q.shape[1] != K or len(Y) != len(rs):
+        raise ValueError("shape mismatch")
+    flags = MQ_FLAG_EXTRA_PRECISION if extra_precision else 0
+    st = _lib.mq_linear_fwd_multi_noalloc(_ptr(X, torch.bfloat16), _ptr(Q, torch.uint8), _ptr(alpha, torch.float32),
+                                          _ptr(zero, torch.float32), M, N, K, _int_array(rs), len(rs), flags,
+                                          _ptr_array(Y, torch.bfloat16), _stream())
+    _check(st, "mq_linear_fwd_multi_noalloc")
     return Y
 
 

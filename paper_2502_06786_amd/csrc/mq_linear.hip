@@ -20,6 +20,7 @@
 // codes, with one pre-scaled gradient operand per bit-width accumulated into a single accumulator;
 // dW is a plain bf16 GEMM of the lambda-weighted gradient sum against X.
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 #include "mq_common.h"
@@ -1404,7 +1405,8 @@ struct FwdLoss {
 
 static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero, int64_t M,
                          int64_t N, int64_t K, const int *rs, int nr, uint32_t flags, uint16_t *const *Y,
-                         const FwdLoss *loss, void *ws, size_t ws_bytes, void *hip_stream) {
+                         const FwdLoss *loss, void *ws, size_t ws_bytes, void *hip_stream,
+                         bool check_only = false) {
     if (M < 0 || N < 0 || K < 1) return MQ_ERR_SHAPE;
     if (M > 0x7FFFFF00 || N > 0x7FFFFF00 || K > (1 << 22)) return MQ_ERR_SHAPE;
     if (cdiv(M, 128) * cdiv(N, FWD_BN) > 0x7FFFFFFF) return MQ_ERR_SHAPE;  // tiles of one launch
@@ -1439,6 +1441,7 @@ static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha
     }
     if (!aligned16(X) || !aligned16(Q) || !aligned16(alpha) || !aligned16(zero)) return MQ_ERR_ALIGN;
     const int op = loss ? MQ_OP_LINEAR_FWD_L2 : MQ_OP_LINEAR_FWD;
+    if (check_only) return MQ_OK;  // every argument but the workspace is fine
     if (!ws || ws_bytes < mq_workspace_bytes(op, M, N, K, nr) || !aligned16(ws)) return MQ_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
@@ -1515,6 +1518,49 @@ extern "C" mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, co
                                          int nr, uint32_t flags, uint16_t *const *Y, void *ws, size_t ws_bytes,
                                          void *hip_stream) {
     return mq::fwd_run(X, Q, alpha, zero, M, N, K, rs, nr, flags, Y, nullptr, ws, ws_bytes, hip_stream);
+}
+
+// ---- the forward for callers that cannot allocate --------------------------------------------------
+// Scratch of mq_linear_fwd_multi_noalloc: the per-token sums of X that the forward's pre-pass writes and
+// its epilogue reads, in device memory that belongs to the library image (one copy per GPU, held until
+// the process ends) instead of a caller workspace.
+namespace mq {
+constexpr int64_t kNoAllocMaxTokens = 1 << 18;
+constexpr int kNoAllocMaxDevices = 64;
+static __device__ __align__(256) float scratch[kNoAllocMaxTokens + 64];
+// device address of `scratch` per GPU (the array's name is only a host-side handle), looked up once per device
+static void *g_scratch_addr[kNoAllocMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static mq_status noalloc_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kNoAllocMaxDevices) return MQ_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_addr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MQ_ERR_DEVICE;
+        g_scratch_addr[dev] = ptr;
+    }
+    *out = g_scratch_addr[dev];
+    return MQ_OK;
+}
+}  // namespace mq
+
+extern "C" mq_status mq_linear_fwd_multi_noalloc(const uint16_t *X, const uint8_t *Q, const float *alpha,
+                                                 const float *zero, int64_t M, int64_t N, int64_t K, const int *rs,
+                                                 int nr, uint32_t flags, uint16_t *const *Y, void *hip_stream) {
+    using namespace mq;
+    if (M > kNoAllocMaxTokens) return MQ_ERR_SHAPE;  // more tokens than the built-in scratch holds
+    const size_t need = M >= 0 && nr >= 1 && nr <= 3 ? mq_workspace_bytes(MQ_OP_LINEAR_FWD, M, N, K, nr) : 0;
+    if (need > sizeof(float) * (kNoAllocMaxTokens + 64)) return MQ_ERR_SHAPE;
+    // the arguments are checked before the device is touched; an empty call launches nothing and needs no scratch
+    mq_status s = fwd_run(X, Q, alpha, zero, M, N, K, rs, nr, flags, Y, nullptr, nullptr, 0, hip_stream, true);
+    if (s != MQ_OK || M == 0 || N == 0) return s;
+    void *ws = nullptr;
+    s = noalloc_scratch(&ws);
+    if (s != MQ_OK) return s;
+    return fwd_run(X, Q, alpha, zero, M, N, K, rs, nr, flags, Y, nullptr, ws, sizeof(float) * (kNoAllocMaxTokens + 64),
+                   hip_stream);
 }
 
 extern "C" mq_status mq_linear_fwd_multi_l2(const uint16_t *X, const uint8_t *Q, const float *alpha,

@@ -32,6 +32,7 @@ def lib():
     lib_.mq_quantize_int8.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp]
     lib_.mq_slice.argtypes = [vp, i64, i64, ci, u32, vp, vp, vp]
     lib_.mq_linear_fwd_multi.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, sz, vp]
+    lib_.mq_linear_fwd_multi_noalloc.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp]
     lib_.mq_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_gemv_sliced.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
@@ -285,3 +286,14 @@ def test_gated_unit_argument_checks(lib):
     assert lib.mq_gated_unit_bwd(None, None, 0, 8, 64, 0, None, None) == BITS
     assert lib.mq_gated_unit_bwd(None, None, 2, 8, 64, 0, None, None) == NULL
 
+
+
+def test_noalloc_forward_argument_checks(lib):
+    """The entry point without a workspace refuses bad arguments before it touches a device."""
+    f = lib.mq_linear_fwd_multi_noalloc
+    rs = (ctypes.c_int * 3)(8, 4, 2)
+    assert f(None, None, None, None, (1 << 18) + 1, 256, 256, rs, 3, 0, None, None) == SHAPE   # beyond the built-in scratch
+    assert f(None, None, None, None, 16, 256, 250, rs, 3, 0, None, None) == ALIGN
+    assert f(None, None, None, None, 16, 256, 256, rs, 4, 0, None, None) == BITS
+    assert f(None, None, None, None, 16, 256, 256, rs, 3, 0, None, None) == NULL
+    assert f(None, None, None, None, 0, 256, 256, rs, 3, 0, None, None) == OK
