@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libmq.so")
 # measurement-only kernels used by bench.py (matrix-core and read ceilings): a library of their own
 PROBE_DIR = os.path.join(HERE, "bench_probes")
 PROBE_LIB = os.path.join(PROBE_DIR, "libmq_probe.so")
-SOURCES = ["mq_quantize.hip", "mq_slice.hip", "mq_gemv.hip", "mq_gemv_quad.hip", "mq_linear.hip", "mq_ffn.hip", "mq_loss.hip", "mq_clip.hip", "mq_affine.hip"]
+SOURCES = ["mq_quantize.hip", "mq_slice.hip", "mq_gemv.hip", "mq_gemv_quad.hip", "mq_gemv_ovf.hip", "mq_gemv_reg.hip", "mq_linear.hip", "mq_ffn.hip", "mq_loss.hip", "mq_clip.hip", "mq_affine.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

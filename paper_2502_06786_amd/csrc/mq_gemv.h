@@ -10,10 +10,9 @@ struct GemvArgs {
     const uint8_t *packed;    // [N, KB]
     const uint16_t *alpha;    // [N] bf16
     const uint16_t *zero;     // [N] bf16
-    const int32_t *row_ptr;   // [N + 1] or null
-    const uint16_t *col_idx;  // overflow columns
-    int ovf_cap;              // entries col_idx holds: list positions at or beyond it are never read
     uint16_t *y;              // [B, N] bf16
+    int add_y;                // != 0: y holds, packed by ovf_sum_pack, a per-output addend to the sum of code * x
+                              // (the overflow sums of the extra-precision slice), read before y is overwritten
     int B, N, K;
     int KB;       // bytes per packed row
     float scale;  // 2^s: one step of the stored codes on the int8 grid
@@ -53,8 +52,26 @@ mq_status gemv_sliced_post(const uint16_t *x, const uint8_t *packed, const uint1
 // GEMVs run them for every one before the first launch).
 mq_status gemv_sliced_check(const uint8_t *packed, int64_t B, int64_t N, int64_t K, int r, int post);
 
-// Small-batch kernel (B <= 4, r = 4 or 2, no overflow list): activations live in registers.
+// The overflow sums of the extra-precision GEMV travel from the kernel that forms them to the dense kernel's
+// epilogue inside the output buffer y, 16 bits per output: IEEE half precision of sum / 256 (11 significant bits,
+// sums up to 1.6e7 in magnitude, saturating beyond; an absolute step of 2^-16 for tiny sums).  Small integers,
+// e.g. the sums of one-hot activations, pass exactly.
+__device__ __forceinline__ uint16_t ovf_sum_pack(float sum) {
+    const float scaled = fminf(fmaxf(sum * 0.00390625f, -65504.0f), 65504.0f);
+    return __builtin_bit_cast(uint16_t, (_Float16)scaled);
+}
+__device__ __forceinline__ float ovf_sum_unpack(uint16_t bits) { return 256.0f * (float)__builtin_bit_cast(_Float16, bits); }
+
+// y[b, n] <- ovf_sum_pack(sum of x[b, k] over the overflow columns k of row n) (mq_gemv_ovf.hip); K <= 65536
+mq_status launch_overflow_sums(const uint16_t *x, const int32_t *row_ptr, const uint16_t *col_idx, int64_t capacity,
+                               int64_t B, int64_t N, int64_t K, uint16_t *y, hipStream_t st);
+
+// Small-batch kernel (B <= 4, r = 4 or 2): activations live in registers.
 // Returns MQ_OK with *handled = false when the shape is outside what it covers.
 mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handled);
+
+// Batches of 5 .. 16 on tall int4 / int2 planes (no residual epilogue restriction): activations in registers as
+// 16x16x32 matrix-core operands.  Same convention for *handled.
+mq_status launch_gemv_reg(const GemvArgs &a, int r, hipStream_t st, bool *handled);
 
 }  // namespace mq

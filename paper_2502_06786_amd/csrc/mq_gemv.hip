@@ -106,9 +106,6 @@ typedef uint32_t u32x3_a4 __attribute__((ext_vector_type(3), aligned(4)));  // a
 // the next ones at bits 3-5 as 16 + c); the six codes that straddle a half or lie alone go last.
 __device__ constexpr uint8_t kOrder3[32] = {0, 6, 1, 7, 2, 8, 3, 9,          11, 16, 12, 17, 13, 18, 14, 19,
                                             22, 27, 23, 28, 24, 29, 25, 30,  15, 20, 4, 5, 10, 21, 26, 31};
-// kPlace3[code] = 8 v + 2 p + h, the inverse
-__device__ constexpr uint8_t kPlace3[32] = {0, 2, 4, 6, 26, 27, 1, 3, 5, 7, 28, 8, 10, 12, 14, 24,
-                                            9, 11, 13, 15, 25, 29, 16, 18, 20, 22, 30, 17, 19, 21, 23, 31};
 // offset under which element (v, p) of the 3-bit order reads: 16 for the registers fed from bits 3-5
 __host__ __device__ constexpr float offset3(int v, int p) { return (v < 3 && (p & 1)) ? 16.f : 128.f; }
 constexpr uint32_t kB16 = 0x41804180u;  // (16, 16)
@@ -249,7 +246,7 @@ __device__ __forceinline__ void gemv_segment(const u32x4 (&wt)[RG], const uint8_
 // loop is over.  single != 0: all of x is staged once per workgroup and stays (area A then is as
 // large as the reduction data); single == 0: x is restaged (in one or more chunks) for every group
 // of row blocks and the reduction data may run over it.
-template <int R, int RG, int D, bool EP>
+template <int R, int RG, int D>
 __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, int KS, int ngroups, int x_off,
                                                     int single_flag) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
@@ -426,8 +423,6 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
             for (int d = 0; d < D; ++d) w[d][0][rg] = w[d][1][rg] = u32x4{0u, 0u, 0u, 0u};
         }
         // alpha and z of the rows this lane will write: requested now and used after the main loop
-        // (later where the registers to hold them that long are missing)
-        constexpr bool kEarlyParams = !EP;
         float pal[RG][4], pze[RG][4];
         auto load_params = [&]() {
 #pragma unroll
@@ -439,7 +434,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                     pze[rg][cc] = bf16_bits_to_float(a.zero[row]);
                 }
         };
-        if constexpr (kEarlyParams) load_params();
+        load_params();
         int off = ks * LINEB + lc * PIECE;  // byte offset, inside the packed row, of the next piece to request
         // Unconditional (an offset past the row is clamped into it), so that the number of loads in
         // flight is known at compile time and a use only waits for its own load.
@@ -516,142 +511,10 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
         // ---- after the main loop ------------------------------------------------------------------
         // Wave ks == 0 of a row block ends up with the sums of its rows in the matrix-core output
         // layout (lane = batch entry b + 16 * (row / 4), component = row % 4) and writes them out
-        // itself.  With KS == 1 and no overflow list nothing is shared between waves here, so they
-        // run on without a barrier; otherwise partial sums and overflow sums meet in LDS.
+        // itself.  With KS == 1 nothing is shared between waves here, so they run on without a barrier;
+        // otherwise the partial sums meet in LDS.
         f32x4 *part = reinterpret_cast<f32x4 *>(area);                    // [wave][rg][lane], over the tiles
-        float *ovf = reinterpret_cast<float *>(area + NW * 2048);         // [row of the group][b]
-        const bool shared = EP || KS > 1;
-        // Extra precision: ovf[row][b] = sum of x[b, k] over the row's overflow columns.  A wave takes a
-        // contiguous range of the group's rows, whose list entries are contiguous too, and walks
-        // them 64 at a time.  Column indices are fetched in chunks of 8 batches (coalesced 2-byte
-        // loads) and parked in the wave's own LDS tile, free now (the K-split partial sums move into
-        // the tiles only afterwards), while the previous chunk is walked.
-        // Lane l keeps, per batch entry b, the sum of what it gathered for the row being walked;
-        // the wave-wide reduction happens once per row, where the row ends.  The row pointers of
-        // the range sit in one register (lane j: the pointer of the j-th row).  x is gathered from
-        // its staged copy in LDS when all of it is resident, from global memory otherwise.  The
-        // walk exists once per padded batch size so that its loops over b carry no branches.
-        if constexpr (EP) {
-            const int rpw = RW * ROWS / NW;  // rows per wave: 16 RG / KS >= 1
-            float *mine = ovf + wave * rpw * 16;
-            for (int t = lane; t < rpw * 16; t += 64) mine[t] = 0.f;
-            const int ra = nb + wave * rpw;
-            const int nrows = min(rpw, a.N - ra);  // wave-uniform
-            if (nrows > 0) {
-                // (a list that mq_slice had to cut short keeps row pointers of the full set: positions
-                // past the capacity of col_idx are dropped here, never read)
-                const int myrp = lane <= nrows ? min(a.row_ptr[ra + lane], a.ovf_cap) : 0x7FFFFFFF;
-                const int e0 = __builtin_amdgcn_readlane(myrp, 0), e1 = __builtin_amdgcn_readlane(myrp, nrows);
-                // x[b, k] as staged: block k / 512 of entry b, 16-byte slot (k % 512) / 8 kept at
-                // slot ^ b, and inside the slot (or the pair of slots, int2) the order the pairing
-                // pass left: elements j and j + 8 (int2) or j and j + 4 (int4) share a dword
-                auto staged_offset = [&](int k) -> uint32_t {  // without the parts that depend on b
-                    const int j = k & 511;
-                    int slot, dw, half;
-                    if constexpr (R == 2) {
-                        const int e16 = j & 15, e8 = e16 & 7;
-                        slot = ((j >> 4) << 1) + (e8 >> 2);
-                        dw = e8 & 3;
-                        half = e16 >> 3;
-                    } else if constexpr (R == 4) {
-                        const int e8 = j & 7;
-                        slot = j >> 3;
-                        dw = e8 & 3;
-                        half = e8 >> 2;
-                    } else if constexpr (R == 3) {
-                        const int place = kPlace3[j & 31];  // 8 v + 2 p + h inside the unit of 32
-                        slot = ((j >> 5) << 2) + (place >> 3);
-                        dw = (place >> 1) & 3;
-                        half = place & 1;
-                    } else {
-                        slot = j >> 3;
-                        dw = (j & 7) >> 1;
-                        half = j & 1;
-                    }
-                    return (uint32_t)(((k >> 9) * bp) * 1024 + (slot << 4) + dw * 4 + half * 2);
-                };
-                uint16_t *ring = reinterpret_cast<uint16_t *>(tb);  // two chunks of 8 x 64 column indices
-                auto walk = [&](auto bp_tag, auto from_lds) {
-                    constexpr int BPC = decltype(bp_tag)::value;
-                    float accb[BPC];
-#pragma unroll
-                    for (int b = 0; b < BPC; ++b) accb[b] = 0.f;
-                    int cur = 0;  // row (relative to ra) being walked
-                    auto flush = [&]() {
-#pragma unroll
-                        for (int b = 0; b < BPC; ++b) {
-                            const float t = wave_sum(accb[b]);
-                            if (lane == 0) mine[cur * 16 + b] = t;
-                            accb[b] = 0.f;
-                        }
-                    };
-                    int colu[8];
-                    auto request = [&](int base) {
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            const int p = base + 64 * u + lane;
-                            colu[u] = p < e1 ? (int)a.col_idx[p] : 0;
-                        }
-                    };
-                    auto park = [&](int buf) {
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) ring[buf * 512 + u * 64 + lane] = (uint16_t)colu[u];
-                    };
-                    request(e0);
-                    park(0);
-                    int buf = 0;
-                    for (int base = e0; base < e1; base += 512, buf ^= 1) {
-                        if (base + 512 < e1) request(base + 512);
-                        for (int u = 0; u < 8 && base + 64 * u < e1; ++u) {
-                            const int bstart = base + 64 * u, p = bstart + lane;
-                            const int col = ring[buf * 512 + u * 64 + lane];
-                            const uint32_t so = staged_offset(col);
-                            while (true) {
-                                const int lo = __builtin_amdgcn_readlane(myrp, cur);
-                                const int hi = __builtin_amdgcn_readlane(myrp, cur + 1);  // cur < nrows: a valid lane
-                                const bool inrow = p >= lo && p < hi;
-                                if (hi > bstart) {  // (an empty or finished row has nothing in this batch)
-                                    constexpr int HB = BPC < 8 ? BPC : 8;  // gathers in flight
-#pragma unroll
-                                    for (int b0 = 0; b0 < BPC; b0 += HB) {
-                                        float v[HB];
-#pragma unroll
-                                        for (int bb = 0; bb < HB; ++bb) {
-                                            const int b = b0 + bb;
-                                            if constexpr (decltype(from_lds)::value) {
-                                                // (entries b >= B read whatever LDS holds; their sums are never used)
-                                                const uint8_t *q = xbuf + b * 1024 + (so ^ (uint32_t)((b & 15) << 4));
-                                                v[bb] = bf16_bits_to_float(*reinterpret_cast<const uint16_t *>(q));
-                                            } else {
-                                                v[bb] = bf16_bits_to_float(a.x[(size_t)min(b, a.B - 1) * a.K + col]);
-                                            }
-                                        }
-#pragma unroll
-                                        for (int bb = 0; bb < HB; ++bb) accb[b0 + bb] += inrow ? v[bb] : 0.f;
-                                    }
-                                }
-                                if (hi >= bstart + 64 || cur + 1 >= nrows) break;  // the row goes on (or was the last)
-                                flush();
-                                ++cur;
-                            }
-                        }
-                        if (base + 512 < e1) park(buf ^ 1);
-                    }
-                    if (e1 > e0) flush();  // the row the walk ended in
-                };
-                auto walk_bp = [&](auto from_lds) {
-                    if (bp == 1) walk(std::integral_constant<int, 1>{}, from_lds);
-                    else if (bp == 2) walk(std::integral_constant<int, 2>{}, from_lds);
-                    else if (bp == 4) walk(std::integral_constant<int, 4>{}, from_lds);
-                    else if (bp == 8) walk(std::integral_constant<int, 8>{}, from_lds);
-                    else walk(std::integral_constant<int, 16>{}, from_lds);
-                };
-                if (single)
-                    walk_bp(std::true_type{});
-                else
-                    walk_bp(std::false_type{});
-            }
-        }
+        const bool shared = KS > 1;
         if (KS > 1) {
             __syncthreads();  // every wave is done with its transposition tile
 #pragma unroll
@@ -659,7 +522,6 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
         }
         if (shared) __syncthreads();
         if (ks == 0) {
-            if constexpr (!kEarlyParams) load_params();
             if (KS > 1) {
 #pragma unroll
                 for (int rg = 0; rg < RG; ++rg)
@@ -689,7 +551,9 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                         float dot = acc[rg][cc];
                         if constexpr (R == 2 || R == 3) dot -= xoff;
                         if constexpr (R == 4 || R == 6) dot -= 128.0f * xsum;
-                        if constexpr (EP) dot += ovf[(rw * ROWS + rl) * 16 + b];
+                        // extra precision: the overflow sum of this output waits in y (written by the kernel
+                        // that ran before this one on the stream)
+                        if (a.add_y && n0 + rl < a.N) dot += ovf_sum_unpack(a.y[(size_t)b * a.N + n0 + rl]);
                         yv[cc] = pal[rg][cc] * (kScale * dot - pze[rg][cc] * xsum);
                     }
                     const int row0 = n0 + rg * 16 + 4 * g;  // the lane's four consecutive rows
@@ -710,7 +574,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(GemvArgs a, int bp, int CB, 
                 }
             }
         }
-        // the next group's tiles, overflow sums or (restaged) x area start behind a barrier
+        // the next group's tiles or (restaged) x area start behind a barrier
         if (shared && single && grp + (int)gridDim.x < ngroups) __syncthreads();
     }
 }
@@ -723,9 +587,9 @@ static mq_status launch_gemv(const GemvArgs &a, int nw, int ks, hipStream_t st) 
     const int lines = (a.KB + line_bytes(R) - 1) / line_bytes(R);
     const int blocks_all = (lines + SSPB - 1) / SSPB;  // 512-k blocks that cover K
     // area A: the 2 KB transposition tiles of the waves (reused for the K-split partial sums, which
-    // need RG <= 2 KB per wave), then the overflow sums of the group's rows
+    // need RG <= 2 KB per wave)
     static_assert(RG <= 2, "partial sums are laid over the transposition tiles");
-    auto area_bytes = [&](int nw_, int ks_) { return (size_t)nw_ * 2048 + (size_t)(nw_ / ks_) * 16 * RG * 16 * 4; };
+    auto area_bytes = [&](int nw_, int) { return (size_t)nw_ * 2048; };
     constexpr size_t kLdsMax = 160 * 1024 - kSumBytes;
     // all of x at once when it fits behind the reduction data; otherwise chunks that are a multiple of
     // KS * D lines, so that the register ring of every wave is in the same phase at each chunk
@@ -765,7 +629,7 @@ static mq_status launch_gemv(const GemvArgs &a, int nw, int ks, hipStream_t st) 
         kern<<<dim3(grid), dim3(64 * nw), lds, st>>>(a, bp, CB, ks, ngroups, (int)x_off, single);
         return launch_status();
     };
-    return a.row_ptr ? go(gemv_kernel<R, RG, D, true>) : go(gemv_kernel<R, RG, D, false>);
+    return go(gemv_kernel<R, RG, D>);
 }
 
 }  // namespace mq
@@ -808,9 +672,7 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     a.packed = packed;
     a.alpha = alpha_bf16;
     a.zero = zero_bf16;
-    a.row_ptr = ovf ? ovf->row_ptr : nullptr;
-    a.col_idx = ovf ? ovf->col_idx : nullptr;
-    a.ovf_cap = ovf ? (int)std::min<int64_t>(ovf->capacity, 0x7FFFFFFF) : 0;
+    a.add_y = ovf ? 1 : 0;
     a.y = y;
     a.B = (int)B;
     a.N = (int)N;
@@ -821,17 +683,24 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
     a.res = res;
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (ovf) {
+        // extra precision: the sparse additions first, as 16-bit sums into y; the dense kernel below adds them to
+        // its products before it scales and overwrites y
+        const mq_status os = launch_overflow_sums(x, ovf->row_ptr, ovf->col_idx, ovf->capacity, B, N, K, y, st);
+        if (os != MQ_OK) return os;
+    }
     {
         bool handled = false;
         const mq_status qs = launch_gemv_quad(a, r, st, &handled);
         if (qs != MQ_OK || handled) return qs;
+        const mq_status rs = launch_gemv_reg(a, r, st, &handled);
+        if (rs != MQ_OK || handled) return rs;
     }
 
     // Rows per wave (16 RG): every activation operand read from LDS serves RG matrix-core products, so
     // tall matrices take two row groups; short ones keep RG = 1 for more waves (measured on the decode
     // shapes at B = 4 and 16: 4096 rows run 10-25 % faster with RG = 1, 14336 rows level or faster with 2).
-    // With an overflow list the waves of a group walk the list together: two row groups from B = 3 on.
-    const int rg = ovf ? (B > 2 ? 2 : 1) : (N >= 8192 ? 2 : 1);
+    const int rg = N >= 8192 ? 2 : 1;
     // K-split: about 2048 waves in total (8 per compute unit measured best across the decode shapes:
     // enough loads in flight, and the whole grid resident at once) when there are few row blocks,
     // none when the rows alone provide them.  Workgroups have 8 waves (KS of them per row block),

@@ -328,6 +328,8 @@ __global__ __launch_bounds__(512) void gemv_quad_kernel(GemvArgs a, int KS, int 
         }
         float dot = 0.f;
         for (int k = 0; k < NSL; ++k) dot += ypart[k * CH * 16 + r][bb];
+        // extra precision: the overflow sum of this output waits in y (the kernel before this one wrote it)
+        if (a.add_y && live) dot += ovf_sum_unpack(a.y[(size_t)bb * a.N + row]);
         float al, ze;
         if (m < PF) {
             al = m == 0 ? pal[0] : pal[1];
@@ -368,7 +370,7 @@ mq_status launch_quad(const GemvArgs &a, const QuadPlan &p, hipStream_t st) {
 
 mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handled) {
     *handled = false;
-    if (a.B > 4 || (r != 2 && r != 4) || a.row_ptr || a.post == kPostResidual) return MQ_OK;
+    if (a.B > 4 || (r != 2 && r != 4) || a.post == kPostResidual) return MQ_OK;
     const int lines = (a.KB + 127) / 128;
     const int nrb = (a.N + 15) / 16;
     // Measured against the general kernel on 4096..36864 rows: 0.85-0.9x the time at 36864 x 4608, level or

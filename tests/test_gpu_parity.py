@@ -480,6 +480,49 @@ def test_gemv_small_batch_tall_matrix(mq, oracle, r, N, K, B):
     assert np.all(err <= 2.0 ** -7 * np.abs(want) + 1e-3 * np.abs(want).max())
 
 
+@pytest.mark.parametrize("r,N,K,B,with_list", [(2, 32775, 1024, 16, False), (4, 32808, 2048, 5, False), (2, 32768, 4608, 9, False),
+                                               (4, 36864, 512, 16, False), (2, 32776, 1536, 8, True), (4, 32768, 1024, 13, True)])
+def test_gemv_mid_batch_tall_matrix(mq, oracle, r, N, K, B, with_list):
+    """At least 32768 rows and 5 <= B <= 16 on int4 / int2 planes: the kernel that keeps the activations of a K slice
+    in registers as 16-column matrix-core operands.  One and several lines per slice, several slices per workgroup,
+    ragged row counts, batch sizes that leave operand columns empty, and the overflow list on top; checked output
+    by output."""
+    from paper_2502_06786_amd import synth
+    q = synth.planted_codes(60 + r + B, N, K, first_overflow_code(r), 0.03) if with_list else synth.uniform_codes(60 + r + B, N, K)
+    a = (torch.rand(N, generator=torch.Generator().manual_seed(26)) * 1e-3 + 1e-4).to(torch.bfloat16)
+    z = (torch.rand(N, generator=torch.Generator().manual_seed(27)) * 255).to(torch.bfloat16)
+    x = _randn(B + r + 13, B, K).to(torch.bfloat16)
+    if with_list:
+        packed, ovf = mq.mq_slice(dev(q), r, packed=True, extra_precision=True)
+        torch.cuda.synchronize()
+        lists = oracle.overflow_csr(q.numpy(), r)
+        assert int(ovf.nnz.item()) == lists[1].size > 0
+    else:
+        packed, ovf, lists = mq.mq_slice(dev(q), r, packed=True), None, None
+    y = mq.mq_gemv_sliced(dev(x), packed, dev(a), dev(z), r, K, ovf=ovf)
+    want = oracle.gemv_sliced(bf16_bits(x), packed.cpu().numpy(), bf16_bits(a), bf16_bits(z), r, K, ovf=lists)
+    assert_close(y.float().cpu().numpy(), want, what=(r, N, K, B, with_list))
+
+
+def test_gemv_mid_batch_tall_matrix_one_hot_exact(mq, oracle):
+    # alpha = 1, z = 0, one-hot activations: y[b, n] is exactly the sliced value of code [n, k_b] (tall matrix, 5 <= B <= 16)
+    N, K = 32790, 1024
+    q = torch.arange(N * K, dtype=torch.int64).mul(7).add(torch.arange(N * K, dtype=torch.int64) // K).remainder(256)
+    q = q.to(torch.uint8).reshape(N, K)
+    a = torch.ones(N).to(torch.bfloat16)
+    z = torch.zeros(N).to(torch.bfloat16)
+    for r in (2, 4):
+        packed = mq.mq_slice(dev(q), r, packed=True)
+        sliced = oracle.slice_values(q.numpy(), r)
+        for B, k0 in ((16, 0), (16, 500), (11, 1008), (5, 37)):
+            cols = (k0 + torch.arange(B) * 3) % K
+            x = torch.zeros(B, K)
+            x[torch.arange(B), cols] = 1.0
+            y = mq.mq_gemv_sliced(dev(x.to(torch.bfloat16)), packed, dev(a), dev(z), r, K)
+            want = sliced[:, cols.numpy()].T.astype(np.float64)
+            assert np.array_equal(y.float().cpu().numpy().astype(np.float64), want), (r, B, k0)
+
+
 def test_gemv_small_batch_tall_matrix_one_hot_exact(mq, oracle):
     # alpha = 1, z = 0, one-hot activations: y[b, n] is exactly the sliced value of code [n, k_b] (tall matrix, B <= 4)
     N, K = 16400, 1024
