@@ -275,6 +275,7 @@ def main():
         out["clip_factor_grads"] = clip_factor_grads(torch, mq, layers, rs, lambdas)
         out["omniquant_step"] = omniquant_step(torch, mq, layers, rs, lambdas)
         out["ffn_block_train"] = ffn_block_train(torch, mq, layers, rs)
+        out["attention_projections"] = attention_projections(torch, mq, synth)
         del layers
         torch.cuda.empty_cache()
         out["config5_forward"] = config5_forward(torch, mq, synth)
@@ -541,13 +542,16 @@ def omniquant_step(torch, mq, layers, rs, lambdas, reps=2):
 
 def ffn_block_train(torch, mq, layers, rs, reps=2):
     """Forward and straight-through backward of the whole gated feed-forward block of the workload for r = 8/4/2,
-    composed from the library's calls: one fused forward over the stacked gate/up weight (rows interleaved), the gate,
-    one down forward per bit-width; back through the three down layers (dW accumulated), the gate, the stacked layer."""
+    composed from the library's calls: one fused forward over the stacked gate/up weight (rows interleaved) with the gate
+    in its epilogue, one down forward per bit-width; back through the three down layers (dW accumulated) and the stacked
+    layer, whose backward forms the gradient of the gated unit in its first pass.  Timed next to it: the same block with
+    the gate as stand-alone kernels (mq_gated_unit_fwd / _bwd between the layer calls)."""
     gate, up, down = layers
     M, d, F = gate.M, gate.K, gate.N
     Wgu = torch.empty(2 * F, d, dtype=torch.float32, device="cuda")
     Wgu[0::2], Wgu[1::2] = gate.W, up.W
     Qg, ag, zg = mq.mq_quantize_int8(Wgu)
+    del Wgu
     Qd, ad, zd = down.Q, down.alpha, down.zero
     mq.mq_quantize_int8(down.W, Q=Qd, alpha=ad, zero=zd)
     X = gate.X
@@ -567,30 +571,65 @@ def ffn_block_train(torch, mq, layers, rs, reps=2):
     ws_bg = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, M, 2 * F, d, len(rs)), **u8)
     ws_bd = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, M, d, F, 1), **u8)
 
-    def one():
-        mq.mq_linear_fwd_multi(X, Qg, ag, zg, rs, Y=GU, ws=ws_fg)
-        mq.mq_gated_unit_fwd(GU, A=A)
+    def down_layers():
         for i, r in enumerate(rs):
             mq.mq_linear_fwd_multi(A[i], Qd, ad, zd, (r,), Y=[Y[i]], ws=ws_fd)
         for i, r in enumerate(rs):
             mq.mq_linear_bwd(A[i], Qd, ad, zd, [dY[i]], None, (r,), dX=dA[i], dW=dWd, accumulate_dW=i > 0, ws=ws_bd)
+
+    def fused():
+        mq.mq_linear_fwd_multi_gated(X, Qg, ag, zg, rs, GU=GU, A=A, ws=ws_fg)
+        down_layers()
+        mq.mq_linear_bwd_gated(X, Qg, ag, zg, GU, dA, None, rs, dX=dX, dW=dWgu, ws=ws_bg)
+
+    def separate():
+        mq.mq_linear_fwd_multi(X, Qg, ag, zg, rs, Y=GU, ws=ws_fg)
+        mq.mq_gated_unit_fwd(GU, A=A)
+        down_layers()
         mq.mq_gated_unit_bwd(GU, dA, dGU=dGU)
         mq.mq_linear_bwd(X, Qg, ag, zg, dGU, None, rs, dX=dX, dW=dWgu, ws=ws_bg)
 
-    one()
-    a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a_.record()
-    for _ in range(reps):
-        one()
-    b_.record()
-    torch.cuda.synchronize()
-    ms = a_.elapsed_time(b_) / reps
     n = len(rs)
     # stacked layer: forward 2 n, dX 2 n, dW 2 (pre-summed); down layers: forward 2, dX 2, dW 2 per bit-width
     flops = (4.0 * n + 2.0) * M * 2 * F * d + 6.0 * n * M * d * F
-    return {"M": M, "d": d, "F": F, "ms": round(ms, 4), "TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),
-            "note": "mq_linear_fwd_multi (stacked gate/up, r = 8/4/2) + mq_gated_unit_fwd + 3 x mq_linear_fwd_multi (down) + "
-                    "3 x mq_linear_bwd (down) + mq_gated_unit_bwd + mq_linear_bwd (stacked)"}
+    ms_f, ms_s = event_ms(torch, fused, reps), event_ms(torch, separate, reps)
+    parts = {
+        "stacked_fwd_with_gate_ms": round(event_ms(torch, lambda: mq.mq_linear_fwd_multi_gated(X, Qg, ag, zg, rs, GU=GU, A=A, ws=ws_fg), reps), 4),
+        "stacked_fwd_ms": round(event_ms(torch, lambda: mq.mq_linear_fwd_multi(X, Qg, ag, zg, rs, Y=GU, ws=ws_fg), reps), 4),
+        "gate_fwd_kernel_ms": round(event_ms(torch, lambda: mq.mq_gated_unit_fwd(GU, A=A), reps), 4),
+        "stacked_bwd_with_gate_ms": round(event_ms(torch, lambda: mq.mq_linear_bwd_gated(X, Qg, ag, zg, GU, dA, None, rs, dX=dX, dW=dWgu, ws=ws_bg), reps), 4),
+        "stacked_bwd_ms": round(event_ms(torch, lambda: mq.mq_linear_bwd(X, Qg, ag, zg, dGU, None, rs, dX=dX, dW=dWgu, ws=ws_bg), reps), 4),
+        "gate_bwd_kernel_ms": round(event_ms(torch, lambda: mq.mq_gated_unit_bwd(GU, dA, dGU=dGU), reps), 4),
+    }
+    return {"M": M, "d": d, "F": F, "ms": round(ms_f, 4), "TFLOPs": round(flops / (ms_f * 1e-3) / 1e12, 1),
+            "ms_with_stand_alone_gate_kernels": round(ms_s, 4), "parts": parts,
+            "note": "mq_linear_fwd_multi_gated (stacked gate/up, r = 8/4/2, gate in the epilogue) + 3 x mq_linear_fwd_multi (down) + "
+                    "3 x mq_linear_bwd (down) + mq_linear_bwd_gated (stacked, gate gradient in the first pass)"}
+
+
+def attention_projections(torch, mq, synth, reps=3):
+    """The fused r = 8/4/2 forward and the straight-through backward on attention-projection shapes of the 9B-shaped model
+    (the paper also quantizes attention weights, section 5 'FFN + Attention'): a square projection d -> d and a
+    grouped-query key/value projection d -> d / 4, 8192 tokens, weights N(0, 0.015^2)."""
+    d, M, rs = 3584, 8192, (8, 4, 2)
+    res = {"tokens": M}
+    for name, N in (("d_to_d", d), ("d_to_d_over_4", d // 4)):
+        g = torch.Generator().manual_seed(N)
+        W = (torch.randn(N, d, generator=g) * 0.015).cuda()
+        X = torch.randn(M, d, generator=g).to(torch.bfloat16).cuda()
+        dY = [(torch.randn(M, N, generator=g) * 1e-3).to(torch.bfloat16).cuda() for _ in rs]
+        Q, a, z = mq.mq_quantize_int8(W)
+        Y = [torch.empty(M, N, dtype=torch.bfloat16, device="cuda") for _ in rs]
+        ws_f = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD, M, N, d, 3), dtype=torch.uint8, device="cuda")
+        ws_b = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, M, N, d, 3), dtype=torch.uint8, device="cuda")
+        dX = torch.empty(M, d, dtype=torch.bfloat16, device="cuda")
+        dW = torch.empty(N, d, dtype=torch.float32, device="cuda")
+        ms_f = event_ms(torch, lambda: mq.mq_linear_fwd_multi(X, Q, a, z, rs, Y=Y, ws=ws_f), reps)
+        ms_b = event_ms(torch, lambda: mq.mq_linear_bwd(X, Q, a, z, dY, None, rs, dX=dX, dW=dW, ws=ws_b), reps)
+        tf, tb = 6.0 * M * N * d / (ms_f * 1e-3) / 1e12, 8.0 * M * N * d / (ms_b * 1e-3) / 1e12
+        res[name] = {"N": N, "K": d, "fwd_ms": round(ms_f, 4), "fwd_TFLOPs": round(tf, 1), "fwd_frac": round(tf / PEAK_BF16_TFLOPS, 4),
+                     "bwd_ms": round(ms_b, 4), "bwd_TFLOPs": round(tb, 1), "bwd_frac": round(tb / PEAK_BF16_TFLOPS, 4)}
+    return res
 
 
 def mixnmatch_decode(torch, mq, synth):

@@ -391,6 +391,40 @@ mq_status mq_gated_unit_fwd(const uint16_t *const *GU, int nr, int64_t M, int64_
 mq_status mq_gated_unit_bwd(const uint16_t *const *GU, const uint16_t *const *dA, int nr, int64_t M,
                             int64_t F, uint32_t flags, uint16_t *const *dGU, void *hip_stream);
 
+/*
+ * mq_linear_fwd_multi of the stacked gate / up layer and mq_gated_unit_fwd in one call: the gated products are
+ * formed from the rounded outputs while a tile is still on chip (the arithmetic of mq_gated_unit_fwd: the A_r are
+ * bit-identical to the two calls in sequence), so the GU_r are not read back.
+ *   X [M, K] bf16;  Q [2F, K] uint8, alpha, zero [2F] fp32 (rows (gate f, up f) pairs);  rs, nr as usual
+ *   GU       NULL, or host array of nr device pointers, each [M, 2F] bf16 out or NULL (an output whose pointer
+ *            is NULL is not stored; the backward of the block needs them)
+ *   A        host array of nr device pointers, each [M, F] bf16 out
+ *   flags    MQ_FLAG_EXTRA_PRECISION, MQ_FLAG_FFN_SILU (GELU-tanh otherwise)
+ *   ws       workspace of at least mq_workspace_bytes(MQ_OP_LINEAR_FWD, M, 2F, K, nr)
+ * K a multiple of 16, F a multiple of 4; A rows 8-byte aligned.
+ */
+mq_status mq_linear_fwd_multi_gated(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero,
+                                    int64_t M, int64_t F, int64_t K, const int *rs, int nr, uint32_t flags,
+                                    uint16_t *const *GU, uint16_t *const *A, void *ws, size_t ws_bytes,
+                                    void *hip_stream);
+
+/*
+ * mq_gated_unit_bwd and mq_linear_bwd of the stacked gate / up layer in one call: the gradients dGU_r of the
+ * gated unit are formed (and rounded to bf16, exactly as mq_gated_unit_bwd writes them) inside the pass that
+ * prepares the operands of the backward, so they never travel to memory and back (section 3.1 straight-through
+ * backward of the layer; the block of section 5).  Results are bit-identical to the two calls in sequence.
+ *   X        [M, K] bf16, the input of the stacked layer;  Q [2F, K] uint8, alpha, zero [2F] fp32
+ *   GU       host array of nr device pointers, each [M, 2F] bf16: the outputs of the stacked layer per bit-width
+ *   dA       host array of nr device pointers, each [M, F] bf16: the gradients of the gated products
+ *   lambda, rs, nr, dX, dW, ws  as for mq_linear_bwd with N = 2F (workspace of MQ_OP_LINEAR_BWD at N = 2F)
+ *   flags    MQ_FLAG_EXTRA_PRECISION, MQ_FLAG_ACCUM_DW, MQ_FLAG_FFN_SILU (GELU-tanh otherwise)
+ * K a multiple of 16, F a multiple of 8 (2F of 16).
+ */
+mq_status mq_linear_bwd_gated(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero,
+                              const uint16_t *const *GU, const uint16_t *const *dA, const float *lambda,
+                              int64_t M, int64_t F, int64_t K, const int *rs, int nr, uint32_t flags,
+                              uint16_t *dX, float *dW, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Bytes of workspace `op` needs at these sizes (0 on invalid arguments).  MQ_OP_FFN_DECODE: M = B, N = F, K = d. */
 size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int nr);
 

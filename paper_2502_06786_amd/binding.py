@@ -33,7 +33,7 @@ EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd
            "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string",
            "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2", "mq_linear_bwd_clip",
            "mq_affine_weight", "mq_affine_input", "mq_affine_bwd", "mq_gated_unit_fwd", "mq_gated_unit_bwd",
-           "mq_linear_fwd_multi_noalloc"]
+           "mq_linear_fwd_multi_noalloc", "mq_linear_bwd_gated", "mq_linear_fwd_multi_gated"]
 
 
 class MqError(RuntimeError):
@@ -67,6 +67,10 @@ def _load() -> ctypes.CDLL:
                                                 ctypes.POINTER(vp), vp]
     lib.mq_linear_bwd.argtypes = [vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float), i64, i64,
                                   i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
+    lib.mq_linear_fwd_multi_gated.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, ctypes.POINTER(vp),
+                                              ctypes.POINTER(vp), vp, sz, vp]
+    lib.mq_linear_bwd_gated.argtypes = [vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float),
+                                        i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib.mq_gemv_sliced.argtypes = [vp, vp, vp, vp, ctypes.POINTER(_Overflow), i64, i64, i64, ci, vp, vp]
     lib.mq_workspace_bytes.argtypes = [ci, i64, i64, i64, ci]
     lib.mq_workspace_bytes.restype = sz
@@ -279,6 +283,56 @@ def mq_linear_bwd(X, Q, alpha, zero, dY, lambdas, rs, extra_precision: bool = Fa
                             _int_array(rs), nr, flags, _ptr(dX if need_dX else None, torch.bfloat16),
                             _ptr(dW if need_dW else None, torch.float32), _ptr(ws), ws.numel(), _stream())
     _check(st, "mq_linear_bwd")
+    return (dX if need_dX else None), (dW if need_dW else None)
+
+
+def mq_linear_fwd_multi_gated(X, Q, alpha, zero, rs, silu: bool = False, extra_precision: bool = False, GU=None, A=None,
+                              store_GU: bool = True, ws=None):
+    """Stacked gate / up layer with the gated unit in its epilogue: returns (list of GU_r bf16 [M, 2F] or None, list of
+    A_r bf16 [M, F])."""
+    M, K = X.shape
+    N = Q.shape[0]
+    nr = len(rs)
+    if Q.shape[1] != K or N % 2:
+        raise ValueError("shape mismatch")
+    if GU is None and store_GU:
+        GU = [torch.empty(M, N, dtype=torch.bfloat16, device=X.device) for _ in range(nr)]
+    if A is None:
+        A = [torch.empty(M, N // 2, dtype=torch.bfloat16, device=X.device) for _ in range(nr)]
+    if ws is None:
+        ws = torch.empty(max(mq_workspace_bytes(MQ_OP_LINEAR_FWD, M, N, K, nr), 16), dtype=torch.uint8, device=X.device)
+    flags = (MQ_FLAG_EXTRA_PRECISION if extra_precision else 0) | (MQ_FLAG_FFN_SILU if silu else 0)
+    st = _lib.mq_linear_fwd_multi_gated(_ptr(X, torch.bfloat16), _ptr(Q, torch.uint8), _ptr(alpha, torch.float32),
+                                        _ptr(zero, torch.float32), M, N // 2, K, _int_array(rs), nr, flags,
+                                        _ptr_array(GU, torch.bfloat16) if GU is not None else None,
+                                        _ptr_array(A, torch.bfloat16), _ptr(ws), ws.numel(), _stream())
+    _check(st, "mq_linear_fwd_multi_gated")
+    return GU, A
+
+
+def mq_linear_bwd_gated(X, Q, alpha, zero, GU, dA, lambdas, rs, silu: bool = False, extra_precision: bool = False,
+                        need_dX: bool = True, need_dW: bool = True, dX=None, dW=None, accumulate_dW: bool = False, ws=None):
+    """Backward of the stacked gate / up layer with the gradient of the gated unit formed on the way: GU[i] bf16
+    [M, 2F], dA[i] bf16 [M, F] -> (dX bf16 [M, K] or None, dW fp32 [2F, K] or None)."""
+    M, K = X.shape
+    N = Q.shape[0]
+    nr = len(rs)
+    if len(GU) != nr or len(dA) != nr or N % 2:
+        raise ValueError("one GU and one dA per r, an even number of stacked rows")
+    if need_dX and dX is None:
+        dX = torch.empty(M, K, dtype=torch.bfloat16, device=X.device)
+    if need_dW and dW is None:
+        dW = (torch.zeros if accumulate_dW else torch.empty)(N, K, dtype=torch.float32, device=X.device)
+    if ws is None:
+        ws = torch.empty(max(mq_workspace_bytes(MQ_OP_LINEAR_BWD, M, N, K, nr), 16), dtype=torch.uint8, device=X.device)
+    lam = None if lambdas is None else (ctypes.c_float * nr)(*[float(v) for v in lambdas])
+    flags = (MQ_FLAG_EXTRA_PRECISION if extra_precision else 0) | (MQ_FLAG_ACCUM_DW if accumulate_dW else 0) | \
+            (MQ_FLAG_FFN_SILU if silu else 0)
+    st = _lib.mq_linear_bwd_gated(_ptr(X, torch.bfloat16), _ptr(Q, torch.uint8), _ptr(alpha, torch.float32),
+                                  _ptr(zero, torch.float32), _ptr_array(GU, torch.bfloat16), _ptr_array(dA, torch.bfloat16), lam,
+                                  M, N // 2, K, _int_array(rs), nr, flags, _ptr(dX if need_dX else None, torch.bfloat16),
+                                  _ptr(dW if need_dW else None, torch.float32), _ptr(ws), ws.numel(), _stream())
+    _check(st, "mq_linear_bwd_gated")
     return (dX if need_dX else None), (dW if need_dW else None)
 
 

@@ -21,16 +21,6 @@ struct GateArgs {
     int nr, silu;
 };
 
-__device__ __forceinline__ float act_grad(float g, bool use_silu) {
-    if (use_silu) {
-        const float sig = 1.0f / (1.0f + __expf(-g));
-        return sig * (1.0f + g * (1.0f - sig));
-    }
-    const float c = 0.7978845608028654f;
-    const float th = tanhf(c * (g + 0.044715f * g * g * g));
-    return 0.5f * (1.0f + th) + 0.5f * g * (1.0f - th * th) * c * (1.0f + 3.0f * 0.044715f * g * g);
-}
-
 template <bool BWD>
 __global__ __launch_bounds__(256) void gate_train_kernel(GateArgs a) {
     const int64_t ch = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -55,7 +45,7 @@ __global__ __launch_bounds__(256) void gate_train_kernel(GateArgs a) {
             for (int j = 0; j < 8; ++j) {
                 const float g = bf16_lo(pairs[j]), u = bf16_hi(pairs[j]);
                 const float da = (j & 1) ? bf16_hi(d[j >> 1]) : bf16_lo(d[j >> 1]);
-                o[j] = pack_bf16x2(da * u * act_grad(g, a.silu != 0), da * (a.silu ? silu(g) : gelu_tanh(g)));
+                o[j] = gated_pair_grad(g, u, da, a.silu != 0);
             }
             reinterpret_cast<u32x4 *>(a.out[i])[2 * ch] = u32x4{o[0], o[1], o[2], o[3]};
             reinterpret_cast<u32x4 *>(a.out[i])[2 * ch + 1] = u32x4{o[4], o[5], o[6], o[7]};

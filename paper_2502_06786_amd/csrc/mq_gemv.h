@@ -27,12 +27,29 @@ struct GemvArgs {
 
 enum { kPostNone = 0, kPostResidual = 1, kPostGelu = 2, kPostSilu = 3 };
 
+// 1 / (1 + exp(-t)) with the hardware exponential and reciprocal (about 1e-6 relative: far below the bf16 rounding
+// that follows every use)
+__device__ __forceinline__ float sigmoid_fast(float t) { return __frcp_rn(1.0f + __expf(-t)); }
 __device__ __forceinline__ float gelu_tanh(float v) {
-    // 0.5 v (1 + tanh(sqrt(2 / pi) (v + 0.044715 v^3)))
+    // 0.5 v (1 + tanh(t)) = v sigmoid(2 t),  t = sqrt(2 / pi) (v + 0.044715 v^3)
     const float t = 0.7978845608028654f * (v + 0.044715f * v * v * v);
-    return 0.5f * v * (1.0f + tanhf(t));
+    return v * sigmoid_fast(2.0f * t);
 }
-__device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
+__device__ __forceinline__ float silu(float v) { return v * sigmoid_fast(v); }
+// derivative of the gate activation (GELU in its tanh form, or SiLU)
+__device__ __forceinline__ float act_grad(float g, bool use_silu) {
+    if (use_silu) {
+        const float sig = sigmoid_fast(g);
+        return sig * (1.0f + g * (1.0f - sig));
+    }
+    const float c = 0.7978845608028654f;
+    const float th = 2.0f * sigmoid_fast(2.0f * c * (g + 0.044715f * g * g * g)) - 1.0f;  // tanh
+    return 0.5f * (1.0f + th) + 0.5f * g * (1.0f - th * th) * c * (1.0f + 3.0f * 0.044715f * g * g);
+}
+// the two gradients of a (gate, up) pair of the gated unit a = act(g) u, rounded to bf16 as a pair (dg, du)
+__device__ __forceinline__ uint32_t gated_pair_grad(float g, float u, float da, bool use_silu) {
+    return pack_bf16x2(da * u * act_grad(g, use_silu), da * (use_silu ? silu(g) : gelu_tanh(g)));
+}
 __device__ __forceinline__ float bf16_rounded(float v) { return __uint_as_float(float_to_bf16_bits(v) << 16); }
 // one gated output from the (gate, up) pair of products
 __device__ __forceinline__ uint16_t gated_bf16(float gate, float up, int post) {

@@ -23,7 +23,7 @@
 #include <mutex>
 #include <type_traits>
 
-#include "mq_common.h"
+#include "mq_gemv.h"
 
 namespace mq {
 
@@ -155,6 +155,10 @@ struct FwdArgs {
     int mix;
     float *partial;  // [workgroup][4] sums of squared differences
     const float *bias;  // [N] added to every output before it is rounded, or null
+    // plain kernels only: the layer is the stacked gate / up projection of a gated unit (channels (g, u) pairs)
+    // and A[i] [M, N / 2] receives act(g) u of the rounded outputs; gate = 0 none, 1 GELU-tanh, 2 SiLU
+    uint16_t *A[3];
+    int gate;
 };
 
 constexpr int FWD_BN = 128;
@@ -194,11 +198,15 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
     uint16_t *k_Y[NR], *k_dY[NR];
     float k_coef[NR];
     int k_teacher[NR], k_mix = LOSS ? a.mix : 0;
+    uint16_t *k_A[NR];
+    int k_gate = LOSS ? 0 : a.gate;
     asm volatile("" : "+s"(k_alpha), "+s"(k_zero), "+s"(k_rowsum));
 #pragma unroll
     for (int i = 0; i < NR; ++i) {
         k_Y[i] = a.Y[i];
         asm volatile("" : "+s"(k_Y[i]));
+        k_A[i] = LOSS ? nullptr : a.A[i];
+        if constexpr (!LOSS) asm volatile("" : "+s"(k_A[i]));
         if constexpr (LOSS) {
             k_dY[i] = a.dY[i];
             k_coef[i] = a.coef[i];
@@ -207,6 +215,7 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
         }
     }
     if constexpr (LOSS) asm volatile("" : "+s"(k_bias), "+s"(k_T), "+s"(k_mix));
+    if constexpr (!LOSS) asm volatile("" : "+s"(k_gate));
 
     // XCD-aware tile order: each XCD walks groups of 4 token tiles across the channel tiles
     const uint32_t lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
@@ -479,8 +488,19 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdArgs a) {
                     const uint8_t *src = smem + i * OT + row * OS + ch * 16;
                     const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
                     const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 8);
-                    __builtin_nontemporal_store(u32x4{lo.x, lo.y, hi.x, hi.y},
-                                                reinterpret_cast<u32x4 *>(k_Y[i] + (size_t)m * a.N + n));
+                    if (k_Y[i])
+                        __builtin_nontemporal_store(u32x4{lo.x, lo.y, hi.x, hi.y},
+                                                    reinterpret_cast<u32x4 *>(k_Y[i] + (size_t)m * a.N + n));
+                    if (k_gate) {
+                        // the gated unit on the rounded outputs, pair by pair (the arithmetic of mq_gated_unit_fwd)
+                        const bool use_silu = k_gate == 2;
+                        auto gated = [&](uint32_t pair) {
+                            const float g = bf16_lo(pair), u = bf16_hi(pair);
+                            return (use_silu ? silu(g) : gelu_tanh(g)) * u;
+                        };
+                        const u32x2 o = {pack_bf16x2(gated(lo.x), gated(lo.y)), pack_bf16x2(gated(hi.x), gated(hi.y))};
+                        __builtin_nontemporal_store(o, reinterpret_cast<u32x2 *>(k_A[i] + (size_t)m * (a.N >> 1) + (n >> 1)));
+                    }
                 }
             }
         }
@@ -640,6 +660,11 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict_
 // ============================================================================================
 struct PrepArgs {
     const uint16_t *dY[3];
+    // GATED kernels: the layer is the stacked gate / up projection of a gated unit a = act(g) u and its output
+    // gradients are formed here from GU_i [M, N] (columns (g, u) pairs) and dA_i [M, N / 2] instead of read from dY_i
+    const uint16_t *GU[3];
+    const uint16_t *dA[3];
+    int silu;
     uint16_t *As[3];     // null pointers when dX is not wanted
     const float *alpha, *zero;
     float lam[3];
@@ -659,6 +684,7 @@ constexpr int PREP_MAX_SPLIT = 16;
 // (r, ch) = (t / 8, t % 8) owns eight consecutive columns of row r, so a row segment is one 128-byte
 // line per gradient tensor.  The summed gradient tile is turned through LDS and leaves as 64-byte
 // row segments of GT.
+template <bool GATED>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(PrepArgs a) {
     __shared__ uint16_t tile[64][PREP_ROWS + 2];
     const int t = threadIdx.x, r = t >> 3, ch = t & 7;
@@ -681,8 +707,20 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(PrepArgs a) {
             }
             u32x4 dy[3];
 #pragma unroll
-            for (int i = 0; i < 3; ++i)
-                if (i < a.nr) dy[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.dY[i] + (size_t)m * a.N + n));
+            for (int i = 0; i < 3; ++i) {
+                if (i >= a.nr) break;
+                if constexpr (GATED) {
+                    // the gradient of the gated unit, pair by pair, rounded to bf16 like mq_gated_unit_bwd does
+                    const u32x4 gu = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.GU[i] + (size_t)m * a.N + n));
+                    const u32x2 da = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(a.dA[i] + (size_t)m * (a.N >> 1) + (n >> 1)));
+#pragma unroll
+                    for (int w = 0; w < 4; ++w)
+                        dy[i][w] = gated_pair_grad(bf16_lo(gu[w]), bf16_hi(gu[w]), (w & 1) ? bf16_hi(da[w >> 1]) : bf16_lo(da[w >> 1]),
+                                                   a.silu != 0);
+                } else {
+                    dy[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.dY[i] + (size_t)m * a.N + n));
+                }
+            }
 #pragma unroll
             for (int i = 0; i < 3; ++i) {
                 if (i >= a.nr) break;
@@ -1406,7 +1444,7 @@ struct FwdLoss {
 static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero, int64_t M,
                          int64_t N, int64_t K, const int *rs, int nr, uint32_t flags, uint16_t *const *Y,
                          const FwdLoss *loss, void *ws, size_t ws_bytes, void *hip_stream,
-                         bool check_only = false) {
+                         bool check_only = false, uint16_t *const *gated_out = nullptr, int gate = 0) {
     if (M < 0 || N < 0 || K < 1) return MQ_ERR_SHAPE;
     if (M > 0x7FFFFF00 || N > 0x7FFFFF00 || K > (1 << 22)) return MQ_ERR_SHAPE;
     if (cdiv(M, 128) * cdiv(N, FWD_BN) > 0x7FFFFFFF) return MQ_ERR_SHAPE;  // tiles of one launch
@@ -1424,11 +1462,14 @@ static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha
     }
     if (M == 0 || N == 0) return MQ_OK;
     if (!X || !Q || !alpha || !zero) return MQ_ERR_NULL;
-    if (!loss && !Y) return MQ_ERR_NULL;
+    if (!loss && !Y && !gate) return MQ_ERR_NULL;
+    if (gate && !gated_out) return MQ_ERR_NULL;
     for (int i = 0; i < nr; ++i) {
         uint16_t *yi = Y ? Y[i] : nullptr;
-        if (!loss && !yi) return MQ_ERR_NULL;
+        if (!loss && !gate && !yi) return MQ_ERR_NULL;
         if (yi && !aligned16(yi)) return MQ_ERR_ALIGN;
+        if (gate && !gated_out[i]) return MQ_ERR_NULL;
+        if (gate && (reinterpret_cast<uintptr_t>(gated_out[i]) & 7u)) return MQ_ERR_ALIGN;
     }
     if (loss) {
         if (!loss->dY || !loss->losses || (need_target && !loss->target)) return MQ_ERR_NULL;
@@ -1459,8 +1500,10 @@ static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha
     int slot_of[3] = {0, 0, 0};
     for (int i = 0; i < 3; ++i) {
         a.Y[i] = nullptr;
+        a.A[i] = nullptr;
         a.r[i] = 8;
     }
+    a.gate = gate;
     for (int i = 0; i < nr; ++i)
         if (rs[i] == 8) {
             has8 = 1;
@@ -1471,6 +1514,7 @@ static mq_status fwd_run(const uint16_t *X, const uint8_t *Q, const float *alpha
         if (rs[i] != 8) slot_of[i] = pos++;
     for (int i = 0; i < nr; ++i) {
         a.Y[slot_of[i]] = Y ? Y[i] : nullptr;
+        a.A[slot_of[i]] = gate ? gated_out[i] : nullptr;
         a.r[slot_of[i]] = rs[i];
     }
     const double mn = (double)M * (double)N;
@@ -1518,6 +1562,16 @@ extern "C" mq_status mq_linear_fwd_multi(const uint16_t *X, const uint8_t *Q, co
                                          int nr, uint32_t flags, uint16_t *const *Y, void *ws, size_t ws_bytes,
                                          void *hip_stream) {
     return mq::fwd_run(X, Q, alpha, zero, M, N, K, rs, nr, flags, Y, nullptr, ws, ws_bytes, hip_stream);
+}
+
+extern "C" mq_status mq_linear_fwd_multi_gated(const uint16_t *X, const uint8_t *Q, const float *alpha,
+                                               const float *zero, int64_t M, int64_t F, int64_t K, const int *rs,
+                                               int nr, uint32_t flags, uint16_t *const *GU, uint16_t *const *A,
+                                               void *ws, size_t ws_bytes, void *hip_stream) {
+    if (F < 0 || F > 0x3FFFFF00) return MQ_ERR_SHAPE;
+    if (F % 4 != 0) return MQ_ERR_ALIGN;  // rows of A start on 8-byte boundaries
+    return mq::fwd_run(X, Q, alpha, zero, M, 2 * F, K, rs, nr, flags, GU, nullptr, ws, ws_bytes, hip_stream, false, A,
+                       (flags & MQ_FLAG_FFN_SILU) ? 2 : 1);
 }
 
 // ---- the forward for callers that cannot allocate --------------------------------------------------
@@ -1573,11 +1627,12 @@ extern "C" mq_status mq_linear_fwd_multi_l2(const uint16_t *X, const uint8_t *Q,
     return mq::fwd_run(X, Q, alpha, zero, M, N, K, rs, nr, flags, Y, &loss, ws, ws_bytes, hip_stream);
 }
 
-extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero,
-                                   const uint16_t *const *dY, const float *lambda, int64_t M, int64_t N,
-                                   int64_t K, const int *rs, int nr, uint32_t flags, uint16_t *dX, float *dW,
-                                   void *ws, size_t ws_bytes, void *hip_stream) {
-    using namespace mq;
+namespace mq {
+// gated: the output gradients come from GU and dA (see PrepArgs) instead of dY
+static mq_status bwd_run(bool gated, const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero,
+                         const uint16_t *const *dY, const uint16_t *const *GU, const uint16_t *const *dA,
+                         const float *lambda, int64_t M, int64_t N, int64_t K, const int *rs, int nr, uint32_t flags,
+                         uint16_t *dX, float *dW, void *ws, size_t ws_bytes, void *hip_stream) {
     if (M < 0 || N < 0 || K < 1) return MQ_ERR_SHAPE;
     if (M > (1 << 22) || N > (1 << 22) || K > (1 << 22)) return MQ_ERR_SHAPE;
     mq_status s = check_rs(rs, nr);
@@ -1600,10 +1655,18 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
         }
         return launch_status();
     }
-    if (!dY) return MQ_ERR_NULL;
-    for (int i = 0; i < nr; ++i) {
-        if (!dY[i]) return MQ_ERR_NULL;
-        if (!aligned16(dY[i])) return MQ_ERR_ALIGN;
+    if (gated) {
+        if (!GU || !dA) return MQ_ERR_NULL;
+        for (int i = 0; i < nr; ++i) {
+            if (!GU[i] || !dA[i]) return MQ_ERR_NULL;
+            if (!aligned16(GU[i]) || !aligned16(dA[i])) return MQ_ERR_ALIGN;
+        }
+    } else {
+        if (!dY) return MQ_ERR_NULL;
+        for (int i = 0; i < nr; ++i) {
+            if (!dY[i]) return MQ_ERR_NULL;
+            if (!aligned16(dY[i])) return MQ_ERR_ALIGN;
+        }
     }
     if (dX && (!Q || !alpha || !zero)) return MQ_ERR_NULL;
     if (dW && !X) return MQ_ERR_NULL;
@@ -1621,7 +1684,9 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
     PrepArgs p;
     for (int i = 0; i < 3; ++i) {
         const int j = i < nr ? i : 0;
-        p.dY[i] = dY[j];
+        p.dY[i] = gated ? nullptr : dY[j];
+        p.GU[i] = gated ? GU[j] : nullptr;
+        p.dA[i] = gated ? dA[j] : nullptr;
         p.As[i] = dX ? reinterpret_cast<uint16_t *>(base + lay.as[j]) : nullptr;
         p.lam[i] = lambda ? lambda[j] : 1.0f;
         p.mult[i] = rs[j] == 8 ? 1.0f : (float)(1 << (8 - rs[j]));
@@ -1640,7 +1705,11 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
     int nsplit = (int)std::min<int64_t>(std::min<int64_t>(PREP_MAX_SPLIT, cdiv(N, 64)), std::max<int64_t>(1, cdiv(1024, strips)));
     p.cols_per_split = (int)(cdiv(cdiv(N, nsplit), 64) * 64);
     nsplit = (int)cdiv(N, p.cols_per_split);
-    bwd_prep_kernel<<<dim3((unsigned)strips, (unsigned)nsplit), dim3(256), 0, st>>>(p);
+    p.silu = (flags & MQ_FLAG_FFN_SILU) ? 1 : 0;
+    if (gated)
+        bwd_prep_kernel<true><<<dim3((unsigned)strips, (unsigned)nsplit), dim3(256), 0, st>>>(p);
+    else
+        bwd_prep_kernel<false><<<dim3((unsigned)strips, (unsigned)nsplit), dim3(256), 0, st>>>(p);
 
     if (dX) {
         uint8_t *QT = base + lay.qt;
@@ -1693,6 +1762,24 @@ extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const fl
         dw_kernel<<<dim3(w.tiles_n * w.tiles_k), dim3(256), DW_LDS, st>>>(w);
     }
     return launch_status();
+}
+}  // namespace mq
+
+extern "C" mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero,
+                                   const uint16_t *const *dY, const float *lambda, int64_t M, int64_t N,
+                                   int64_t K, const int *rs, int nr, uint32_t flags, uint16_t *dX, float *dW,
+                                   void *ws, size_t ws_bytes, void *hip_stream) {
+    return mq::bwd_run(false, X, Q, alpha, zero, dY, nullptr, nullptr, lambda, M, N, K, rs, nr, flags, dX, dW, ws, ws_bytes,
+                       hip_stream);
+}
+
+extern "C" mq_status mq_linear_bwd_gated(const uint16_t *X, const uint8_t *Q, const float *alpha, const float *zero,
+                                         const uint16_t *const *GU, const uint16_t *const *dA, const float *lambda,
+                                         int64_t M, int64_t F, int64_t K, const int *rs, int nr, uint32_t flags,
+                                         uint16_t *dX, float *dW, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (F < 0 || F > (1 << 21)) return MQ_ERR_SHAPE;
+    return mq::bwd_run(true, X, Q, alpha, zero, nullptr, GU, dA, lambda, M, 2 * F, K, rs, nr, flags, dX, dW, ws, ws_bytes,
+                       hip_stream);
 }
 
 extern "C" const char *mq_status_string(mq_status status) {

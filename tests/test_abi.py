@@ -33,6 +33,8 @@ def lib():
     lib_.mq_slice.argtypes = [vp, i64, i64, ci, u32, vp, vp, vp]
     lib_.mq_linear_fwd_multi.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, sz, vp]
     lib_.mq_linear_fwd_multi_noalloc.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp]
+    lib_.mq_linear_fwd_multi_gated.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
+    lib_.mq_linear_bwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_gemv_sliced.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
@@ -297,3 +299,25 @@ def test_noalloc_forward_argument_checks(lib):
     assert f(None, None, None, None, 16, 256, 256, rs, 4, 0, None, None) == BITS
     assert f(None, None, None, None, 16, 256, 256, rs, 3, 0, None, None) == NULL
     assert f(None, None, None, None, 0, 256, 256, rs, 3, 0, None, None) == OK
+
+
+def test_gated_backward_argument_checks(lib):
+    f = lib.mq_linear_bwd_gated
+    rs = (ctypes.c_int * 3)(8, 4, 2)
+    assert f(None, None, None, None, None, None, None, 16, 128, 256, rs, 0, 0, None, None, None, 0, None) == BITS
+    assert f(None, None, None, None, None, None, None, 16, 128, 250, rs, 3, 0, None, None, None, 0, None) == ALIGN
+    assert f(None, None, None, None, None, None, None, 16, 60, 256, rs, 3, 0, None, None, None, 0, None) == ALIGN    # 2F = 120
+    assert f(None, None, None, None, None, None, None, 16, -1, 256, rs, 3, 0, None, None, None, 0, None) == SHAPE
+    assert f(None, None, None, None, None, None, None, 16, 128, 256, rs, 3, 0, None, None, None, 0, None) == NULL    # no GU, no dA
+    assert f(None, None, None, None, None, None, None, 0, 128, 256, rs, 3, 0, None, None, None, 0, None) == OK
+
+
+def test_gated_forward_argument_checks(lib):
+    f = lib.mq_linear_fwd_multi_gated
+    rs = (ctypes.c_int * 3)(8, 4, 2)
+    assert f(None, None, None, None, 16, 128, 256, rs, 4, 0, None, None, None, 0, None) == BITS
+    assert f(None, None, None, None, 16, 126, 256, rs, 3, 0, None, None, None, 0, None) == ALIGN   # F not a multiple of 4
+    assert f(None, None, None, None, 16, 128, 250, rs, 3, 0, None, None, None, 0, None) == ALIGN
+    assert f(None, None, None, None, 16, -4, 256, rs, 3, 0, None, None, None, 0, None) == SHAPE
+    assert f(None, None, None, None, 16, 128, 256, rs, 3, 0, None, None, None, 0, None) == NULL    # X, Q, ... and A missing
+    assert f(None, None, None, None, 0, 128, 256, rs, 3, 0, None, None, None, 0, None) == OK

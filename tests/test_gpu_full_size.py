@@ -178,6 +178,95 @@ def test_training_path_full_size(mq, oracle, config, name):
     assert_close(_cols(dW, kcols), oracle.linear_bwd_dw(np.ascontiguousarray(xb[:, kcols]), dyb, lam), C_GRAD, what="dW columns")
 
 
+def test_training_block_full_size(mq, oracle):
+    """The whole gated feed-forward block of configuration 2 on the training path (4096 tokens, d 2304, F 9216; r = 8/4/2):
+    stacked gate / up layer with the gate in its epilogue, one down layer per bit-width, and the way back (down
+    backward per bit-width, stacked backward with the gate gradient in its first pass), against the oracle's own
+    chain of the same steps on 48 whole token rows (GU_r, A_r, Y_r, dA_r, dX) and on 32 whole (gate, up) channel
+    pairs (the rows of dW of the stacked layer and the columns of dW of the down layer that belong to them)."""
+    from paper_2502_06786_amd import synth
+    shapes, M = synth.mlp_shapes(2)
+    F, d = shapes["gate"]
+    rs, lam = (8, 4, 2), (0.3, 0.6, 1.0)
+    Wgu = torch.empty(2 * F, d)
+    Wgu[0::2], Wgu[1::2] = synth.weight(2, "gate"), synth.weight(2, "up")
+    Wd = synth.weight(2, "down") * 4.0        # (a down layer whose outputs are of order one)
+    X = synth.activations(2, "gate", M, d)
+    dYs = [(torch.randn(M, d, generator=torch.Generator().manual_seed(70 + i)) * 1e-2).to(torch.bfloat16) for i in range(3)]
+    Qg, ag, zg = mq.mq_quantize_int8(Wgu.cuda())
+    Qd, ad, zd = mq.mq_quantize_int8(Wd.cuda())
+    qg, aog, zog = oracle.quantize_int8(Wgu.numpy())
+    qd, aod, zod = oracle.quantize_int8(Wd.numpy())
+    assert np.array_equal(Qg.cpu().numpy(), qg) and np.array_equal(Qd.cpu().numpy(), qd)
+    # ---- library, in full
+    Xd = X.cuda()
+    GU, A = mq.mq_linear_fwd_multi_gated(Xd, Qg, ag, zg, rs)
+    Y = [mq.mq_linear_fwd_multi(A[i], Qd, ad, zd, (r,))[0] for i, r in enumerate(rs)]
+    dA, dWd = [], torch.zeros(d, F, device="cuda")
+    for i, r in enumerate(rs):
+        dx, _ = mq.mq_linear_bwd(A[i], Qd, ad, zd, [dYs[i].cuda()], (lam[i],), (r,), dW=dWd, accumulate_dW=True)
+        dA.append(dx)
+    dX, dWgu = mq.mq_linear_bwd_gated(Xd, Qg, ag, zg, GU, dA, None, rs)
+    torch.cuda.synchronize()
+    # ---- oracle on 48 token rows: every step of the chain is per token
+    xb = bf16_bits(X)
+    mrows = _lines(91, M, 48)
+    ones = (1.0,) * 3
+    wide = dict(c_rms=2.0 ** -5, tol=2 * TOL)   # a GU or dA rounded to the other bf16 neighbour moves what follows by a step
+    GU_o, A_o, dA_o, dGU_o = [], [], [], []
+    for i, r in enumerate(rs):
+        GU_o.append(oracle.bf16_round(oracle.linear_fwd(xb[mrows], qg, aog, zog, r)))
+        assert_close(_rows(GU[i], mrows), oracle.bf16_to_f64(GU_o[i]), C_Y, what=f"GU_{r} rows")
+        A_o.append(oracle.gated_unit(GU_o[i]))
+        assert_close(_rows(A[i], mrows), oracle.bf16_to_f64(A_o[i]), what=f"A_{r} rows", **wide)
+        assert_close(_rows(Y[i], mrows), oracle.linear_fwd(A_o[i], qd, aod, zod, r), what=f"Y_{r} rows", **wide)
+        dyb = bf16_bits(dYs[i][torch.from_numpy(mrows)])
+        dA_o.append(oracle.bf16_round(oracle.linear_bwd_dx(qd, aod, zod, [dyb], (lam[i],), (r,))))
+        assert_close(_rows(dA[i], mrows), oracle.bf16_to_f64(dA_o[i]), C_GRAD, what=f"dA_{r} rows")
+        dGU_o.append(oracle.bf16_round(oracle.gated_unit_bwd(GU_o[i], dA_o[i])))
+    assert_close(_rows(dX, mrows), oracle.linear_bwd_dx(qg, aog, zog, dGU_o, ones, rs), what="dX rows", **wide)
+    print("  token rows ok", flush=True)
+    # ---- oracle on 32 (gate, up) pairs, all tokens: the columns of GU, A, dA, dGU that belong to them
+    fs = _lines(92, F, 32)
+    cols = np.stack([2 * fs, 2 * fs + 1], axis=1).ravel()          # stacked channels of the pairs, pair by pair
+    dWd_o, dGUc = np.zeros((d, fs.size)), []
+    for i, r in enumerate(rs):
+        GUc = oracle.bf16_round(oracle.linear_fwd(xb, np.ascontiguousarray(qg[cols]), aog[cols], zog[cols], r))     # [M, 64]
+        Ac = oracle.gated_unit(GUc)                                                                                # [M, 32]
+        dyb = bf16_bits(dYs[i])
+        dAc = oracle.bf16_round(oracle.linear_bwd_dx(np.ascontiguousarray(qd[:, fs]), aod, zod, [dyb], (lam[i],), (r,)))   # [M, 32]
+        dWd_o += oracle.linear_bwd_dw(Ac, [dyb], (lam[i],))                                                         # [d, 32]
+        dGUc.append(oracle.bf16_round(oracle.gated_unit_bwd(GUc, dAc)))
+    assert_close(_cols(dWd, fs), dWd_o, what="dW down columns", **wide)
+    assert_close(_rows(dWgu, cols), oracle.linear_bwd_dw(xb, dGUc, ones), what="dW stacked rows", **wide)
+
+
+@pytest.mark.parametrize("N", [3584, 896])
+def test_attention_projection_shapes(mq, oracle, N):
+    """The fused forward and the backward on attention-projection shapes of the 9B-shaped model (section 5 also quantizes
+    attention weights): a square projection d -> d and a grouped-query key / value projection d -> d / 4, 8192 tokens;
+    stratified samples as in test_training_path_full_size."""
+    K, M, rs, lam = 3584, 8192, (8, 4, 2), (0.1, 0.1, 1.0)
+    g = torch.Generator().manual_seed(N)
+    W = torch.randn(N, K, generator=g) * 0.015
+    X = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    dYs = [(torch.randn(M, N, generator=g) * 1e-3).to(torch.bfloat16) for _ in rs]
+    Q, alpha, zero = mq.mq_quantize_int8(W.cuda())
+    qo, ao, zo = oracle.quantize_int8(W.numpy())
+    assert np.array_equal(Q.cpu().numpy(), qo)
+    xb, dyb = bf16_bits(X), [bf16_bits(t) for t in dYs]
+    Ys = mq.mq_linear_fwd_multi(X.cuda(), Q, alpha, zero, rs)
+    ms, ns = _strata(N + 1, M, N, 32, 32)
+    for r, Y in zip(rs, Ys):
+        extra = accumulation_allowance(K, 1.0, ao[ns].astype(np.float64) * float(1 << (8 - r)))
+        assert_close(_pick(Y, ms, ns), oracle.linear_fwd_sampled(xb, qo, ao, zo, r, ms, ns), C_Y, what=f"Y_{r}", extra=extra)
+    dX, dW = mq.mq_linear_bwd(X.cuda(), Q, alpha, zero, [t.cuda() for t in dYs], lam, rs)
+    ms, ks = _strata(N + 2, M, K, 32, 64)
+    assert_close(_pick(dX, ms, ks), oracle.linear_bwd_dx_sampled(qo, ao, zo, dyb, lam, rs, ms, ks), C_GRAD, what="dX")
+    ns, ks = _strata(N + 3, N, K, 64, 64)
+    assert_close(_pick(dW, ns, ks), oracle.linear_bwd_dw_sampled(xb, dyb, lam, ns, ks), C_GRAD, what="dW")
+
+
 @pytest.mark.parametrize("N,K", [(4096, 4096), (14336, 4096), (4096, 14336)])
 def test_decode_gemv_7b_shapes(mq, oracle, N, K):
     from paper_2502_06786_amd import synth

@@ -854,7 +854,10 @@ def test_ffn_block_training_step_composes(mq, oracle):
         dA.append(dx)
     dGU = mq.mq_gated_unit_bwd(GU, dA)
     dX, dWgu = mq.mq_linear_bwd(dev(X), Qg, ag, zg, dGU, None, rs)
+    # the same two steps in one call: the gradients of the gated unit are formed inside the backward's first pass
+    dX1, dWgu1 = mq.mq_linear_bwd_gated(dev(X), Qg, ag, zg, GU, dA, None, rs)
     torch.cuda.synchronize()
+    assert torch.equal(dX1, dX) and torch.equal(dWgu1, dWgu)
     # ---- oracle
     ones = (1.0,) * 3
     GU_o = [oracle.bf16_round(oracle.linear_fwd(xb, qg, aog, zog, r)) for r in rs]
@@ -871,6 +874,49 @@ def test_ffn_block_training_step_composes(mq, oracle):
     assert rel_l2(dX.float().cpu().numpy(), oracle.linear_bwd_dx(qg, aog, zog, dGU_o, ones, rs)) <= 2 * TOL
     assert rel_l2(dWgu.cpu().numpy().astype(np.float64), oracle.linear_bwd_dw(xb, dGU_o, ones)) <= 2 * TOL
 
+
+@pytest.mark.parametrize("M,F,K,rs,silu,ep", [(72, 64, 96, (8, 4, 2), False, False), (301, 136, 208, (4, 2), True, False),
+                                              (520, 200, 320, (8, 6, 3), False, True), (1, 8, 16, (2,), True, False)])
+def test_gated_backward_matches_the_two_calls_and_the_oracle(mq, oracle, M, F, K, rs, silu, ep):
+    """mq_linear_bwd_gated = mq_gated_unit_bwd followed by mq_linear_bwd on the stacked gate / up layer: bit-identical to
+    the two calls (lambda weights, accumulation into dW, dX only, dW only), and within the backward's bars of the oracle's
+    composition of the same two steps."""
+    nr = len(rs)
+    lam = (0.25, 0.5, 1.0)[:nr]
+    W = _randn(M + F + K, 2 * F, K, scale=1.0 / K ** 0.5)
+    X = _randn(M + 1, M, K).to(torch.bfloat16)
+    Q, a, z, qo, ao, zo = _quantized(mq, oracle, W)
+    GU = mq.mq_linear_fwd_multi(dev(X), Q, a, z, rs, extra_precision=ep)
+    # forward: the gated unit in the epilogue of the stacked layer = the two calls in sequence, bit for bit
+    A0 = mq.mq_gated_unit_fwd(GU, silu=silu)
+    GU1, A1 = mq.mq_linear_fwd_multi_gated(dev(X), Q, a, z, rs, silu=silu, extra_precision=ep)
+    _, A2 = mq.mq_linear_fwd_multi_gated(dev(X), Q, a, z, rs, silu=silu, extra_precision=ep, store_GU=False)
+    dA_host = [(_randn(40 + i, M, F) * 1e-2).to(torch.bfloat16) for i in range(nr)]
+    dA = [dev(t) for t in dA_host]
+    dGU = mq.mq_gated_unit_bwd(GU, dA, silu=silu)
+    dX0, dW0 = mq.mq_linear_bwd(dev(X), Q, a, z, dGU, lam, rs, extra_precision=ep)
+    dX1, dW1 = mq.mq_linear_bwd_gated(dev(X), Q, a, z, GU, dA, lam, rs, silu=silu, extra_precision=ep)
+    assert torch.equal(dX1, dX0) and torch.equal(dW1, dW0)
+    base = dev(_randn(41, 2 * F, K, scale=1e-2))
+    acc0, acc1 = base.clone(), base.clone()
+    mq.mq_linear_bwd(dev(X), Q, a, z, dGU, lam, rs, extra_precision=ep, need_dX=False, dW=acc0, accumulate_dW=True)
+    none, _ = mq.mq_linear_bwd_gated(dev(X), Q, a, z, GU, dA, lam, rs, silu=silu, extra_precision=ep, need_dX=False, dW=acc1,
+                                     accumulate_dW=True)
+    assert none is None and torch.equal(acc0, acc1)
+    dX2, none = mq.mq_linear_bwd_gated(dev(X), Q, a, z, GU, dA, lam, rs, silu=silu, extra_precision=ep, need_dW=False)
+    assert none is None and torch.equal(dX2, dX0)
+    # against the oracle's own chain (forward, rounding to bf16, gate, gate backward, linear backward): a GU that the
+    # two sides round to different bf16 neighbours moves the gated values by one more step, hence the wider bars
+    GU_o = [oracle.bf16_round(oracle.linear_fwd(bf16_bits(X), qo, ao, zo, r, ep=ep)) for r in rs]
+    dGU_o = []
+    for i in range(nr):
+        assert torch.equal(GU1[i], GU[i]) and torch.equal(A1[i], A0[i]) and torch.equal(A2[i], A0[i]), rs[i]
+        assert_close(GU1[i].float().cpu().numpy(), oracle.bf16_to_f64(GU_o[i]), what=("GU", rs[i]))
+        assert_close(A1[i].float().cpu().numpy(), oracle.bf16_to_f64(oracle.gated_unit(GU_o[i], silu=silu)), c_rms=2.0 ** -5,
+                     tol=2 * TOL, what=("A", rs[i]))
+        dGU_o.append(oracle.bf16_round(oracle.gated_unit_bwd(GU_o[i], bf16_bits(dA_host[i]), silu=silu)))
+    assert_close(dX1.float().cpu().numpy(), oracle.linear_bwd_dx(qo, ao, zo, dGU_o, lam, rs, ep=ep), c_rms=2.0 ** -5, tol=2 * TOL, what="dX")
+    assert_close(dW1.cpu().numpy(), oracle.linear_bwd_dw(bf16_bits(X), dGU_o, lam), c_rms=2.0 ** -5, tol=2 * TOL, what="dW")
 
 # --------------------------------------------------------------------------
 # the whole step under HIP graph capture
