@@ -135,8 +135,7 @@ def main():
             timed("quantize", L, lambda: mq.mq_quantize_int8(L.W, Q=L.Q, alpha=L.alpha, zero=L.zero), rec)
 
             def do_slice():
-                mq.mq_slice(L.Q, 4, packed=True, out=L.p4)
-                mq.mq_slice(L.Q, 2, packed=True, extra_precision=True, out=L.p2, ovf=L.ovf2)
+                mq.mq_slice_multi(L.Q, (4, 2), out=[L.p4, L.p2], ovf_r=2, ovf=L.ovf2)
                 mq.mq_params_to_bf16(L.alpha, L.zero, L.alpha16, L.zero16)
             timed("slice", L, do_slice, rec)
             # forward for r = 8, 4, 2 with the L2 reconstruction losses against y' and the gradients the
@@ -186,7 +185,7 @@ def main():
         "fwd_TFLOPs": fwd_tf,
         "bwd_TFLOPs": flops_bwd / (op_ms["bwd"] * 1e-3) / 1e12,
         "quantize_GBs": 5.0 * nk / (op_ms["quantize"] * 1e-3) / 1e9,
-        "slice_GBs": (2.0 + 0.5 + 0.25) * nk / (op_ms["slice"] * 1e-3) / 1e9,
+        "slice_GBs": (1.0 + 0.5 + 0.25) * nk / (op_ms["slice"] * 1e-3) / 1e9,   # codes read once, int4 and int2 planes written
         "gemv_GBs": gemv_bytes / (op_ms["gemv"] * 1e-3) / 1e9,
         "ms": {k: round(v, 4) for k, v in op_ms.items()},
     }

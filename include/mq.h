@@ -134,6 +134,22 @@ mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uint32_t flags
                    uint8_t *out, const mq_overflow *ovf, void *hip_stream);
 
 /*
+ * Several packed planes of the same codes in one call (the nested model of section 3.2 is served at several
+ * bit-widths from one set of int8 codes): out[i] = the packed rs[i]-bit plane exactly as mq_slice with
+ * MQ_FLAG_PACKED writes it.  The int4 and int2 planes and the sizes of the overflow set are produced by a single
+ * pass over Q (rows that are whole 16-byte chunks), so slicing a layer for decode reads the codes twice (planes
+ * and counts, then the columns of the list) instead of once per kernel of every plane.
+ *   rs         host int[nr], distinct values out of {8, 6, 4, 3, 2}; nr in 1..3
+ *   out        host array of nr device pointers, out[i] [N, K*rs[i]/8]
+ *   flags      0, or MQ_FLAG_EXTRA_PRECISION: the overflow set of bit-width rs[ovf_index] is also listed in *ovf
+ *              (every plane is the clamped one); MQ_FLAG_EP_DENSE is not accepted here
+ *   ovf_index  index into rs (ignored without MQ_FLAG_EXTRA_PRECISION; pass -1)
+ * Status codes and limits as for mq_slice.
+ */
+mq_status mq_slice_multi(const uint8_t *Q, int64_t N, int64_t K, const int *rs, int nr, uint32_t flags,
+                         uint8_t *const *out, int ovf_index, const mq_overflow *ovf, void *hip_stream);
+
+/*
  * Fused multi-precision forward, the F(S(Q(theta, c), r), x) of the MatQuant
  * objective (section 3.2) for every r in rs[] in ONE pass over X and Q:
  *     Y_i[m,n] = sum_k X[m,k] * alpha_n * (S(Q[n,k], rs[i]) - z_n)

@@ -33,7 +33,7 @@ EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd
            "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string",
            "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2", "mq_linear_bwd_clip",
            "mq_affine_weight", "mq_affine_input", "mq_affine_bwd", "mq_gated_unit_fwd", "mq_gated_unit_bwd",
-           "mq_linear_fwd_multi_noalloc", "mq_linear_bwd_gated", "mq_linear_fwd_multi_gated"]
+           "mq_linear_fwd_multi_noalloc", "mq_linear_bwd_gated", "mq_linear_fwd_multi_gated", "mq_slice_multi"]
 
 
 class MqError(RuntimeError):
@@ -67,6 +67,7 @@ def _load() -> ctypes.CDLL:
                                                 ctypes.POINTER(vp), vp]
     lib.mq_linear_bwd.argtypes = [vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float), i64, i64,
                                   i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
+    lib.mq_slice_multi.argtypes = [vp, i64, i64, ctypes.POINTER(ci), ci, u32, ctypes.POINTER(vp), ci, ctypes.POINTER(_Overflow), vp]
     lib.mq_linear_fwd_multi_gated.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, ctypes.POINTER(vp),
                                               ctypes.POINTER(vp), vp, sz, vp]
     lib.mq_linear_bwd_gated.argtypes = [vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float),
@@ -213,6 +214,25 @@ def mq_slice(Q, r: int, packed: bool = False, extra_precision: bool = False, out
     st = _lib.mq_slice(_ptr(Q, torch.uint8), N, K, r, flags, _ptr(out, torch.uint8), c_ovf, _stream())
     _check(st, "mq_slice")
     return (out, ovf) if extra_precision else out
+
+
+def mq_slice_multi(Q, rs, out=None, ovf_r: int | None = None, ovf: Overflow | None = None, capacity: int | None = None):
+    """Packed planes of the codes for every r in rs in one call; with ovf_r also the overflow list of that bit-width.
+    Returns the list of planes, or (planes, Overflow)."""
+    N, K = Q.shape
+    rs = list(rs)
+    if out is None:
+        out = [torch.empty(N, K * r // 8, dtype=torch.uint8, device=Q.device) for r in rs]
+    c_ovf, idx, flags = None, -1, 0
+    if ovf_r is not None:
+        idx, flags = rs.index(ovf_r), MQ_FLAG_EXTRA_PRECISION
+        if ovf is None:
+            ovf = Overflow(N, N * K if capacity is None else capacity, Q.device)
+        c_ovf = ctypes.byref(ovf.c_struct())
+    st = _lib.mq_slice_multi(_ptr(Q, torch.uint8), N, K, _int_array(rs), len(rs), flags, _ptr_array(out, torch.uint8), idx,
+                             c_ovf, _stream())
+    _check(st, "mq_slice_multi")
+    return (out, ovf) if ovf_r is not None else out
 
 
 def _int_array(vals):

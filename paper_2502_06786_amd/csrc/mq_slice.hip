@@ -168,6 +168,53 @@ __global__ __launch_bounds__(256) void overflow_count_kernel(const uint8_t *__re
     }
 }
 
+// Several products of one pass over the codes (mq_slice_multi): the packed int4 plane, the packed int2 plane and
+// the per-row size of the overflow set of one of them, any subset.  A wave owns a row (rows are whole 16-byte
+// chunks), so the count is a wave reduction and the planes leave as 8- and 4-byte pieces next to each other.
+template <bool P4, bool P2, bool CNT>
+__global__ __launch_bounds__(256) void slice_multi_kernel(const uint8_t *__restrict__ Q, int64_t N, int64_t K,
+                                                          uint8_t *__restrict__ out4, uint8_t *__restrict__ out2,
+                                                          uint32_t thr, int32_t *__restrict__ row_ptr) {
+    const int lane = threadIdx.x & 63;
+    const int64_t n = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(Q + n * K);
+    const int64_t chunks = K >> 4;
+    constexpr uint32_t kHalf4 = 8u | (8u << 16), kTop4 = 15u | (15u << 16), kHalf2 = 32u | (32u << 16), kTop2 = 3u | (3u << 16);
+    int cnt = 0;
+    for (int64_t c = lane; c < chunks; c += 64) {
+        const u32x4 d = __builtin_nontemporal_load(row + c);
+        if constexpr (P4) {
+            auto nib = [](uint32_t x) {
+                const uint32_t y = (x | (x >> 4)) & 0x00FF00FFu;
+                return (y | (y >> 8)) & 0xFFFFu;
+            };
+            u32x2 p;
+            p.x = nib(slice4(d.x, kHalf4, 4, kTop4)) | (nib(slice4(d.y, kHalf4, 4, kTop4)) << 16);
+            p.y = nib(slice4(d.z, kHalf4, 4, kTop4)) | (nib(slice4(d.w, kHalf4, 4, kTop4)) << 16);
+            __builtin_nontemporal_store(p, reinterpret_cast<u32x2 *>(out4 + n * (K >> 1)) + c);
+        }
+        if constexpr (P2) {
+            auto crumb = [](uint32_t x) {
+                const uint32_t y = (x | (x >> 6)) & 0x000F000Fu;
+                return (y | (y >> 12)) & 0xFFu;
+            };
+            const uint32_t p = crumb(slice4(d.x, kHalf2, 6, kTop2)) | (crumb(slice4(d.y, kHalf2, 6, kTop2)) << 8) |
+                               (crumb(slice4(d.z, kHalf2, 6, kTop2)) << 16) | (crumb(slice4(d.w, kHalf2, 6, kTop2)) << 24);
+            __builtin_nontemporal_store(p, reinterpret_cast<uint32_t *>(out2 + n * (K >> 2)) + c);
+        }
+        if constexpr (CNT) cnt += count_ge4(d.x, thr) + count_ge4(d.y, thr) + count_ge4(d.z, thr) + count_ge4(d.w, thr);
+    }
+    if constexpr (CNT) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+        if (lane == 0) {
+            row_ptr[n + 1] = cnt;
+            if (n == 0) row_ptr[0] = 0;
+        }
+    }
+}
+
 // Single block, in place: row_ptr[1..N] counts -> inclusive prefix sums; *nnz = total.  Every thread sums
 // its run of counts, the 1024 sums are scanned inside the waves with lane shuffles and across the 16 waves
 // through LDS (two barriers in all).
@@ -323,6 +370,70 @@ extern "C" mq_status mq_slice(const uint8_t *Q, int64_t N, int64_t K, int r, uin
         else
             overflow_fill_kernel<<<dim3((unsigned)N), dim3(256), 0, st>>>(Q, K, thr, ovf->row_ptr, ovf->col_idx,
                                                                          ovf->capacity);
+    }
+    return launch_status();
+}
+
+extern "C" mq_status mq_slice_multi(const uint8_t *Q, int64_t N, int64_t K, const int *rs, int nr, uint32_t flags,
+                                    uint8_t *const *out, int ovf_index, const mq_overflow *ovf, void *hip_stream) {
+    using namespace mq;
+    if (N < 0 || K < 0) return MQ_ERR_SHAPE;
+    if (!rs || nr < 1 || nr > 3) return MQ_ERR_BITS;
+    const bool ep = flags & MQ_FLAG_EXTRA_PRECISION;
+    if ((flags & MQ_FLAG_EP_DENSE) || (ep && (ovf_index < 0 || ovf_index >= nr)) || (!ep && ovf_index >= 0 && ovf)) return MQ_ERR_BITS;
+    for (int i = 0; i < nr; ++i) {
+        if (rs[i] != 8 && rs[i] != 6 && rs[i] != 4 && rs[i] != 3 && rs[i] != 2) return MQ_ERR_BITS;
+        for (int j = 0; j < i; ++j)
+            if (rs[j] == rs[i]) return MQ_ERR_BITS;
+        if ((K * rs[i]) % 8 != 0) return MQ_ERR_ALIGN;
+    }
+    if (ep) {
+        if (!ovf) return MQ_ERR_NULL;
+        if (N > 0 && (!ovf->row_ptr || !ovf->nnz || (ovf->capacity > 0 && !ovf->col_idx))) return MQ_ERR_NULL;
+        if (ovf->capacity < 0) return MQ_ERR_CAPACITY;
+        if (K > 65536 || N > 0x7FFFFFFE || (N > 0 && K > 0x7FFFFFFF / N)) return MQ_ERR_SHAPE;
+    }
+    if (N == 0 || K == 0) return MQ_OK;
+    if (!Q || !out) return MQ_ERR_NULL;
+    for (int i = 0; i < nr; ++i) {
+        if (!out[i]) return MQ_ERR_NULL;
+        if (!aligned16(out[i])) return MQ_ERR_ALIGN;
+    }
+    if (!aligned16(Q)) return MQ_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // The int4 and int2 planes and the size of the overflow set come out of one pass over the codes when rows are whole
+    // 16-byte chunks; every other plane (and every plane of a ragged matrix) takes the single-plane route.
+    uint8_t *p4 = nullptr, *p2 = nullptr;
+    bool fused[3] = {false, false, false};
+    if ((K & 15) == 0)
+        for (int i = 0; i < nr; ++i) {
+            if (rs[i] == 4) p4 = out[i], fused[i] = true;
+            if (rs[i] == 2) p2 = out[i], fused[i] = true;
+        }
+    const int r_ovf = ep ? rs[ovf_index] : 8;
+    const bool count_fused = ep && (K & 15) == 0 && (p4 || p2);
+    for (int i = 0; i < nr; ++i) {
+        if (fused[i]) continue;
+        const bool with_list = ep && i == ovf_index && !count_fused;
+        const mq_status s = mq_slice(Q, N, K, rs[i], MQ_FLAG_PACKED | (with_list ? MQ_FLAG_EXTRA_PRECISION : 0), out[i],
+                                     with_list ? ovf : nullptr, hip_stream);
+        if (s != MQ_OK) return s;
+    }
+    if (p4 || p2) {
+        const uint32_t half = (1u << (8 - r_ovf)) >> 1, thr = r_ovf == 8 ? 256u : 256u - half;
+        const dim3 grid((unsigned)cdiv(N, 4)), block(256);
+        int32_t *rp = count_fused ? ovf->row_ptr : nullptr;
+#define MQ_SM(P4_, P2_) \
+    if ((p4 != nullptr) == P4_ && (p2 != nullptr) == P2_) { \
+        if (count_fused) slice_multi_kernel<P4_, P2_, true><<<grid, block, 0, st>>>(Q, N, K, p4, p2, thr, rp); \
+        else slice_multi_kernel<P4_, P2_, false><<<grid, block, 0, st>>>(Q, N, K, p4, p2, thr, rp); \
+    }
+        MQ_SM(true, true) MQ_SM(true, false) MQ_SM(false, true)
+#undef MQ_SM
+        if (count_fused) {
+            overflow_scan_kernel<<<dim3(1), dim3(1024), 0, st>>>(ovf->row_ptr, N, ovf->nnz);
+            overflow_fill16_kernel<<<dim3((unsigned)N), dim3(256), 0, st>>>(Q, K, thr, ovf->row_ptr, ovf->col_idx, ovf->capacity);
+        }
     }
     return launch_status();
 }

@@ -33,6 +33,7 @@ def lib():
     lib_.mq_slice.argtypes = [vp, i64, i64, ci, u32, vp, vp, vp]
     lib_.mq_linear_fwd_multi.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, sz, vp]
     lib_.mq_linear_fwd_multi_noalloc.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp]
+    lib_.mq_slice_multi.argtypes = [vp, i64, i64, ctypes.POINTER(ci), ci, u32, vp, ci, vp, vp]
     lib_.mq_linear_fwd_multi_gated.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_linear_bwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
@@ -321,3 +322,17 @@ def test_gated_forward_argument_checks(lib):
     assert f(None, None, None, None, 16, -4, 256, rs, 3, 0, None, None, None, 0, None) == SHAPE
     assert f(None, None, None, None, 16, 128, 256, rs, 3, 0, None, None, None, 0, None) == NULL    # X, Q, ... and A missing
     assert f(None, None, None, None, 0, 128, 256, rs, 3, 0, None, None, None, 0, None) == OK
+
+
+def test_slice_multi_argument_checks(lib):
+    f = lib.mq_slice_multi
+    ci = ctypes.c_int
+    assert f(None, 4, 64, (ci * 2)(4, 2), 0, 0, None, -1, None, None) == BITS
+    assert f(None, 4, 64, (ci * 2)(4, 5), 2, 0, None, -1, None, None) == BITS       # no packed 5-bit planes
+    assert f(None, 4, 64, (ci * 2)(4, 4), 2, 0, None, -1, None, None) == BITS       # duplicate
+    assert f(None, 4, 62, (ci * 2)(4, 6), 2, 0, None, -1, None, None) == ALIGN      # 372 bits per row at r = 6
+    assert f(None, 4, 64, (ci * 2)(4, 2), 2, 1, None, 5, None, None) == BITS        # overflow index outside rs
+    assert f(None, 4, 64, (ci * 2)(4, 2), 2, 1, None, 1, None, None) == NULL        # extra precision without a list
+    assert f(None, 4, 64, (ci * 2)(4, 2), 2, 8 | 1, None, 1, None, None) == BITS    # dense extra-precision plane: mq_slice
+    assert f(None, 0, 64, (ci * 2)(4, 2), 2, 0, None, -1, None, None) == OK
+    assert f(None, 4, 64, (ci * 2)(4, 2), 2, 0, None, -1, None, None) == NULL
