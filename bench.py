@@ -381,35 +381,41 @@ def gemv_sweep(torch, mq, synth):
             for B in (1, 4, 16):
                 x = synth.activations(4, f"x{B}:{N}x{K}", B, K).cuda()
                 y = torch.empty(B, N, dtype=torch.bfloat16, device="cuda")
-                for p in planes[:2]:
-                    mq.mq_gemv_sliced(x, p, a16, z16, r, K, y=y)
-                torch.cuda.synchronize()
-
-                def sweep():
-                    for p in planes:
-                        mq.mq_gemv_sliced(x, p, a16, z16, r, K, y=y)
-
-                # A decode loop is launch-bound from Python (several microseconds per call), so the sweep
-                # is captured once into a HIP graph and replayed; the kernels and their order are the same.
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(graph):
-                    sweep()
-                graph.replay()
-                torch.cuda.synchronize()
-                times = []
-                for _ in range(5):
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    graph.replay()
-                    e1.record()
-                    torch.cuda.synchronize()
-                    times.append(e0.elapsed_time(e1) / len(planes))
-                del graph
-                ms = sorted(times)[len(times) // 2]
                 nbytes = N * kb + 4 * N + 2 * B * K + 2 * B * N
-                gbs = nbytes / (ms * 1e-3) / 1e9
-                res[f"int{r}_{N}x{K}_B{B}"] = {"us": round(ms * 1e3, 2), "GBs": round(gbs, 1),
-                                                "frac": round(gbs / PEAK_HBM_GBS, 4)}
+
+                def measure(call):
+                    for p in planes[:2]:
+                        call(p)
+                    torch.cuda.synchronize()
+                    # A decode loop is launch-bound from Python (several microseconds per call), so the sweep
+                    # is captured once into a HIP graph and replayed; the kernels and their order are the same.
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph):
+                        for p in planes:
+                            call(p)
+                    graph.replay()
+                    torch.cuda.synchronize()
+                    times = []
+                    for _ in range(5):
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        graph.replay()
+                        e1.record()
+                        torch.cuda.synchronize()
+                        times.append(e0.elapsed_time(e1) / len(planes))
+                    del graph
+                    ms = sorted(times)[len(times) // 2]
+                    gbs = nbytes / (ms * 1e-3) / 1e9
+                    return gbs, {"us": round(ms * 1e3, 2), "GBs": round(gbs, 1), "frac": round(gbs / PEAK_HBM_GBS, 4)}
+
+                gbs, res[f"int{r}_{N}x{K}_B{B}"] = measure(lambda p: mq.mq_gemv_sliced(x, p, a16, z16, r, K, y=y))
+                ws_bytes = mq.mq_workspace_bytes(mq.MQ_OP_GEMV, B, N, K, r)
+                if B > 4 and ws_bytes > 256 and N <= 8192:
+                    # the entry point that may split K over workgroups (long rows, few of them)
+                    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+                    gbs_ws, res[f"int{r}_{N}x{K}_B{B}_with_workspace"] = measure(
+                        lambda p: mq.mq_gemv_sliced_ws(x, p, a16, z16, r, K, y=y, ws=ws))
+                    gbs = max(gbs, gbs_ws)
                 if r == 2 and (best is None or gbs > best[1]):
                     best = (f"int{r}_{N}x{K}_B{B}", gbs)
             del planes
@@ -653,7 +659,7 @@ def mixnmatch_decode(torch, mq, synth):
             layers.append(dict(gate_up=gu, down=dn, alpha_gu=a_gu, zero_gu=z_gu, alpha_dn=a_dn, zero_dn=z_dn, r=r))
             wbytes += gu.numel() + dn.numel() + 4 * (2 * F + d)
         entry = {"bits_per_weight": round(sum(rs) / len(rs), 3), "weight_MB": round(wbytes / 1e6, 1)}
-        for B in (1, 4):
+        for B in (1, 4, 16):
             x = synth.activations(4, f"mnm{B}", B, d).cuda()
             y = torch.empty(B, d, dtype=torch.bfloat16, device="cuda")
             ws = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_FFN_DECODE, B, F, d, 1), dtype=torch.uint8, device="cuda")

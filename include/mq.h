@@ -58,7 +58,7 @@ enum {
 };
 
 enum { MQ_OP_LINEAR_FWD = 0, MQ_OP_LINEAR_BWD = 1, MQ_OP_FFN_DECODE = 2, MQ_OP_L2_LOSS = 3, MQ_OP_LINEAR_FWD_L2 = 4,
-       MQ_OP_LINEAR_BWD_CLIP = 5, MQ_OP_AFFINE_BWD = 6 };
+       MQ_OP_LINEAR_BWD_CLIP = 5, MQ_OP_AFFINE_BWD = 6, MQ_OP_GEMV = 7 };
 
 /*
  * Extra-precision overflow set (errata section: weights whose rounded r-bit
@@ -229,6 +229,21 @@ mq_status mq_linear_bwd(const uint16_t *X, const uint8_t *Q, const float *alpha,
 mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                          const uint16_t *zero_bf16, const mq_overflow *ovf,
                          int64_t B, int64_t N, int64_t K, int r, uint16_t *y, void *hip_stream);
+
+/*
+ * mq_gemv_sliced for callers that can lend scratch memory (section 1: the decode GEMV moves the weights out of
+ * HBM once; with few rows and a long K, e.g. the down projection at B = 16, one workgroup per row block leaves
+ * most of the chip idle, so K is also split over workgroups and a second kernel adds the parts in a fixed order).
+ * Same arguments, result to the same tolerance (the order of the fp32 additions differs), plus
+ *   ws      device, 16-byte aligned, at least mq_workspace_bytes(MQ_OP_GEMV, B, N, K, r) bytes (else
+ *           MQ_ERR_WORKSPACE); contents undefined on entry and exit; calls that share it must not overlap
+ * Shapes the split form is not used for (B <= 4, r not in {4, 2}, packed rows that are not whole 128-byte lines or
+ * shorter than 1664 bytes, more than 8192 rows) run exactly as mq_gemv_sliced does and leave ws untouched.
+ */
+mq_status mq_gemv_sliced_ws(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
+                            const uint16_t *zero_bf16, const mq_overflow *ovf,
+                            int64_t B, int64_t N, int64_t K, int r, uint16_t *y,
+                            void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * The same GEMV on a dense extra-precision plane (mq_slice with MQ_FLAG_EXTRA_PRECISION |
@@ -441,7 +456,8 @@ mq_status mq_linear_bwd_gated(const uint16_t *X, const uint8_t *Q, const float *
                               int64_t M, int64_t F, int64_t K, const int *rs, int nr, uint32_t flags,
                               uint16_t *dX, float *dW, void *ws, size_t ws_bytes, void *hip_stream);
 
-/* Bytes of workspace `op` needs at these sizes (0 on invalid arguments).  MQ_OP_FFN_DECODE: M = B, N = F, K = d. */
+/* Bytes of workspace `op` needs at these sizes (0 on invalid arguments).  MQ_OP_FFN_DECODE: M = B, N = F, K = d.
+ * MQ_OP_GEMV: M = B, nr = r (bits per code). */
 size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int nr);
 
 /* Static, human-readable name of a status code. */

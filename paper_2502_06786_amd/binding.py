@@ -25,6 +25,7 @@ MQ_OP_L2_LOSS = 3
 MQ_OP_LINEAR_FWD_L2 = 4
 MQ_OP_LINEAR_BWD_CLIP = 5
 MQ_OP_AFFINE_BWD = 6
+MQ_OP_GEMV = 7
 MQ_FLAG_LOSS_MIX = 64
 MQ_FLAG_FFN_SILU = 16
 MQ_FLAG_FFN_RESIDUAL = 32
@@ -33,7 +34,7 @@ EXPORTS = ["mq_quantize_int8", "mq_slice", "mq_linear_fwd_multi", "mq_linear_bwd
            "mq_params_to_bf16", "mq_workspace_bytes", "mq_status_string",
            "mq_gemv_sliced_dense_ep", "mq_ffn_mixnmatch", "mq_matquant_l2_loss", "mq_linear_fwd_multi_l2", "mq_linear_bwd_clip",
            "mq_affine_weight", "mq_affine_input", "mq_affine_bwd", "mq_gated_unit_fwd", "mq_gated_unit_bwd",
-           "mq_linear_fwd_multi_noalloc", "mq_linear_bwd_gated", "mq_linear_fwd_multi_gated", "mq_slice_multi"]
+           "mq_linear_fwd_multi_noalloc", "mq_linear_bwd_gated", "mq_linear_fwd_multi_gated", "mq_slice_multi", "mq_gemv_sliced_ws"]
 
 
 class MqError(RuntimeError):
@@ -73,6 +74,7 @@ def _load() -> ctypes.CDLL:
     lib.mq_linear_bwd_gated.argtypes = [vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_float),
                                         i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib.mq_gemv_sliced.argtypes = [vp, vp, vp, vp, ctypes.POINTER(_Overflow), i64, i64, i64, ci, vp, vp]
+    lib.mq_gemv_sliced_ws.argtypes = [vp, vp, vp, vp, ctypes.POINTER(_Overflow), i64, i64, i64, ci, vp, vp, sz, vp]
     lib.mq_workspace_bytes.argtypes = [ci, i64, i64, i64, ci]
     lib.mq_workspace_bytes.restype = sz
     lib.mq_status_string.argtypes = [ci]
@@ -368,6 +370,24 @@ def mq_gemv_sliced(x, packed, alpha_bf16, zero_bf16, r: int, K: int, ovf: Overfl
     st = _lib.mq_gemv_sliced(_ptr(x, torch.bfloat16), _ptr(packed, torch.uint8), _ptr(alpha_bf16, torch.bfloat16),
                              _ptr(zero_bf16, torch.bfloat16), c_ovf, B, N, K, r, _ptr(y, torch.bfloat16), _stream())
     _check(st, "mq_gemv_sliced")
+    return y
+
+
+def mq_gemv_sliced_ws(x, packed, alpha_bf16, zero_bf16, r: int, K: int, ovf: Overflow | None = None, y=None, ws=None):
+    """mq_gemv_sliced with a workspace (allocated here when not given): K may be split over workgroups."""
+    B = x.shape[0]
+    N = packed.shape[0]
+    if x.shape[1] != K or packed.shape[1] != K * r // 8:
+        raise ValueError("shape mismatch")
+    if y is None:
+        y = torch.empty(B, N, dtype=torch.bfloat16, device=x.device)
+    if ws is None:
+        ws = torch.empty(mq_workspace_bytes(MQ_OP_GEMV, B, N, K, r), dtype=torch.uint8, device=x.device)
+    c_ovf = ctypes.byref(ovf.c_struct()) if ovf is not None else None
+    st = _lib.mq_gemv_sliced_ws(_ptr(x, torch.bfloat16), _ptr(packed, torch.uint8), _ptr(alpha_bf16, torch.bfloat16),
+                                _ptr(zero_bf16, torch.bfloat16), c_ovf, B, N, K, r, _ptr(y, torch.bfloat16),
+                                _ptr(ws, torch.uint8), ws.numel(), _stream())
+    _check(st, "mq_gemv_sliced_ws")
     return y
 
 

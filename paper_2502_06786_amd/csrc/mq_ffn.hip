@@ -4,6 +4,8 @@
 // products come out of a single pass over the activations and meet in the epilogue, which applies the
 // gate activation; the epilogue of the down product adds the residual.  (As separate element-wise
 // kernels the two small operations cost about a quarter of a layer's time at batch 1.)
+#include <algorithm>
+
 #include "mq_gemv.h"
 
 namespace mq {
@@ -56,7 +58,7 @@ __global__ __launch_bounds__(256) void gate_train_kernel(GateArgs a) {
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct FfnLayout {
-    size_t act, h0, h1, total;
+    size_t act, h0, h1, split, split_bytes, total;
 };
 inline FfnLayout ffn_layout(int64_t B, int64_t F, int64_t d) {
     FfnLayout l;
@@ -64,6 +66,9 @@ inline FfnLayout ffn_layout(int64_t B, int64_t F, int64_t d) {
     l.act = off, off += align256((size_t)B * F * 2);
     l.h0 = off, off += align256((size_t)B * d * 2);
     l.h1 = off, off += align256((size_t)B * d * 2);
+    // parts of the down product when its K (= F) is split over workgroups
+    l.split_bytes = std::max(gemv_split_workspace_bytes(B, d, F, 4), gemv_split_workspace_bytes(B, d, F, 2));
+    l.split = off, off += align256(l.split_bytes);
     l.total = off;
     return l;
 }
@@ -116,7 +121,7 @@ extern "C" mq_status mq_ffn_mixnmatch(const uint16_t *x, const mq_ffn_layer *lay
                                        use_silu ? kPostSilu : kPostGelu, nullptr, hip_stream);
         if (s != MQ_OK) return s;
         s = gemv_sliced_post(act, L.down, L.alpha_dn, L.zero_dn, B, d, F, L.r, hn, residual ? kPostResidual : kPostNone,
-                             residual ? h : nullptr, hip_stream);
+                             residual ? h : nullptr, hip_stream, lay.split_bytes ? base + lay.split : nullptr, lay.split_bytes);
         if (s != MQ_OK) return s;
         h = hn;
     }

@@ -63,7 +63,7 @@ __device__ __forceinline__ uint16_t residual_bf16(uint16_t res, float o) {
 // The decode GEMV with an epilogue of the list above (the public mq_gemv_sliced is kPostNone).
 mq_status gemv_sliced_post(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                            const uint16_t *zero_bf16, int64_t B, int64_t N, int64_t K, int r, uint16_t *y, int post,
-                           const uint16_t *res, void *hip_stream);
+                           const uint16_t *res, void *hip_stream, void *split_ws = nullptr, size_t split_ws_bytes = 0);
 
 // The host-side checks of such a call that do not involve x or y (callers that enqueue several
 // GEMVs run them for every one before the first launch).
@@ -90,5 +90,10 @@ mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handl
 // Batches of 5 .. 16 on tall int4 / int2 planes (no residual epilogue restriction): activations in registers as
 // 16x16x32 matrix-core operands.  Same convention for *handled.
 mq_status launch_gemv_reg(const GemvArgs &a, int r, hipStream_t st, bool *handled);
+
+// The same kernel with K split over workgroups and a second kernel that adds the parts (any number of rows; for long
+// rows and few of them).  ws: gemv_split_workspace_bytes() bytes of device memory (0 = shape not covered).
+size_t gemv_split_workspace_bytes(int64_t B, int64_t N, int64_t K, int r);
+mq_status launch_gemv_reg_split(const GemvArgs &a, int r, void *ws, size_t ws_bytes, hipStream_t st, bool *handled);
 
 }  // namespace mq

@@ -653,7 +653,7 @@ mq_status mq::gemv_sliced_check(const uint8_t *packed, int64_t B, int64_t N, int
 static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                                const uint16_t *zero_bf16, const mq_overflow *ovf, int64_t B, int64_t N, int64_t K,
                                int r, int shift, uint16_t *y, void *hip_stream, int post = mq::kPostNone,
-                               const uint16_t *res = nullptr) {
+                               const uint16_t *res = nullptr, void *ws = nullptr, size_t ws_bytes = 0) {
     using namespace mq;
     if (post == kPostResidual && !res && N > 0) return MQ_ERR_NULL;
     if (ovf && K > 65536) return MQ_ERR_SHAPE;
@@ -688,6 +688,11 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
         // its products before it scales and overwrites y
         const mq_status os = launch_overflow_sums(x, ovf->row_ptr, ovf->col_idx, ovf->capacity, B, N, K, y, st);
         if (os != MQ_OK) return os;
+    }
+    if (ws) {
+        bool handled = false;
+        const mq_status ss = launch_gemv_reg_split(a, r, ws, ws_bytes, st, &handled);
+        if (ss != MQ_OK || handled) return ss;
     }
     {
         bool handled = false;
@@ -725,9 +730,11 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
 
 mq_status mq::gemv_sliced_post(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
                                const uint16_t *zero_bf16, int64_t B, int64_t N, int64_t K, int r, uint16_t *y, int post,
-                               const uint16_t *res, void *hip_stream) {
+                               const uint16_t *res, void *hip_stream, void *split_ws, size_t split_ws_bytes) {
     if (r < 1 || r > 8) return MQ_ERR_BITS;
-    return gemv_dispatch(x, packed, alpha_bf16, zero_bf16, nullptr, B, N, K, r, 8 - r, y, hip_stream, post, res);
+    const bool split = split_ws && gemv_split_workspace_bytes(B, N, K, r) != 0;
+    return gemv_dispatch(x, packed, alpha_bf16, zero_bf16, nullptr, B, N, K, r, 8 - r, y, hip_stream, post, res,
+                         split ? split_ws : nullptr, split_ws_bytes);
 }
 
 extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
@@ -735,6 +742,16 @@ extern "C" mq_status mq_gemv_sliced(const uint16_t *x, const uint8_t *packed, co
                                     int64_t K, int r, uint16_t *y, void *hip_stream) {
     if (r < 1 || r > 8) return MQ_ERR_BITS;
     return gemv_dispatch(x, packed, alpha_bf16, zero_bf16, ovf, B, N, K, r, 8 - r, y, hip_stream);
+}
+
+extern "C" mq_status mq_gemv_sliced_ws(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,
+                                       const uint16_t *zero_bf16, const mq_overflow *ovf, int64_t B, int64_t N,
+                                       int64_t K, int r, uint16_t *y, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (r < 1 || r > 8) return MQ_ERR_BITS;
+    const size_t need = mq::gemv_split_workspace_bytes(B, N, K, r);
+    if (!ws || ws_bytes < std::max<size_t>(256, need) || !mq::aligned16(ws)) return MQ_ERR_WORKSPACE;
+    return gemv_dispatch(x, packed, alpha_bf16, zero_bf16, ovf, B, N, K, r, 8 - r, y, hip_stream, mq::kPostNone, nullptr,
+                         need ? ws : nullptr, ws_bytes);
 }
 
 extern "C" mq_status mq_gemv_sliced_dense_ep(const uint16_t *x, const uint8_t *packed, const uint16_t *alpha_bf16,

@@ -54,11 +54,40 @@ __device__ __forceinline__ Consts consts() {
 template <int R>
 constexpr int ops_per_line() { return R == 2 ? 16 : 8; }
 
+// Outputs of rows row0 .. row0 + 3 for batch entry b from the sum of (offset + code) x, the offsets' share xoff and
+// the activations' sum xsum.
+__device__ __forceinline__ void finish_outputs(const GemvArgs &a, int b, int row0, const f32x4 &dot, float xsum, float xoff,
+                                               const float (&al)[4], const float (&ze)[4]) {
+    float yv[4];
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+        float d = dot[cc] - xoff;
+        // extra precision: the overflow sum of this output waits in y (the kernel before this one wrote it)
+        if (a.add_y && row0 + cc < a.N) d += ovf_sum_unpack(a.y[(size_t)b * a.N + row0 + cc]);
+        yv[cc] = al[cc] * (a.scale * d - ze[cc] * xsum);
+    }
+    if (a.post >= kPostGelu) {
+#pragma unroll
+        for (int cc = 0; cc < 4; cc += 2)
+            if (row0 + cc < a.N) a.y[(size_t)b * (a.N >> 1) + ((row0 + cc) >> 1)] = gated_bf16(yv[cc], yv[cc + 1], a.post);
+    } else {
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            const size_t at = (size_t)b * a.N + row0 + cc;
+            if (row0 + cc < a.N)
+                a.y[at] = a.post == kPostResidual ? residual_bf16(a.res[at], yv[cc]) : (uint16_t)float_to_bf16_bits(yv[cc]);
+        }
+    }
+}
+
 // R = bits per code (2 or 4); NL = 128-byte lines per K slice; S = ring depth (tiles per wave)
 // Workgroup = KS * RW waves; wave (ks, rw).  Slices ks, ks + KS, ... (rounds) of row blocks rw, rw + RW, ... of the
 // workgroup's CH row blocks c * G + blockIdx.
-template <int R, int NL, int S, int MAXT>
-__global__ __launch_bounds__(MAXT) void gemv_reg_kernel(GemvArgs a, int KS, int RW, int CH, int NSL) {
+// SPLIT: blockIdx.y picks a group of KS slices (one round); the workgroup leaves its partial products and activation
+// sums in global memory (pdot [groups][row blocks][64] x 4 floats, psum [groups][16][2]) for split_reduce_kernel.
+template <int R, int NL, int S, int MAXT, bool SPLIT>
+__global__ __launch_bounds__(MAXT) void gemv_reg_kernel(GemvArgs a, int KS, int RW, int CH, int NSL_all, f32x4 *pdot,
+                                                        float *psum) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     constexpr int OPL = ops_per_line<R>();
     constexpr int CPB = 8 / R;  // codes per byte
@@ -74,6 +103,8 @@ __global__ __launch_bounds__(MAXT) void gemv_reg_kernel(GemvArgs a, int KS, int 
     const int G = gridDim.x, wg = blockIdx.x;
     const int nblk = (NRB - wg + G - 1) / G;            // row blocks of this workgroup (>= 1)
     const int nv = max(0, (nblk - rw + RW - 1) / RW);   // visits per round (wave-uniform)
+    const int SB = SPLIT ? (int)blockIdx.y * KS : 0;    // first slice of this workgroup
+    const int NSL = SPLIT ? min(KS, NSL_all - SB) : NSL_all;
     const int nr = (NSL - ks + KS - 1) / KS;            // rounds of this wave
     const int nsteps = nr * nv * NL;
 
@@ -95,7 +126,7 @@ __global__ __launch_bounds__(MAXT) void gemv_reg_kernel(GemvArgs a, int KS, int 
         const int last = a.N - 1 - rb * 16;
         const uint32_t r_a = (uint32_t)max(min(li, last), 0) * (uint32_t)a.KB;
         const uint32_t r_b = (uint32_t)max(min(li + 8, last), 0) * (uint32_t)a.KB;
-        const int lb = ((ks + KS * iround) * NL + iln) * 128;
+        const int lb = ((SB + ks + KS * iround) * NL + iln) * 128;
         const uint32_t p_a = (uint32_t)max(min(lb + lp0 * 16, a.KB - 16), 0);
         const uint32_t p_b = (uint32_t)max(min(lb + lp1 * 16, a.KB - 16), 0);
         uint8_t *dst = ring + islot * kTile;
@@ -168,7 +199,7 @@ __global__ __launch_bounds__(MAXT) void gemv_reg_kernel(GemvArgs a, int KS, int 
     // alpha, z of the first epilogue item of this thread (item = (row block c, output lane): 4 rows x 1 batch entry)
     const int items = nblk * 64;
     float pal[4], pze[4];
-    {
+    if constexpr (!SPLIT) {
         const int it = tid < items ? tid : 0;
         const int c = it >> 6, ol = it & 63;
         const int row0 = (c * G + wg) * 16 + 4 * (ol >> 4);
@@ -180,7 +211,7 @@ __global__ __launch_bounds__(MAXT) void gemv_reg_kernel(GemvArgs a, int KS, int 
         }
     }
 
-    if (nr > 0 && nv > 0) load_x(ks);
+    if (nr > 0 && nv > 0) load_x(SB + ks);
 #pragma unroll
     for (int st = 0; st < S; ++st) issue_next();
 
@@ -257,7 +288,7 @@ __global__ __launch_bounds__(MAXT) void gemv_reg_kernel(GemvArgs a, int KS, int 
                         sums[((ks + KS * rcur) * 16 + lane) * 2 + 1] = R == 2 ? s2 : 128.f * s1;
                     }
                     s1 = s2 = 0.f;
-                    if (++rcur < nr) load_x(ks + KS * rcur);
+                    if (++rcur < nr) load_x(SB + ks + KS * rcur);
                 }
             }
         }
@@ -266,7 +297,6 @@ __global__ __launch_bounds__(MAXT) void gemv_reg_kernel(GemvArgs a, int KS, int 
 
     // ---- epilogue ---------------------------------------------------------------------------------------
     __syncthreads();
-    const float kScale = a.scale;
     for (int it = tid, m = 0; it < items; it += nthreads, ++m) {
         const int c = it >> 6, ol = it & 63, b = ol & 15;
         if (b >= a.B) continue;
@@ -292,34 +322,63 @@ __global__ __launch_bounds__(MAXT) void gemv_reg_kernel(GemvArgs a, int KS, int 
                     dot += dp[q];
                 }
         }
-        float yv[4];
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-            float al, ze;
-            if (m == 0) {
-                al = pal[cc], ze = pze[cc];
-            } else {
-                const int row = min(row0 + cc, a.N - 1);
-                al = bf16_bits_to_float(a.alpha[row]), ze = bf16_bits_to_float(a.zero[row]);
+        if constexpr (SPLIT) {
+            pdot[((size_t)blockIdx.y * NRB + (c * G + wg)) * 64 + ol] = dot;
+            if (wg == 0 && c == 0 && ol < 16) {
+                psum[(blockIdx.y * 16 + b) * 2] = xsum;
+                psum[(blockIdx.y * 16 + b) * 2 + 1] = xoff;
             }
-            float d = dot[cc] - xoff;
-            // extra precision: the overflow sum of this output waits in y (the kernel before this one wrote it)
-            if (a.add_y && row0 + cc < a.N) d += ovf_sum_unpack(a.y[(size_t)b * a.N + row0 + cc]);
-            yv[cc] = al * (kScale * d - ze * xsum);
-        }
-        if (a.post >= kPostGelu) {
-#pragma unroll
-            for (int cc = 0; cc < 4; cc += 2)
-                if (row0 + cc < a.N) a.y[(size_t)b * (a.N >> 1) + ((row0 + cc) >> 1)] = gated_bf16(yv[cc], yv[cc + 1], a.post);
         } else {
+            float al[4], ze[4];
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
-                const size_t at = (size_t)b * a.N + row0 + cc;
-                if (row0 + cc < a.N)
-                    a.y[at] = a.post == kPostResidual ? residual_bf16(a.res[at], yv[cc]) : (uint16_t)float_to_bf16_bits(yv[cc]);
+                if (m == 0) {
+                    al[cc] = pal[cc], ze[cc] = pze[cc];
+                } else {
+                    const int row = min(row0 + cc, a.N - 1);
+                    al[cc] = bf16_bits_to_float(a.alpha[row]), ze[cc] = bf16_bits_to_float(a.zero[row]);
+                }
             }
+            finish_outputs(a, b, row0, dot, xsum, xoff, al, ze);
         }
     }
+}
+
+// second kernel of the split form: adds the groups' partial results in a fixed order and finishes the outputs
+__global__ __launch_bounds__(256) void split_reduce_kernel(GemvArgs a, int SG, const f32x4 *pdot, const float *psum) {
+    const int NRB = (a.N + 15) >> 4;
+    const int it = blockIdx.x * 256 + threadIdx.x;
+    if (it >= NRB * 64) return;
+    const int rb = it >> 6, ol = it & 63, b = ol & 15;
+    const int row0 = rb * 16 + 4 * (ol >> 4);
+    if (b >= a.B || row0 >= a.N) return;
+    float al[4], ze[4];
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+        const int row = min(row0 + cc, a.N - 1);
+        al[cc] = bf16_bits_to_float(a.alpha[row]), ze[cc] = bf16_bits_to_float(a.zero[row]);
+    }
+    float xsum = 0.f, xoff = 0.f;
+    f32x4 dot = {0.f, 0.f, 0.f, 0.f};
+    for (int g0 = 0; g0 < SG; g0 += 8) {
+        f32x4 dp[8];
+        float xs[8], xo[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int sg = min(g0 + q, SG - 1);
+            dp[q] = pdot[((size_t)sg * NRB + rb) * 64 + ol];
+            xs[q] = psum[(sg * 16 + b) * 2];
+            xo[q] = psum[(sg * 16 + b) * 2 + 1];
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (g0 + q < SG) {
+                dot += dp[q];
+                xsum += xs[q];
+                xoff += xo[q];
+            }
+    }
+    finish_outputs(a, b, row0, dot, xsum, xoff, al, ze);
 }
 
 
@@ -330,12 +389,51 @@ struct RegPlan {
 
 template <int R, int NL, int S, int MAXT>
 mq_status launch_reg(const GemvArgs &a, const RegPlan &p, hipStream_t st) {
-    auto kern = gemv_reg_kernel<R, NL, S, MAXT>;
+    auto kern = gemv_reg_kernel<R, NL, S, MAXT, false>;
     if (p.lds > 65536 && hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                              (int)p.lds) != hipSuccess)
         return MQ_ERR_DEVICE;
-    kern<<<dim3(p.grid), dim3(64 * p.ks), p.lds, st>>>(a, p.ks, 1, p.ch, p.nsl);
+    kern<<<dim3(p.grid), dim3(64 * p.ks), p.lds, st>>>(a, p.ks, 1, p.ch, p.nsl, nullptr, nullptr);
     return launch_status();
+}
+
+// the split form: groups of p.ks slices in blockIdx.y, then the reduction
+template <int R, int NL, int S>
+mq_status launch_reg_split(const GemvArgs &a, const RegPlan &p, int groups, void *ws, hipStream_t st) {
+    auto kern = gemv_reg_kernel<R, NL, S, 256, true>;
+    if (p.lds > 65536 && hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)p.lds) != hipSuccess)
+        return MQ_ERR_DEVICE;
+    const int nrb = (a.N + 15) / 16;
+    f32x4 *pdot = static_cast<f32x4 *>(ws);
+    float *psum = reinterpret_cast<float *>(pdot + (size_t)groups * nrb * 64);
+    kern<<<dim3(p.grid, groups), dim3(64 * p.ks), p.lds, st>>>(a, p.ks, 1, p.ch, p.nsl, pdot, psum);
+    mq_status s = launch_status();
+    if (s != MQ_OK) return s;
+    split_reduce_kernel<<<dim3((nrb * 64 + 255) / 256), dim3(256), 0, st>>>(a, groups, pdot, psum);
+    return launch_status();
+}
+
+// Split plan: workgroups of four waves (four slices), every wave visiting p.ch row blocks; about one workgroup per
+// compute unit (measured best on 4096 x 14336 and 4608 x 36864 at B = 8 and 16: 13 us against 25, 25 against 94; two
+// to four per compute unit cost 10-35 % more, their activation loads grow with the number of workgroups).
+// Used for long rows and few of them: at least four groups of slices and at most 8192 rows; elsewhere the one-kernel
+// forms are level or faster (4096 x 4096, 14336 x 4096 and taller: 1.0-1.5x the time).
+bool split_plan(const GemvArgs &a, int r, RegPlan *p, int *groups) {
+    if (a.B <= 4 || (r != 2 && r != 4) || (a.KB & 127) != 0 || (int64_t)a.N * a.KB > 0x7FFFFFFFll) return false;
+    const int lines = a.KB >> 7, nrb = (a.N + 15) / 16;
+    p->nl = r == 2 ? 1 : 2;
+    if (lines % p->nl) p->nl = 1;
+    p->nsl = lines / p->nl;
+    p->ks = std::min(4, p->nsl);
+    *groups = (p->nsl + p->ks - 1) / p->ks;
+    if (*groups < 4 || a.N > 8192) return false;
+    p->depth = 3;
+    const int row_groups = std::max(1, 256 / *groups);
+    p->ch = (nrb + row_groups - 1) / row_groups;
+    p->grid = (nrb + p->ch - 1) / p->ch;
+    p->lds = (size_t)p->ks * 128 + (size_t)p->ks * p->depth * kTile + (size_t)p->ks * p->ch * 1024;
+    return p->lds <= 160 * 1024;
 }
 
 }  // namespace
@@ -380,6 +478,27 @@ mq_status launch_gemv_reg(const GemvArgs &a, int r, hipStream_t st, bool *handle
 #undef MQ_REG_CASE
     *handled = false;
     return MQ_OK;
+}
+
+size_t gemv_split_workspace_bytes(int64_t B, int64_t N, int64_t K, int r) {
+    if (B < 1 || N < 1 || K < 1 || (r != 2 && r != 4) || (K * r) % 8 != 0) return 0;
+    const int64_t kb = K * r / 8;
+    if (kb & 127) return 0;
+    const int64_t lines = kb >> 7, nl = (r == 4 && lines % 2 == 0) ? 2 : 1, nsl = lines / nl;
+    const int64_t groups = (nsl + 3) / 4, nrb = (N + 15) / 16;
+    return (size_t)(groups * nrb * 1024 + groups * 128);
+}
+
+mq_status launch_gemv_reg_split(const GemvArgs &a, int r, void *ws, size_t ws_bytes, hipStream_t st, bool *handled) {
+    *handled = false;
+    RegPlan p{};
+    int groups = 0;
+    if (!split_plan(a, r, &p, &groups)) return MQ_OK;
+    if (!ws || ws_bytes < gemv_split_workspace_bytes(a.B, a.N, a.K, r) || !aligned16(ws)) return MQ_ERR_WORKSPACE;
+    *handled = true;
+    if (r == 2) return launch_reg_split<2, 1, 3>(a, p, groups, ws, st);
+    if (p.nl == 2) return launch_reg_split<4, 2, 3>(a, p, groups, ws, st);
+    return launch_reg_split<4, 1, 3>(a, p, groups, ws, st);
 }
 
 }  // namespace mq

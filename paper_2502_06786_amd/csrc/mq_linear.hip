@@ -1417,6 +1417,8 @@ static mq_status launch_dx(const DxArgs &d, int nr, bool has8, bool ep, hipStrea
 
 extern "C" size_t mq_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int nr) {
     using namespace mq;
+    if (op == MQ_OP_GEMV)  // M = B, nr = bits per code
+        return M < 1 || M > 16 || N < 0 || K < 1 || nr < 1 || nr > 8 ? 0 : std::max<size_t>(256, gemv_split_workspace_bytes(M, N, K, nr));
     if (M < 0 || N < 0 || K < 0 || nr < 1 || nr > 3) return 0;
     if (op == MQ_OP_LINEAR_FWD) return align256((size_t)M * 4) + 256;
     if (op == MQ_OP_LINEAR_FWD_L2) return align256((size_t)M * 4) + (size_t)fwd_max_blocks(M, N) * 16 + 256;

@@ -38,6 +38,7 @@ def lib():
     lib_.mq_linear_bwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(ci), ci, u32, vp, vp, vp, sz, vp]
     lib_.mq_gemv_sliced.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
+    lib_.mq_gemv_sliced_ws.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, sz, vp]
     lib_.mq_params_to_bf16.argtypes = [vp, vp, i64, vp, vp, vp]
     lib_.mq_gemv_sliced_dense_ep.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib_.mq_matquant_l2_loss.argtypes = [vp, vp, ctypes.POINTER(ci), vp, i64, i64, ci, u32, vp, vp, vp, sz, vp]
@@ -336,3 +337,23 @@ def test_slice_multi_argument_checks(lib):
     assert f(None, 4, 64, (ci * 2)(4, 2), 2, 8 | 1, None, 1, None, None) == BITS    # dense extra-precision plane: mq_slice
     assert f(None, 0, 64, (ci * 2)(4, 2), 2, 0, None, -1, None, None) == OK
     assert f(None, 4, 64, (ci * 2)(4, 2), 2, 0, None, -1, None, None) == NULL
+
+
+def test_gemv_with_workspace_argument_checks(lib):
+    f, wsb = lib.mq_gemv_sliced_ws, lib.mq_workspace_bytes
+    # (MQ_OP_GEMV = 7: M = B, nr = bits per code) four floats per (group of four slices, row, batch column) where K is
+    # split: 14336 int2 codes = 28 lines = 7 groups; at least 256 bytes otherwise
+    assert wsb(7, 16, 4096, 14336, 2) >= 7 * 4096 * 16 * 4
+    assert wsb(7, 16, 4096, 14336, 4) >= 7 * 4096 * 16 * 4
+    assert wsb(7, 16, 4096, 14336, 8) == 256 and wsb(7, 16, 4096, 100, 2) == 256
+    assert wsb(7, 17, 4096, 14336, 2) == 0 and wsb(7, 0, 4096, 14336, 2) == 0 and wsb(7, 4, 4096, 14336, 9) == 0
+    p = ctypes.c_void_p(256)   # never dereferenced: every call below fails (or has nothing to do) on the host
+    assert f(p, p, p, p, None, 16, 64, 14336, 9, p, p, 1 << 30, None) == BITS
+    assert f(p, p, p, p, None, 16, 64, 14336, 2, p, None, 1 << 30, None) == WORKSPACE
+    assert f(p, p, p, p, None, 16, 64, 14336, 2, p, p, wsb(7, 16, 64, 14336, 2) - 1, None) == WORKSPACE
+    assert f(p, p, p, p, None, 16, 64, 14336, 2, p, ctypes.c_void_p(264), 1 << 30, None) == WORKSPACE   # not 16-byte aligned
+    assert f(p, p, p, p, None, 16, 64, 100, 8, p, p, 255, None) == WORKSPACE
+    assert f(p, p, p, p, None, 17, 64, 14336, 2, p, p, 1 << 30, None) == SHAPE
+    assert f(p, p, p, p, None, 16, 64, 14330, 2, p, p, 1 << 30, None) == ALIGN
+    assert f(None, p, p, p, None, 16, 64, 14336, 2, p, p, 1 << 30, None) == NULL
+    assert f(p, p, p, p, None, 16, 0, 14336, 2, p, p, 1 << 30, None) == OK

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.util import assert_close, bf16_bits, first_overflow_code, rel_l2
+from tests.util import accumulation_allowance, assert_close, bf16_bits, first_overflow_code, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -560,6 +560,51 @@ def test_gemv_small_batch_tall_matrix_one_hot_exact(mq, oracle):
             assert np.array_equal(y.float().cpu().numpy().astype(np.float64), want), (r, k0)
 
 
+@pytest.mark.parametrize("r,N,K,B,with_list", [(2, 150, 7168, 16, False), (4, 150, 7168, 5, False), (4, 64, 6912, 9, False),
+                                               (2, 8192, 6656, 8, False), (2, 200, 14336, 16, True), (4, 40, 36864, 13, True),
+                                               (2, 100, 4096, 16, False), (8, 100, 7168, 16, False), (2, 100, 7168, 3, False)])
+def test_gemv_with_workspace_split_k(mq, oracle, r, N, K, B, with_list):
+    """mq_gemv_sliced_ws: long rows and few of them at 5 <= B <= 16 on int4 / int2 planes run with K split over
+    workgroups (groups of four slices, the last group partial; one and two lines per slice; ragged row blocks; the
+    overflow sums added by the reducing kernel), other shapes as mq_gemv_sliced does; all against the oracle, output
+    by output."""
+    from paper_2502_06786_amd import synth
+    q = synth.planted_codes(80 + r + B, N, K, first_overflow_code(r), 0.03) if with_list else synth.uniform_codes(80 + r + B, N, K)
+    a = (torch.rand(N, generator=torch.Generator().manual_seed(28)) * 1e-3 + 1e-4).to(torch.bfloat16)
+    z = (torch.rand(N, generator=torch.Generator().manual_seed(29)) * 255).to(torch.bfloat16)
+    x = _randn(B + r + 17, B, K).to(torch.bfloat16)
+    if with_list:
+        packed, ovf = mq.mq_slice(dev(q), r, packed=True, extra_precision=True)
+        torch.cuda.synchronize()
+        lists = oracle.overflow_csr(q.numpy(), r)
+        assert int(ovf.nnz.item()) == lists[1].size > 0
+    else:
+        packed, ovf, lists = mq.mq_slice(dev(q), r, packed=True), None, None
+    y = mq.mq_gemv_sliced_ws(dev(x), packed, dev(a), dev(z), r, K, ovf=ovf)
+    want = oracle.gemv_sliced(bf16_bits(x), packed.cpu().numpy(), bf16_bits(a), bf16_bits(z), r, K, ovf=lists)
+    assert_close(y.float().cpu().numpy(), want, what=(r, N, K, B, with_list),
+                 extra=accumulation_allowance(K, 1.0, a.double().numpy() * float(1 << (8 - r)))[None, :])
+
+
+def test_gemv_with_workspace_one_hot_exact(mq, oracle):
+    # alpha = 1, z = 0, one-hot activations: y[b, n] is exactly the sliced value of code [n, k_b], through the split form
+    N, K = 72, 7168
+    q = torch.arange(N * K, dtype=torch.int64).mul(7).add(torch.arange(N * K, dtype=torch.int64) // K).remainder(256)
+    q = q.to(torch.uint8).reshape(N, K)
+    a = torch.ones(N).to(torch.bfloat16)
+    z = torch.zeros(N).to(torch.bfloat16)
+    for r in (2, 4):
+        packed = mq.mq_slice(dev(q), r, packed=True)
+        sliced = oracle.slice_values(q.numpy(), r)
+        for B, k0 in ((16, 0), (16, 5000), (11, 7150), (5, 37)):
+            cols = (k0 + torch.arange(B) * 449) % K     # the batch entries fall into different slices and groups
+            x = torch.zeros(B, K)
+            x[torch.arange(B), cols] = 1.0
+            y = mq.mq_gemv_sliced_ws(dev(x.to(torch.bfloat16)), packed, dev(a), dev(z), r, K)
+            want = sliced[:, cols.numpy()].T.astype(np.float64)
+            assert np.array_equal(y.float().cpu().numpy().astype(np.float64), want), (r, B, k0)
+
+
 def test_gemv_one_hot_exact(mq, oracle):
     # alpha = 1, z = 0, one-hot activations: y[b, n] is exactly the sliced value of code [n, b].
     N, K = 64, 256
@@ -616,7 +661,8 @@ def _ffn_layer_by_layer(mq, oracle, layers, host, x, d, F, silu, residual):
 
 @pytest.mark.parametrize("d,F,rs,B,silu,residual", [
     (256, 512, (2, 8, 4), 1, False, False), (256, 512, (2, 8, 4), 4, True, False), (256, 512, (3, 6, 2, 4), 16, False, True),
-    (512, 1536, (4,), 3, False, False), (128, 256, (), 2, False, False)])
+    (512, 1536, (4,), 3, False, False), (128, 256, (), 2, False, False),
+    (128, 7168, (2, 4), 16, False, True), (128, 6912, (4, 2), 6, True, False)])   # (down product: K split over workgroups)
 def test_ffn_mixnmatch_small(mq, oracle, d, F, rs, B, silu, residual):
     layers, host = _ffn_stack(mq, oracle, 70, d, F, rs, scale=1.5)
     x = _randn(77 + B, B, d).to(torch.bfloat16)
