@@ -656,7 +656,7 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict_
 // backward, preparation (HBM-bound): one pass over the nr gradient tensors produces
 //   As_i[m, n] = bf16(lambda_i * alpha_n * 2^s_i * dY_i[m, n])     (operand of the dX contraction)
 //   c[m]       = sum_i sum_n As_i[m, n] * (bias_i + z_n / 2^s_i)   (what the 128 + code form and z add to dX[m, :])
-//   GT[n, m]   = bf16(sum_i lambda_i * dY_i[m, n])                  (transposed operand of the dW GEMM)
+//   GT[n, m]   = bf16(sum_i lambda_i * dY_i[m, n])                  (transposed operand of the dW GEMM, in token blocks)
 // ============================================================================================
 struct PrepArgs {
     const uint16_t *dY[3];
@@ -671,9 +671,9 @@ struct PrepArgs {
     float mult[3];       // 2^s_i
     float bias[3];       // 128 for sliced slots, 0 for the r = 8 slot
     float *cpart;        // [nsplit][M] partial sums of c over column ranges, or null
-    uint16_t *GT;        // [N, ldm] or null (columns M .. ldm - 1 are written as zeros)
+    uint16_t *GT;        // [M / 32][N][32] (blocks of 32 tokens; see DwArgs) or null; tokens M .. ldm - 1 are written as zeros
     int nr, M, N;
-    int ldm;             // M rounded up to a multiple of 8: rows of GT start on 16-byte boundaries
+    int ldm;             // M rounded up to a multiple of 8
     int cols_per_split;  // multiple of 64
 };
 
@@ -748,7 +748,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(PrepArgs a) {
             const int nn = t >> 2, part = t & 3;  // 64 rows of GT, four 16-byte pieces each
             if (n0 + nn < a.N && m0 + part * 8 < a.M) {  // (a piece that straddles M ends with zeros)
                 const uint32_t *src = reinterpret_cast<const uint32_t *>(&tile[nn][part * 8]);
-                *reinterpret_cast<u32x4 *>(a.GT + (size_t)(n0 + nn) * a.ldm + m0 + part * 8) =
+                *reinterpret_cast<u32x4 *>(a.GT + ((size_t)blockIdx.x * a.N + n0 + nn) * 32 + part * 8) =
                     u32x4{src[0], src[1], src[2], src[3]};
             }
         }
@@ -765,7 +765,9 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(PrepArgs a) {
 // bytes' worth of elements, the rows of out are ld_out elements apart (rows rounded up to such a
 // multiple) and end with zeros.  64 x (64 bytes) tiles, 16-byte global accesses on both sides, the
 // turn happens in LDS.
-template <typename T>
+// BLOCKED (2-byte elements): out is [rows / 32][cols][32] instead, i.e. element (c, r) sits at ((r / 32) cols + c) 32 + r % 32
+// (the operand layout of dw_kernel).
+template <typename T, bool BLOCKED = false>
 __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in, T *__restrict__ out, int rows,
                                                         int cols, int ld_out) {
     constexpr int E = 16 / sizeof(T);  // elements per 16 bytes
@@ -791,8 +793,9 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in
         const int c = t / PIECES, piece = t % PIECES;
         if (c < TC && c0 + c < cols && r0 + piece * E < rows) {
             const uint32_t *src = reinterpret_cast<const uint32_t *>(&tile[c][piece * E]);
-            *reinterpret_cast<u32x4 *>(out + (size_t)(c0 + c) * ld_out + r0 + piece * E) =
-                u32x4{src[0], src[1], src[2], src[3]};
+            const int r = r0 + piece * E;
+            const size_t at = BLOCKED ? ((size_t)(r >> 5) * cols + c0 + c) * 32 + (r & 31) : (size_t)(c0 + c) * ld_out + r;
+            *reinterpret_cast<u32x4 *>(out + at) = u32x4{src[0], src[1], src[2], src[3]};
         }
     }
 }
@@ -1110,30 +1113,64 @@ __global__ __launch_bounds__(256) void dx_kernel(DxArgs a) {
 // backward dW: dW[n, k] (+)= sum_m GT[n, m] * XT[k, m]   (plain bf16 GEMM, fp32 out)
 // ============================================================================================
 struct DwArgs {
-    const uint16_t *GT;  // [N, ldm]
-    const uint16_t *XT;  // [K, ldm]
+    // Both operands come in blocks of 32 tokens, [M / 32][rows][32]: the 64-byte row segments that one LDS stage takes
+    // from a tile's 256 rows are then one contiguous 16 KB piece of memory, i.e. whole 128-byte lines.  (With rows of
+    // M tokens a stage would use half of every line it touches and the other half 32 tokens later, when the line has
+    // left the first-level cache: twice the traffic between the caches.)
+    const uint16_t *GT;  // [M / 32][N][32]
+    const uint16_t *XT;  // [M / 32][K][32]
     float *dW;           // [N, K]
+    float *part;         // [split tiles][parts][256][256]: partial tiles of the split last round
     int M, N, K;
-    int ldm;             // M rounded up to a multiple of 8; columns M .. ldm - 1 hold zeros
+    int ldm;             // M rounded up to a multiple of 8; tokens M .. ldm - 1 hold zeros
     int accumulate;
     int tiles_n, tiles_k;
+    int whole;           // work items [0, whole) are whole tiles; the others are token ranges of the remaining tiles
+    int parts;           // token ranges per remaining tile
 };
 
-constexpr int DW_RB = 2;                   // 32-row blocks of n per wave
-constexpr int DW_MB = 6;                   // 32-column blocks of k per wave
-constexpr int DW_BN = 4 * 32 * DW_RB;      // rows of n per workgroup (4 waves)
-constexpr int DW_BK = 32 * DW_MB;          // columns of k per workgroup
+constexpr int DW_RB = 4;                   // 32-row blocks of n per wave
+constexpr int DW_MB = 4;                   // 32-column blocks of k per wave
+constexpr int DW_BN = 2 * 32 * DW_RB;      // rows of n per workgroup (2 x 2 waves)
+constexpr int DW_BK = 2 * 32 * DW_MB;      // columns of k per workgroup
 constexpr int DW_BM = 32;                  // contraction elements (tokens) per stage: 64-byte rows
 constexpr int DW_A_TILE = DW_BN * 64, DW_B_TILE = DW_BK * 64;
 constexpr int DW_STAGE = DW_A_TILE + DW_B_TILE;
 constexpr int DW_NST = 5;                  // LDS stages
 constexpr int DW_LDS = DW_NST * DW_STAGE;
+constexpr int DW_CUS = 256;                // compute units a round of workgroups fills
 
-// Same pipeline as the forward and dX kernels (one wave per SIMD, direct-to-LDS stages, one small
-// fenced group of operand work per MFMA), without any code conversion: both operands are bf16 rows
-// with the contraction index (tokens) contiguous.  Wave w owns rows [64 w, 64 w + 64) of the n tile
-// for all 192 k columns: 12 accumulators, 8 operand reads per 12 MFMAs.  Stages are 32 tokens deep
-// (64-byte rows) so that five of them fit: three stages of loads stay in flight.
+// How the tiles of dW are dealt to workgroups.  Whole rounds of 256 tiles run one tile per workgroup; the tiles of a
+// last partial round (at most half a round) are cut along the tokens into `parts` ranges each, so that the round
+// still occupies every compute unit for 1 / parts of a tile's time; the ranges leave fp32 partial tiles in the
+// workspace and dw_reduce_kernel adds them in a fixed order.
+struct DwPlan {
+    int tiles_n, tiles_k, whole, rest, parts;
+    size_t part_bytes;
+};
+static DwPlan dw_plan(int64_t M, int64_t N, int64_t K) {
+    DwPlan p;
+    p.tiles_n = (int)cdiv(N, DW_BN);
+    p.tiles_k = (int)cdiv(K, DW_BK);
+    const int64_t tiles = (int64_t)p.tiles_n * p.tiles_k;
+    const int64_t stages = cdiv(M, DW_BM);
+    int rest = (int)(tiles % DW_CUS);
+    int parts = rest > 0 ? DW_CUS / rest : 1;
+    parts = (int)std::min<int64_t>(parts, std::max<int64_t>(1, stages / 8));   // at least eight stages per range
+    if (tiles < DW_CUS || parts < 2) rest = 0, parts = 1;
+    p.whole = (int)(tiles - rest);
+    p.rest = rest;
+    p.parts = parts;
+    p.part_bytes = (size_t)rest * parts * DW_BN * DW_BK * 4;
+    return p;
+}
+
+// Same pipeline as the forward and dX kernels (one wave per SIMD, direct-to-LDS stages, one small fenced group of
+// operand work per MFMA), without any code conversion: both operands are bf16 rows with the contraction index
+// (tokens) contiguous.  The four waves form a 2 x 2 grid over the 256 x 256 tile, 128 x 128 each: 16 accumulators
+// (all 256 accumulator registers), 8 operand reads per 16 MFMAs - the square wave tile is what keeps the LDS traffic
+// (32 KB read + 16 KB written per 16-token step and compute unit, 94 bytes per clock at the matrix-core rate) under
+// the 128 bytes per clock the LDS delivers.  Stages are 32 tokens deep (64-byte rows); five of them fill the LDS.
 __global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
@@ -1143,9 +1180,25 @@ __global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
     static_assert(RB + MB <= NM && LPS <= NM, "not enough MFMAs to hide the operand work");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wn = wave >> 1, wk = wave & 1;
     const int h = lane >> 5, l32 = lane & 31;
 
-    const uint32_t lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    // work item -> tile and token range
+    const int nmt_all = (a.M + DW_BM - 1) / DW_BM;
+    uint32_t lid;
+    int mt0 = 0, mt1 = nmt_all;
+    float *dst = a.dW;
+    bool to_part = false;
+    if ((int)blockIdx.x < a.whole) {
+        lid = xcd_contiguous_id(blockIdx.x, (uint32_t)a.whole);
+    } else {
+        const int idx = (int)blockIdx.x - a.whole, part = idx % a.parts;
+        lid = (uint32_t)(a.whole + idx / a.parts);
+        mt0 = (int)((int64_t)nmt_all * part / a.parts);
+        mt1 = (int)((int64_t)nmt_all * (part + 1) / a.parts);
+        dst = a.part + (size_t)idx * (DW_BN * DW_BK);
+        to_part = true;
+    }
     constexpr int GROUP = 4;
     const int width = GROUP * a.tiles_k;
     const int first_n = (int)(lid / width) * GROUP;
@@ -1154,26 +1207,28 @@ __global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
     const int tk = (int)(lid % width) / gsz;
     const int n0 = tn * DW_BN, k0 = tk * DW_BK;
 
-    const __amdgpu_buffer_rsrc_t rG = make_rsrc(a.GT + (size_t)n0 * a.ldm, (uint64_t)(a.N - n0) * a.ldm * 2);
-    const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.XT + (size_t)k0 * a.ldm, (uint64_t)(a.K - k0) * a.ldm * 2);
-
     uint32_t off0;
     int colb;  // byte column of this lane's 16-byte piece inside a 64-byte row
-    u8_tile_lane<4>(wave, lane, 0, (uint32_t)a.ldm * 2u, off0, colb);
-    const uint32_t rstep = 64u * (uint32_t)a.ldm * 2u;  // 64 rows further down
+    u8_tile_lane<4>(wave, lane, 0, 64u, off0, colb);
+    const uint32_t rstep = 64u * 64u;  // 64 rows further down
 
-    // load i of the stage of token tile mt into LDS buffer `buf`; a tile past M is requested at an
-    // out-of-range offset and answered with zeros, so the loads in flight are the same every stage
+    // load i of the stage of token block mt into LDS buffer `buf`.  The descriptor of a stage starts at the tile's
+    // first row inside that block and ends with the block, so rows past N (K) are out of range; a block or a piece
+    // past M is requested at an out-of-range offset.  Both are answered with zeros without touching memory, so the
+    // loads in flight are the same every stage.
     auto issue_one = [&](int mt, int buf, int i) {
         const int mm = mt * DW_BM;
         uint8_t *base = smem + buf * DW_STAGE;
-        const uint32_t o = (mm + colb / 2 < a.M) ? off0 + (uint32_t)mm * 2u : kOOB;
-        if (i < AL)
+        const uint32_t o = (mm + colb / 2 < a.M) ? off0 : kOOB;
+        if (i < AL) {
+            const __amdgpu_buffer_rsrc_t rG = make_rsrc(a.GT + ((size_t)mt * a.N + n0) * 32, (uint64_t)(a.N - n0) * 64);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rG, (lds_ptr)(base + (wave + i * 4) * 1024), 16,
                                                      o + (uint32_t)i * rstep, 0, 0, 0);
-        else
+        } else {
+            const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.XT + ((size_t)mt * a.K + k0) * 32, (uint64_t)(a.K - k0) * 64);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rX, (lds_ptr)(base + DW_A_TILE + (wave + (i - AL) * 4) * 1024), 16,
                                                      o + (uint32_t)(i - AL) * rstep, 0, 0, 0);
+        }
     };
 
     // LDS fragment offsets inside a stage for the two 16-token steps of a stage
@@ -1181,8 +1236,8 @@ __global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         const uint32_t chunk = (uint32_t)((2 * t + h) ^ ((l32 >> 2) & 3)) << 4;
-        ab[t] = (uint32_t)(wave * 64 + l32) * 64u + chunk;
-        bb[t] = (uint32_t)DW_A_TILE + (uint32_t)l32 * 64u + chunk;
+        ab[t] = (uint32_t)(wn * 128 + l32) * 64u + chunk;
+        bb[t] = (uint32_t)DW_A_TILE + (uint32_t)(wk * 128 + l32) * 64u + chunk;
     }
 
     f32x16 acc[RB][MB];
@@ -1193,11 +1248,11 @@ __global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[rb][j][v] = 0.f;
 
-    const int nmt = (a.M + DW_BM - 1) / DW_BM;
+    const int nmt = mt1 - mt0;   // >= 1 (the host plans at least eight stages per range)
 #pragma unroll
     for (int st = 0; st < DW_NST - 1; ++st)
 #pragma unroll
-        for (int i = 0; i < LPS; ++i) issue_one(st, st, i);
+        for (int i = 0; i < LPS; ++i) issue_one(mt0 + st, st, i);
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DW_NST - 2) * LPS) : "memory");
     __syncthreads();
 
@@ -1246,45 +1301,49 @@ __global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
         // is free for stage mt + 4
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DW_NST - 3) * LPS) : "memory");
         __syncthreads();
-        tile(std::true_type{}, mt, cb);
+        tile(std::true_type{}, mt0 + mt, cb);
         cb = cb + 1 == DW_NST ? 0 : cb + 1;
     }
-    tile(std::false_type{}, nmt - 1, cb);
-    wait_vm0();  // zero-fill loads of dead stages must have landed before the workgroup ends
+    tile(std::false_type{}, mt0 + nmt - 1, cb);
+    wait_vm0();  // loads of stages that nobody consumes must have landed before the workgroup ends
 
     // Rows of the product are n, columns k: a store instruction writes 32 consecutive k (one 128-byte line)
     // of two rows.  Branch-free: every store goes through a buffer descriptor that starts at the first
-    // element of the wave's 32-row block and ends with dW, so rows past N fall out of range and are
+    // element of the wave's 32-row block and ends with the destination, so rows past N fall out of range and are
     // dropped by the memory unit; a column past K is sent out of range explicitly.  The row part of the
     // address (wave-uniform) travels in the scalar offset, the lane part in one register per k block.
-    // All workgroups of a round reach this point together, so the phase lasts as long as the memory takes
-    // to absorb their 50 MB (about 10 us); when accumulating, the old values of four rows are requested
-    // together, one memory round trip per 24 values.
+    // A token range of a split tile writes its whole 256 x 256 partial tile instead (row length 256, no edges).
+    // When accumulating, the old values of four rows are requested together, one memory round trip per 16 values.
+    const int ld = to_part ? DW_BK : a.K;              // row length of the destination
+    const int rows = to_part ? DW_BN : a.N - n0;       // rows and columns of the destination from this tile's origin
+    const int cols = to_part ? DW_BK : a.K - k0;
+    float *origin = to_part ? dst : dst + (int64_t)n0 * a.K + k0;
     auto store_tile = [&](auto accumulate_tag) {
         constexpr bool ACCUMULATE = decltype(accumulate_tag)::value;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            const int nb = n0 + wave * 64 + rb * 32;
-            const int64_t left = ((int64_t)a.N - nb) * a.K - k0;  // elements from (nb, k0) to the end of dW
-            const __amdgpu_buffer_rsrc_t rW =
-                make_rsrc(a.dW + (int64_t)nb * a.K + k0, left > 0 ? (uint64_t)left * 4u : 0u);
+            const int r0 = wn * 128 + rb * 32;                      // first row of the block inside the tile
+            const int64_t left = ((int64_t)rows - r0) * ld - (to_part ? 0 : k0);  // elements to the end of the destination
+            const __amdgpu_buffer_rsrc_t rW = make_rsrc(origin + (int64_t)r0 * ld, left > 0 ? (uint64_t)left * 4u : 0u);
             uint32_t voff[MB];
 #pragma unroll
-            for (int j = 0; j < MB; ++j)
-                voff[j] = k0 + j * 32 + l32 < a.K ? ((uint32_t)(4 * h) * (uint32_t)a.K + (uint32_t)(j * 32 + l32)) * 4u : kOOB;
+            for (int j = 0; j < MB; ++j) {
+                const int c = wk * 128 + j * 32 + l32;
+                voff[j] = c < cols ? ((uint32_t)(4 * h) * (uint32_t)ld + (uint32_t)c) * 4u : kOOB;
+            }
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 uint32_t old[ACCUMULATE ? 4 : 1][MB];
-                if constexpr (ACCUMULATE) {  // the 24 values of four rows are requested together
+                if constexpr (ACCUMULATE) {  // the values of four rows are requested together
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
 #pragma unroll
                         for (int j = 0; j < MB; ++j)
-                            old[e][j] = __builtin_amdgcn_raw_buffer_load_b32(rW, voff[j], (uint32_t)(8 * g + e) * (uint32_t)a.K * 4u, 0);
+                            old[e][j] = __builtin_amdgcn_raw_buffer_load_b32(rW, voff[j], (uint32_t)(8 * g + e) * (uint32_t)ld * 4u, 0);
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const uint32_t row = (uint32_t)(8 * g + e) * (uint32_t)a.K * 4u;
+                    const uint32_t row = (uint32_t)(8 * g + e) * (uint32_t)ld * 4u;
 #pragma unroll
                     for (int j = 0; j < MB; ++j) {
                         float v = acc[rb][j][4 * g + e];
@@ -1295,7 +1354,7 @@ __global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
             }
         }
     };
-    if (a.accumulate)
+    if (a.accumulate && !to_part)
         store_tile(std::true_type{});
     else
         store_tile(std::false_type{});
@@ -1304,13 +1363,40 @@ __global__ __launch_bounds__(256) void dw_kernel(DwArgs a) {
 #endif
 }
 
+// dW tile (+)= the partial tiles of its token ranges, added in the order of the ranges.  One workgroup per 16 rows of
+// a split tile, a thread per four columns.
+__global__ __launch_bounds__(256) void dw_reduce_kernel(DwArgs a) {
+    const int t = blockIdx.x / (DW_BN / 16), r16 = blockIdx.x % (DW_BN / 16);   // split tile, 16-row block
+    const uint32_t lid = (uint32_t)(a.whole + t);
+    constexpr int GROUP = 4;
+    const int width = GROUP * a.tiles_k;
+    const int first_n = (int)(lid / width) * GROUP;
+    const int gsz = min(a.tiles_n - first_n, GROUP);
+    const int tn = first_n + (int)(lid % width) % gsz;
+    const int tk = (int)(lid % width) / gsz;
+    const int row = r16 * 16 + (threadIdx.x >> 6) * 4, col = (threadIdx.x & 63) * 4;
+    const int k = tk * DW_BK + col;
+    if (k >= a.K) return;   // (K is a multiple of 8: four columns are inside or outside together)
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int n = tn * DW_BN + row + rr;
+        if (n >= a.N) return;
+        const float *src = a.part + (size_t)t * a.parts * (DW_BN * DW_BK) + (size_t)(row + rr) * DW_BK + col;
+        f32x4 sum = *reinterpret_cast<const f32x4 *>(src);
+        for (int p = 1; p < a.parts; ++p) sum += *reinterpret_cast<const f32x4 *>(src + (size_t)p * (DW_BN * DW_BK));
+        f32x4 *out = reinterpret_cast<f32x4 *>(a.dW + (size_t)n * a.K + k);
+        if (a.accumulate) sum += *out;
+        *out = sum;
+    }
+}
+
 // ============================================================================================
 // host side
 // ============================================================================================
 static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 struct BwdWorkspace {
-    size_t cvec, as[3], gt, xt, qt, total;
+    size_t cvec, as[3], gt, xt, qt, dwp, total;
 };
 
 static BwdWorkspace bwd_layout(int64_t M, int64_t N, int64_t K, int nr) {
@@ -1322,13 +1408,15 @@ static BwdWorkspace bwd_layout(int64_t M, int64_t N, int64_t K, int nr) {
         w.as[i] = o;
         if (i < nr) o += align256((size_t)M * N * 2);
     }
-    const size_t ldm = ((size_t)M + 7) & ~(size_t)7;
+    const size_t m32 = ((size_t)M + 31) & ~(size_t)31;   // the transposed operands of dW come in blocks of 32 tokens
     w.gt = o;
-    o += align256(ldm * N * 2);
+    o += align256(m32 * N * 2);
     w.xt = o;
-    o += align256(ldm * K * 2);
+    o += align256(m32 * K * 2);
     w.qt = o;
     o += align256((size_t)N * K);
+    w.dwp = o;
+    o += align256(dw_plan(M, N, K).part_bytes);
     w.total = o;
     return w;
 }
@@ -1747,7 +1835,7 @@ static mq_status bwd_run(bool gated, const uint16_t *X, const uint8_t *Q, const 
     }
     if (dW) {
         uint16_t *XT = reinterpret_cast<uint16_t *>(base + lay.xt);
-        transpose_kernel<uint16_t><<<dim3((unsigned)cdiv(K, 32), (unsigned)cdiv(M, 64)), dim3(256), 0, st>>>(
+        transpose_kernel<uint16_t, true><<<dim3((unsigned)cdiv(K, 32), (unsigned)cdiv(M, 64)), dim3(256), 0, st>>>(
             X, XT, (int)M, (int)K, p.ldm);
         DwArgs w;
         w.GT = p.GT;
@@ -1758,10 +1846,15 @@ static mq_status bwd_run(bool gated, const uint16_t *X, const uint8_t *Q, const 
         w.K = (int)K;
         w.ldm = p.ldm;
         w.accumulate = (flags & MQ_FLAG_ACCUM_DW) ? 1 : 0;
-        w.tiles_n = (int)cdiv(N, DW_BN);
-        w.tiles_k = (int)cdiv(K, DW_BK);
+        const DwPlan plan = dw_plan(M, N, K);
+        w.tiles_n = plan.tiles_n;
+        w.tiles_k = plan.tiles_k;
+        w.whole = plan.whole;
+        w.parts = plan.parts;
+        w.part = reinterpret_cast<float *>(base + lay.dwp);
         if (!allow_lds(dw_kernel, DW_LDS)) return MQ_ERR_DEVICE;
-        dw_kernel<<<dim3(w.tiles_n * w.tiles_k), dim3(256), DW_LDS, st>>>(w);
+        dw_kernel<<<dim3(plan.whole + plan.rest * plan.parts), dim3(256), DW_LDS, st>>>(w);
+        if (plan.rest > 0) dw_reduce_kernel<<<dim3(plan.rest * (DW_BN / 16)), dim3(256), 0, st>>>(w);
     }
     return launch_status();
 }

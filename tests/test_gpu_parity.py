@@ -272,6 +272,28 @@ def test_bwd_bit_width_sets_and_accumulate(mq, oracle, rs, lambdas):
     assert none is None and torch.equal(dX3, dX)
 
 
+def test_bwd_dw_last_round_split_over_tokens(mq, oracle):
+    """289 tiles of dW on 256 compute units: the 33 tiles of the last partial round are computed as four token ranges
+    each and summed by a second kernel.  Ragged in all three sizes (the last tile row and column are 16 wide, the last
+    token block holds 8 tokens), with and without accumulation; only dW is asked for."""
+    M, N, K = 1000, 4112, 4112
+    X = _randn(31, M, K).to(torch.bfloat16)
+    dYs = [_randn(300 + i, M, N, scale=1e-3).to(torch.bfloat16) for i in range(2)]
+    lambdas, rs = (0.5, 1.0), (4, 2)
+    Q = dev(torch.zeros(N, K, dtype=torch.uint8))
+    a = dev(torch.ones(N))
+    z = dev(torch.zeros(N))
+    none, dW = mq.mq_linear_bwd(dev(X), Q, a, z, [dev(d) for d in dYs], lambdas, rs, need_dX=False)
+    assert none is None
+    want_dw = oracle.linear_bwd_dw(bf16_bits(X), [bf16_bits(d) for d in dYs], lambdas)
+    assert_close(dW.cpu().numpy(), want_dw, c_rms=2.0 ** -6, what="dW")
+    base = dev(_randn(33, N, K, scale=1e-2))
+    dW2 = base.clone()
+    mq.mq_linear_bwd(dev(X), Q, a, z, [dev(d) for d in dYs], lambdas, rs, need_dX=False, dW=dW2, accumulate_dW=True)
+    assert_close((dW2 - base).cpu().numpy(), want_dw, c_rms=2.0 ** -6, what="dW accumulated",
+                 extra=2.0 ** -22 * np.abs(base.cpu().numpy()))      # (fp32 rounding of base + dW, then of the difference)
+
+
 @pytest.mark.parametrize("rs", RS_SETS)
 @pytest.mark.parametrize("ep", [False, True])
 def test_bwd_exact_integers(mq, oracle, rs, ep):
