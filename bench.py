@@ -33,7 +33,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per launch of the fused forward kernel on the headline workload, per linear, from the
 # FETCH_SIZE / WRITE_SIZE counter passes summarised in profiles/ (scale factors stated there); None until taken.
-FWD_TRAFFIC_BYTES = {3: {"gate": None, "up": None, "down": None}, 2: {"gate": None, "up": None, "down": None}}
+FWD_TRAFFIC_BYTES = {3: {"gate": 2526042 * 1024, "up": 2526042 * 1024, "down": 1950774 * 1024},
+                     2: {"gate": None, "up": None, "down": None}}
 WORKLOADS = {
     3: "configs[2]: Gemma-2-9B-shaped MLP, d_model 3584, ffn 14336, 8192 tokens, outlier weights, lambda = (0.1, 0.1, 1.0)",
     2: "configs[1]: Gemma-2-2B-shaped MLP, d_model 2304, ffn 9216, 4096 tokens",
@@ -410,7 +411,7 @@ def gemv_sweep(torch, mq, synth):
 
                 gbs, res[f"int{r}_{N}x{K}_B{B}"] = measure(lambda p: mq.mq_gemv_sliced(x, p, a16, z16, r, K, y=y))
                 ws_bytes = mq.mq_workspace_bytes(mq.MQ_OP_GEMV, B, N, K, r)
-                if B > 4 and ws_bytes > 256 and N <= 8192:
+                if ws_bytes > 256:
                     # the entry point that may split K over workgroups (long rows, few of them)
                     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
                     gbs_ws, res[f"int{r}_{N}x{K}_B{B}_with_workspace"] = measure(

@@ -486,6 +486,7 @@ size_t gemv_split_workspace_bytes(int64_t B, int64_t N, int64_t K, int r) {
     if (kb & 127) return 0;
     const int64_t lines = kb >> 7, nl = (r == 4 && lines % 2 == 0) ? 2 : 1, nsl = lines / nl;
     const int64_t groups = (nsl + 3) / 4, nrb = (N + 15) / 16;
+    if (B <= 4 || groups < 4 || N > 8192) return 0;   // (the conditions of split_plan)
     return (size_t)(groups * nrb * 1024 + groups * 128);
 }
 
