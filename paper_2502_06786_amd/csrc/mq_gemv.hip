@@ -704,8 +704,10 @@ static mq_status gemv_dispatch(const uint16_t *x, const uint8_t *packed, const u
 
     // Rows per wave (16 RG): every activation operand read from LDS serves RG matrix-core products, so
     // tall matrices take two row groups; short ones keep RG = 1 for more waves (measured on the decode
-    // shapes at B = 4 and 16: 4096 rows run 10-25 % faster with RG = 1, 14336 rows level or faster with 2).
-    const int rg = N >= 8192 ? 2 : 1;
+    // shapes at B = 4 and 16: 4096 rows run 10-25 % faster with RG = 1, 14336 rows level or faster with 2;
+    // at B = 1 the columns are idle anyway and 11008 and 14336 rows run 6-13 % faster with RG = 1.  A
+    // deeper ring did not help at any of these sizes: D = 4 and 5 were 2-10 % slower than 3).
+    const int rg = (N >= 8192 && (B > 2 || N >= 16384)) ? 2 : 1;
     // K-split: about 2048 waves in total (8 per compute unit measured best across the decode shapes:
     // enough loads in flight, and the whole grid resident at once) when there are few row blocks,
     // none when the rows alone provide them.  Workgroups have 8 waves (KS of them per row block),
