@@ -369,9 +369,10 @@ def gemv_sweep(torch, mq, synth):
     exceed the 256 MB last-level cache, and one stream-ordered sweep over all copies is timed."""
     res = {}
     best = None
-    for (N, K) in synth.DECODE_SHAPES:
+    # (the last two are the stacked gate/up planes that mq_ffn_mixnmatch reads: 7B- and 27B-shaped, int2 and int4)
+    for (N, K) in list(synth.DECODE_SHAPES) + [(28672, 4096), (73728, 4608)]:
         g = torch.Generator().manual_seed(N * 7 + K)
-        for r in (2, 4, 3, 6):
+        for r in ((2, 4, 3, 6) if (N, K) in synth.DECODE_SHAPES else (2, 4)):
             kb = K * r // 8
             copies = max(8, int(640e6 // (N * kb)) + 1)
             planes = [torch.randint(0, 256, (N, kb), generator=g, dtype=torch.int32).to(torch.uint8).cuda()

@@ -1087,6 +1087,77 @@ def test_step_replays_from_a_hip_graph(mq):
             assert torch.equal(g_, w_), (trial, i)
 
 
+def test_later_entry_points_replay_from_a_hip_graph(mq):
+    """The same for the calls added later: mq_slice_multi, the forward with the gate in its epilogue, the backward with
+    the gate gradient in its first pass (dW with a split last round needs no clearing between calls), the GEMV with a
+    workspace in its K-split form and a Mix'n'Match stack at B = 16 whose down products run K-split.  Captured once,
+    replayed on new inputs, compared bit for bit with eager calls."""
+    M, F, K, rs, lam = 136, 72, 256, (8, 4, 2), (0.2, 0.5, 1.0)
+    N = 2 * F
+    u8 = dict(dtype=torch.uint8, device="cuda")
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    W = dev(_randn(1, N, K, scale=0.05))
+    X = dev(_randn(2, M, K).to(torch.bfloat16))
+    dA = [dev(_randn(30 + i, M, F, scale=1e-2).to(torch.bfloat16)) for i in range(3)]
+    Q, a, z = torch.empty(N, K, **u8), torch.empty(N, device="cuda"), torch.empty(N, device="cuda")
+    planes = [torch.empty(N, K // 2, **u8), torch.empty(N, K // 4, **u8)]
+    ovf = mq.Overflow(N, N * K // 4)
+    GU = [torch.empty(M, N, **bf) for _ in rs]
+    A = [torch.empty(M, F, **bf) for _ in rs]
+    dX, dW = torch.empty(M, K, **bf), torch.empty(N, K, device="cuda")
+    ws_f = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_FWD, M, N, K, 3), **u8)
+    ws_b = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_LINEAR_BWD, M, N, K, 3), **u8)
+    # decode side: a long-row plane (K-split GEMV) and a two-layer stack with F = 7168
+    Bd, Nd, Kd = 16, 96, 7168
+    qd = dev(torch.randint(0, 256, (Nd, Kd), dtype=torch.int32, generator=torch.Generator().manual_seed(5)).to(torch.uint8))
+    pd = mq.mq_slice(qd, 2, packed=True)
+    ad = dev((torch.rand(Nd, generator=torch.Generator().manual_seed(6)) * 1e-3 + 1e-4).to(torch.bfloat16))
+    zd = dev((torch.rand(Nd, generator=torch.Generator().manual_seed(7)) * 255).to(torch.bfloat16))
+    xd = dev(_randn(8, Bd, Kd).to(torch.bfloat16))
+    yd = torch.empty(Bd, Nd, **bf)
+    ws_g = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_GEMV, Bd, Nd, Kd, 2), **u8)
+    assert ws_g.numel() > 256                       # (the split form is what runs)
+    d_, F_ = 128, 7168
+    layers, _ = _ffn_stack(mq, None, 40, d_, F_, (2, 4), scale=1.5)
+    xs = dev(_randn(9, Bd, d_).to(torch.bfloat16))
+    ys = torch.empty(Bd, d_, **bf)
+    ws_s = torch.empty(mq.mq_workspace_bytes(mq.MQ_OP_FFN_DECODE, Bd, F_, d_, 1), **u8)
+
+    def step():
+        mq.mq_quantize_int8(W, Q=Q, alpha=a, zero=z)
+        mq.mq_slice_multi(Q, (4, 2), out=planes, ovf_r=2, ovf=ovf)
+        mq.mq_linear_fwd_multi_gated(X, Q, a, z, rs, GU=GU, A=A, ws=ws_f)
+        mq.mq_linear_bwd_gated(X, Q, a, z, GU, dA, lam, rs, dX=dX, dW=dW, ws=ws_b)
+        mq.mq_gemv_sliced_ws(xd, pd, ad, zd, 2, Kd, y=yd, ws=ws_g)
+        mq.mq_ffn_mixnmatch(xs, layers, F_, residual=True, y=ys, ws=ws_s)
+
+    outs = (Q, *planes, ovf.row_ptr, *GU, *A, dX, dW, yd, ys)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for trial in range(3):
+        W.copy_(dev(_randn(50 + trial, N, K, scale=0.05)))
+        X.copy_(dev(_randn(60 + trial, M, K).to(torch.bfloat16)))
+        xd.copy_(dev(_randn(70 + trial, Bd, Kd).to(torch.bfloat16)))
+        xs.copy_(dev(_randn(80 + trial, Bd, d_).to(torch.bfloat16)))
+        torch.cuda.synchronize()
+        step()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in outs]
+        for t in outs:
+            t.zero_()
+        ws_g.zero_(), ws_s.zero_(), ws_b.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (g_, w_) in enumerate(zip(outs, want)):
+            assert torch.equal(g_, w_), (trial, i)
+
+
 # --------------------------------------------------------------------------
 # the calls as a training loop
 # --------------------------------------------------------------------------
