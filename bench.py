@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--no-gemv-sweep", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the 27B-shaped forward block and the added operations")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured-ceiling probes")
+    ap.add_argument("--only-decode", action="store_true",
+                    help="run only the decode GEMV sweeps and the read probe (for counter passes over the decode kernels); "
+                         "prints their sections, not the bench line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 256 MiB device-to-device copies before the timed region: a kernel of "
                          "known traffic against which hardware byte counters of a profiling run are scaled")
@@ -113,6 +116,11 @@ def main():
 
     mq.lib()  # fails loudly when libmq.so is missing
     torch.cuda.set_device(0)
+    if args.only_decode:
+        from paper_2502_06786_amd import bench_probes
+        print(json.dumps({"only": "decode", "measured_peaks": measured_peaks(torch, bench_probes),
+                          "gemv_roofline": gemv_sweep(torch, mq, synth), "extra_precision_gemv": ep_gemv(torch, mq, synth)}))
+        return
     cfg = args.config
     rs, lambdas = (8, 4, 2), synth.LAMBDAS[cfg]
     _, M = synth.mlp_shapes(cfg)

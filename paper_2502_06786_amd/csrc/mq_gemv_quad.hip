@@ -22,7 +22,6 @@
 // epilogue through sum_k x_k * offset_k, which comes out of the activation registers next to
 // sum_k x_k (the zero-point term).
 #include <algorithm>
-#include <cstdlib>
 
 #include "mq_gemv.h"
 
@@ -401,7 +400,10 @@ mq_status launch_gemv_quad(const GemvArgs &a, int r, hipStream_t st, bool *handl
                 break;
             }
     if (p.ks < 1 || p.ks > 8) return MQ_ERR_SHAPE;
-    const int wpc = 12;  // waves per compute unit the grid is sized for
+    // waves per compute unit the grid is sized for (measured on 16384..73728 rows: 12 is best at B = 1, within 2 % of the
+    // best everywhere; at B = 4, where a wave's activation registers take four times as long to fill, 8 is 5-10 % faster
+    // on the tall planes; 6, 16 and 24 are slower)
+    const int wpc = a.B > 2 ? 8 : 12;
     // Row-block waves per workgroup and row blocks per workgroup: the whole grid resident at once
     // (wpc waves per compute unit), every wave the same number of visits where the shape allows.
     p.rw = 1;
