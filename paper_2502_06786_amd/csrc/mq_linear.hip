@@ -1451,14 +1451,16 @@ static mq_status launch_fwd_mb(FwdArgs a, hipStream_t st, int64_t *blocks) {
 // Token-tile height: the tallest tile amortises the code conversion and the epilogue best, but the
 // number of tiles rarely divides evenly over the 256 compute units; one block less can save a whole
 // round of workgroups.  Cost of a choice = rounds x (main loop + epilogue) in matrix-core cycles
-// (32 per MFMA; prologue and epilogue constants measured on the Gemma-2-2B shapes).
+// (32 per MFMA, plus about 180 cycles per 64-wide k stage and bit-width that do not shrink with the tile:
+// conversions and the stage barrier - fitted on the 9B gate shape, where 160 tokens run 2.5-4 % faster than
+// 128 although both fill their rounds; prologue and epilogue constants measured on the Gemma-2-2B shapes).
 template <int NR, bool HAS8, bool EP, bool LOSS>
 static mq_status launch_fwd(const FwdArgs &a, hipStream_t st, int64_t *blocks) {
     constexpr int HI = fwd_mb(NR), LO = HI - 1;
     auto cost = [&](int mb) {
         const int64_t tiles = cdiv(a.M, 32 * mb) * cdiv(a.N, FWD_BN);
         const int64_t rounds = cdiv(tiles, 256);
-        const int64_t per_tile = cdiv(a.K, BKT) * NR * mb * 128 + 3000 + 890 * NR * mb;
+        const int64_t per_tile = cdiv(a.K, BKT) * (NR * mb * 128 + 180 * NR) + 3000 + 890 * NR * mb;
         return rounds * per_tile;
     };
     return cost(LO) < cost(HI) ? launch_fwd_mb<NR, HAS8, EP, LO, LOSS>(a, st, blocks)
