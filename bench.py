@@ -33,7 +33,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per launch of the fused forward kernel on the headline workload, per linear, from the
 # FETCH_SIZE / WRITE_SIZE counter passes summarised in profiles/ (scale factors stated there); None until taken.
-FWD_TRAFFIC_BYTES = {3: {"gate": 2526042 * 1024, "up": 2526042 * 1024, "down": 1950774 * 1024},
+FWD_TRAFFIC_BYTES = {3: {"gate": 2424021 * 1024, "up": 2424021 * 1024, "down": 1950779 * 1024},
                      2: {"gate": None, "up": None, "down": None}}
 WORKLOADS = {
     3: "configs[2]: Gemma-2-9B-shaped MLP, d_model 3584, ffn 14336, 8192 tokens, outlier weights, lambda = (0.1, 0.1, 1.0)",
