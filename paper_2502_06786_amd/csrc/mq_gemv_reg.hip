@@ -452,21 +452,23 @@ mq_status launch_gemv_reg(const GemvArgs &a, int r, hipStream_t st, bool *handle
     p.nsl = lines / p.nl;
     if (p.nsl > 16) return MQ_OK;          // one wave per slice, at most 16 waves
     p.ks = p.nsl;
-    // the whole grid resident at once: as many workgroups per compute unit as LDS and the 16 wave slots allow
+    // The whole grid resident at once, as many workgroups per compute unit as LDS and the 16 wave slots allow; planes
+    // with so many row blocks that a workgroup's partial outputs would not fit LDS run in two to four equal rounds.
     p.depth = 0;
-    for (int depth : {3, 2}) {
-        for (int per_cu = std::max(1, 16 / p.ks); per_cu >= 1 && !p.depth; --per_cu) {
-            const int grid = std::min(nrb, 256 * per_cu), ch = (nrb + grid - 1) / grid;
-            const size_t lds = (size_t)p.nsl * 128 + (size_t)p.ks * depth * kTile + (size_t)p.nsl * ch * 1024;
-            if (lds * per_cu <= 160 * 1024) {
-                p.depth = depth;
-                p.ch = ch;
-                p.grid = (nrb + ch - 1) / ch;
-                p.lds = lds;
+    for (int rounds = 1; rounds <= 4 && !p.depth; ++rounds)
+        for (int depth : {3, 2}) {
+            for (int per_cu = std::max(1, 16 / p.ks); per_cu >= 1 && !p.depth; --per_cu) {
+                const int grid = std::min(nrb, 256 * per_cu * rounds), ch = (nrb + grid - 1) / grid;
+                const size_t lds = (size_t)p.nsl * 128 + (size_t)p.ks * depth * kTile + (size_t)p.nsl * ch * 1024;
+                if (lds * per_cu <= 160 * 1024) {
+                    p.depth = depth;
+                    p.ch = ch;
+                    p.grid = (nrb + ch - 1) / ch;
+                    p.lds = lds;
+                }
             }
+            if (p.depth) break;
         }
-        if (p.depth) break;
-    }
     if (!p.depth || (int64_t)a.N * a.KB > 0x7FFFFFFFll) return MQ_OK;
     *handled = true;
 #define MQ_REG_CASE(R_, NL_)                                                   \

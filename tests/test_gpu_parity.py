@@ -523,7 +523,8 @@ def test_gemv_small_batch_tall_matrix(mq, oracle, r, N, K, B):
 
 
 @pytest.mark.parametrize("r,N,K,B,with_list", [(2, 32775, 1024, 16, False), (4, 32808, 2048, 5, False), (2, 32768, 4608, 9, False),
-                                               (4, 36864, 512, 16, False), (2, 32776, 1536, 8, True), (4, 32768, 1024, 13, True)])
+                                               (4, 36864, 512, 16, False), (2, 32776, 1536, 8, True), (4, 32768, 1024, 13, True),
+                                               (2, 32776, 8192, 5, False)])     # (16 slices: the plane runs in two rounds of workgroups)
 def test_gemv_mid_batch_tall_matrix(mq, oracle, r, N, K, B, with_list):
     """At least 32768 rows and 5 <= B <= 16 on int4 / int2 planes: the kernel that keeps the activations of a K slice
     in registers as 16-column matrix-core operands.  One and several lines per slice, several slices per workgroup,
