@@ -92,6 +92,13 @@ def test_workspace_bytes(lib):
     # three scaled gradient copies + transposed gradient sum + X^T + Q^T
     assert bwd >= 3 * M * N * 2 + M * N * 2 + M * K * 2 + N * K
     assert f(1, M, N, K, 1) < bwd
+    # dW tiles of 256 x 256 on 256 compute units: the tiles of a last partial round (at most half a round) are cut into
+    # token ranges that leave fp32 partial tiles in the workspace: 784 tiles on the 9B gate shape = 3 rounds + 16 tiles,
+    # 16 ranges each; none when the last round is more than half full (289 + ... tiles) or there is less than one round
+    base9 = 3 * 8192 * 14336 * 2 + 8192 * 14336 * 2 + 8192 * 3584 * 2 + 14336 * 3584
+    assert f(1, 8192, 14336, 3584, 3) >= base9 + 16 * 16 * 256 * 256 * 4
+    assert f(1, 8192, 14336, 3584, 3) < base9 + 16 * 16 * 256 * 256 * 4 + (8 << 20)
+    assert f(1, 8192, 2048, 2048, 3) < 3 * 8192 * 2048 * 2 + 8192 * 2048 * 2 + 8192 * 2048 * 2 + 2048 * 2048 + (4 << 20)   # 64 tiles
     assert f(0, -1, N, K, 3) == 0 and f(1, M, N, K, 4) == 0 and f(1, M, N, K, 0) == 0
     # decode feed-forward stack (M = B, N = F, K = d): the gated product and two copies of the state
     assert f(2, 4, 14336, 4096, 1) >= 4 * (14336 + 2 * 4096) * 2
